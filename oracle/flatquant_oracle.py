@@ -1,0 +1,233 @@
+"""Plain fp64 CPU oracle of the FlatQuant online transform + quantization path.
+
+TEST INFRASTRUCTURE ONLY.  This module is deliberately slow and literal: it
+materialises the dense n x n matrix P = P1 (x) P2, multiplies, clips and rounds,
+exactly in the order the method is stated in the paper.  It shares no code,
+tables or helpers with the HIP library and must never be imported by it.
+
+What each function follows
+--------------------------
+* kron_dense / affine_transform : Sec. 3.1 "Kronecker Product" -- P = P1 (x) P2
+  and the product X P of Eq. (2)'s left factor, with X~ the row-major reshape
+  of a token row to n1 x n2.
+* quantize_sym_int4            : Sec. 2.1 (uniform quantizer s * Pi(W / s)),
+  Sec. 4.1 "Quantization" (per-token symmetric for activations) and Sec. 3.1
+  "Learnable Clipping Thresholds" (alpha in (0, 1], applied after the
+  transform, shrinking the range that the grid covers).
+* kv_quantize_asym_int4        : Sec. 4.1 "Quantization" and App. "KV Cache
+  Quantization": group-wise asymmetric INT4, group = head_dim.  The paper
+  prints no formula for the asymmetric grid; the textbook min/max affine grid
+  that contains zero is used.  PARITY UNPINNED by the paper for this function;
+  it is pinned by invariants in the CPU tests.
+* kv_transform                 : Sec. 3.2 "Self-Attention": a dense per-head
+  matrix P_h applied head by head (not decomposed).
+* dequantize                   : Sec. 2.1, s * q (symmetric) or s * (q - z).
+
+Conventions fixed where the paper is silent (all listed in the design notes):
+row-major reshape (channel c = i * n2 + j); signed grid [-8, 7] with step
+alpha * max|y| / 7; the step is rounded once to fp16 (round-to-nearest-even,
+directly from fp64) and the *rounded* step divides; round-half-to-even; two
+codes per byte, even channel in the low nibble, two's complement nibbles.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+QMAX_SYM = 7          # largest positive symmetric INT4 code
+QMIN_SYM = -8
+QMAX_ASYM = 15        # unsigned INT4 grid of the KV-cache variant
+
+
+def as_f64(a) -> np.ndarray:
+    """fp16 (or any float) array -> fp64; exact for fp16/fp32 inputs."""
+    return np.asarray(a).astype(np.float64)
+
+
+def round_to_fp16(v) -> np.ndarray:
+    """One correctly rounded fp64 -> fp16 conversion (no fp32 stop-over)."""
+    return np.asarray(v, dtype=np.float64).astype(np.float16)
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.1, Kronecker product and Eq. (2)
+# --------------------------------------------------------------------------
+def kron_dense(P1, P2) -> np.ndarray:
+    """P = P1 (x) P2 as a dense fp64 matrix.
+
+    Block convention: P[i*n2 + j, i'*n2 + j'] = P1[i, i'] * P2[j, j'].
+    """
+    P1 = as_f64(P1)
+    P2 = as_f64(P2)
+    n1, n2 = P1.shape[0], P2.shape[0]
+    assert P1.shape == (n1, n1) and P2.shape == (n2, n2)
+    return np.kron(P1, P2)
+
+
+def affine_transform(x, P1, P2, P=None) -> np.ndarray:
+    """y = x P for every token row of x ([T, n]), fp64.  `P` may be a
+    pre-built kron_dense(P1, P2) to avoid rebuilding it."""
+    x = as_f64(x)
+    if P is None:
+        P = kron_dense(P1, P2)
+    assert x.ndim == 2 and x.shape[1] == P.shape[0]
+    return x @ P
+
+
+# --------------------------------------------------------------------------
+# Sec. 2.1 / 3.1 / 4.1: per-token symmetric INT4 with a clipping ratio
+# --------------------------------------------------------------------------
+def sym_scale(y, clip) -> np.ndarray:
+    """Per-row step s = fp16(alpha * max|y| / 7).  `clip` is a scalar or [T]."""
+    y = as_f64(y)
+    alpha = np.broadcast_to(as_f64(clip), (y.shape[0],))
+    m = np.max(np.abs(y), axis=1) if y.shape[1] else np.zeros(y.shape[0])
+    return round_to_fp16(alpha * m / QMAX_SYM)
+
+
+def preround_sym(y, scale_fp16) -> np.ndarray:
+    """u = y / s with the emitted (fp16) step; rows with s == 0 give u = 0."""
+    y = as_f64(y)
+    s = as_f64(scale_fp16).reshape(-1, 1)
+    u = np.zeros_like(y)
+    np.divide(y, s, out=u, where=(s != 0))
+    return u
+
+
+def round_clamp_sym(u) -> np.ndarray:
+    """q = clamp(round_half_even(u), -8, 7) as int8."""
+    return np.clip(np.rint(u), QMIN_SYM, QMAX_SYM).astype(np.int8)
+
+
+def quantize_sym_int4(y, clip, scale_fp16=None):
+    """Returns (q int8 [T, n], s fp16 [T], u fp64 [T, n]).
+
+    If `scale_fp16` is given it replaces the step this function would compute
+    (used by the comparator when two adjacent fp16 steps are both legitimate).
+    """
+    s = sym_scale(y, clip) if scale_fp16 is None else np.asarray(scale_fp16, dtype=np.float16)
+    u = preround_sym(y, s)
+    return round_clamp_sym(u), s, u
+
+
+def pack_nibbles(q) -> np.ndarray:
+    """Two 4-bit codes per byte: channel 2k -> low nibble, 2k+1 -> high nibble.
+    Works for signed (two's complement) and unsigned codes alike."""
+    q = np.asarray(q)
+    assert q.shape[-1] % 2 == 0
+    b = (q.astype(np.int16) & 0xF).astype(np.uint8)
+    return (b[..., 0::2] | (b[..., 1::2] << 4)).astype(np.uint8)
+
+
+def unpack_nibbles(packed, signed: bool) -> np.ndarray:
+    packed = np.asarray(packed, dtype=np.uint8)
+    lo = (packed & 0xF).astype(np.int8)
+    hi = (packed >> 4).astype(np.int8)
+    out = np.empty(packed.shape[:-1] + (packed.shape[-1] * 2,), dtype=np.int8)
+    out[..., 0::2] = lo
+    out[..., 1::2] = hi
+    if signed:
+        out = np.where(out >= 8, out - 16, out).astype(np.int8)
+    return out
+
+
+def transform_quant(x, P1, P2, clip, P=None):
+    """The whole online path for activations: Q(x (P1 (x) P2)).
+
+    Returns a dict with the packed codes (u8 [T, n/2]), the fp16 steps [T],
+    and the fp64 intermediates the comparator needs: y (transformed), u
+    (pre-round values), q (codes before packing).
+    """
+    y = affine_transform(x, P1, P2, P=P)
+    q, s, u = quantize_sym_int4(y, clip)
+    return {"codes": pack_nibbles(q), "scales": s, "q": q, "u": u, "y": y}
+
+
+# --------------------------------------------------------------------------
+# KV-cache variant (Sec. 3.2 per-head transform; Sec. 4.1 asymmetric groups)
+# --------------------------------------------------------------------------
+def kv_transform(kv, P) -> np.ndarray:
+    """kv [T, H, D] times P [Hp, D, D] (Hp == 1: shared; Hp == H: per head)."""
+    kv = as_f64(kv)
+    P = as_f64(P)
+    T, H, D = kv.shape
+    assert P.shape[1:] == (D, D) and P.shape[0] in (1, H)
+    y = np.empty_like(kv)
+    for h in range(H):
+        y[:, h, :] = kv[:, h, :] @ P[h if P.shape[0] == H else 0]
+    return y
+
+
+def kv_scale_zero(y, clip):
+    """Per group (last axis): mx = max(y, 0), mn = min(y, 0) scaled by alpha;
+    step s = fp16((mx - mn) / 15); zero point z = round(-mn / s) in [0, 15].
+    Returns (s fp16, z int8, zf fp64 = pre-round zero point)."""
+    y = as_f64(y)
+    a = float(clip)
+    mx = a * np.maximum(np.max(y, axis=-1), 0.0)
+    mn = a * np.minimum(np.min(y, axis=-1), 0.0)
+    s = round_to_fp16((mx - mn) / QMAX_ASYM)
+    s64 = as_f64(s)
+    zf = np.zeros_like(s64)
+    np.divide(-mn, s64, out=zf, where=(s64 != 0))
+    z = np.clip(np.rint(zf), 0, QMAX_ASYM).astype(np.int8)
+    return s, z, zf
+
+
+def kv_preround(y, scale_fp16) -> np.ndarray:
+    y = as_f64(y)
+    s = as_f64(scale_fp16)[..., None]
+    u = np.zeros_like(y)
+    np.divide(y, s, out=u, where=(s != 0))
+    return u
+
+
+def kv_quantize_asym_int4(y, clip, scale_fp16=None, zero=None):
+    """Returns (q uint8 in [0, 15], s fp16, z int8, u fp64, zf fp64)."""
+    s0, z0, zf = kv_scale_zero(y, clip)
+    s = s0 if scale_fp16 is None else np.asarray(scale_fp16, dtype=np.float16)
+    z = z0 if zero is None else np.asarray(zero).astype(np.int8)
+    u = kv_preround(y, s)
+    q = np.clip(np.rint(u) + z[..., None], 0, QMAX_ASYM).astype(np.uint8)
+    return q, s, z, u, zf
+
+
+def kv_transform_quant(kv, P, clip):
+    y = kv_transform(kv, P)
+    q, s, z, u, zf = kv_quantize_asym_int4(y, clip)
+    return {"codes": pack_nibbles(q), "scales": s, "zeros": z, "q": q, "u": u, "y": y, "zf": zf}
+
+
+# --------------------------------------------------------------------------
+# Sec. 2.1: de-quantization
+# --------------------------------------------------------------------------
+def dequantize(codes_packed, scales_fp16, zeros=None) -> np.ndarray:
+    """s * q (zeros is None: signed nibbles) or s * (q - z) (unsigned nibbles).
+    codes [..., n/2] u8, scales [...] fp16, zeros [...] -> fp64 [..., n]."""
+    q = unpack_nibbles(codes_packed, signed=zeros is None).astype(np.float64)
+    s = as_f64(scales_fp16)[..., None]
+    if zeros is not None:
+        q = q - as_f64(zeros)[..., None]
+    return s * q
+
+
+# --------------------------------------------------------------------------
+# Closed forms of the paper's cost analysis (App. "Overhead Analysis")
+# --------------------------------------------------------------------------
+def choose_factors(n: int):
+    """argmin (n1 + n2) s.t. n1 * n2 = n, n1 <= n2  (Sec. 3.1)."""
+    best = None
+    for n1 in range(1, int(np.sqrt(n)) + 1):
+        if n % n1 == 0:
+            best = (n1, n // n1)
+    return best
+
+
+def flops_per_token(n1: int, n2: int) -> int:
+    """Multiply-adds counted as 2 flops: X~ P2 then P1^T (.)."""
+    return 2 * n1 * n2 * n2 + 2 * n1 * n1 * n2
+
+
+def extra_param_bytes_per_block(h_d: int, h_i: int, a: int) -> int:
+    """fp16 bytes of the online transforms of one Transformer block with
+    perfect-square factorizations (App. "Memory Consumption")."""
+    return 2 * (4 * h_d + 2 * h_i + a * a + (h_d // a) ** 2)
