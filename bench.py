@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused FlatQuant transform + INT4 quantization kernel on one MI355X.
+
+A step is one pass of the whole online path (load tile, both contractions, absmax,
+clip, round, pack, store) over one batch: one flatquant_transform_quant launch on the
+LLaMA-2-7B prefill shape (T=2048 tokens, n=4096 = 64 x 64).  Inputs are resident in
+HBM before the timed region; launches rotate over enough distinct input/output sets
+that no launch finds its data in the 256 MB last-level cache ("cold", the headline),
+and the same is repeated on a single set ("warm").  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA, published
+
+
+def alg_bytes_per_token(n: int, per_token_clip: bool = True) -> int:
+    """fp16 row in + packed codes out + fp16 step out (+ fp32 clip in)."""
+    return 2 * n + n // 2 + 2 + (4 if per_token_clip else 0)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--no-extras", action="store_true", help="skip the secondary shapes (decode, 70B, KV cache)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing and the parity check")
+    ap.add_argument("--wide", action="store_true", help="also time the n=28672 (112 x 256) shape")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; the path shards over tokens without any exchange "
+              "(see DESIGN.md), so no multi-GPU figure is produced. Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2410_09426_amd import binding as fq
+    from paper_2410_09426_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    fq.lib()
+
+    def dev(a):
+        if a.dtype == np.float16:
+            return torch.from_numpy(a.view(np.uint16).copy()).view(torch.float16).cuda()
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    def time_region(fn, steps, warmup):
+        """fn(i) enqueues step i on the current stream. Returns ms per step (events on that stream)."""
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for i in range(steps):
+            fn(i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+    # ------------------------------------------------------------------ headline: prefill 7B
+    c = synth.prefill_7b()
+    T, n, n1, n2 = c.T, c.n, c.n1, c.n2
+    P1, P2, clip = dev(c.P1), dev(c.P2), dev(c.clip)
+    bytes_per_launch = T * alg_bytes_per_token(n)
+    nsets = max(2, int(np.ceil(1.25e9 / bytes_per_launch)))          # > 1 GB of distinct lines in rotation
+    x0 = dev(c.x)
+    xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
+    codes = [torch.empty((T, n // 2), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+    scales = [torch.empty((T,), dtype=torch.float16, device="cuda") for _ in range(nsets)]
+    clips = [clip] + [clip.clone() for _ in range(nsets - 1)]
+
+    def step_cold(i):
+        k = i % nsets
+        fq.flatquant_transform_quant(xs[k], P1, P2, clips[k], 1, T, n1, n2, n, codes[k], scales[k], stream=stream)
+
+    def step_warm(i):
+        fq.flatquant_transform_quant(xs[0], P1, P2, clips[0], 1, T, n1, n2, n, codes[0], scales[0], stream=stream)
+
+    ms_cold, wall_cold = time_region(step_cold, args.steps, args.warmup)
+    ms_warm, _ = time_region(step_warm, args.steps, args.warmup)
+    for k in range(1, nsets):                                         # every rotation set produced the same bytes
+        assert torch.equal(codes[k], codes[0]) and torch.equal(scales[k].view(torch.int16), scales[0].view(torch.int16))
+
+    tokens_per_s = T / (ms_cold * 1e-3)
+    achieved = bytes_per_launch / (ms_cold * 1e-3) / 1e9
+    flops_min = 2 * n * (n1 + n2) * T
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "tq_prefill_7b_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+
+    out = {
+        "metric": "fused transform+INT4-quant tokens/s (n=4096, T=2048)",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_cold,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "LLaMA-2-7B prefill shape: T=2048, n=4096 (n1=n2=64), per-token clip, fp16 in, INT4 codes + fp16 step out",
+                   "cache": f"cold: rotation over {nsets} input/output sets ({nsets * bytes_per_launch / 1e9:.2f} GB)"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic},
+        "detail": {
+            "algorithmic_bytes_per_launch": bytes_per_launch,
+            "us_per_call_cold": ms_cold * 1e3, "us_per_call_warm": ms_warm * 1e3,
+            "host_wall_us_per_call_cold": wall_cold * 1e3,
+            "tokens_per_s_warm": T / (ms_warm * 1e-3),
+            "gbs_warm": bytes_per_launch / (ms_warm * 1e-3) / 1e9,
+            "mfma_tflops_min_count": flops_min / (ms_cold * 1e-3) / 1e12,
+            "mfma_frac_of_f16_peak_min_count": flops_min / (ms_cold * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS,
+        },
+    }
+
+    # ------------------------------------------------------------------ reference point: plain copy with the same 4:1 mix
+    src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda")      # 256 MB read
+    dst = torch.empty((64 << 20,), dtype=torch.uint8, device="cuda")       # 64 MB written
+
+    def step_copy(i):
+        dst.copy_(src[:dst.numel()])
+        src[dst.numel():].sum(dtype=torch.int64) if False else None
+
+    ms_copy, _ = time_region(lambda i: dst.copy_(src[:dst.numel()]), 50, 10)
+    out["detail"]["torch_copy_64MB_gbs"] = 2 * dst.numel() / (ms_copy * 1e-3) / 1e9
+    del src, dst
+
+    # ------------------------------------------------------------------ secondary shapes
+    if not args.no_extras:
+        extras = {}
+
+        def time_shape(name, Tn, a, b, steps, warmup, cold_sets=1):
+            nn = a * b
+            g = torch.Generator(device="cuda").manual_seed(1234 + nn)
+            col = torch.ones(nn, device="cuda")
+            idx = torch.randperm(nn, generator=g, device="cuda")[: max(1, nn // 100)]
+            col[idx] = torch.empty(idx.numel(), device="cuda").uniform_(20, 100, generator=g)
+            xsets = []
+            for _ in range(cold_sets):
+                xx = torch.empty((Tn, nn), dtype=torch.float16, device="cuda")
+                for r0 in range(0, Tn, 2048):
+                    r1 = min(Tn, r0 + 2048)
+                    blk = torch.randn((r1 - r0, nn), generator=g, device="cuda") * col
+                    xx[r0:r1] = blk.clamp_(-30000, 30000).half()
+                xsets.append(xx)
+            p1 = (torch.eye(a, device="cuda") + 0.05 * torch.randn((a, a), generator=g, device="cuda")).half()
+            p2 = (torch.eye(b, device="cuda") + 0.05 * torch.randn((b, b), generator=g, device="cuda")).half()
+            cl = torch.sigmoid(torch.empty(Tn, device="cuda").uniform_(1.5, 3.0, generator=g)).float()
+            oc = [torch.empty((Tn, nn // 2), dtype=torch.uint8, device="cuda") for _ in range(cold_sets)]
+            os_ = [torch.empty((Tn,), dtype=torch.float16, device="cuda") for _ in range(cold_sets)]
+
+            def st(i):
+                k = i % cold_sets
+                fq.flatquant_transform_quant(xsets[k], p1, p2, cl, 1, Tn, a, b, nn, oc[k], os_[k], stream=stream)
+            ms, _ = time_region(st, steps, warmup)
+            by = Tn * alg_bytes_per_token(nn)
+            extras[name] = {"T": Tn, "n1": a, "n2": b, "us_per_call": ms * 1e3, "tokens_per_s": Tn / (ms * 1e-3),
+                            "gbs": by / (ms * 1e-3) / 1e9, "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "mfma_tflops_min_count": 2 * nn * (a + b) * Tn / (ms * 1e-3) / 1e12}
+
+        time_shape("decode_4096", 64, 64, 64, 500, 50)
+        time_shape("decode_11008", 64, 86, 128, 500, 50)
+        time_shape("prefill_70b_8192", 16384, 64, 128, 30, 5, cold_sets=4)
+        if args.wide:
+            time_shape("prefill_70b_28672", 16384, 112, 256, 10, 2, cold_sets=1)
+
+        # KV-cache variant: 32768 tokens x 8 heads x 128, K and V alternate (two distinct 67 MB inputs + more sets for cold)
+        Tk, H, D = 32768, 8, 128
+        g = torch.Generator(device="cuda").manual_seed(99)
+        kvsets = [torch.randn((Tk, H, D), generator=g, device="cuda").half() for _ in range(8)]
+        Pk = (torch.eye(D, device="cuda").expand(H, D, D) + 0.05 * torch.randn((H, D, D), generator=g, device="cuda")).half().contiguous()
+        kc = [torch.empty((Tk * H, D // 2), dtype=torch.uint8, device="cuda") for _ in range(8)]
+        ks = [torch.empty((Tk * H,), dtype=torch.float16, device="cuda") for _ in range(8)]
+        kz = [torch.empty((Tk * H,), dtype=torch.float16, device="cuda") for _ in range(8)]
+
+        def st_kv(i):
+            k = i % 8
+            fq.flatquant_kv_transform_quant(kvsets[k], Pk, H, 0.95, Tk, H, D, kc[k], ks[k], kz[k], stream=stream)
+        ms, _ = time_region(st_kv, 100, 10)
+        by = Tk * H * (2 * D + D // 2 + 4)
+        extras["kv_cache"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms * 1e3, "groups_per_s": Tk * H / (ms * 1e-3),
+                              "gbs": by / (ms * 1e-3) / 1e9, "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del kvsets, kc, ks, kz
+        out["extras"] = extras
+
+    # ------------------------------------------------------------------ CPU oracle: baseline timing + parity of the timed buffers
+    if not args.no_cpu:
+        from oracle import flatquant_oracle as fo
+        from oracle import parity
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        t0 = time.perf_counter()
+        P = fo.kron_dense(c.P1, c.P2)
+        t_kron = time.perf_counter() - t0
+        reps, t_run = 0, 0.0
+        while reps < 3 or (t_run < 10.0 and reps < 12):
+            t0 = time.perf_counter()
+            res = fo.transform_quant(c.x, c.P1, c.P2, c.clip, P=P)
+            t_run += time.perf_counter() - t0
+            reps += 1
+        out["cpu_baseline"] = {"value": T * reps / t_run, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"all {T} tokens of the headline workload, {reps} passes of the fp64 dense-Kronecker oracle "
+                                         f"(numpy); building the {n}x{n} matrix once took {t_kron:.2f} s and is not in the rate"}
+        rep = parity.check_sym(res["y"], c.clip, codes[0].cpu().numpy(),
+                               scales[0].cpu().view(torch.int16).numpy().view(np.float16))
+        out["detail"]["parity_on_timed_buffers"] = rep
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

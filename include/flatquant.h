@@ -1,0 +1,125 @@
+/*
+ * flatquant.h -- C ABI of the MI355X (gfx950) FlatQuant online path.
+ *
+ * The library fuses, in one kernel launch per call and with no intermediate
+ * trip through device memory, the per-token Kronecker affine transform and the
+ * low-bit quantization that FlatQuant runs in front of every quantized linear
+ * layer (Sec. 3.1 "Kronecker Product", Eq. (2); Sec. 3.3 "Efficient Kernel
+ * Design"; App. "Detailed Design of Kernel Fusion").
+ *
+ * General rules for every entry point
+ *   - All data pointers are DEVICE pointers unless a comment says "host".
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no
+ *     state besides a thread-local last-HIP-error code, and never synchronises:
+ *     work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and outputs are valid once the stream reaches that point.
+ *   - Inputs are never modified.  Inputs and outputs must not overlap.
+ *   - Errors are reported through the return value only (no abort, no output).
+ *     On any error nothing is launched and no output byte is written.
+ *   - fp16 means IEEE binary16 bit patterns.
+ */
+#ifndef FLATQUANT_H_
+#define FLATQUANT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int fq_status;
+enum {
+    FQ_OK = 0,
+    FQ_INVALID_ARG = 1,       /* null pointer, negative size, odd n1*n2, bad mode, stride < n */
+    FQ_UNSUPPORTED_SHAPE = 2, /* no kernel variant for this (n1, n2) / (H, D); see fq_supported() */
+    FQ_MISALIGNED = 3,        /* a pointer or stride violates the alignment stated below */
+    FQ_LAUNCH_FAILED = 4      /* the HIP runtime refused the launch; see fq_last_hip_error() */
+};
+
+/*
+ * Activation path:  Q( P1^T x_1 X~ x_2 P2 )  ==  Q( X (P1 (x) P2) )
+ * (Eq. (2), left factor; Sec. 3.3).  For every token row x_t of width
+ * n = n1*n2, viewed row-major as X~_t (n1 x n2, channel c = i*n2 + j):
+ *     Y_t = P1^T X~_t P2
+ *     s_t = fp16( clip_t * max_c |Y_t[c]| / 7 )            (Sec. 3.1 "Learnable Clipping Thresholds",
+ *     q_t[c] = clamp( round_half_even( Y_t[c] / s_t ), -8, 7 )   Sec. 4.1 "Quantization": per-token symmetric)
+ * A row whose step rounds to zero gets step +0 and all-zero codes.
+ *
+ *   x          fp16 [T, n], row t starts at x + t*x_stride halves; x_stride >= n.
+ *              Alignment: 4 bytes (base and row pitch, i.e. x_stride even).
+ *   P1         fp16 [n1, n1] row-major, NOT transposed (the kernel applies P1^T).
+ *   P2         fp16 [n2, n2] row-major.
+ *   clip       fp32; clip_mode 0: one value shared by all tokens (the paper's
+ *              layer-wise threshold); clip_mode 1: T values, one per token.
+ *              Values are the thresholds after the sigmoid, expected in (0, 1].
+ *   out_codes  u8 [T, n/2] contiguous; byte k of a row = (q[2k] & 15) | (q[2k+1] & 15) << 4,
+ *              two's-complement nibbles.  Alignment: 4 bytes.
+ *   out_scales fp16 [T].
+ * T == 0 returns FQ_OK without launching.  n1*n2 must be even, 1 <= n1 <= 128,
+ * 2 <= n2 <= 256 and n2 even (fq_supported).  The result is defined while x, the
+ * intermediate X~ P2 and Y stay finite in fp16 range (|.| < 65504).
+ */
+fq_status flatquant_transform_quant(const void* x, const void* P1, const void* P2,
+                                    const float* clip, int clip_mode,
+                                    int64_t T, int n1, int n2, int64_t x_stride,
+                                    uint8_t* out_codes, void* out_scales, void* stream);
+
+/*
+ * KV-cache path (Sec. 3.2 "Self-Attention": P_h / P_v applied head by head,
+ * not decomposed; Sec. 4.1: group-wise asymmetric INT4, group = head_dim).
+ * For every (token, head) group g of D values:
+ *     y  = kv_g P_h
+ *     mx = clip * max(max y, 0),  mn = clip * min(min y, 0)
+ *     s  = fp16( (mx - mn) / 15 ),  z = clamp( round_half_even( -mn / s ), 0, 15 )
+ *     q[d] = clamp( round_half_even( y[d] / s ) + z, 0, 15 )
+ *
+ *   kv         fp16 [T, H, D] contiguous, 16-byte aligned.  D must be 128.
+ *   P          fp16 [Hp, D, D] row-major; Hp == 1 (one matrix shared by all
+ *              heads) or Hp == H (one per head).
+ *   out_codes  u8 [T, H, D/2], unsigned nibbles, even channel in the low nibble; 16-byte aligned.
+ *   out_scales fp16 [T, H];  out_zeros fp16 [T, H] holding the integer z.
+ */
+fq_status flatquant_kv_transform_quant(const void* kv, const void* P, int Hp, float clip,
+                                       int64_t T, int H, int D,
+                                       uint8_t* out_codes, void* out_scales, void* out_zeros,
+                                       void* stream);
+
+/*
+ * De-quantization check helper (Sec. 2.1: W^ = s * Pi(W / s)).
+ *   zeros == NULL : out[r, c] = s[r] * q[r, c]            (signed nibbles)
+ *   zeros != NULL : out[r, c] = s[r] * (q[r, c] - z[r])   (unsigned nibbles)
+ *   codes u8 [rows, n/2]; scales, zeros fp16 [rows]; out fp32 [rows, n]; n even.
+ */
+fq_status flatquant_dequant(const uint8_t* codes, const void* scales, const void* zeros,
+                            int64_t rows, int n, float* out, void* stream);
+
+/* ---- host-only helpers: no GPU is touched ---------------------------------- */
+
+/* 1 if flatquant_transform_quant has a kernel variant for (n1, n2), else 0. */
+int fq_supported(int n1, int n2);
+
+/* The paper's factor rule (Sec. 3.1): argmin (n1 + n2) s.t. n1*n2 == n, n1 <= n2.
+ * n < 1 leaves the outputs untouched and returns FQ_INVALID_ARG.  Host pointers. */
+fq_status fq_choose_factors(int64_t n, int* n1, int* n2);
+
+/* On-chip footprint test of App. "Detailed Design of Kernel Fusion": returns 1
+ * when (n1*n1 + 2*n1*n2)*2 < m and (n2*n2 + 2*n1*n2)*2 < m for m bytes of
+ * on-chip memory per workgroup (the paper's "default design" condition). */
+int fq_default_design_fits(int n1, int n2, int64_t m_bytes);
+
+/* LDS bytes the fused kernel of this library requests for (n1, n2); 0 if unsupported. */
+int64_t fq_lds_bytes(int n1, int n2);
+
+const char* fq_status_string(fq_status s);
+
+/* hipError_t of the most recent failed launch on this thread (0 if none). */
+int fq_last_hip_error(void);
+
+/* Library version, bumped when the ABI changes. */
+int fq_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLATQUANT_H_ */

@@ -1,0 +1,138 @@
+"""ctypes binding of libflatquant.so: argument marshalling only.
+
+Functions have the names of the C entry points (see include/flatquant.h).  They
+accept raw device addresses (ints) or objects with ``data_ptr()`` (torch
+tensors); nothing is computed in Python.  There is no fallback: if the shared
+library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libflatquant.so")
+
+FQ_OK, FQ_INVALID_ARG, FQ_UNSUPPORTED_SHAPE, FQ_MISALIGNED, FQ_LAUNCH_FAILED = range(5)
+
+EXPORTS = (
+    "flatquant_transform_quant", "flatquant_kv_transform_quant", "flatquant_dequant",
+    "fq_supported", "fq_choose_factors", "fq_default_design_fits", "fq_lds_bytes",
+    "fq_status_string", "fq_last_hip_error", "fq_abi_version",
+)
+
+_lib = None
+
+
+class FlatQuantError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status}, hip error {last_hip_error()})")
+
+
+def lib() -> ctypes.CDLL:
+    """Load the shared library once.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2410_09426_amd.build` "
+                "(there is no CPU fallback for the FlatQuant kernels)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float
+        L.flatquant_transform_quant.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i64, vp, vp, vp]
+        L.flatquant_transform_quant.restype = i32
+        L.flatquant_kv_transform_quant.argtypes = [vp, vp, i32, f32, i64, i32, i32, vp, vp, vp, vp]
+        L.flatquant_kv_transform_quant.restype = i32
+        L.flatquant_dequant.argtypes = [vp, vp, vp, i64, i32, vp, vp]
+        L.flatquant_dequant.restype = i32
+        L.fq_supported.argtypes = [i32, i32]
+        L.fq_supported.restype = i32
+        L.fq_choose_factors.argtypes = [i64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.fq_choose_factors.restype = i32
+        L.fq_default_design_fits.argtypes = [i32, i32, i64]
+        L.fq_default_design_fits.restype = i32
+        L.fq_lds_bytes.argtypes = [i32, i32]
+        L.fq_lds_bytes.restype = i64
+        L.fq_status_string.argtypes = [i32]
+        L.fq_status_string.restype = ctypes.c_char_p
+        L.fq_last_hip_error.argtypes = []
+        L.fq_last_hip_error.restype = i32
+        L.fq_abi_version.argtypes = []
+        L.fq_abi_version.restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(obj) -> Optional[int]:
+    if obj is None:
+        return None
+    if isinstance(obj, int):
+        return obj
+    return int(obj.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None      # torch.cuda.Stream
+
+
+def status_string(status: int) -> str:
+    return lib().fq_status_string(int(status)).decode()
+
+
+def last_hip_error() -> int:
+    return int(lib().fq_last_hip_error())
+
+
+def flatquant_transform_quant(x, P1, P2, clip, clip_mode: int, T: int, n1: int, n2: int, x_stride: int,
+                              out_codes, out_scales, stream=None, check: bool = True) -> int:
+    st = lib().flatquant_transform_quant(_ptr(x), _ptr(P1), _ptr(P2), _ptr(clip), int(clip_mode), int(T), int(n1),
+                                         int(n2), int(x_stride), _ptr(out_codes), _ptr(out_scales), _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_transform_quant")
+    return st
+
+
+def flatquant_kv_transform_quant(kv, P, Hp: int, clip: float, T: int, H: int, D: int, out_codes, out_scales, out_zeros,
+                                 stream=None, check: bool = True) -> int:
+    st = lib().flatquant_kv_transform_quant(_ptr(kv), _ptr(P), int(Hp), float(clip), int(T), int(H), int(D),
+                                            _ptr(out_codes), _ptr(out_scales), _ptr(out_zeros), _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_kv_transform_quant")
+    return st
+
+
+def flatquant_dequant(codes, scales, zeros, rows: int, n: int, out, stream=None, check: bool = True) -> int:
+    st = lib().flatquant_dequant(_ptr(codes), _ptr(scales), _ptr(zeros), int(rows), int(n), _ptr(out), _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_dequant")
+    return st
+
+
+def fq_supported(n1: int, n2: int) -> bool:
+    return bool(lib().fq_supported(int(n1), int(n2)))
+
+
+def fq_choose_factors(n: int):
+    a, b = ctypes.c_int(0), ctypes.c_int(0)
+    st = lib().fq_choose_factors(int(n), ctypes.byref(a), ctypes.byref(b))
+    if st != FQ_OK:
+        raise FlatQuantError(st, "fq_choose_factors")
+    return a.value, b.value
+
+
+def fq_default_design_fits(n1: int, n2: int, m_bytes: int) -> bool:
+    return bool(lib().fq_default_design_fits(int(n1), int(n2), int(m_bytes)))
+
+
+def fq_lds_bytes(n1: int, n2: int) -> int:
+    return int(lib().fq_lds_bytes(int(n1), int(n2)))
+
+
+def fq_abi_version() -> int:
+    return int(lib().fq_abi_version())

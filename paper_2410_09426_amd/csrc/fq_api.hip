@@ -1,0 +1,141 @@
+// C ABI of libflatquant: argument checks, variant selection, launch.  No compute here.
+#include "../../include/flatquant.h"
+#include "fq_internal.h"
+
+#include <cstdlib>
+
+namespace fq {
+
+static thread_local int g_last_hip_error = 0;
+
+int cu_count() {
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+int env_int(const char* name, int dflt) {
+    const char* v = std::getenv(name);
+    if (!v || !*v) return dflt;
+    return std::atoi(v);
+}
+
+static fq_status finish(hipError_t e) {
+    if (e == hipSuccess) return FQ_OK;
+    g_last_hip_error = (int)e;
+    return FQ_LAUNCH_FAILED;
+}
+
+static bool overlap(const void* a, int64_t na, const void* b, int64_t nb) {
+    const char* pa = static_cast<const char*>(a);
+    const char* pb = static_cast<const char*>(b);
+    return pa < pb + nb && pb < pa + na;
+}
+
+}  // namespace fq
+
+extern "C" {
+
+fq_status flatquant_transform_quant(const void* x, const void* P1, const void* P2, const float* clip, int clip_mode,
+                                    int64_t T, int n1, int n2, int64_t x_stride, uint8_t* out_codes, void* out_scales,
+                                    void* stream) {
+    if (T < 0 || n1 < 1 || n2 < 1 || (clip_mode != 0 && clip_mode != 1)) return FQ_INVALID_ARG;
+    const int64_t n = (int64_t)n1 * n2;
+    if (n % 2 != 0 || x_stride < n) return FQ_INVALID_ARG;
+    if (!fq::tq_supported(n1, n2)) return FQ_UNSUPPORTED_SHAPE;
+    if (T == 0) return FQ_OK;
+    if (!x || !P1 || !P2 || !clip || !out_codes || !out_scales) return FQ_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(x) & 3) || (x_stride & 1) || (reinterpret_cast<uintptr_t>(P1) & 1) ||
+        (reinterpret_cast<uintptr_t>(P2) & 1) || (reinterpret_cast<uintptr_t>(clip) & 3) ||
+        (reinterpret_cast<uintptr_t>(out_scales) & 1))
+        return FQ_MISALIGNED;
+    const int64_t xbytes = ((T - 1) * x_stride + n) * 2;
+    if (fq::overlap(x, xbytes, out_codes, T * (n / 2)) || fq::overlap(x, xbytes, out_scales, T * 2) ||
+        fq::overlap(out_codes, T * (n / 2), out_scales, T * 2))
+        return FQ_INVALID_ARG;
+    fq::TqArgs a;
+    a.x = static_cast<const _Float16*>(x);
+    a.P1 = static_cast<const _Float16*>(P1);
+    a.P2 = static_cast<const _Float16*>(P2);
+    a.clip = clip; a.clip_mode = clip_mode; a.T = T; a.n1 = n1; a.n2 = n2; a.x_stride = x_stride;
+    a.out_codes = out_codes; a.out_scales = static_cast<_Float16*>(out_scales);
+    return fq::finish(fq::tq_launch(a, static_cast<hipStream_t>(stream)));
+}
+
+fq_status flatquant_kv_transform_quant(const void* kv, const void* P, int Hp, float clip, int64_t T, int H, int D,
+                                       uint8_t* out_codes, void* out_scales, void* out_zeros, void* stream) {
+    if (T < 0 || H < 1 || D < 1 || !(clip > 0.0f)) return FQ_INVALID_ARG;
+    if (Hp != 1 && Hp != H) return FQ_INVALID_ARG;
+    if (D != 128 || H > 65535) return FQ_UNSUPPORTED_SHAPE;
+    if (T == 0) return FQ_OK;
+    if (!kv || !P || !out_codes || !out_scales || !out_zeros) return FQ_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(kv) & 15) || (reinterpret_cast<uintptr_t>(out_codes) & 15) ||
+        (reinterpret_cast<uintptr_t>(P) & 1) || (reinterpret_cast<uintptr_t>(out_scales) & 1) ||
+        (reinterpret_cast<uintptr_t>(out_zeros) & 1))
+        return FQ_MISALIGNED;
+    const int64_t g = T * H;
+    if (fq::overlap(kv, g * D * 2, out_codes, g * D / 2) || fq::overlap(kv, g * D * 2, out_scales, g * 2) ||
+        fq::overlap(kv, g * D * 2, out_zeros, g * 2) || fq::overlap(out_scales, g * 2, out_zeros, g * 2))
+        return FQ_INVALID_ARG;
+    fq::KvArgs a;
+    a.kv = static_cast<const _Float16*>(kv); a.P = static_cast<const _Float16*>(P); a.Hp = Hp; a.clip = clip;
+    a.T = T; a.H = H; a.D = D; a.out_codes = out_codes;
+    a.out_scales = static_cast<_Float16*>(out_scales); a.out_zeros = static_cast<_Float16*>(out_zeros);
+    return fq::finish(fq::kv_launch(a, static_cast<hipStream_t>(stream)));
+}
+
+fq_status flatquant_dequant(const uint8_t* codes, const void* scales, const void* zeros, int64_t rows, int n, float* out,
+                            void* stream) {
+    if (rows < 0 || n < 2 || (n & 1)) return FQ_INVALID_ARG;
+    if (rows == 0) return FQ_OK;
+    if (!codes || !scales || !out) return FQ_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(scales) & 1) || (reinterpret_cast<uintptr_t>(zeros) & 1) ||
+        (reinterpret_cast<uintptr_t>(out) & 3))
+        return FQ_MISALIGNED;
+    return fq::finish(fq::dequant_launch(codes, static_cast<const _Float16*>(scales), static_cast<const _Float16*>(zeros),
+                                         rows, n, out, static_cast<hipStream_t>(stream)));
+}
+
+int fq_supported(int n1, int n2) { return fq::tq_supported(n1, n2) ? 1 : 0; }
+
+fq_status fq_choose_factors(int64_t n, int* n1, int* n2) {
+    if (n < 1 || !n1 || !n2) return FQ_INVALID_ARG;
+    int64_t best = 1;
+    for (int64_t d = 1; d * d <= n; ++d)
+        if (n % d == 0) best = d;
+    *n1 = (int)best;
+    *n2 = (int)(n / best);
+    return FQ_OK;
+}
+
+int fq_default_design_fits(int n1, int n2, int64_t m_bytes) {
+    if (n1 < 1 || n2 < 1) return 0;
+    const int64_t a = ((int64_t)n1 * n1 + 2LL * n1 * n2) * 2;
+    const int64_t b = ((int64_t)n2 * n2 + 2LL * n1 * n2) * 2;
+    return (a < m_bytes && b < m_bytes) ? 1 : 0;
+}
+
+int64_t fq_lds_bytes(int n1, int n2) { return fq::tq_lds_bytes(n1, n2); }
+
+const char* fq_status_string(fq_status s) {
+    switch (s) {
+        case FQ_OK: return "ok";
+        case FQ_INVALID_ARG: return "invalid argument";
+        case FQ_UNSUPPORTED_SHAPE: return "unsupported shape";
+        case FQ_MISALIGNED: return "misaligned pointer or stride";
+        case FQ_LAUNCH_FAILED: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int fq_last_hip_error(void) { return fq::g_last_hip_error; }
+
+int fq_abi_version(void) { return 1; }
+
+}  // extern "C"

@@ -1,0 +1,41 @@
+// De-quantization check helper: out = s * q (signed nibbles) or s * (q - z)
+// (unsigned nibbles), Sec. 2.1.  Plain bandwidth kernel: one thread per 4 code bytes.
+#include "fq_internal.h"
+
+namespace fq {
+
+__global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict__ codes, const _Float16* __restrict__ scales,
+                                                       const _Float16* __restrict__ zeros, int64_t rows, int n, float* __restrict__ out) {
+    const int nbytes = n >> 1;
+    const int units = (nbytes + 3) >> 2;                 // 4-byte units per row (last one may be partial)
+    const int64_t total = rows * units;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = g / units;
+        const int b0 = (int)(g - r * units) * 4;
+        const float s = (float)scales[r];
+        const float z = zeros ? (float)zeros[r] : 0.0f;
+        const uint8_t* src = codes + r * nbytes;
+        float* dst = out + r * (int64_t)n;
+        for (int b = b0; b < b0 + 4 && b < nbytes; ++b) {
+            const uint32_t v = src[b];
+            int lo = v & 15, hi = v >> 4;
+            if (!zeros) { lo = (lo ^ 8) - 8; hi = (hi ^ 8) - 8; }   // two's complement nibble -> int
+            dst[2 * b] = s * ((float)lo - z);
+            dst[2 * b + 1] = s * ((float)hi - z);
+        }
+    }
+}
+
+hipError_t dequant_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,
+                          int64_t rows, int n, float* out, hipStream_t stream) {
+    const int units = ((n >> 1) + 3) >> 2;
+    const int64_t total = rows * units;
+    int64_t grid = (total + 255) / 256;
+    const int64_t cap = (int64_t)cu_count() * 16;
+    if (grid > cap) grid = cap;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(dequant_kernel, dim3((unsigned)grid), dim3(256), 0, stream, codes, scales, zeros, rows, n, out);
+    return hipGetLastError();
+}
+
+}  // namespace fq

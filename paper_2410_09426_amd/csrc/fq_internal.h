@@ -1,0 +1,54 @@
+// Internal declarations shared by the translation units of libflatquant.
+// Nothing here is part of the public ABI (see include/flatquant.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fq {
+
+constexpr int kTile = 32;          // MFMA tile edge (v_mfma_f32_32x32x16_f16)
+constexpr int kMaxN1 = 128;        // up to 4 row tiles
+constexpr int kMaxN2 = 256;        // up to 8 column slabs (one wavefront each)
+constexpr int kLdsPad = 8;         // halves of padding per LDS row (keeps 16-byte reads off one bank group)
+
+struct TqArgs {
+    const _Float16* x;
+    const _Float16* P1;
+    const _Float16* P2;
+    const float* clip;
+    int clip_mode;
+    int64_t T;
+    int n1, n2;
+    int64_t x_stride;
+    uint8_t* out_codes;
+    _Float16* out_scales;
+};
+
+// LDS bytes of the fused activation kernel for (n1, n2); 0 if unsupported.
+int64_t tq_lds_bytes(int n1, int n2);
+bool tq_supported(int n1, int n2);
+// Enqueue the fused kernel; returns hipSuccess or the launch error.
+hipError_t tq_launch(const TqArgs& a, hipStream_t stream);
+
+struct KvArgs {
+    const _Float16* kv;
+    const _Float16* P;
+    int Hp;
+    float clip;
+    int64_t T;
+    int H, D;
+    uint8_t* out_codes;
+    _Float16* out_scales;
+    _Float16* out_zeros;
+};
+hipError_t kv_launch(const KvArgs& a, hipStream_t stream);
+
+hipError_t dequant_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,
+                          int64_t rows, int n, float* out, hipStream_t stream);
+
+// Number of compute units of the current device (cached per device).
+int cu_count();
+// Integer tuning override from the environment (bench / sweep aid); `dflt` if unset.
+int env_int(const char* name, int dflt);
+
+}  // namespace fq

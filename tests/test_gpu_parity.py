@@ -1,0 +1,199 @@
+"""Parity of the HIP path against the fp64 oracle, through the C ABI, on a real MI355X.
+
+Bars (written here as the comparator enforces them, see oracle/parity.py):
+steps within 1e-3 relative; codes bit-exact wherever the fp64 pre-round value is
+more than 1e-3 away from a rounding boundary; de-quantized values within
+1e-2 * step outside that band.
+"""
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import flatquant_oracle as fo  # noqa: E402
+from oracle import parity  # noqa: E402
+from paper_2410_09426_amd import binding as fq  # noqa: E402
+from paper_2410_09426_amd import synth  # noqa: E402
+
+from gpu_util import dev, run_dequant, run_tq  # noqa: E402
+
+
+def check_case(c, rows=None, with_dequant=True, label=""):
+    """Run the whole case on the GPU, compare `rows` (default: all) with the oracle."""
+    print(f"[case] {c.name} T={c.T} n1={c.n1} n2={c.n2} {label}", flush=True)
+    x, P1, P2, clip = dev(c.x), dev(c.P1), dev(c.P2), dev(c.clip)
+    codes, scales, codes_d, scales_d = run_tq(x, P1, P2, clip, c.clip_mode, c.n1, c.n2)
+    rows = np.arange(c.T) if rows is None else np.asarray(rows)
+    P = fo.kron_dense(c.P1, c.P2)
+    y = fo.affine_transform(c.x[rows], None, None, P=P)
+    del P
+    clipv = c.clip[rows] if c.clip_mode == 1 else float(c.clip[0])
+    deq = None
+    if with_dequant:
+        deq = run_dequant(codes_d, scales_d, None, c.T, c.n)[rows]
+    rep = parity.check_sym(y, clipv, codes[rows], scales[rows], deq_dev=deq, rows=rows)
+    print(f"[parity] {c.name}: {rep}", flush=True)
+    assert rep["band_flips"] <= max(4, rep["in_band"])
+    return rep, codes, scales
+
+
+def subset_rows(T, k, seed, must=(0,)):
+    r = np.random.Generator(np.random.PCG64(seed))
+    rows = set(int(t) for t in must if t < T)
+    rows.update(int(v) for v in r.choice(T, size=min(k, T), replace=False))
+    rows.add(T - 1)
+    return np.array(sorted(rows))
+
+
+def test_tiny():
+    check_case(synth.tiny())
+
+
+def test_prefill_7b_full():
+    rep, _, _ = check_case(synth.prefill_7b())
+    assert rep["rows"] == 2048
+
+
+def test_prefill_7b_forced_persistent_loop(monkeypatch):
+    # one workgroup per CU: every workgroup walks 8 tokens through the prefetch / double barrier loop
+    monkeypatch.setenv("FLATQUANT_WG_PER_CU", "1")
+    c = synth.prefill_7b(2048 + 37)
+    check_case(c, rows=subset_rows(c.T, 300, 5, must=(0, 255, 256, 257, 2047, 2048)), with_dequant=False, label="wg_per_cu=1")
+
+
+def test_decode_shapes():
+    check_case(synth.decode_7b(64))
+    check_case(synth.decode_7b(64, wide=True))
+
+
+def test_prefill_70b_8192_sampled():
+    c = synth.prefill_70b()
+    check_case(c, rows=subset_rows(c.T, 192, 7, must=(0, 2048, 4096, 16383)), with_dequant=False)
+
+
+def test_prefill_70b_28672_sampled():
+    c = synth.prefill_70b(wide=True)
+    check_case(c, rows=subset_rows(c.T, 40, 9, must=(0, 2048)), with_dequant=False)
+
+
+@pytest.mark.parametrize("n1,n2,T", [(64, 172, 33), (128, 224, 19), (1, 2, 5), (2, 2, 7), (3, 6, 70), (33, 34, 11),
+                                      (16, 256, 9), (128, 32, 13), (96, 64, 300), (32, 96, 1), (50, 20, 64)])
+def test_shape_sweep(n1, n2, T):
+    check_case(synth.generic(n1 * 1000 + n2, T, n1, n2, sigma=0.05 if n1 * n2 > 64 else 0.3))
+
+
+def test_scalar_clip_and_clip_one():
+    c = synth.generic(77, 130, 64, 64, clip_mode=0)
+    check_case(c)
+    c.clip[:] = 1.0
+    rep, codes, _ = check_case(c, label="clip=1")
+    q = fo.unpack_nibbles(codes, signed=True)
+    assert q.min() >= -7 and np.all(np.abs(q).max(axis=1) == 7)
+
+
+def test_hadamard_factors_and_identity():
+    from test_oracle_pins import sylvester
+    c = synth.generic(78, 65, 64, 64)
+    c.P1 = (sylvester(64) / 8).astype(np.float16)
+    c.P2 = (sylvester(64) / 8).astype(np.float16)
+    check_case(c, label="hadamard")
+    c.P1 = np.eye(64, dtype=np.float16)
+    c.P2 = np.eye(64, dtype=np.float16)
+    rep, codes, scales = check_case(c, label="identity")
+    # identity transform is exact in fp32 as well: plain per-token INT4 of x, bit for bit
+    q, s, _ = fo.quantize_sym_int4(c.x.astype(np.float64), c.clip, scale_fp16=scales)
+    assert rep["band_flips"] == 0 and np.array_equal(fo.pack_nibbles(q), codes)
+
+
+def test_degenerate_rows_and_small_magnitudes():
+    c = synth.generic(79, 40, 64, 64, massive_tokens=())
+    c.x[3] = 0                                   # all-zero token: step 0, codes 0
+    c.x[5] = 0
+    c.x[5, 4095] = -1.0                          # single non-zero in the last channel
+    c.x[7] = (c.x[7].astype(np.float32) * 2.0 ** -12).astype(np.float16)   # fp16 subnormal-heavy row
+    c.x[9] = (c.x[9].astype(np.float32) * 2.0 ** -6).astype(np.float16)
+    rep, codes, scales = check_case(c)
+    assert not codes[3].any() and float(scales[3]) == 0.0
+
+
+def test_power_of_two_scaling_keeps_codes():
+    c = synth.generic(80, 48, 64, 64, massive_tokens=())
+    _, codes, scales = check_case(c)
+    c2 = synth.generic(80, 48, 64, 64, massive_tokens=())
+    c2.x = (c.x.astype(np.float32) * 0.125).astype(np.float16)
+    _, codes2, scales2 = check_case(c2, label="x/8")
+    same = scales2.astype(np.float64) * 8 == scales.astype(np.float64)
+    assert same.mean() > 0.9 and np.array_equal(codes[same], codes2[same])
+
+
+def test_strided_and_unaligned_buffers():
+    c = synth.generic(81, 21, 64, 64)
+    n = c.n
+    ref_codes, ref_scales, _, _ = run_tq(dev(c.x), dev(c.P1), dev(c.P2), dev(c.clip), c.clip_mode, c.n1, c.n2)
+    # (a) row stride larger than n
+    xs = torch.zeros((c.T, n + 72), dtype=torch.float16, device="cuda")
+    xs[:, :n] = dev(c.x)
+    a_codes, a_scales, _, _ = run_tq(xs, dev(c.P1), dev(c.P2), dev(c.clip), c.clip_mode, c.n1, c.n2, x_stride=n + 72)
+    assert np.array_equal(a_codes, ref_codes) and np.array_equal(a_scales.view(np.uint16), ref_scales.view(np.uint16))
+    # (b) x only 4-byte aligned (slow loader), odd guard so codes land on an odd address (byte stores)
+    flat = torch.zeros((c.T * n + 8,), dtype=torch.float16, device="cuda")
+    flat[2:2 + c.T * n] = dev(c.x).reshape(-1)
+    xu = flat[2:2 + c.T * n].view(c.T, n)
+    b_codes, b_scales, _, _ = run_tq(xu, dev(c.P1), dev(c.P2), dev(c.clip), c.clip_mode, c.n1, c.n2, guard=63)
+    assert np.array_equal(b_codes, ref_codes) and np.array_equal(b_scales.view(np.uint16), ref_scales.view(np.uint16))
+
+
+def test_determinism_and_empty_input():
+    c = synth.prefill_7b(512)
+    x, P1, P2, clip = dev(c.x), dev(c.P1), dev(c.P2), dev(c.clip)
+    first = None
+    for _ in range(5):
+        codes, scales, _, _ = run_tq(x, P1, P2, clip, c.clip_mode, c.n1, c.n2)
+        if first is None:
+            first = (codes.copy(), scales.copy())
+        assert np.array_equal(first[0], codes) and np.array_equal(first[1].view(np.uint16), scales.view(np.uint16))
+    assert fq.flatquant_transform_quant(x, P1, P2, clip, 1, 0, 64, 64, 4096, None, None) == fq.FQ_OK
+
+
+# ---- KV-cache variant --------------------------------------------------------------------
+def run_kv(kv, P, Hp, clip):
+    T, H, D = kv.shape
+    G = T * H
+    kvd, Pd = dev(kv), dev(P)
+    codes = torch.full((G * D // 2 + 128,), 0xCD, dtype=torch.uint8, device="cuda")
+    sc = torch.full((G + 64,), -1.0, dtype=torch.float16, device="cuda")
+    zr = torch.full((G + 64,), -1.0, dtype=torch.float16, device="cuda")
+    fq.flatquant_kv_transform_quant(kvd, Pd, Hp, clip, T, H, D, codes, sc, zr, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert bool((codes[G * D // 2:] == 0xCD).all()) and bool((sc[G:] == -1).all()) and bool((zr[G:] == -1).all())
+    deq = run_dequant(codes, sc, zr, G, D)
+    from gpu_util import host_f16
+    return codes[:G * D // 2].cpu().numpy().reshape(G, D // 2), host_f16(sc[:G]), host_f16(zr[:G]), deq
+
+
+@pytest.mark.parametrize("T,H,shared", [(32768, 8, False), (1, 8, False), (77, 3, False), (200, 8, True), (33, 1, True)])
+def test_kv_cache(T, H, shared):
+    kv = synth.kv_cache(T=T, H=H)
+    P = kv.P[:1] if shared else kv.P
+    for name, tensor in (("K", kv.k), ("V", kv.v)):
+        print(f"[case] kv {name} T={T} H={H} shared={shared}", flush=True)
+        codes, sc, zr, deq = run_kv(tensor, P, P.shape[0], kv.clip)
+        y = fo.kv_transform(tensor, P).reshape(T * H, kv.D)
+        rep = parity.check_kv(y, kv.clip, codes, sc, zr, deq_dev=deq)
+        print(f"[parity] kv {name}: {rep}", flush=True)
+
+
+def test_dequant_helper_ragged():
+    r = np.random.Generator(np.random.PCG64(3))
+    for rows, n in [(5, 6), (3, 2), (17, 250), (4, 4096)]:
+        codes = r.integers(0, 256, size=(rows, n // 2), dtype=np.uint8)
+        scales = (r.uniform(0.1, 4, rows)).astype(np.float16)
+        zeros = r.integers(0, 16, rows).astype(np.float16)
+        out = run_dequant(dev(codes), dev(scales), None, rows, n)
+        assert np.array_equal(out.astype(np.float64), fo.dequantize(codes, scales))
+        out = run_dequant(dev(codes), dev(scales), dev(zeros), rows, n)
+        assert np.array_equal(out.astype(np.float64), fo.dequantize(codes, scales, zeros))

@@ -1,0 +1,98 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header
+declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2410_09426_amd import binding as fq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "flatquant.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(flatquant_\w+|fq_\w+)\s*\(", hdr))
+    declared -= {"fq_status"}
+    assert declared == set(fq.EXPORTS)
+    L = fq.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert fq.fq_abi_version() == 1
+
+
+def test_factor_rule_and_fit_conditions():
+    # Sec. 3.1: argmin(n1 + n2), n1 <= n2; (64, 128) for 8192
+    assert fq.fq_choose_factors(8192) == (64, 128)
+    assert fq.fq_choose_factors(4096) == (64, 64)
+    assert fq.fq_choose_factors(11008) == (86, 128)
+    assert fq.fq_choose_factors(28672) == (128, 224)
+    assert fq.fq_choose_factors(7) == (1, 7)
+    assert fq.fq_choose_factors(1) == (1, 1)
+    with pytest.raises(fq.FlatQuantError):
+        fq.fq_choose_factors(0)
+    # App. "Detailed Design of Kernel Fusion": default-design inequalities, with 160 KB of LDS
+    m = 160 * 1024
+    assert fq.fq_default_design_fits(64, 64, m) and fq.fq_default_design_fits(64, 128, m) and fq.fq_default_design_fits(86, 128, m)
+    assert not fq.fq_default_design_fits(112, 256, m)            # (256^2 + 2*112*256)*2 = 245760 > m
+    assert (64 * 64 + 2 * 64 * 64) * 2 == 24576 and fq.fq_default_design_fits(64, 64, 24577) and not fq.fq_default_design_fits(64, 64, 24576)
+    # what this library actually keeps on chip stays under the 160 KB of a CU for every supported shape
+    for n1, n2 in [(16, 16), (64, 64), (86, 128), (64, 128), (112, 256), (128, 256), (64, 172), (128, 224), (1, 2)]:
+        assert fq.fq_supported(n1, n2)
+        assert 0 < fq.fq_lds_bytes(n1, n2) <= 160 * 1024
+    for n1, n2 in [(129, 64), (64, 258), (64, 63), (0, 64), (64, 0), (3, 5)]:
+        assert not fq.fq_supported(n1, n2) and fq.fq_lds_bytes(n1, n2) == 0
+
+
+def test_status_strings():
+    assert fq.status_string(fq.FQ_OK) == "ok"
+    seen = {fq.status_string(s) for s in range(5)}
+    assert len(seen) == 5 and fq.status_string(99) == "unknown status"
+
+
+def test_argument_validation_without_a_device():
+    A = 0x10000   # fake, suitably aligned "device" addresses; validation must reject before any launch
+    tq = lambda **k: fq.flatquant_transform_quant(**{**dict(x=A, P1=A + 0x100000, P2=A + 0x200000, clip=A + 0x300000, clip_mode=0, T=4,
+                                                          n1=64, n2=64, x_stride=4096, out_codes=A + 0x400000, out_scales=A + 0x500000,
+                                                          check=False), **k})
+    assert tq(T=0) == fq.FQ_OK                      # empty input: nothing launched
+    assert tq(T=0, x=None, out_codes=None) == fq.FQ_OK
+    assert tq(T=-1) == fq.FQ_INVALID_ARG
+    assert tq(x=None) == fq.FQ_INVALID_ARG
+    assert tq(out_scales=None) == fq.FQ_INVALID_ARG
+    assert tq(clip_mode=2) == fq.FQ_INVALID_ARG
+    assert tq(x_stride=4095) == fq.FQ_INVALID_ARG   # stride shorter than a row
+    assert tq(n1=3, n2=5, x_stride=15) == fq.FQ_INVALID_ARG     # odd n
+    assert tq(n1=129, n2=64, x_stride=129 * 64) == fq.FQ_UNSUPPORTED_SHAPE
+    assert tq(n1=2, n2=63, x_stride=126) == fq.FQ_UNSUPPORTED_SHAPE
+    assert tq(x=A + 2) == fq.FQ_MISALIGNED
+    assert tq(x_stride=4097) == fq.FQ_MISALIGNED
+    assert tq(out_codes=A + 64) == fq.FQ_INVALID_ARG            # output overlaps the input
+    with pytest.raises(fq.FlatQuantError):
+        fq.flatquant_transform_quant(None, A, A, A, 0, 4, 64, 64, 4096, A, A)
+
+    kv = lambda **k: fq.flatquant_kv_transform_quant(**{**dict(kv=A, P=A + 0x100000, Hp=8, clip=0.95, T=4, H=8, D=128,
+                                                            out_codes=A + 0x400000, out_scales=A + 0x500000, out_zeros=A + 0x600000,
+                                                            check=False), **k})
+    assert kv(T=0) == fq.FQ_OK
+    assert kv(Hp=3) == fq.FQ_INVALID_ARG
+    assert kv(clip=0.0) == fq.FQ_INVALID_ARG
+    assert kv(D=64) == fq.FQ_UNSUPPORTED_SHAPE
+    assert kv(kv=A + 8) == fq.FQ_MISALIGNED
+    assert kv(out_zeros=None) == fq.FQ_INVALID_ARG
+    assert kv(out_zeros=A + 0x500000) == fq.FQ_INVALID_ARG      # scales and zeros alias
+
+    dq = lambda **k: fq.flatquant_dequant(**{**dict(codes=A, scales=A + 0x100000, zeros=None, rows=4, n=64, out=A + 0x200000, check=False), **k})
+    assert dq(rows=0) == fq.FQ_OK
+    assert dq(n=63) == fq.FQ_INVALID_ARG
+    assert dq(codes=None) == fq.FQ_INVALID_ARG
+    assert dq(out=A + 0x200002) == fq.FQ_MISALIGNED
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(fq, "_lib", None)
+    monkeypatch.setattr(fq, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libflatquant.so"))
+    with pytest.raises(FileNotFoundError):
+        fq.lib()
