@@ -24,6 +24,27 @@ struct TqArgs {
     _Float16* out_scales;
 };
 
+// Kernel-side argument block of the activation kernels.
+struct TqDev {
+    const _Float16* x;
+    const _Float16* P1;
+    const _Float16* P2;
+    const float* clip;
+    uint8_t* out_codes;
+    _Float16* out_scales;
+    int64_t x_stride;
+    int64_t T;
+    int n1, n2;
+    int clip_mode;
+    int vec8;       // rows can be moved in 16-byte chunks that never straddle a row of X~
+    int out_vec16;  // code rows are whole 16-byte units at 16-byte aligned addresses
+};
+
+// Specialised kernels for n2 a multiple of 32 and 16-byte aligned buffers (fq_tq_fast.hip).
+bool tq_fast_applicable(const TqDev& d);
+int64_t tq_fast_lds_bytes(int n1, int n2);
+hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream);
+
 // LDS bytes of the fused activation kernel for (n1, n2); 0 if unsupported.
 int64_t tq_lds_bytes(int n1, int n2);
 bool tq_supported(int n1, int n2);

@@ -31,20 +31,6 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-struct TqDev {
-    const _Float16* x;
-    const _Float16* P1;
-    const _Float16* P2;
-    const float* clip;
-    uint8_t* out_codes;
-    _Float16* out_scales;
-    int64_t x_stride;
-    int64_t T;
-    int n1, n2;
-    int clip_mode;
-    int vec8;       // rows can be moved in 16-byte chunks that never straddle a row of X~
-    int out_vec16;  // code rows are whole 16-byte units at 16-byte aligned addresses
-};
 
 __device__ __forceinline__ half8 split_hi(const float* z, float* resid) {
     // hi = fp16(z) rounded toward zero (never overflows to inf), resid = z - hi exactly
@@ -305,19 +291,35 @@ bool tq_supported(int n1, int n2) {
     return n1 >= 1 && n1 <= kMaxN1 && n2 >= 2 && n2 <= kMaxN2 && (n2 % 2) == 0;
 }
 
-int64_t tq_lds_bytes(int n1, int n2) {
-    if (!tq_supported(n1, n2)) return 0;
+static int64_t generic_lds_bytes(int n1, int n2) {
     const int A = (n1 + 31) / 32, B = (n2 + 31) / 32;
     int64_t b = (int64_t)32 * A * (32 * B + kLdsPad) * 2 + 512 * A * B + 32;
     if (A >= 3) b += (int64_t)A * 2 * A * 64 * 16;
     return b;
 }
 
+int64_t tq_lds_bytes(int n1, int n2) {
+    if (!tq_supported(n1, n2)) return 0;
+    const int64_t b = generic_lds_bytes(n1, n2);
+    const int64_t f = tq_fast_lds_bytes(n1, n2);   // the specialised kernels stage P1/P2 in LDS as well
+    return f > b ? f : b;
+}
+
 hipError_t tq_launch(const TqArgs& a, hipStream_t stream) {
     const int A = (a.n1 + 31) / 32, B = (a.n2 + 31) / 32;
     KernelFn fn = kernel_table(A, B);
-    const int lds = (int)tq_lds_bytes(a.n1, a.n2);
+    const int lds = (int)generic_lds_bytes(a.n1, a.n2);
     const int nt = 64 * B;
+
+    TqDev d;
+    d.x = a.x; d.P1 = a.P1; d.P2 = a.P2; d.clip = a.clip;
+    d.out_codes = a.out_codes; d.out_scales = a.out_scales;
+    d.x_stride = a.x_stride; d.T = a.T; d.n1 = a.n1; d.n2 = a.n2; d.clip_mode = a.clip_mode;
+    d.vec8 = (a.n2 % 8 == 0) && (a.x_stride % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0);
+    const int64_t n = (int64_t)a.n1 * a.n2;
+    d.out_vec16 = (n % 32 == 0) && ((reinterpret_cast<uintptr_t>(a.out_codes) & 15) == 0);
+    // FLATQUANT_FORCE_GENERIC=1 keeps the general kernel testable on shapes the specialised ones would take
+    if (tq_fast_applicable(d) && env_int("FLATQUANT_FORCE_GENERIC", 0) == 0) return tq_fast_launch(d, stream);
 
     // per-variant launch facts, computed once per process (benign race: same values)
     static int wg_per_cu[4][8];
@@ -337,13 +339,6 @@ hipError_t tq_launch(const TqArgs& a, hipStream_t stream) {
     int64_t grid = (int64_t)cu_count() * occ;
     if (grid > a.T) grid = a.T;
 
-    TqDev d;
-    d.x = a.x; d.P1 = a.P1; d.P2 = a.P2; d.clip = a.clip;
-    d.out_codes = a.out_codes; d.out_scales = a.out_scales;
-    d.x_stride = a.x_stride; d.T = a.T; d.n1 = a.n1; d.n2 = a.n2; d.clip_mode = a.clip_mode;
-    d.vec8 = (a.n2 % 8 == 0) && (a.x_stride % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0);
-    const int64_t n = (int64_t)a.n1 * a.n2;
-    d.out_vec16 = (n % 32 == 0) && ((reinterpret_cast<uintptr_t>(a.out_codes) & 15) == 0);
     hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(nt), lds, stream, d);
     return hipGetLastError();
 }

@@ -65,6 +65,14 @@ def test_prefill_7b_forced_persistent_loop(monkeypatch):
     check_case(c, rows=subset_rows(c.T, 300, 5, must=(0, 255, 256, 257, 2047, 2048)), with_dequant=False, label="wg_per_cu=1")
 
 
+def test_general_kernel_on_aligned_shapes(monkeypatch):
+    # the specialised kernels would take these shapes; force the general one so that it stays covered
+    monkeypatch.setenv("FLATQUANT_FORCE_GENERIC", "1")
+    c = synth.prefill_7b(700)
+    check_case(c, rows=subset_rows(c.T, 120, 6), with_dequant=False, label="general kernel")
+    check_case(synth.decode_7b(64, wide=True), with_dequant=False, label="general kernel")
+
+
 def test_decode_shapes():
     check_case(synth.decode_7b(64))
     check_case(synth.decode_7b(64, wide=True))
