@@ -57,22 +57,31 @@ __device__ __forceinline__ float wave_max(float x) {
     return __builtin_fmaxf(__builtin_fmaxf(r0, r1), __builtin_fmaxf(r2, r3));
 }
 
+// z - (float)half(hi or lo 16 bits of `packed`), in one mixed-precision fma (the fp16 operand is read in place)
+template <int HI>
+__device__ __forceinline__ float sub_half(float z, unsigned int packed) {
+    float r;
+    if constexpr (HI) asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(z));
+    else asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(z));
+    return r;
+}
+
 // fp32 x8 -> fp16 hi (round toward zero, cannot overflow to inf) and fp16 lo = fp16(z - hi)
 __device__ __forceinline__ void split_hi_lo(const f32x16& acc, int base, half8& hi, half8& lo) {
+    u32x4 h, l;
 #pragma unroll
-    for (int k = 0; k < 8; k += 2) {
-        const float z0 = acc[base + k], z1 = acc[base + k + 1];
-        auto ph = __builtin_amdgcn_cvt_pkrtz(z0, z1);
-        hi[k] = (_Float16)ph[0];
-        hi[k + 1] = (_Float16)ph[1];
-        auto pl = __builtin_amdgcn_cvt_pkrtz(z0 - (float)ph[0], z1 - (float)ph[1]);
-        lo[k] = (_Float16)pl[0];
-        lo[k + 1] = (_Float16)pl[1];
+    for (int k = 0; k < 4; ++k) {
+        const float z0 = acc[base + 2 * k], z1 = acc[base + 2 * k + 1];
+        const unsigned int ph = __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_pkrtz(z0, z1));
+        h[k] = ph;
+        l[k] = __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_pkrtz(sub_half<0>(z0, ph), sub_half<1>(z1, ph)));
     }
+    hi = __builtin_bit_cast(half8, h);
+    lo = __builtin_bit_cast(half8, l);
 }
 
 template <int A, int B, bool FULL1>
-__global__ __launch_bounds__(64 * B) void tq_fast_kernel(TqDev p) {
+__global__ __launch_bounds__(64 * B) __attribute__((amdgpu_waves_per_eu(2))) void tq_fast_kernel(TqDev p) {
     using L = FastLds<A, B>;
     constexpr int NT = 64 * B, N2 = L::N2, PITCH = L::PITCH;
     constexpr int KB1 = 2 * A, KB2 = 2 * B, NPRE = 2 * A;
@@ -108,10 +117,15 @@ __global__ __launch_bounds__(64 * B) void tq_fast_kernel(TqDev p) {
             if (FULL1 || xrow0 + 16 * k < n1) *reinterpret_cast<u32x4*>(Xs + xbase + 16 * k * PITCH) = pre[k];
     };
 
-    // ---- the first token's row is requested before anything else
-    u32x4 pre[NPRE];
+    // ---- the first two token rows of this workgroup are requested before anything else
+    constexpr bool DEEP = (A <= 2);   // two rows in flight per workgroup when the registers allow it
+    u32x4 pre0[NPRE], pre1[DEEP ? NPRE : 1];
     int64_t t = blockIdx.x;
-    issue(t, pre);
+    const int64_t G = gridDim.x;
+    issue(t, pre0);
+    if constexpr (DEEP) {
+        if (t + G < p.T) issue(t + G, pre1);
+    }
 
     // ---- stage P1 (flat, n1 x n1) and the first pass of P2 rows in LDS with coalesced loads
     {
@@ -176,13 +190,15 @@ __global__ __launch_bounds__(64 * B) void tq_fast_kernel(TqDev p) {
         for (int q = tid; q < (32 * A - n1) * (PITCH / 8); q += NT)
             reinterpret_cast<u32x4*>(Xs + n1 * PITCH)[q] = u32x4{0u, 0u, 0u, 0u};
     }
-    commit(pre);
+    commit(pre0);
     __syncthreads();
 
-    for (; t < p.T; t += gridDim.x) {
-        const int64_t tn = t + gridDim.x;
-        const bool have_next = tn < p.T;
-        if (have_next) issue(tn, pre);
+    // One token: the tile of token t is in LDS, `pre_next` holds (or is receiving) the row of token t + G and is
+    // written to LDS once every wave is done with the current tile; the row of token t + 2G is requested into
+    // `pre_far`.  The caller alternates the two register sets.
+    auto body = [&](int64_t t, u32x4 (&pre_next)[NPRE], u32x4 (&pre_far)[NPRE]) {
+        const bool have_next = t + G < p.T;
+        if (t + (DEEP ? 2 : 1) * G < p.T) issue(t + (DEEP ? 2 : 1) * G, pre_far);
         const float clipv = p.clip[p.clip_mode ? t : 0];
 
         f32x16 acc2[A];
@@ -191,33 +207,46 @@ __global__ __launch_bounds__(64 * B) void tq_fast_kernel(TqDev p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc2[It][r] = 0.0f;
 
+        // row tiles of X~ go through the first contraction in pairs so that consecutive MFMAs are independent
 #pragma unroll
-        for (int I = 0; I < A; ++I) {
-            f32x16 acc1;
+        for (int I0 = 0; I0 < A; I0 += 2) {
+            constexpr int NI_MAX = 2;
+            const int ni = (A - I0) < NI_MAX ? (A - I0) : NI_MAX;
+            f32x16 acc1[NI_MAX];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
-            const _Float16* arow = Xs + (32 * I + c) * PITCH + 8 * h;
+            for (int d = 0; d < NI_MAX; ++d)
 #pragma unroll
-            for (int kb = 0; kb < KB2; ++kb) {
-                const half8 a = *reinterpret_cast<const half8*>(arow + 16 * kb);
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p2f[kb], acc1, 0, 0, 0);
-            }
+                for (int r = 0; r < 16; ++r) acc1[d][r] = 0.0f;
+            const _Float16* arow = Xs + (32 * I0 + c) * PITCH + 8 * h;
 #pragma unroll
-            for (int kq = 0; kq < 2; ++kq) {
-                const int kk = 2 * I + kq;
-                if (FULL1 || 16 * kk < n1) {
-                    half8 zh, zl;
-                    split_hi_lo(acc1, 8 * kq, zh, zl);
+            for (int kb = 0; kb < KB2; ++kb)
 #pragma unroll
-                    for (int It = 0; It < A; ++It) {
-                        half8 b;
-                        if constexpr (P1LDS) b = *reinterpret_cast<const half8*>(&P1s[(It * KB1 + kk) * 64 + l]);
-                        else b = p1f[It][kk];
-                        acc2[It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh, b, acc2[It], 0, 0, 0);
-                        acc2[It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zl, b, acc2[It], 0, 0, 0);
+                for (int d = 0; d < NI_MAX; ++d)
+                    if (d < ni) {
+                        const half8 a = *reinterpret_cast<const half8*>(arow + d * 32 * PITCH + 16 * kb);
+                        acc1[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p2f[kb], acc1[d], 0, 0, 0);
+                    }
+            // Y^T[slab, :] += Z^T[slab, K block] P1[K block, :], hi and lo parts of Z
+#pragma unroll
+            for (int d = 0; d < NI_MAX; ++d)
+#pragma unroll
+                for (int kq = 0; kq < 2; ++kq) {
+                    const int kk = 2 * (I0 + d) + kq;
+                    if (d < ni && (FULL1 || 16 * kk < n1)) {
+                        half8 zh, zl;
+                        split_hi_lo(acc1[d], 8 * kq, zh, zl);
+                        half8 b[A];
+#pragma unroll
+                        for (int It = 0; It < A; ++It) {
+                            if constexpr (P1LDS) b[It] = *reinterpret_cast<const half8*>(&P1s[(It * KB1 + kk) * 64 + l]);
+                            else b[It] = p1f[It][kk];
+                        }
+#pragma unroll
+                        for (int It = 0; It < A; ++It) acc2[It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh, b[It], acc2[It], 0, 0, 0);
+#pragma unroll
+                        for (int It = 0; It < A; ++It) acc2[It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zl, b[It], acc2[It], 0, 0, 0);
                     }
                 }
-            }
         }
 
         // ---- per-token absmax: in-lane, DPP over the wave, one float per wave through LDS
@@ -232,13 +261,15 @@ __global__ __launch_bounds__(64 * B) void tq_fast_kernel(TqDev p) {
 #pragma unroll
         for (int b = 0; b < B; ++b) m = __builtin_fmaxf(m, red[b]);
 
-        const _Float16 sh = (_Float16)(clipv * m / 7.0f);   // step, round-to-nearest-even to fp16
+        const _Float16 sh = (_Float16)(clipv * m * 0.142857149f);   // step = alpha * max / 7, round-to-nearest-even to fp16
         const float s = (float)sh;
-        const float inv = (s > 0.0f && s <= 65504.0f) ? 1.0f / s : 0.0f;
+        const float inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;   // 1 ulp: < 1e-6 code units
         const float sl = (inv != 0.0f) ? s : 0.0f;
         const float lim_hi = 7.0f * sl, lim_lo = -8.0f * sl;
 
-        // ---- clamp, round (fma against 1.5 * 2^23 leaves the two's complement code in the low mantissa bits), pack
+        // ---- clamp, round, pack.  fma against 1.5 * 2^23 + 8 leaves code + 8 (0..15) in the low mantissa bits with
+        // zeros above up to bit 21, so four results chain with shift-adds and one xor turns offset-binary
+        // nibbles into two's complement ones.
 #pragma unroll
         for (int It = 0; It < A; ++It) {
             const int ip = 32 * It + c;
@@ -248,15 +279,15 @@ __global__ __launch_bounds__(64 * B) void tq_fast_kernel(TqDev p) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const float yc = __builtin_amdgcn_fmed3f(acc2[It][4 * g + k], lim_lo, lim_hi);
-                    bits[k] = __builtin_bit_cast(uint32_t, __builtin_fmaf(yc, inv, 12582912.0f));
+                    bits[k] = __builtin_bit_cast(uint32_t, __builtin_fmaf(yc, inv, 12582920.0f));
                 }
-                const uint32_t pk = (bits[0] & 0xFu) | ((bits[1] << 4) & 0xF0u) | ((bits[2] << 8) & 0xF00u) | ((bits[3] << 12) & 0xF000u);
+                const uint32_t pk = ((((bits[3] << 4) + bits[2]) << 8) + ((bits[1] << 4) + bits[0])) ^ 0x8888u;
                 const int jp = 32 * w + 8 * g + 4 * h;
                 if (FULL1 || It < A - 1 || ip < n1)
                     *reinterpret_cast<uint16_t*>(stage + ((ip * N2 + jp) >> 1)) = (uint16_t)pk;
             }
         }
-        if (have_next) commit(pre);
+        if (have_next) commit(pre_next);
         __syncthreads();   // (B) staged codes and the next tile are visible
 
         u32x4* dst = reinterpret_cast<u32x4*>(p.out_codes + t * row_bytes_out);
@@ -264,6 +295,19 @@ __global__ __launch_bounds__(64 * B) void tq_fast_kernel(TqDev p) {
         for (int q = tid; q < nq; q += NT)
             __builtin_nontemporal_store(reinterpret_cast<const u32x4*>(stage)[q], dst + q);
         if (tid == 0) p.out_scales[t] = sh;
+    };
+
+    if constexpr (DEEP) {
+        while (true) {
+            body(t, pre1, pre0);
+            t += G;
+            if (t >= p.T) break;
+            body(t, pre0, pre1);
+            t += G;
+            if (t >= p.T) break;
+        }
+    } else {
+        for (; t < p.T; t += G) body(t, pre0, pre0);
     }
 }
 
@@ -338,8 +382,10 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     }
     const int cap = env_int("FLATQUANT_WG_PER_CU", 0);
     if (cap > 0 && cap < occ) occ = cap;
-    int64_t grid = (int64_t)cu_count() * occ;
-    if (grid > d.T) grid = d.T;
+    // every workgroup gets the same number of tokens (+-1): grid = ceil(T / ceil(T / resident workgroups))
+    const int64_t resident = (int64_t)cu_count() * occ;
+    const int64_t rounds = (d.T + resident - 1) / resident;
+    const int64_t grid = (d.T + rounds - 1) / rounds;
     hipLaunchKernelGGL(v.fn, dim3((unsigned)grid), dim3(nt), v.lds, stream, d);
     return hipGetLastError();
 }
