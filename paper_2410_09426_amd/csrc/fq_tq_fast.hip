@@ -11,6 +11,9 @@
 //     workgroup and the strided MFMA fragments are gathered from LDS, not HBM/L2.
 //   * The loop body has no shape conditionals, the wave reduction uses DPP, and
 //     rounding + nibble extraction is one fused multiply-add against 1.5 * 2^23.
+//   * A wave may own SPW adjacent slabs (template parameter).  With SPW = n2/32 a
+//     token belongs to a single wave: no workgroup barrier partner to wait for,
+//     and the token tile is read from LDS once instead of once per slab.
 #include "fq_internal.h"
 
 namespace fq {
@@ -22,13 +25,13 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 __host__ __device__ constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
 // LDS carve-up, shared by host and device.
-template <int A, int B>
+template <int A, int B, int NBUF = 1>
 struct FastLds {
     static constexpr int N2 = 32 * B;
     static constexpr int PITCH = N2 + kLdsPad;                       // halves per row of the token tile
     static constexpr int XS_BYTES = 32 * A * PITCH * 2;
     static constexpr int STAGE_BYTES = 512 * A * B;                  // packed codes of one token
-    static constexpr int BODY_BYTES = XS_BYTES + STAGE_BYTES + 32;   // + one absmax float per wave
+    static constexpr int BODY_BYTES = NBUF * (XS_BYTES + STAGE_BYTES) + 64;   // + one absmax float per wave and buffer
     static constexpr int P2ROWS = (B <= 4) ? N2 : N2 / 2;            // rows of P2 staged per pass
     static constexpr int P2PASSES = N2 / P2ROWS;
     static constexpr int P1FLAT_BYTES = 32 * A * 32 * A * 2;
@@ -80,18 +83,23 @@ __device__ __forceinline__ void split_hi_lo(const f32x16& acc, int base, half8& 
     lo = __builtin_bit_cast(half8, l);
 }
 
-template <int A, int B, bool FULL1>
-__global__ __launch_bounds__(64 * B) __attribute__((amdgpu_waves_per_eu(2))) void tq_fast_kernel(TqDev p) {
-    using L = FastLds<A, B>;
-    constexpr int NT = 64 * B, N2 = L::N2, PITCH = L::PITCH;
-    constexpr int KB1 = 2 * A, KB2 = 2 * B, NPRE = 2 * A;
+template <int A, int B, int SPW, bool FULL1, bool PIPE>
+__global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(2))) void tq_fast_kernel(TqDev p, const float* __restrict__ clip) {
+    static_assert(B % SPW == 0 && 16 % SPW == 0, "slabs per wave must divide the slab count and 16");
+    using L = FastLds<A, B, PIPE ? 2 : 1>;
+    constexpr int WPT = B / SPW;                  // waves per token = waves per workgroup
+    constexpr int NT = 64 * WPT, N2 = L::N2, PITCH = L::PITCH;
+    constexpr int KB1 = 2 * A, KB2 = 2 * B, NPRE = 2 * A * SPW;
+    constexpr int RSTEP = 16 / SPW;               // rows of X~ covered by one 16-byte chunk per thread
     constexpr int CPR = 4 * B;                    // 16-byte chunks per row of X~
     constexpr bool P1LDS = L::P1LDS;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    // body layout: [tile 0][tile 1 if PIPE][stage 0][stage 1 if PIPE][absmax exchange: 8 floats per buffer]
+    constexpr int NBUF = PIPE ? 2 : 1;
     _Float16* Xs = reinterpret_cast<_Float16*>(smem);
-    uint8_t* stage = smem + L::XS_BYTES;
-    float* red = reinterpret_cast<float*>(stage + L::STAGE_BYTES);
+    uint8_t* stage = smem + NBUF * L::XS_BYTES;
+    float* red = reinterpret_cast<float*>(smem + NBUF * (L::XS_BYTES + L::STAGE_BYTES));
     u32x4* P1s = reinterpret_cast<u32x4*>(smem + L::R0);
     _Float16* P1flat = reinterpret_cast<_Float16*>(smem);
     _Float16* P2flat = reinterpret_cast<_Float16*>(smem + L::P1FLAT_BYTES);
@@ -101,7 +109,7 @@ __global__ __launch_bounds__(64 * B) __attribute__((amdgpu_waves_per_eu(2))) voi
     const int n1 = FULL1 ? 32 * A : p.n1;
     const int64_t row_bytes_out = (int64_t)n1 * (N2 / 2);
 
-    // chunk k of this thread: row (tid / CPR) + 16k of X~, 8 halves at column (tid % CPR) * 8
+    // chunk k of this thread: row (tid / CPR) + RSTEP * k of X~, 8 halves at column (tid % CPR) * 8
     const int xrow0 = tid / CPR;
     const int xbase = xrow0 * PITCH + (tid % CPR) * 8;
 
@@ -109,23 +117,21 @@ __global__ __launch_bounds__(64 * B) __attribute__((amdgpu_waves_per_eu(2))) voi
         const u32x4* src = reinterpret_cast<const u32x4*>(p.x + t * p.x_stride) + tid;
 #pragma unroll
         for (int k = 0; k < NPRE; ++k)
-            if (FULL1 || xrow0 + 16 * k < n1) pre[k] = __builtin_nontemporal_load(src + k * NT);
+            if (FULL1 || xrow0 + RSTEP * k < n1) pre[k] = __builtin_nontemporal_load(src + k * NT);
     };
-    auto commit = [&](const u32x4 (&pre)[NPRE]) {
+    auto commit = [&](const u32x4 (&pre)[NPRE], int buf = 0) {
+        _Float16* Xt = Xs + buf * (L::XS_BYTES / 2);
 #pragma unroll
         for (int k = 0; k < NPRE; ++k)
-            if (FULL1 || xrow0 + 16 * k < n1) *reinterpret_cast<u32x4*>(Xs + xbase + 16 * k * PITCH) = pre[k];
+            if (FULL1 || xrow0 + RSTEP * k < n1) *reinterpret_cast<u32x4*>(Xt + xbase + RSTEP * k * PITCH) = pre[k];
     };
 
-    // ---- the first two token rows of this workgroup are requested before anything else
-    constexpr bool DEEP = (A <= 2);   // two rows in flight per workgroup when the registers allow it
+    // ---- the first token row of this workgroup is requested before anything else
+    constexpr bool DEEP = PIPE || (NPRE <= 4);   // two rows in flight per workgroup when the registers allow it
     u32x4 pre0[NPRE], pre1[DEEP ? NPRE : 1];
     int64_t t = blockIdx.x;
     const int64_t G = gridDim.x;
     issue(t, pre0);
-    if constexpr (DEEP) {
-        if (t + G < p.T) issue(t + G, pre1);
-    }
 
     // ---- stage P1 (flat, n1 x n1) and the first pass of P2 rows in LDS with coalesced loads
     {
@@ -139,7 +145,7 @@ __global__ __launch_bounds__(64 * B) __attribute__((amdgpu_waves_per_eu(2))) voi
             if ((n1sq & 1) && tid == 0) P1flat[n1sq - 1] = p.P1[n1sq - 1];
         }
     }
-    half8 p2f[KB2];
+    half8 p2f[SPW][KB2];
     half8 p1f[P1LDS ? 1 : A][P1LDS ? 1 : KB1];
 #pragma unroll
     for (int pass = 0; pass < L::P2PASSES; ++pass) {
@@ -153,8 +159,10 @@ __global__ __launch_bounds__(64 * B) __attribute__((amdgpu_waves_per_eu(2))) voi
 #pragma unroll
         for (int kb = pass * (L::P2ROWS / 16); kb < (pass + 1) * (L::P2ROWS / 16); ++kb)
 #pragma unroll
-            for (int s = 0; s < 8; ++s)
-                p2f[kb][s] = P2flat[(16 * kb - pass * L::P2ROWS + 8 * h + s) * N2 + 32 * w + c];
+            for (int q = 0; q < SPW; ++q)
+#pragma unroll
+                for (int s = 0; s < 8; ++s)
+                    p2f[q][kb][s] = P2flat[(16 * kb - pass * L::P2ROWS + 8 * h + s) * N2 + 32 * (w * SPW + q) + c];
         if (pass == 0) {
             // P1 fragments, gathered with the k-permutation of the first contraction's accumulator layout:
             // K block kk, slot s, half-wave h  <->  i = 32(kk/2) + 8(2(kk%2) + s/4) + 4h + s%4
@@ -187,27 +195,34 @@ __global__ __launch_bounds__(64 * B) __attribute__((amdgpu_waves_per_eu(2))) voi
     }
     __syncthreads();   // staging area is free: it becomes the token tile
     if constexpr (!FULL1) {   // rows n1 .. 32A-1 of the tile are never loaded: make them exact zeros once
-        for (int q = tid; q < (32 * A - n1) * (PITCH / 8); q += NT)
-            reinterpret_cast<u32x4*>(Xs + n1 * PITCH)[q] = u32x4{0u, 0u, 0u, 0u};
+        for (int bf = 0; bf < NBUF; ++bf)
+            for (int q = tid; q < (32 * A - n1) * (PITCH / 8); q += NT)
+                reinterpret_cast<u32x4*>(Xs + bf * (L::XS_BYTES / 2) + n1 * PITCH)[q] = u32x4{0u, 0u, 0u, 0u};
+    }
+    // the second row is requested only now, so that across the chip every first row is served before any second row
+    if constexpr (PIPE) {
+        issue((t + G < p.T) ? t + G : p.T - 1, pre1);
+    } else if constexpr (DEEP) {
+        if (t + G < p.T) issue(t + G, pre1);
     }
     commit(pre0);
     __syncthreads();
 
-    // One token: the tile of token t is in LDS, `pre_next` holds (or is receiving) the row of token t + G and is
-    // written to LDS once every wave is done with the current tile; the row of token t + 2G is requested into
-    // `pre_far`.  The caller alternates the two register sets.
-    auto body = [&](int64_t t, u32x4 (&pre_next)[NPRE], u32x4 (&pre_far)[NPRE]) {
-        const bool have_next = t + G < p.T;
-        if (t + (DEEP ? 2 : 1) * G < p.T) issue(t + (DEEP ? 2 : 1) * G, pre_far);
-        const float clipv = p.clip[p.clip_mode ? t : 0];
-
-        f32x16 acc2[A];
+    // ---- both contractions for the token tile in LDS buffer `buf`: acc2 = (P1^T X~ P2)^T for this wave's slabs
+    // `side(slot)` is called NSLOT times at even intervals of the MFMA stream; the pipelined loop uses it to
+    // interleave the previous token's rounding and packing (vector ALU only) with this token's MFMAs.
+    constexpr int NSLOT1 = SPW * ((A + 1) / 2) * KB2, NSLOT = NSLOT1 + SPW * A * 2;
+    auto gemm = [&](int buf, f32x16 (&acc2)[SPW][A], auto&& side) {
+        const _Float16* Xt = Xs + buf * (L::XS_BYTES / 2);
 #pragma unroll
-        for (int It = 0; It < A; ++It)
+        for (int q = 0; q < SPW; ++q)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc2[It][r] = 0.0f;
-
+            for (int It = 0; It < A; ++It)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc2[q][It][r] = 0.0f;
         // row tiles of X~ go through the first contraction in pairs so that consecutive MFMAs are independent
+#pragma unroll
+        for (int q = 0; q < SPW; ++q)
 #pragma unroll
         for (int I0 = 0; I0 < A; I0 += 2) {
             constexpr int NI_MAX = 2;
@@ -217,15 +232,17 @@ __global__ __launch_bounds__(64 * B) __attribute__((amdgpu_waves_per_eu(2))) voi
             for (int d = 0; d < NI_MAX; ++d)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc1[d][r] = 0.0f;
-            const _Float16* arow = Xs + (32 * I0 + c) * PITCH + 8 * h;
+            const _Float16* arow = Xt + (32 * I0 + c) * PITCH + 8 * h;
 #pragma unroll
-            for (int kb = 0; kb < KB2; ++kb)
+            for (int kb = 0; kb < KB2; ++kb) {
 #pragma unroll
                 for (int d = 0; d < NI_MAX; ++d)
                     if (d < ni) {
                         const half8 a = *reinterpret_cast<const half8*>(arow + d * 32 * PITCH + 16 * kb);
-                        acc1[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p2f[kb], acc1[d], 0, 0, 0);
+                        acc1[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p2f[q][kb], acc1[d], 0, 0, 0);
                     }
+                side((q * ((A + 1) / 2) + I0 / 2) * KB2 + kb);
+            }
             // Y^T[slab, :] += Z^T[slab, K block] P1[K block, :], hi and lo parts of Z
 #pragma unroll
             for (int d = 0; d < NI_MAX; ++d)
@@ -242,109 +259,211 @@ __global__ __launch_bounds__(64 * B) __attribute__((amdgpu_waves_per_eu(2))) voi
                             else b[It] = p1f[It][kk];
                         }
 #pragma unroll
-                        for (int It = 0; It < A; ++It) acc2[It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh, b[It], acc2[It], 0, 0, 0);
+                        for (int It = 0; It < A; ++It) acc2[q][It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh, b[It], acc2[q][It], 0, 0, 0);
 #pragma unroll
-                        for (int It = 0; It < A; ++It) acc2[It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zl, b[It], acc2[It], 0, 0, 0);
+                        for (int It = 0; It < A; ++It) acc2[q][It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zl, b[It], acc2[q][It], 0, 0, 0);
                     }
+                    if (d < ni) side(NSLOT1 + (q * A + I0 + d) * 2 + kq);
                 }
         }
-
-        // ---- per-token absmax: in-lane, DPP over the wave, one float per wave through LDS
-        float m = 0.0f;
-#pragma unroll
-        for (int It = 0; It < A; ++It)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(acc2[It][r]));
-        m = wave_max(m);
-        if (l == 0) red[w] = m;
-        __syncthreads();   // (A) every wave is also done reading the token tile
-#pragma unroll
-        for (int b = 0; b < B; ++b) m = __builtin_fmaxf(m, red[b]);
-
-        const _Float16 sh = (_Float16)(clipv * m * 0.142857149f);   // step = alpha * max / 7, round-to-nearest-even to fp16
-        const float s = (float)sh;
-        const float inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;   // 1 ulp: < 1e-6 code units
-        const float sl = (inv != 0.0f) ? s : 0.0f;
-        const float lim_hi = 7.0f * sl, lim_lo = -8.0f * sl;
-
-        // ---- clamp, round, pack.  fma against 1.5 * 2^23 + 8 leaves code + 8 (0..15) in the low mantissa bits with
-        // zeros above up to bit 21, so four results chain with shift-adds and one xor turns offset-binary
-        // nibbles into two's complement ones.
-#pragma unroll
-        for (int It = 0; It < A; ++It) {
-            const int ip = 32 * It + c;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                uint32_t bits[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float yc = __builtin_amdgcn_fmed3f(acc2[It][4 * g + k], lim_lo, lim_hi);
-                    bits[k] = __builtin_bit_cast(uint32_t, __builtin_fmaf(yc, inv, 12582920.0f));
-                }
-                const uint32_t pk = ((((bits[3] << 4) + bits[2]) << 8) + ((bits[1] << 4) + bits[0])) ^ 0x8888u;
-                const int jp = 32 * w + 8 * g + 4 * h;
-                if (FULL1 || It < A - 1 || ip < n1)
-                    *reinterpret_cast<uint16_t*>(stage + ((ip * N2 + jp) >> 1)) = (uint16_t)pk;
-            }
-        }
-        if (have_next) commit(pre_next);
-        __syncthreads();   // (B) staged codes and the next tile are visible
-
-        u32x4* dst = reinterpret_cast<u32x4*>(p.out_codes + t * row_bytes_out);
-        const int nq = n1 * B;   // 16-byte units of one code row (n1 * N2 / 32)
-        for (int q = tid; q < nq; q += NT)
-            __builtin_nontemporal_store(reinterpret_cast<const u32x4*>(stage)[q], dst + q);
-        if (tid == 0) p.out_scales[t] = sh;
     };
 
-    if constexpr (DEEP) {
-        while (true) {
-            body(t, pre1, pre0);
-            t += G;
-            if (t >= p.T) break;
-            body(t, pre0, pre1);
-            t += G;
-            if (t >= p.T) break;
+    // ---- this wave's share of the per-token absmax (in-lane, then DPP over the wave), left in red[buf][w]
+    auto absmax_to_lds = [&](const f32x16 (&acc2)[SPW][A], int buf) {
+        float m = 0.0f;
+#pragma unroll
+        for (int q = 0; q < SPW; ++q)
+#pragma unroll
+            for (int It = 0; It < A; ++It)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(acc2[q][It][r]));
+        m = wave_max(m);
+        if (l == 0) red[buf * 8 + w] = m;
+    };
+    auto absmax_from_lds = [&](int buf) {
+        float m = 0.0f;
+#pragma unroll
+        for (int b = 0; b < WPT; ++b) m = __builtin_fmaxf(m, red[buf * 8 + b]);
+        return m;
+    };
+
+    // ---- step from the absmax; clamp, round, pack into stage buffer `buf`.  fma against 1.5 * 2^23 + 8 leaves
+    // code + 8 (0..15) in the low mantissa bits with zeros above up to bit 21, so four results chain with shift-adds
+    // and one xor turns offset-binary nibbles into two's complement ones.
+    struct Step { _Float16 sh; float inv, lim_lo, lim_hi; };
+    auto make_step = [&](float m, float clipv) {
+        Step st;
+        st.sh = (_Float16)(clipv * m * 0.142857149f);   // step = alpha * max / 7, round-to-nearest-even to fp16
+        const float s = (float)st.sh;
+        st.inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;   // 1 ulp: < 1e-6 code units
+        const float sl = (st.inv != 0.0f) ? s : 0.0f;
+        st.lim_hi = 7.0f * sl;
+        st.lim_lo = -8.0f * sl;
+        return st;
+    };
+    // one unit = 4 consecutive channels of one lane: clamp, round, pack, 2 bytes into the stage buffer
+    constexpr int NUNIT = SPW * A * 4;
+    auto quant_unit = [&](const f32x16 (&acc2)[SPW][A], const Step& st, int buf, int u) {
+        const int q = u / (4 * A), It = (u / 4) % A, g = u % 4;
+        uint8_t* stg = stage + buf * L::STAGE_BYTES;
+        const int ip = 32 * It + c;
+        uint32_t bits[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float yc = __builtin_amdgcn_fmed3f(acc2[q][It][4 * g + k], st.lim_lo, st.lim_hi);
+            bits[k] = __builtin_bit_cast(uint32_t, __builtin_fmaf(yc, st.inv, 12582920.0f));
+        }
+        const uint32_t pk = ((((bits[3] << 4) + bits[2]) << 8) + ((bits[1] << 4) + bits[0])) ^ 0x8888u;
+        const int jp = 32 * (w * SPW + q) + 8 * g + 4 * h;
+        if (FULL1 || It < A - 1 || ip < n1)
+            *reinterpret_cast<uint16_t*>(stg + ((ip * N2 + jp) >> 1)) = (uint16_t)pk;
+    };
+    auto quant_to_stage = [&](const f32x16 (&acc2)[SPW][A], float m, float clipv, int buf) -> _Float16 {
+        const Step st = make_step(m, clipv);
+#pragma unroll
+        for (int u = 0; u < NUNIT; ++u) quant_unit(acc2, st, buf, u);
+        return st.sh;
+    };
+
+    // ---- staged codes of token t -> global memory with 16-byte stores; no branch around the stores when the
+    // row divides evenly, so that the compiler's count of outstanding memory operations stays exact
+    auto copy_out = [&](int64_t t, int buf, _Float16 sh) {
+        const u32x4* stg = reinterpret_cast<const u32x4*>(stage + buf * L::STAGE_BYTES);
+        u32x4* dst = reinterpret_cast<u32x4*>(p.out_codes + t * row_bytes_out);
+        constexpr int NQ_FULL = 32 * A * B;   // 16-byte units of one code row when n1 = 32A
+        if constexpr (FULL1 && NQ_FULL % NT == 0) {
+#pragma unroll
+            for (int k = 0; k < NQ_FULL / NT; ++k) __builtin_nontemporal_store(stg[tid + k * NT], dst + tid + k * NT);
+        } else {
+            const int nq = n1 * B;
+            for (int q = tid; q < nq; q += NT) __builtin_nontemporal_store(stg[q], dst + q);
+        }
+        p.out_scales[t] = sh;   // every lane writes the same two bytes: cheaper than a branch around the store
+    };
+    // Requests are always issued (past the end they re-read the last row): an unconditional request lets the
+    // compiler count outstanding loads exactly, so a later wait covers only the older row.
+    auto issue_clamped = [&](int64_t tf, u32x4 (&pre)[NPRE]) {
+        issue(tf < p.T ? tf : p.T - 1, pre);
+        __builtin_amdgcn_sched_barrier(0);   // keep the requests here, ahead of the MFMA work, with their registers reserved
+    };
+
+    if constexpr (!PIPE) {
+        // One token per step: the tile of token t is in LDS, `pre_next` holds (or is receiving) the row of token t + G
+        // and is written to LDS once every wave is done with the current tile; the row of token t + 2G is requested
+        // into `pre_far`.  The caller alternates the two register sets.
+        auto body = [&](int64_t t, u32x4 (&pre_next)[NPRE], u32x4 (&pre_far)[NPRE]) {
+            issue_clamped(t + (DEEP ? 2 : 1) * G, pre_far);
+            const float clipv = clip[p.clip_mode ? t : 0];   // wave-uniform address, read-only: a scalar load
+            f32x16 acc2[SPW][A];
+            gemm(0, acc2, [](int) {});
+            absmax_to_lds(acc2, 0);
+            __syncthreads();   // (A) every wave is also done reading the token tile
+            const float m = absmax_from_lds(0);
+            const _Float16 sh = quant_to_stage(acc2, m, clipv, 0);
+            commit(pre_next);   // past the end this is the re-read last row; nobody uses it
+            __syncthreads();    // (B) staged codes and the next tile are visible
+            copy_out(t, 0, sh);
+        };
+        if constexpr (DEEP) {
+            while (true) {
+                body(t, pre1, pre0);
+                t += G;
+                if (t >= p.T) break;
+                body(t, pre0, pre1);
+                t += G;
+                if (t >= p.T) break;
+            }
+        } else {
+            for (; t < p.T; t += G) body(t, pre0, pre0);
         }
     } else {
-        for (; t < p.T; t += G) body(t, pre0, pre0);
+        // Software-pipelined over tokens: while the MFMA pipe works on token j+1, the vector ALU rounds and packs
+        // token j, and there is a single workgroup barrier per token.  Token j's tile, staged codes and absmax
+        // slots live in LDS buffer j % 2.  Register sets: pre0 receives tokens t0, t2, ..., pre1 receives t1, t3, ...
+        f32x16 accX[SPW][A], accY[SPW][A];
+        // prime: token t0 through the contractions; t1's row into tile 1; t2's row requested
+        issue_clamped(t + 2 * G, pre0);
+        gemm(0, accX, [](int) {});
+        absmax_to_lds(accX, 0);
+        commit(pre1, 1);
+        __syncthreads();
+        float m_cur = absmax_from_lds(0);
+        float clip_cur = clip[p.clip_mode ? t : 0];
+        // step j (token t = t_j in acc_cur): request t_{j+3}; contractions for t_{j+1} overlap with quantizing t_j;
+        // t_{j+2}'s row, which arrived during the previous step, replaces t_j's tile
+        auto step = [&](int64_t t, int jb, f32x16 (&acc_cur)[SPW][A], f32x16 (&acc_next)[SPW][A],
+                        u32x4 (&pre_commit)[NPRE], u32x4 (&pre_issue)[NPRE]) {
+            issue_clamped(t + 3 * G, pre_issue);
+            const int64_t tn = (t + G < p.T) ? t + G : p.T - 1;
+            const float clip_next = clip[p.clip_mode ? tn : 0];
+            const Step st = make_step(m_cur, clip_cur);
+            gemm(jb ^ 1, acc_next, [&](int slot) {
+#pragma unroll
+                for (int u = slot * NUNIT / NSLOT; u < (slot + 1) * NUNIT / NSLOT; ++u) quant_unit(acc_cur, st, jb, u);
+            });
+            absmax_to_lds(acc_next, jb ^ 1);
+            commit(pre_commit, jb);
+            __syncthreads();
+            copy_out(t, jb, st.sh);
+            m_cur = absmax_from_lds(jb ^ 1);
+            clip_cur = clip_next;
+        };
+        while (true) {
+            if (t + G >= p.T) { const _Float16 sh = quant_to_stage(accX, m_cur, clip_cur, 0); __syncthreads(); copy_out(t, 0, sh); break; }
+            step(t, 0, accX, accY, pre0, pre1);
+            t += G;
+            if (t + G >= p.T) { const _Float16 sh = quant_to_stage(accY, m_cur, clip_cur, 1); __syncthreads(); copy_out(t, 1, sh); break; }
+            step(t, 1, accY, accX, pre1, pre0);
+            t += G;
+        }
     }
 }
 
 // ------------------------------------------------------------------------------------
-using KernelFn = void (*)(TqDev);
+using KernelFn = void (*)(TqDev, const float*);
 
 struct Variant {
     KernelFn fn;
     int lds;
 };
 
+// mode 0: one slab per wave; mode 1: two slabs per wave; mode 2: one slab per wave, software-pipelined over tokens
 template <int A, int B>
-static Variant variant_ab(bool full1) {
-    return full1 ? Variant{&tq_fast_kernel<A, B, true>, FastLds<A, B>::TOTAL}
-                 : Variant{&tq_fast_kernel<A, B, false>, FastLds<A, B>::TOTAL};
+static Variant variant_ab(bool full1, int mode) {
+    if constexpr (A <= 2 && (B == 2 || B == 4 || B == 8)) {
+        if (mode == 1)
+            return full1 ? Variant{&tq_fast_kernel<A, B, 2, true, false>, FastLds<A, B>::TOTAL}
+                         : Variant{&tq_fast_kernel<A, B, 2, false, false>, FastLds<A, B>::TOTAL};
+    }
+    if constexpr (A <= 3) {
+        if (mode == 2)
+            return full1 ? Variant{&tq_fast_kernel<A, B, 1, true, true>, FastLds<A, B, 2>::TOTAL}
+                         : Variant{&tq_fast_kernel<A, B, 1, false, true>, FastLds<A, B, 2>::TOTAL};
+    }
+    return full1 ? Variant{&tq_fast_kernel<A, B, 1, true, false>, FastLds<A, B>::TOTAL}
+                 : Variant{&tq_fast_kernel<A, B, 1, false, false>, FastLds<A, B>::TOTAL};
 }
 
 template <int A>
-static Variant variant_a(int B, bool full1) {
+static Variant variant_a(int B, bool full1, int mode) {
     switch (B) {
-        case 1: return variant_ab<A, 1>(full1);
-        case 2: return variant_ab<A, 2>(full1);
-        case 3: return variant_ab<A, 3>(full1);
-        case 4: return variant_ab<A, 4>(full1);
-        case 5: return variant_ab<A, 5>(full1);
-        case 6: return variant_ab<A, 6>(full1);
-        case 7: return variant_ab<A, 7>(full1);
-        default: return variant_ab<A, 8>(full1);
+        case 1: return variant_ab<A, 1>(full1, mode);
+        case 2: return variant_ab<A, 2>(full1, mode);
+        case 3: return variant_ab<A, 3>(full1, mode);
+        case 4: return variant_ab<A, 4>(full1, mode);
+        case 5: return variant_ab<A, 5>(full1, mode);
+        case 6: return variant_ab<A, 6>(full1, mode);
+        case 7: return variant_ab<A, 7>(full1, mode);
+        default: return variant_ab<A, 8>(full1, mode);
     }
 }
 
-static Variant variant(int A, int B, bool full1) {
+static Variant variant(int A, int B, bool full1, int mode) {
     switch (A) {
-        case 1: return variant_a<1>(B, full1);
-        case 2: return variant_a<2>(B, full1);
-        case 3: return variant_a<3>(B, full1);
-        default: return variant_a<4>(B, full1);
+        case 1: return variant_a<1>(B, full1, mode);
+        case 2: return variant_a<2>(B, full1, mode);
+        case 3: return variant_a<3>(B, full1, mode);
+        default: return variant_a<4>(B, full1, mode);
     }
 }
 
@@ -359,17 +478,25 @@ bool tq_fast_applicable(const TqDev& d) {
 
 int64_t tq_fast_lds_bytes(int n1, int n2) {
     if (n1 < 1 || n1 > kMaxN1 || n2 < 32 || n2 > kMaxN2 || n2 % 32) return 0;
-    return variant((n1 + 31) / 32, n2 / 32, n1 % 32 == 0).lds;
+    const int A = (n1 + 31) / 32;
+    const int a = variant(A, n2 / 32, n1 % 32 == 0, 0).lds, b = variant(A, n2 / 32, n1 % 32 == 0, 2).lds;
+    return a > b ? a : b;
 }
 
 hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     const int A = (d.n1 + 31) / 32, B = d.n2 / 32;
     const bool full1 = (d.n1 % 32) == 0;
-    const Variant v = variant(A, B, full1);
-    const int nt = 64 * B;
+    // kernel flavour (see variant_ab); FLATQUANT_MODE overrides the default for tuning and tests
+    int mode = (A <= 3) ? 2 : 0;
+    const int mode_env = env_int("FLATQUANT_MODE", -1);
+    if (mode_env == 0 || (mode_env == 1 && A <= 2 && (B == 2 || B == 4 || B == 8)) || (mode_env == 2 && A <= 3)) mode = mode_env;
+    const int spw = (mode == 1) ? 2 : 1;
+    const Variant v = variant(A, B, full1, mode);
+    const int nt = 64 * (B / spw);
 
-    static int wg_per_cu[4][8][2];   // per-variant occupancy, computed once per process (benign race: same value)
-    int occ = wg_per_cu[A - 1][B - 1][full1];
+    static int wg_per_cu[4][8][2][3];   // per-variant occupancy, computed once per process (benign race: same value)
+    int& occ_slot = wg_per_cu[A - 1][B - 1][full1][mode];
+    int occ = occ_slot;
     if (occ == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.fn), hipFuncAttributeMaxDynamicSharedMemorySize, v.lds);
         if (e != hipSuccess) return e;
@@ -378,7 +505,7 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
         if (e != hipSuccess) return e;
         if (nb < 1) return hipErrorLaunchOutOfResources;
         occ = nb;
-        wg_per_cu[A - 1][B - 1][full1] = occ;
+        occ_slot = occ;
     }
     const int cap = env_int("FLATQUANT_WG_PER_CU", 0);
     if (cap > 0 && cap < occ) occ = cap;
@@ -386,7 +513,7 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     const int64_t resident = (int64_t)cu_count() * occ;
     const int64_t rounds = (d.T + resident - 1) / resident;
     const int64_t grid = (d.T + rounds - 1) / rounds;
-    hipLaunchKernelGGL(v.fn, dim3((unsigned)grid), dim3(nt), v.lds, stream, d);
+    hipLaunchKernelGGL(v.fn, dim3((unsigned)grid), dim3(nt), v.lds, stream, d, d.clip);
     return hipGetLastError();
 }
 
