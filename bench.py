@@ -135,16 +135,11 @@ def main() -> int:
         },
     }
 
-    # ------------------------------------------------------------------ reference point: plain copy with the same 4:1 mix
-    src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda")      # 256 MB read
-    dst = torch.empty((64 << 20,), dtype=torch.uint8, device="cuda")       # 64 MB written
-
-    def step_copy(i):
-        dst.copy_(src[:dst.numel()])
-        src[dst.numel():].sum(dtype=torch.int64) if False else None
-
-    ms_copy, _ = time_region(lambda i: dst.copy_(src[:dst.numel()]), 50, 10)
-    out["detail"]["torch_copy_64MB_gbs"] = 2 * dst.numel() / (ms_copy * 1e-3) / 1e9
+    # ------------------------------------------------------------------ reference point: what a plain copy reaches on this machine
+    src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")       # 1 GB: far larger than the 256 MB last-level cache
+    dst = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")
+    ms_copy, _ = time_region(lambda i: dst.copy_(src), 20, 3)
+    out["detail"]["torch_copy_1GB_gbs_read_plus_write"] = 2 * dst.numel() / (ms_copy * 1e-3) / 1e9
     del src, dst
 
     # ------------------------------------------------------------------ secondary shapes

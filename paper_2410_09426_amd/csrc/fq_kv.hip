@@ -5,25 +5,39 @@
 // then asymmetric INT4 with one step and one zero point per group (Sec. 4.1
 // "Quantization": group size 128 = head_dim).
 //
-// Mapping: blockIdx.y is the head, so every wave of a workgroup shares one P_h,
-// kept in LDS as ready-made MFMA A-operand fragments.  A wave takes 32 tokens:
+// Mapping: blockIdx.y is the head, so every wave of a workgroup shares one P_h.
+// P_h is fetched once per workgroup with coalesced 16-byte loads and re-laid in
+// LDS as ready-made MFMA A-operand fragments.  Workgroups are persistent; a wave
+// takes 32 tokens at a time:
 //   Y^T[d', token] = sum_d P_h[d, d'] kv[token, d]
 // with M = d' (4 tiles of 32), N = 32 tokens, K = d (8 blocks of 16).  The B
 // operand comes straight from global memory (lane <-> token, 16 bytes <-> 8
-// consecutive d).  In the result a lane holds, for its token, 64 of the 128
-// outputs (the other half-wave holds the rest) in runs of 4 consecutive d', so
-// min/max need one cross-half exchange and 4 codes pack into 2 bytes in-lane.
+// consecutive d) and the next 32 tokens are prefetched into registers while the
+// current ones are in the MFMA pipe.  In the result a lane holds, for its token,
+// 64 of the 128 outputs (the other half-wave holds the rest) in runs of 4
+// consecutive d', so min/max need one cross-half exchange and 4 codes pack into
+// 2 bytes in-lane.  Packed rows are staged per wave in LDS and leave with
+// 16-byte stores.
 #include "fq_internal.h"
 
 namespace fq {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KV_D = 128;
 constexpr int KV_WAVES = 4;
-constexpr int KV_TOK_PER_WAVE = 32;
-constexpr int KV_STAGE_PITCH = 80;   // bytes per staged code row (64 + pad)
+constexpr int KV_NT = 64 * KV_WAVES;
+constexpr int KV_TOK = 32;                 // tokens per wave per step
+constexpr int KV_STAGE_PITCH = 80;         // bytes per staged code row (64 + pad)
+constexpr int KV_MT = KV_D / 32;           // 4 tiles over d'
+constexpr int KV_KB = KV_D / 16;           // 8 K blocks over d
+constexpr int KV_FRAG_BYTES = KV_MT * KV_KB * 64 * 16;        // 32 KB of A fragments
+constexpr int KV_FLAT_ROWS = KV_D / 2;                        // P_h is re-laid in two passes of 64 rows
+constexpr int KV_FLAT_BYTES = KV_FLAT_ROWS * (KV_D + 8) * 2;  // row-major, padded pitch, while fragments are built
+constexpr int KV_STAGE_BYTES = KV_WAVES * 32 * KV_STAGE_PITCH;
+constexpr int KV_LDS_BYTES = KV_FRAG_BYTES + (KV_FLAT_BYTES > KV_STAGE_BYTES ? KV_FLAT_BYTES : KV_STAGE_BYTES);
 
 struct KvDev {
     const _Float16* kv;
@@ -36,117 +50,176 @@ struct KvDev {
     float clip;
 };
 
-__global__ __launch_bounds__(64 * KV_WAVES) void kv_kernel(KvDev p) {
-    constexpr int MT = KV_D / 32;   // 4 tiles over d'
-    constexpr int KB = KV_D / 16;   // 8 K blocks over d
-    __shared__ __attribute__((aligned(16))) uint4 Pf[MT * KB * 64];                       // 32 KB of A fragments
-    __shared__ __attribute__((aligned(16))) uint8_t stage[KV_WAVES][32 * KV_STAGE_PITCH];  // per-wave code rows
+__global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void kv_kernel(KvDev p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    u32x4* Pf = reinterpret_cast<u32x4*>(smem);                               // fragment table
+    _Float16* Pflat = reinterpret_cast<_Float16*>(smem + KV_FRAG_BYTES);      // prologue only
+    uint8_t* stage_all = smem + KV_FRAG_BYTES;                                // loop only (reuses Pflat's space)
 
     const int tid = threadIdx.x;
     const int l = tid & 63, w = tid >> 6, c = l & 31, h = l >> 5;
     const int head = blockIdx.y;
     const _Float16* Ph = p.P + (size_t)(p.Hp == 1 ? 0 : head) * KV_D * KV_D;
+    const int64_t nblk = (p.T + KV_TOK - 1) / KV_TOK;
+    const int64_t bstep = (int64_t)gridDim.x * KV_WAVES;
 
-    // A fragment (M tile mt, K block kb): lane (c, h) holds P_h[16kb + 8h + s][32mt + c], s = 0..7
-    for (int e = tid; e < MT * KB * 64; e += 64 * KV_WAVES) {
-        const int ln = e & 63, kb = (e >> 6) % KB, mt = (e >> 6) / KB;
-        const int cc = ln & 31, hh = ln >> 5;
-        half8 f;
+    auto row_ptr = [&](int64_t blk) {
+        int64_t tok = blk * KV_TOK + c;
+        if (tok >= p.T) tok = p.T - 1;                      // lanes past the end re-read the last token and later store its (identical) results onto it
+        return reinterpret_cast<const u32x4*>(p.kv + (tok * p.H + head) * KV_D);
+    };
+    auto issue = [&](int64_t blk, u32x4 (&r)[KV_KB]) {
+        const u32x4* row = row_ptr(blk < nblk ? blk : nblk - 1);
 #pragma unroll
-        for (int s = 0; s < 8; ++s) f[s] = Ph[(16 * kb + 8 * hh + s) * KV_D + 32 * mt + cc];
-        *reinterpret_cast<half8*>(&Pf[e]) = f;
-    }
-    __syncthreads();
+        for (int kb = 0; kb < KV_KB; ++kb) r[kb] = row[2 * kb + h];   // cached: a 128-byte line is shared by 4 of these loads
+    };
 
-    const int64_t nblk = (p.T + KV_TOK_PER_WAVE - 1) / KV_TOK_PER_WAVE;   // 32-token blocks
-    for (int64_t blk = (int64_t)blockIdx.x * KV_WAVES + w; blk < nblk; blk += (int64_t)gridDim.x * KV_WAVES) {
-        const int64_t tok = blk * KV_TOK_PER_WAVE + c;
-        const bool live = tok < p.T;
-        const int64_t grp = (live ? tok : p.T - 1) * p.H + head;          // clamp: dead lanes re-read the last token
-        const uint4* row = reinterpret_cast<const uint4*>(p.kv + grp * KV_D);
+    // ---- the first rows are requested before the transform matrix
+    int64_t blk = (int64_t)blockIdx.x * KV_WAVES + w;
+    u32x4 cur[KV_KB], nxt[KV_KB];
+    issue(blk, cur);
 
-        half8 bf[KB];
+    // ---- P_h: coalesced loads -> LDS (padded pitch) -> A fragments: lane (c, h) of fragment (mt, kb) holds
+    // P_h[16kb + 8h + s][32mt + c], s = 0..7.  Two passes of 64 rows keep the LDS footprint at 3 workgroups per CU.
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            uint4 v = row[2 * kb + h];
-            bf[kb] = *reinterpret_cast<half8*>(&v);
+    for (int pass = 0; pass < 2; ++pass) {
+        constexpr int CH = KV_FLAT_ROWS * KV_D / 8;   // 1024 chunks of 16 bytes, 4 per thread
+        u32x4 v[CH / KV_NT];
+#pragma unroll
+        for (int k = 0; k < CH / KV_NT; ++k) v[k] = reinterpret_cast<const u32x4*>(Ph)[pass * CH + tid + k * KV_NT];
+        if (pass > 0) __syncthreads();   // previous pass fully consumed
+#pragma unroll
+        for (int k = 0; k < CH / KV_NT; ++k) {
+            const int q = tid + k * KV_NT, r = q >> 4, cc = q & 15;
+            *reinterpret_cast<u32x4*>(Pflat + r * (KV_D + 8) + cc * 8) = v[k];
         }
-        f32x16 acc[MT];
+        __syncthreads();
+        for (int e = tid; e < KV_MT * (KV_KB / 2) * 64; e += KV_NT) {
+            const int ln = e & 63, kbl = (e >> 6) % (KV_KB / 2), mt = (e >> 6) / (KV_KB / 2);
+            const int cc = ln & 31, hh = ln >> 5;
+            half8 f;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
+            for (int s = 0; s < 8; ++s) f[s] = Pflat[(16 * kbl + 8 * hh + s) * (KV_D + 8) + 32 * mt + cc];
+            *reinterpret_cast<half8*>(&Pf[(mt * KV_KB + pass * (KV_KB / 2) + kbl) * 64 + ln]) = f;
+        }
+    }
+    __syncthreads();   // fragments ready; the flat copy's space becomes the stage buffers
+
+    uint8_t* stage = stage_all + w * 32 * KV_STAGE_PITCH;
+    const float clip = p.clip;
+
+    // one step: 32 tokens whose rows are in `rows`; the rows of the next step are requested into `far`
+    auto step = [&](int64_t blk, const u32x4 (&rows)[KV_KB], u32x4 (&far)[KV_KB]) {
+        issue(blk + bstep, far);                            // always issued (clamped): exact outstanding-load counts
+        __builtin_amdgcn_sched_barrier(0);
+
+        f32x16 acc[KV_MT];
+#pragma unroll
+        for (int mt = 0; mt < KV_MT; ++mt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                const half8 a = *reinterpret_cast<const half8*>(&Pf[(mt * KB + kb) * 64 + l]);
-                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bf[kb], acc[mt], 0, 0, 0);
+        for (int kb = 0; kb < KV_KB; ++kb) {
+            const half8 b = __builtin_bit_cast(half8, rows[kb]);
+#pragma unroll
+            for (int mt = 0; mt < KV_MT; ++mt) {
+                const half8 a = *reinterpret_cast<const half8*>(&Pf[(mt * KV_KB + kb) * 64 + l]);
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[mt], 0, 0, 0);
             }
         }
-        // group range: in-lane over 64 values, then the other half-wave's 64
+        // ---- group range (always containing 0): in-lane over 64 values, then the other half-wave's 64
         float mx = 0.0f, mn = 0.0f;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < KV_MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                mx = __builtin_fmaxf(mx, acc[mt][r]);
-                mn = __builtin_fminf(mn, acc[mt][r]);
+            for (int r = 0; r < 16; r += 2) {
+                mx = __builtin_fmaxf(mx, __builtin_fmaxf(acc[mt][r], acc[mt][r + 1]));
+                mn = __builtin_fminf(mn, __builtin_fminf(acc[mt][r], acc[mt][r + 1]));
             }
         mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
         mn = __builtin_fminf(mn, __shfl_xor(mn, 32));
-        mx *= p.clip;
-        mn *= p.clip;
-        const _Float16 sh = (_Float16)((mx - mn) / 15.0f);
+        mx *= clip;
+        mn *= clip;
+        const _Float16 sh = (_Float16)((mx - mn) * 0.0666666701f);   // (mx - mn) / 15, round-to-nearest-even to fp16
         const float s = (float)sh;
-        const float inv = (s > 0.0f && s <= 65504.0f) ? 1.0f / s : 0.0f;
+        const float inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;
         const float z = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(-mn * inv), 0.0f), 15.0f);
+        // q = clamp(round(y / s) + z, 0, 15) = round(clamp(y, -z s, (15 - z) s) / s + z): clamp, then one fma against
+        // 1.5 * 2^23 leaves the code in the low mantissa bits (zeros above), so codes chain with shift-adds
+        const float sl = (inv != 0.0f) ? s : 0.0f;
+        const float lim_lo = -z * sl, lim_hi = (15.0f - z) * sl;
+        const float magic = 12582912.0f + z;
 
-        uint8_t* srow = &stage[w][c * KV_STAGE_PITCH];
+        uint8_t* srow = stage + c * KV_STAGE_PITCH;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < KV_MT; ++mt)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                uint32_t pk = 0;
+                uint32_t bits[4];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const float q = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(acc[mt][4 * g + k] * inv) + z, 0.0f), 15.0f);
-                    pk |= (uint32_t)(int)q << (4 * k);
+                    const float yc = __builtin_amdgcn_fmed3f(acc[mt][4 * g + k], lim_lo, lim_hi);
+                    bits[k] = __builtin_bit_cast(uint32_t, __builtin_fmaf(yc, inv, magic));
                 }
+                const uint32_t pk = (((bits[3] << 4) + bits[2]) << 8) + ((bits[1] << 4) + bits[0]);
                 const int dp = 32 * mt + 8 * g + 4 * h;   // first of 4 consecutive output channels
                 *reinterpret_cast<uint16_t*>(srow + (dp >> 1)) = (uint16_t)pk;
             }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // 32 rows x 64 bytes: lane -> (row l/4 + 16k, 16-byte chunk l%4)
+        // 32 rows x 64 bytes: lane -> (row l/4 + 16k, 16-byte chunk l%4).  Rows past the end hold a copy of the last
+        // token's row (their lanes re-read its input), so they are stored onto it: same bytes, no branch.
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const int r = (l >> 2) + 16 * k, ch = l & 3;
-            const int64_t tk = blk * KV_TOK_PER_WAVE + r;
-            if (tk < p.T) {
-                const uint4 v = *reinterpret_cast<const uint4*>(&stage[w][r * KV_STAGE_PITCH + 16 * ch]);
-                *reinterpret_cast<uint4*>(p.out_codes + (tk * p.H + head) * (KV_D / 2) + 16 * ch) = v;
-            }
+            int64_t tk = blk * KV_TOK + r;
+            if (tk >= p.T) tk = p.T - 1;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * KV_STAGE_PITCH + 16 * ch);
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.out_codes + (tk * p.H + head) * (KV_D / 2) + 16 * ch));
         }
-        if (live && h == 0) {
-            p.out_scales[grp] = sh;
-            p.out_zeros[grp] = (_Float16)z;
+        {
+            int64_t tok = blk * KV_TOK + c;
+            if (tok >= p.T) tok = p.T - 1;
+            p.out_scales[tok * p.H + head] = sh;           // both half-waves hold the same step and zero point
+            p.out_zeros[tok * p.H + head] = (_Float16)z;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();   // staged rows are consumed before the next block overwrites them
+        __builtin_amdgcn_wave_barrier();   // staged rows are consumed before the next step overwrites them
+    };
+    while (blk < nblk) {
+        step(blk, cur, nxt);
+        blk += bstep;
+        if (blk >= nblk) break;
+        step(blk, nxt, cur);
+        blk += bstep;
     }
 }
 
 hipError_t kv_launch(const KvArgs& a, hipStream_t stream) {
-    const int64_t nblk = (a.T + KV_TOK_PER_WAVE - 1) / KV_TOK_PER_WAVE;
-    int64_t gx = (nblk + KV_WAVES - 1) / KV_WAVES;
-    const int64_t cap = (int64_t)cu_count() * 2 * 8 / (a.H < 8 ? a.H : 8) + 1;   // about 2 workgroups per CU in total
-    const int wg_cap = env_int("FLATQUANT_KV_GRID_X", 0);
-    if (gx > cap) gx = cap;
-    if (wg_cap > 0 && gx > wg_cap) gx = wg_cap;
+    static int wg_per_cu = 0;   // computed once per process (benign race: same value)
+    if (wg_per_cu == 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kv_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, KV_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        int nb = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kv_kernel, KV_NT, KV_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        if (nb < 1) return hipErrorLaunchOutOfResources;
+        wg_per_cu = nb;
+    }
+    int occ = wg_per_cu;
+    const int cap = env_int("FLATQUANT_KV_WG_PER_CU", 0);
+    if (cap > 0 && cap < occ) occ = cap;
+    const int64_t nblk = (a.T + KV_TOK - 1) / KV_TOK;
+    const int64_t need = (nblk + KV_WAVES - 1) / KV_WAVES;               // workgroups per head if each wave took one step
+    int64_t gx = ((int64_t)cu_count() * occ + a.H - 1) / a.H;            // resident workgroups, shared among the heads
+    if (gx < 1) gx = 1;
+    const int64_t rounds = (need + gx - 1) / gx;                         // same number of steps (+-1) for every workgroup
+    gx = (need + rounds - 1) / rounds;
     KvDev d;
     d.kv = a.kv; d.P = a.P; d.out_codes = a.out_codes; d.out_scales = a.out_scales; d.out_zeros = a.out_zeros;
     d.T = a.T; d.H = a.H; d.Hp = a.Hp; d.clip = a.clip;
-    hipLaunchKernelGGL(kv_kernel, dim3((unsigned)gx, (unsigned)a.H), dim3(64 * KV_WAVES), 0, stream, d);
+    hipLaunchKernelGGL(kv_kernel, dim3((unsigned)gx, (unsigned)a.H), dim3(KV_NT), KV_LDS_BYTES, stream, d);
     return hipGetLastError();
 }
 

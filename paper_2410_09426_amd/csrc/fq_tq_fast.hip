@@ -133,27 +133,51 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     const int64_t G = gridDim.x;
     issue(t, pre0);
 
-    // ---- stage P1 (flat, n1 x n1) and the first pass of P2 rows in LDS with coalesced loads
-    {
+    // ---- stage P1 (flat, n1 x n1) and P2 (in one or two passes of rows) in LDS with coalesced loads.  All loads of
+    // a stage are issued before any of them is consumed, so the stage costs one memory latency, not one per element.
+    auto stage_p1 = [&]() {
         const int n1sq = n1 * n1;
-        if ((n1sq & 7) == 0) {
-            for (int q = tid; q < (n1sq >> 3); q += NT)
-                reinterpret_cast<u32x4*>(P1flat)[q] = reinterpret_cast<const u32x4*>(p.P1)[q];
-        } else {   // n1 * n1 not a multiple of 8 halves: pairs, plus a last odd element
-            for (int q = tid; q < (n1sq >> 1); q += NT)
-                reinterpret_cast<uint32_t*>(P1flat)[q] = reinterpret_cast<const uint32_t*>(p.P1)[q];
-            if ((n1sq & 1) && tid == 0) P1flat[n1sq - 1] = p.P1[n1sq - 1];
+        auto copy_batched = [&](auto* dst, const auto* src, int count) {
+            constexpr int BATCH = 8;
+            for (int base = 0; base < count; base += BATCH * NT) {
+                decltype(*src + 0) v[BATCH];
+#pragma unroll
+                for (int k = 0; k < BATCH; ++k) {
+                    const int idx = base + k * NT + tid;
+                    v[k] = src[idx < count ? idx : count - 1];
+                }
+#pragma unroll
+                for (int k = 0; k < BATCH; ++k) {
+                    const int idx = base + k * NT + tid;
+                    if (idx < count) dst[idx] = v[k];
+                }
+            }
+        };
+        if ((reinterpret_cast<uintptr_t>(p.P1) & 15) == 0) {   // bulk in 16-byte chunks, then up to 7 single elements
+            const int done = n1sq & ~7;
+            const int ti = done + tid < n1sq ? done + tid : n1sq - 1;
+            const _Float16 tail = p.P1[ti];
+            copy_batched(reinterpret_cast<u32x4*>(P1flat), reinterpret_cast<const u32x4*>(p.P1), n1sq >> 3);
+            if (done + tid < n1sq) P1flat[ti] = tail;
+        } else {   // only 4-byte aligned: pairs, plus a last odd element
+            const _Float16 tail = p.P1[n1sq - 1];
+            copy_batched(reinterpret_cast<uint32_t*>(P1flat), reinterpret_cast<const uint32_t*>(p.P1), n1sq >> 1);
+            if ((n1sq & 1) && tid == 0) P1flat[n1sq - 1] = tail;
         }
-    }
+    };
     half8 p2f[SPW][KB2];
     half8 p1f[P1LDS ? 1 : A][P1LDS ? 1 : KB1];
 #pragma unroll
     for (int pass = 0; pass < L::P2PASSES; ++pass) {
-        if (pass > 0) __syncthreads();   // previous pass fully consumed
         constexpr int CH = L::P2ROWS * N2 / 8;
         const u32x4* src = reinterpret_cast<const u32x4*>(p.P2) + pass * CH;
+        u32x4 v2[CH / NT];
 #pragma unroll
-        for (int k = 0; k < CH / NT; ++k) reinterpret_cast<u32x4*>(P2flat)[tid + k * NT] = src[tid + k * NT];
+        for (int k = 0; k < CH / NT; ++k) v2[k] = src[tid + k * NT];
+        if (pass == 0) stage_p1();          // its loads queue behind the ones just issued: one latency for both
+        else __syncthreads();               // previous pass fully consumed
+#pragma unroll
+        for (int k = 0; k < CH / NT; ++k) reinterpret_cast<u32x4*>(P2flat)[tid + k * NT] = v2[k];
         __syncthreads();
         // B-operand fragments of this wave's slab: lane (c, h) holds P2[16kb + 8h + s][32w + c], s = 0..7
 #pragma unroll
@@ -174,7 +198,9 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
                     for (int s = 0; s < 8; ++s) {
                         const int i = 32 * (kk >> 1) + 8 * (2 * (kk & 1) + (s >> 2)) + 4 * hh + (s & 3);
-                        f[s] = (FULL1 || (i < n1 && ip < n1)) ? P1flat[i * n1 + ip] : (_Float16)0;
+                        const bool ok = FULL1 || (i < n1 && ip < n1);
+                        const _Float16 v = P1flat[ok ? i * n1 + ip : 0];   // unconditional read, then select: no branch per element
+                        f[s] = ok ? v : (_Float16)0;
                     }
                     *reinterpret_cast<half8*>(&P1s[e]) = f;
                 }
@@ -187,7 +213,9 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
                         for (int s = 0; s < 8; ++s) {
                             const int i = 32 * (kk >> 1) + 8 * (2 * (kk & 1) + (s >> 2)) + 4 * h + (s & 3);
-                            p1f[It][kk][s] = (FULL1 || (i < n1 && ip < n1)) ? P1flat[i * n1 + ip] : (_Float16)0;
+                            const bool ok = FULL1 || (i < n1 && ip < n1);
+                            const _Float16 v = P1flat[ok ? i * n1 + ip : 0];
+                            p1f[It][kk][s] = ok ? v : (_Float16)0;
                         }
                     }
             }
@@ -435,7 +463,7 @@ static Variant variant_ab(bool full1, int mode) {
             return full1 ? Variant{&tq_fast_kernel<A, B, 2, true, false>, FastLds<A, B>::TOTAL}
                          : Variant{&tq_fast_kernel<A, B, 2, false, false>, FastLds<A, B>::TOTAL};
     }
-    if constexpr (A <= 3) {
+    if constexpr (A <= 2) {
         if (mode == 2)
             return full1 ? Variant{&tq_fast_kernel<A, B, 1, true, true>, FastLds<A, B, 2>::TOTAL}
                          : Variant{&tq_fast_kernel<A, B, 1, false, true>, FastLds<A, B, 2>::TOTAL};
@@ -472,7 +500,7 @@ bool tq_fast_applicable(const TqDev& d) {
     if (reinterpret_cast<uintptr_t>(d.P2) & 15) return false;
     const int n1sq = d.n1 * d.n1;
     const uintptr_t a1 = reinterpret_cast<uintptr_t>(d.P1);
-    if ((n1sq & 7) == 0) return (a1 & 15) == 0;
+    (void)n1sq;
     return (a1 & 3) == 0;
 }
 
@@ -487,9 +515,9 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     const int A = (d.n1 + 31) / 32, B = d.n2 / 32;
     const bool full1 = (d.n1 % 32) == 0;
     // kernel flavour (see variant_ab); FLATQUANT_MODE overrides the default for tuning and tests
-    int mode = (A <= 3) ? 2 : 0;
+    int mode = (A <= 2) ? 2 : 0;
     const int mode_env = env_int("FLATQUANT_MODE", -1);
-    if (mode_env == 0 || (mode_env == 1 && A <= 2 && (B == 2 || B == 4 || B == 8)) || (mode_env == 2 && A <= 3)) mode = mode_env;
+    if (mode_env == 0 || (mode_env == 1 && A <= 2 && (B == 2 || B == 4 || B == 8)) || (mode_env == 2 && A <= 2)) mode = mode_env;
     const int spw = (mode == 1) ? 2 : 1;
     const Variant v = variant(A, B, full1, mode);
     const int nt = 64 * (B / spw);
