@@ -131,7 +131,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     u32x4 pre0[NPRE], pre1[DEEP ? NPRE : 1];
     int64_t t = blockIdx.x;
     const int64_t G = gridDim.x;
-    issue(t, pre0);
+    issue(t, pre0);   // [phase:rows requested]
 
     // ---- stage P1 (flat, n1 x n1) and P2 (in one or two passes of rows) in LDS with coalesced loads.  All loads of
     // a stage are issued before any of them is consumed, so the stage costs one memory latency, not one per element.
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         else __syncthreads();               // previous pass fully consumed
 #pragma unroll
         for (int k = 0; k < CH / NT; ++k) reinterpret_cast<u32x4*>(P2flat)[tid + k * NT] = v2[k];
-        __syncthreads();
+        __syncthreads();   // [phase:transforms staged]
         // B-operand fragments of this wave's slab: lane (c, h) holds P2[16kb + 8h + s][32w + c], s = 0..7
 #pragma unroll
         for (int kb = pass * (L::P2ROWS / 16); kb < (pass + 1) * (L::P2ROWS / 16); ++kb)
@@ -221,6 +221,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
             }
         }
     }
+    // [phase:fragments built]
     __syncthreads();   // staging area is free: it becomes the token tile
     if constexpr (!FULL1) {   // rows n1 .. 32A-1 of the tile are never loaded: make them exact zeros once
         for (int bf = 0; bf < NBUF; ++bf)
@@ -234,7 +235,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         if (t + G < p.T) issue(t + G, pre1);
     }
     commit(pre0);
-    __syncthreads();
+    __syncthreads();   // [phase:first tile in LDS]
 
     // ---- both contractions for the token tile in LDS buffer `buf`: acc2 = (P1^T X~ P2)^T for this wave's slabs
     // `side(slot)` is called NSLOT times at even intervals of the MFMA stream; the pipelined loop uses it to
@@ -383,14 +384,15 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
             issue_clamped(t + (DEEP ? 2 : 1) * G, pre_far);
             const float clipv = clip[p.clip_mode ? t : 0];   // wave-uniform address, read-only: a scalar load
             f32x16 acc2[SPW][A];
-            gemm(0, acc2, [](int) {});
+            gemm(0, acc2, [](int) {});   // [phase:contractions done]
             absmax_to_lds(acc2, 0);
-            __syncthreads();   // (A) every wave is also done reading the token tile
+            __syncthreads();   // (A) every wave is also done reading the token tile [phase:absmax exchanged]
             const float m = absmax_from_lds(0);
             const _Float16 sh = quant_to_stage(acc2, m, clipv, 0);
+            // [phase:codes staged]
             commit(pre_next);   // past the end this is the re-read last row; nobody uses it
-            __syncthreads();    // (B) staged codes and the next tile are visible
-            copy_out(t, 0, sh);
+            __syncthreads();    // (B) staged codes and the next tile are visible [phase:next tile in LDS]
+            copy_out(t, 0, sh);   // [phase:token done]
         };
         if constexpr (DEEP) {
             while (true) {
@@ -411,10 +413,10 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         f32x16 accX[SPW][A], accY[SPW][A];
         // prime: token t0 through the contractions; t1's row into tile 1; t2's row requested
         issue_clamped(t + 2 * G, pre0);
-        gemm(0, accX, [](int) {});
+        gemm(0, accX, [](int) {});   // [phase:prime contractions done]
         absmax_to_lds(accX, 0);
         commit(pre1, 1);
-        __syncthreads();
+        __syncthreads();   // [phase:primed]
         float m_cur = absmax_from_lds(0);
         float clip_cur = clip[p.clip_mode ? t : 0];
         // step j (token t = t_j in acc_cur): request t_{j+3}; contractions for t_{j+1} overlap with quantizing t_j;
@@ -429,10 +431,11 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
                 for (int u = slot * NUNIT / NSLOT; u < (slot + 1) * NUNIT / NSLOT; ++u) quant_unit(acc_cur, st, jb, u);
             });
+            // [phase:contractions done]
             absmax_to_lds(acc_next, jb ^ 1);
-            commit(pre_commit, jb);
-            __syncthreads();
-            copy_out(t, jb, st.sh);
+            commit(pre_commit, jb);   // [phase:codes staged]
+            __syncthreads();          // [phase:next tile in LDS]
+            copy_out(t, jb, st.sh);   // [phase:token done]
             m_cur = absmax_from_lds(jb ^ 1);
             clip_cur = clip_next;
         };
