@@ -83,6 +83,22 @@ __device__ __forceinline__ void split_hi_lo(const f32x16& acc, int base, half8& 
     lo = __builtin_bit_cast(half8, l);
 }
 
+// Eight fp16 values of one column of a row-major fp16 matrix in LDS, rows r0..r0+3 and r0+gap..r0+gap+3, for every
+// lane: two transposing LDS reads (ds_read_b64_tr_b16).  Within each block of 16 lanes, lane s supplies the address
+// of a 64-bit chunk and lane i receives element i%4 of the chunks supplied by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4
+// (measured on gfx950).  So lane s points at row r0 + s/4, columns col0 + 4(s%4).., and lane i ends up with rows
+// r0..r0+3 of column col0 + i.  `lane16` = lane % 16; `col0` is the first column of the lane's 16-lane block.
+typedef short short4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ half8 lds_column8(const _Float16* m, int pitch, int r0, int gap, int col0, int lane16) {
+    const _Float16* a0 = m + (r0 + (lane16 >> 2)) * pitch + col0 + 4 * (lane16 & 3);
+    typedef short4v __attribute__((address_space(3))) * lds_ptr;
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(a0));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(a0 + gap * pitch));
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    const short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(half8, v);
+}
+
 template <int A, int B, int SPW, bool FULL1, bool PIPE>
 __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(2))) void tq_fast_kernel(TqDev p, const float* __restrict__ clip) {
     static_assert(B % SPW == 0 && 16 % SPW == 0, "slabs per wave must divide the slab count and 16");
@@ -184,9 +200,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         for (int kb = pass * (L::P2ROWS / 16); kb < (pass + 1) * (L::P2ROWS / 16); ++kb)
 #pragma unroll
             for (int q = 0; q < SPW; ++q)
-#pragma unroll
-                for (int s = 0; s < 8; ++s)
-                    p2f[q][kb][s] = P2flat[(16 * kb - pass * L::P2ROWS + 8 * h + s) * N2 + 32 * (w * SPW + q) + c];
+                p2f[q][kb] = lds_column8(P2flat, N2, 16 * kb - pass * L::P2ROWS + 8 * h, 4, 32 * (w * SPW + q) + (c & 16), l & 15);
         if (pass == 0) {
             // P1 fragments, gathered with the k-permutation of the first contraction's accumulator layout:
             // K block kk, slot s, half-wave h  <->  i = 32(kk/2) + 8(2(kk%2) + s/4) + 4h + s%4
@@ -195,12 +209,16 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
                     const int ln = e & 63, kk = (e >> 6) % KB1, It = (e >> 6) / KB1;
                     const int cc = ln & 31, hh = ln >> 5, ip = 32 * It + cc;
                     half8 f;
+                    if constexpr (FULL1) {   // e % 64 is the lane: whole 16-lane blocks cooperate in the transposing reads
+                        f = lds_column8(P1flat, 32 * A, 32 * (kk >> 1) + 16 * (kk & 1) + 4 * hh, 8, 32 * It + (cc & 16), ln & 15);
+                    } else {
 #pragma unroll
-                    for (int s = 0; s < 8; ++s) {
-                        const int i = 32 * (kk >> 1) + 8 * (2 * (kk & 1) + (s >> 2)) + 4 * hh + (s & 3);
-                        const bool ok = FULL1 || (i < n1 && ip < n1);
-                        const _Float16 v = P1flat[ok ? i * n1 + ip : 0];   // unconditional read, then select: no branch per element
-                        f[s] = ok ? v : (_Float16)0;
+                        for (int s = 0; s < 8; ++s) {
+                            const int i = 32 * (kk >> 1) + 8 * (2 * (kk & 1) + (s >> 2)) + 4 * hh + (s & 3);
+                            const bool ok = i < n1 && ip < n1;
+                            const _Float16 v = P1flat[ok ? i * n1 + ip : 0];   // unconditional read, then select: no branch per element
+                            f[s] = ok ? v : (_Float16)0;
+                        }
                     }
                     *reinterpret_cast<half8*>(&P1s[e]) = f;
                 }
@@ -210,12 +228,16 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
                     for (int kk = 0; kk < KB1; ++kk) {
                         const int ip = 32 * It + c;
+                        if constexpr (FULL1) {
+                            p1f[It][kk] = lds_column8(P1flat, 32 * A, 32 * (kk >> 1) + 16 * (kk & 1) + 4 * h, 8, 32 * It + (c & 16), l & 15);
+                        } else {
 #pragma unroll
-                        for (int s = 0; s < 8; ++s) {
-                            const int i = 32 * (kk >> 1) + 8 * (2 * (kk & 1) + (s >> 2)) + 4 * h + (s & 3);
-                            const bool ok = FULL1 || (i < n1 && ip < n1);
-                            const _Float16 v = P1flat[ok ? i * n1 + ip : 0];
-                            p1f[It][kk][s] = ok ? v : (_Float16)0;
+                            for (int s = 0; s < 8; ++s) {
+                                const int i = 32 * (kk >> 1) + 8 * (2 * (kk & 1) + (s >> 2)) + 4 * h + (s & 3);
+                                const bool ok = i < n1 && ip < n1;
+                                const _Float16 v = P1flat[ok ? i * n1 + ip : 0];
+                                p1f[It][kk][s] = ok ? v : (_Float16)0;
+                            }
                         }
                     }
             }
