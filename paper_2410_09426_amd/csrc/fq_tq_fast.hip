@@ -151,7 +151,9 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
 
     // ---- stage P1 (flat, n1 x n1) and P2 (in one or two passes of rows) in LDS with coalesced loads.  All loads of
     // a stage are issued before any of them is consumed, so the stage costs one memory latency, not one per element.
-    auto stage_p1 = [&]() {
+    // `after_first_loads()` runs once, right after the first batch of loads has been issued and before anything waits
+    // for it: the place to queue further requests that nothing in the prologue depends on.
+    auto stage_p1 = [&](auto&& after_first_loads) {
         const int n1sq = n1 * n1;
         auto copy_batched = [&](auto* dst, const auto* src, int count) {
             constexpr int BATCH = 8;
@@ -161,6 +163,11 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
                 for (int k = 0; k < BATCH; ++k) {
                     const int idx = base + k * NT + tid;
                     v[k] = src[idx < count ? idx : count - 1];
+                }
+                if (base == 0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    after_first_loads();
+                    __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
                 for (int k = 0; k < BATCH; ++k) {
@@ -190,7 +197,14 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         u32x4 v2[CH / NT];
 #pragma unroll
         for (int k = 0; k < CH / NT; ++k) v2[k] = src[tid + k * NT];
-        if (pass == 0) stage_p1();          // its loads queue behind the ones just issued: one latency for both
+        if (pass == 0) {
+            // P1's loads queue behind P2's: one latency for both.  The second token row is requested behind them, so
+            // it is in flight during the whole prologue without delaying the transforms (loads return in order).
+            stage_p1([&]() {
+                if constexpr (PIPE) issue((t + G < p.T) ? t + G : p.T - 1, pre1);
+                else if constexpr (DEEP) { if (t + G < p.T) issue(t + G, pre1); }
+            });
+        }
         else __syncthreads();               // previous pass fully consumed
 #pragma unroll
         for (int k = 0; k < CH / NT; ++k) reinterpret_cast<u32x4*>(P2flat)[tid + k * NT] = v2[k];
@@ -249,12 +263,6 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         for (int bf = 0; bf < NBUF; ++bf)
             for (int q = tid; q < (32 * A - n1) * (PITCH / 8); q += NT)
                 reinterpret_cast<u32x4*>(Xs + bf * (L::XS_BYTES / 2) + n1 * PITCH)[q] = u32x4{0u, 0u, 0u, 0u};
-    }
-    // the second row is requested only now, so that across the chip every first row is served before any second row
-    if constexpr (PIPE) {
-        issue((t + G < p.T) ? t + G : p.T - 1, pre1);
-    } else if constexpr (DEEP) {
-        if (t + G < p.T) issue(t + G, pre1);
     }
     commit(pre0);
     __syncthreads();   // [phase:first tile in LDS]
@@ -540,7 +548,10 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     const int A = (d.n1 + 31) / 32, B = d.n2 / 32;
     const bool full1 = (d.n1 % 32) == 0;
     // kernel flavour (see variant_ab); FLATQUANT_MODE overrides the default for tuning and tests
+    // Measured on MI355X: the pipelined loop wins or ties everywhere except very long 64-wide streams, where one
+    // wave per token (no barrier partner, tile read once) sustains ~10 % more.
     int mode = (A <= 2) ? 2 : 0;
+    if (A <= 2 && B == 2 && d.T >= 32768) mode = 1;
     const int mode_env = env_int("FLATQUANT_MODE", -1);
     if (mode_env == 0 || (mode_env == 1 && A <= 2 && (B == 2 || B == 4 || B == 8)) || (mode_env == 2 && A <= 2)) mode = mode_env;
     const int spw = (mode == 1) ? 2 : 1;

@@ -73,6 +73,23 @@ def test_general_kernel_on_aligned_shapes(monkeypatch):
     check_case(synth.decode_7b(64, wide=True), with_dequant=False, label="general kernel")
 
 
+@pytest.mark.parametrize("mode", ["0", "1", "2"])
+def test_every_kernel_flavour(monkeypatch, mode):
+    # 0: one slab per wave; 1: two slabs per wave; 2: software-pipelined loop (the library picks one by shape and T)
+    monkeypatch.setenv("FLATQUANT_MODE", mode)
+    c = synth.prefill_7b(1024 + 3)
+    check_case(c, rows=subset_rows(c.T, 150, 11, must=(0, 1, 1023, 1024)), with_dequant=False, label=f"mode {mode}")
+    c = synth.generic(90 + int(mode), 600, 64, 128)
+    check_case(c, rows=subset_rows(c.T, 80, 12), with_dequant=False, label=f"mode {mode}")
+    c = synth.generic(95 + int(mode), 40, 32, 64)
+    check_case(c, with_dequant=False, label=f"mode {mode}")
+
+
+def test_long_stream_uses_wave_per_token_path():
+    c = synth.prefill_7b(32768 + 5)
+    check_case(c, rows=subset_rows(c.T, 200, 13, must=(0, 32767, 32768)), with_dequant=False, label="T >= 32768")
+
+
 def test_decode_shapes():
     check_case(synth.decode_7b(64))
     check_case(synth.decode_7b(64, wide=True))
