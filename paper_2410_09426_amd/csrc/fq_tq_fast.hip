@@ -99,9 +99,12 @@ __device__ __forceinline__ half8 lds_column8(const _Float16* m, int pitch, int r
     return __builtin_bit_cast(half8, v);
 }
 
-template <int A, int B, int SPW, bool FULL1, bool PIPE>
-__global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(2))) void tq_fast_kernel(TqDev p, const float* __restrict__ clip) {
+// KIND 0: persistent loop, one token per step; 1: persistent loop, software-pipelined over tokens;
+// 2: one token per workgroup (small T: every token gets its own workgroup, all resident at once, 4 waves per SIMD)
+template <int A, int B, int SPW, bool FULL1, int KIND>
+__global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(KIND == 2 ? 4 : 2))) void tq_fast_kernel(TqDev p, const float* __restrict__ clip) {
     static_assert(B % SPW == 0 && 16 % SPW == 0, "slabs per wave must divide the slab count and 16");
+    constexpr bool PIPE = (KIND == 1), ONE = (KIND == 2);
     using L = FastLds<A, B, PIPE ? 2 : 1>;
     constexpr int WPT = B / SPW;                  // waves per token = waves per workgroup
     constexpr int NT = 64 * WPT, N2 = L::N2, PITCH = L::PITCH;
@@ -143,7 +146,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     };
 
     // ---- the first token row of this workgroup is requested before anything else
-    constexpr bool DEEP = PIPE || (NPRE <= 4);   // two rows in flight per workgroup when the registers allow it
+    constexpr bool DEEP = !ONE && (PIPE || (NPRE <= 4));   // two rows in flight per workgroup when the registers allow it
     u32x4 pre0[NPRE], pre1[DEEP ? NPRE : 1];
     int64_t t = blockIdx.x;
     const int64_t G = gridDim.x;
@@ -406,7 +409,17 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         __builtin_amdgcn_sched_barrier(0);   // keep the requests here, ahead of the MFMA work, with their registers reserved
     };
 
-    if constexpr (!PIPE) {
+    if constexpr (ONE) {
+        const float clipv = clip[p.clip_mode ? t : 0];
+        f32x16 acc2[SPW][A];
+        gemm(0, acc2, [](int) {});   // [phase:contractions done]
+        absmax_to_lds(acc2, 0);
+        __syncthreads();             // [phase:absmax exchanged]
+        const float m = absmax_from_lds(0);
+        const _Float16 sh = quant_to_stage(acc2, m, clipv, 0);   // [phase:codes staged]
+        __syncthreads();
+        copy_out(t, 0, sh);          // [phase:token done]
+    } else if constexpr (!PIPE) {
         // One token per step: the tile of token t is in LDS, `pre_next` holds (or is receiving) the row of token t + G
         // and is written to LDS once every wave is done with the current tile; the row of token t + 2G is requested
         // into `pre_far`.  The caller alternates the two register sets.
@@ -488,21 +501,25 @@ struct Variant {
     int lds;
 };
 
-// mode 0: one slab per wave; mode 1: two slabs per wave; mode 2: one slab per wave, software-pipelined over tokens
+// mode 0: one slab per wave; mode 1: two slabs per wave; mode 2: one slab per wave, software-pipelined over tokens;
+// mode 3: one slab per wave, one token per workgroup (only when every token can have a resident workgroup)
 template <int A, int B>
 static Variant variant_ab(bool full1, int mode) {
     if constexpr (A <= 2 && (B == 2 || B == 4 || B == 8)) {
         if (mode == 1)
-            return full1 ? Variant{&tq_fast_kernel<A, B, 2, true, false>, FastLds<A, B>::TOTAL}
-                         : Variant{&tq_fast_kernel<A, B, 2, false, false>, FastLds<A, B>::TOTAL};
+            return full1 ? Variant{&tq_fast_kernel<A, B, 2, true, 0>, FastLds<A, B>::TOTAL}
+                         : Variant{&tq_fast_kernel<A, B, 2, false, 0>, FastLds<A, B>::TOTAL};
     }
     if constexpr (A <= 2) {
         if (mode == 2)
-            return full1 ? Variant{&tq_fast_kernel<A, B, 1, true, true>, FastLds<A, B, 2>::TOTAL}
-                         : Variant{&tq_fast_kernel<A, B, 1, false, true>, FastLds<A, B, 2>::TOTAL};
+            return full1 ? Variant{&tq_fast_kernel<A, B, 1, true, 1>, FastLds<A, B, 2>::TOTAL}
+                         : Variant{&tq_fast_kernel<A, B, 1, false, 1>, FastLds<A, B, 2>::TOTAL};
+        if (mode == 3)
+            return full1 ? Variant{&tq_fast_kernel<A, B, 1, true, 2>, FastLds<A, B>::TOTAL}
+                         : Variant{&tq_fast_kernel<A, B, 1, false, 2>, FastLds<A, B>::TOTAL};
     }
-    return full1 ? Variant{&tq_fast_kernel<A, B, 1, true, false>, FastLds<A, B>::TOTAL}
-                 : Variant{&tq_fast_kernel<A, B, 1, false, false>, FastLds<A, B>::TOTAL};
+    return full1 ? Variant{&tq_fast_kernel<A, B, 1, true, 0>, FastLds<A, B>::TOTAL}
+                 : Variant{&tq_fast_kernel<A, B, 1, false, 0>, FastLds<A, B>::TOTAL};
 }
 
 template <int A>
@@ -547,36 +564,55 @@ int64_t tq_fast_lds_bytes(int n1, int n2) {
 hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     const int A = (d.n1 + 31) / 32, B = d.n2 / 32;
     const bool full1 = (d.n1 % 32) == 0;
-    // kernel flavour (see variant_ab); FLATQUANT_MODE overrides the default for tuning and tests
-    // Measured on MI355X: the pipelined loop wins or ties everywhere except very long 64-wide streams, where one
-    // wave per token (no barrier partner, tile read once) sustains ~10 % more.
+    // Kernel flavour (see variant_ab), from measurements on MI355X: the pipelined loop wins or ties the plain loop
+    // wherever it fits; very long 64-wide streams sustain ~10 % more with one wave per token; and when every token can
+    // have its own resident workgroup (4 waves per SIMD) the loop-free kernel is ~10 % faster still.
+    // FLATQUANT_MODE overrides the choice for tuning and tests.
+    static int wg_per_cu[4][8][2][4];   // per-variant occupancy, computed once per process (benign race: same value)
+    auto occupancy = [&](int mode, int& occ) -> hipError_t {
+        int& slot = wg_per_cu[A - 1][B - 1][full1][mode];
+        if (slot == 0) {
+            const Variant v = variant(A, B, full1, mode);
+            const int nt = 64 * (B / (mode == 1 ? 2 : 1));
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.fn), hipFuncAttributeMaxDynamicSharedMemorySize, v.lds);
+            if (e != hipSuccess) return e;
+            int nb = 0;
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, v.fn, nt, v.lds);
+            if (e != hipSuccess) return e;
+            if (nb < 1) return hipErrorLaunchOutOfResources;
+            slot = nb;
+        }
+        occ = slot;
+        return hipSuccess;
+    };
     int mode = (A <= 2) ? 2 : 0;
     if (A <= 2 && B == 2 && d.T >= 32768) mode = 1;
+    if (A <= 2 && B <= 2) {
+        int occ3 = 0;
+        hipError_t e = occupancy(3, occ3);
+        if (e != hipSuccess) return e;
+        if (d.T <= (int64_t)cu_count() * occ3) mode = 3;
+    }
     const int mode_env = env_int("FLATQUANT_MODE", -1);
-    if (mode_env == 0 || (mode_env == 1 && A <= 2 && (B == 2 || B == 4 || B == 8)) || (mode_env == 2 && A <= 2)) mode = mode_env;
+    if (mode_env == 0 || (mode_env == 1 && A <= 2 && (B == 2 || B == 4 || B == 8)) || (mode_env == 2 && A <= 2) || (mode_env == 3 && A <= 2)) mode = mode_env;
     const int spw = (mode == 1) ? 2 : 1;
     const Variant v = variant(A, B, full1, mode);
     const int nt = 64 * (B / spw);
-
-    static int wg_per_cu[4][8][2][3];   // per-variant occupancy, computed once per process (benign race: same value)
-    int& occ_slot = wg_per_cu[A - 1][B - 1][full1][mode];
-    int occ = occ_slot;
-    if (occ == 0) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.fn), hipFuncAttributeMaxDynamicSharedMemorySize, v.lds);
+    int occ = 0;
+    {
+        hipError_t e = occupancy(mode, occ);
         if (e != hipSuccess) return e;
-        int nb = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, v.fn, nt, v.lds);
-        if (e != hipSuccess) return e;
-        if (nb < 1) return hipErrorLaunchOutOfResources;
-        occ = nb;
-        occ_slot = occ;
     }
     const int cap = env_int("FLATQUANT_WG_PER_CU", 0);
     if (cap > 0 && cap < occ) occ = cap;
     // every workgroup gets the same number of tokens (+-1): grid = ceil(T / ceil(T / resident workgroups))
     const int64_t resident = (int64_t)cu_count() * occ;
     const int64_t rounds = (d.T + resident - 1) / resident;
-    const int64_t grid = (d.T + rounds - 1) / rounds;
+    int64_t grid = (d.T + rounds - 1) / rounds;
+    if (mode == 3) {
+        if (d.T > resident) return hipErrorInvalidConfiguration;   // only reachable through the tuning overrides
+        grid = d.T;
+    }
     hipLaunchKernelGGL(v.fn, dim3((unsigned)grid), dim3(nt), v.lds, stream, d, d.clip);
     return hipGetLastError();
 }

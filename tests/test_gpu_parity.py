@@ -73,9 +73,10 @@ def test_general_kernel_on_aligned_shapes(monkeypatch):
     check_case(synth.decode_7b(64, wide=True), with_dequant=False, label="general kernel")
 
 
-@pytest.mark.parametrize("mode", ["0", "1", "2"])
+@pytest.mark.parametrize("mode", ["0", "1", "2", "3"])
 def test_every_kernel_flavour(monkeypatch, mode):
-    # 0: one slab per wave; 1: two slabs per wave; 2: software-pipelined loop (the library picks one by shape and T)
+    # 0: one slab per wave; 1: two slabs per wave; 2: software-pipelined loop; 3: one token per workgroup
+    # (the library picks one by shape and T)
     monkeypatch.setenv("FLATQUANT_MODE", mode)
     c = synth.prefill_7b(1024 + 3)
     check_case(c, rows=subset_rows(c.T, 150, 11, must=(0, 1, 1023, 1024)), with_dequant=False, label=f"mode {mode}")
