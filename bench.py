@@ -93,6 +93,11 @@ def main() -> int:
     def step_warm(i):
         fq.flatquant_transform_quant(xs[0], P1, P2, clips[0], 1, T, n1, n2, n, codes[0], scales[0], stream=stream)
 
+    def step_probe(i):   # same buffers, same rotation, no arithmetic: the ceiling for a launch of this size
+        k = i % nsets
+        fq.flatquant_stream_probe(xs[k], T, n, n, codes[k], stream=stream)
+
+    ms_probe, _ = time_region(step_probe, args.steps, args.warmup)
     ms_cold, wall_cold = time_region(step_cold, args.steps, args.warmup)
     ms_warm, _ = time_region(step_warm, args.steps, args.warmup)
     for k in range(1, nsets):                                         # every rotation set produced the same bytes
@@ -128,6 +133,8 @@ def main() -> int:
             "algorithmic_bytes_per_launch": bytes_per_launch,
             "us_per_call_cold": ms_cold * 1e3, "us_per_call_warm": ms_warm * 1e3,
             "host_wall_us_per_call_cold": wall_cold * 1e3,
+            "stream_probe_us_per_call_cold": ms_probe * 1e3,
+            "stream_probe_gbs": T * (2 * n + n // 2) / (ms_probe * 1e-3) / 1e9,
             "tokens_per_s_warm": T / (ms_warm * 1e-3),
             "gbs_warm": bytes_per_launch / (ms_warm * 1e-3) / 1e9,
             "mfma_tflops_min_count": flops_min / (ms_cold * 1e-3) / 1e12,

@@ -94,6 +94,15 @@ fq_status flatquant_kv_transform_quant(const void* kv, const void* P, int Hp, fl
 fq_status flatquant_dequant(const uint8_t* codes, const void* scales, const void* zeros,
                             int64_t rows, int n, float* out, void* stream);
 
+/*
+ * Measurement aid (not part of the method): moves the bytes of flatquant_transform_quant without its arithmetic.
+ * Reads every row of x once (fp16 [T, n], x_stride halves apart) and writes n/2 bytes per row to out ([T, n/2],
+ * an xor-fold of the row, contents meaningless).  Same persistent one-workgroup-per-row traffic pattern, 16-byte
+ * non-temporal accesses.  Requires n % 32 == 0, x and out 16-byte aligned, x_stride % 8 == 0.  The time of one
+ * call is the ceiling that launch cost and memory latency leave for a launch of that size on this machine.
+ */
+fq_status flatquant_stream_probe(const void* x, int64_t T, int n, int64_t x_stride, uint8_t* out, void* stream);
+
 /* ---- host-only helpers: no GPU is touched ---------------------------------- */
 
 /* 1 if flatquant_transform_quant has a kernel variant for (n1, n2), else 0. */

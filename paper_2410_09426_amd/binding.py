@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libflatquant.so")
 FQ_OK, FQ_INVALID_ARG, FQ_UNSUPPORTED_SHAPE, FQ_MISALIGNED, FQ_LAUNCH_FAILED = range(5)
 
 EXPORTS = (
-    "flatquant_transform_quant", "flatquant_kv_transform_quant", "flatquant_dequant",
+    "flatquant_transform_quant", "flatquant_kv_transform_quant", "flatquant_dequant", "flatquant_stream_probe",
     "fq_supported", "fq_choose_factors", "fq_default_design_fits", "fq_lds_bytes",
     "fq_status_string", "fq_last_hip_error", "fq_abi_version",
 )
@@ -47,6 +47,8 @@ def lib() -> ctypes.CDLL:
         L.flatquant_kv_transform_quant.restype = i32
         L.flatquant_dequant.argtypes = [vp, vp, vp, i64, i32, vp, vp]
         L.flatquant_dequant.restype = i32
+        L.flatquant_stream_probe.argtypes = [vp, i64, i32, i64, vp, vp]
+        L.flatquant_stream_probe.restype = i32
         L.fq_supported.argtypes = [i32, i32]
         L.fq_supported.restype = i32
         L.fq_choose_factors.argtypes = [i64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
@@ -111,6 +113,13 @@ def flatquant_dequant(codes, scales, zeros, rows: int, n: int, out, stream=None,
     st = lib().flatquant_dequant(_ptr(codes), _ptr(scales), _ptr(zeros), int(rows), int(n), _ptr(out), _stream(stream))
     if check and st != FQ_OK:
         raise FlatQuantError(st, "flatquant_dequant")
+    return st
+
+
+def flatquant_stream_probe(x, T: int, n: int, x_stride: int, out, stream=None, check: bool = True) -> int:
+    st = lib().flatquant_stream_probe(_ptr(x), int(T), int(n), int(x_stride), _ptr(out), _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_stream_probe")
     return st
 
 

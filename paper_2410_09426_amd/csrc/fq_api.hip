@@ -102,6 +102,15 @@ fq_status flatquant_dequant(const uint8_t* codes, const void* scales, const void
                                          rows, n, out, static_cast<hipStream_t>(stream)));
 }
 
+fq_status flatquant_stream_probe(const void* x, int64_t T, int n, int64_t x_stride, uint8_t* out, void* stream) {
+    if (T < 0 || n < 32 || x_stride < n) return FQ_INVALID_ARG;
+    if (n % 32 != 0) return FQ_UNSUPPORTED_SHAPE;
+    if (T == 0) return FQ_OK;
+    if (!x || !out) return FQ_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(out) & 15) || (x_stride & 7)) return FQ_MISALIGNED;
+    return fq::finish(fq::stream_probe_launch(x, T, n, x_stride, out, static_cast<hipStream_t>(stream)));
+}
+
 int fq_supported(int n1, int n2) { return fq::tq_supported(n1, n2) ? 1 : 0; }
 
 fq_status fq_choose_factors(int64_t n, int* n1, int* n2) {

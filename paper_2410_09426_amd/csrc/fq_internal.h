@@ -67,6 +67,9 @@ hipError_t kv_launch(const KvArgs& a, hipStream_t stream);
 hipError_t dequant_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,
                           int64_t rows, int n, float* out, hipStream_t stream);
 
+// Copy-like probe with the activation kernel's traffic (fq_probe.hip).
+hipError_t stream_probe_launch(const void* x, int64_t T, int n, int64_t x_stride, uint8_t* out, hipStream_t stream);
+
 // Number of compute units of the current device (cached per device).
 int cu_count();
 // Integer tuning override from the environment (bench / sweep aid); `dflt` if unset.

@@ -83,6 +83,13 @@ __device__ __forceinline__ void split_hi_lo(const f32x16& acc, int base, half8& 
     lo = __builtin_bit_cast(half8, l);
 }
 
+// (a << sh) + b in one instruction (the compiler otherwise re-associates the nibble chain into more operations)
+__device__ __forceinline__ uint32_t lshl_add(uint32_t a, int sh, uint32_t b) {
+    uint32_t r;
+    asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "n"(sh), "v"(b));
+    return r;
+}
+
 // Eight fp16 values of one column of a row-major fp16 matrix in LDS, rows r0..r0+3 and r0+gap..r0+gap+3, for every
 // lane: two transposing LDS reads (ds_read_b64_tr_b16).  Within each block of 16 lanes, lane s supplies the address
 // of a 64-bit chunk and lane i receives element i%4 of the chunks supplied by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4
@@ -352,6 +359,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     // ---- step from the absmax; clamp, round, pack into stage buffer `buf`.  fma against 1.5 * 2^23 + 8 leaves
     // code + 8 (0..15) in the low mantissa bits with zeros above up to bit 21, so four results chain with shift-adds
     // and one xor turns offset-binary nibbles into two's complement ones.
+    const int stage_lane = (c * N2 + 32 * w * SPW + 4 * h) >> 1;   // this lane's byte offset inside a staged code row
     struct Step { _Float16 sh; float inv, lim_lo, lim_hi; };
     auto make_step = [&](float m, float clipv) {
         Step st;
@@ -375,10 +383,10 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
             const float yc = __builtin_amdgcn_fmed3f(acc2[q][It][4 * g + k], st.lim_lo, st.lim_hi);
             bits[k] = __builtin_bit_cast(uint32_t, __builtin_fmaf(yc, st.inv, 12582920.0f));
         }
-        const uint32_t pk = ((((bits[3] << 4) + bits[2]) << 8) + ((bits[1] << 4) + bits[0])) ^ 0x8888u;
-        const int jp = 32 * (w * SPW + q) + 8 * g + 4 * h;
+        const uint32_t pk = lshl_add(lshl_add(bits[3], 4, bits[2]), 8, lshl_add(bits[1], 4, bits[0])) ^ 0x8888u;
+        // byte offset of channel (ip, jp) / 2 with ip = 32 It + c, jp = 32 (w SPW + q) + 8 g + 4 h: lane part + constant
         if (FULL1 || It < A - 1 || ip < n1)
-            *reinterpret_cast<uint16_t*>(stg + ((ip * N2 + jp) >> 1)) = (uint16_t)pk;
+            *reinterpret_cast<uint16_t*>(stg + stage_lane + (32 * It * N2 + 32 * q + 8 * g) / 2) = (uint16_t)pk;
     };
     auto quant_to_stage = [&](const f32x16 (&acc2)[SPW][A], float m, float clipv, int buf) -> _Float16 {
         const Step st = make_step(m, clipv);

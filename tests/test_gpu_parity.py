@@ -223,3 +223,21 @@ def test_dequant_helper_ragged():
         assert np.array_equal(out.astype(np.float64), fo.dequantize(codes, scales))
         out = run_dequant(dev(codes), dev(scales), dev(zeros), rows, n)
         assert np.array_equal(out.astype(np.float64), fo.dequantize(codes, scales, zeros))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("T,n,pad", [(2048, 4096, 0), (5000, 4096, 64), (7, 8192, 0), (3, 32, 32)])
+def test_stream_probe_moves_every_byte_once(T, n, pad):
+    """The measurement aid folds each row's four quarters with xor: every input byte reaches exactly one output byte."""
+    rng = np.random.default_rng(77)
+    x = rng.integers(0, 65536, size=(T, n + pad), dtype=np.uint16)
+    xd = torch.from_numpy(x.view(np.int16)).cuda()
+    out = torch.full((64 + T * (n // 2) + 64,), 0xCD, dtype=torch.uint8, device="cuda")
+    fq.flatquant_stream_probe(xd, T, n, n + pad, out[64:], stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert (got[:64] == 0xCD).all() and (got[-64:] == 0xCD).all()
+    q = n // 4
+    v = x[:, :n]
+    want = v[:, :q] ^ v[:, q:2 * q] ^ v[:, 2 * q:3 * q] ^ v[:, 3 * q:]
+    assert np.array_equal(got[64:-64].view(np.uint16).reshape(T, q), want)

@@ -84,6 +84,11 @@ def test_argument_validation_without_a_device():
     assert kv(out_zeros=None) == fq.FQ_INVALID_ARG
     assert kv(out_zeros=A + 0x500000) == fq.FQ_INVALID_ARG      # scales and zeros alias
 
+    assert fq.flatquant_stream_probe(A, 0, 4096, 4096, A + 0x400000, check=False) == fq.FQ_OK
+    assert fq.flatquant_stream_probe(A, 4, 4100, 4100, A + 0x400000, check=False) == fq.FQ_UNSUPPORTED_SHAPE
+    assert fq.flatquant_stream_probe(A + 2, 4, 4096, 4096, A + 0x400000, check=False) == fq.FQ_MISALIGNED
+    assert fq.flatquant_stream_probe(None, 4, 4096, 4096, A + 0x400000, check=False) == fq.FQ_INVALID_ARG
+
     dq = lambda **k: fq.flatquant_dequant(**{**dict(codes=A, scales=A + 0x100000, zeros=None, rows=4, n=64, out=A + 0x200000, check=False), **k})
     assert dq(rows=0) == fq.FQ_OK
     assert dq(n=63) == fq.FQ_INVALID_ARG
