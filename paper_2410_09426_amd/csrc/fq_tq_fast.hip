@@ -69,7 +69,9 @@ __device__ __forceinline__ float sub_half(float z, unsigned int packed) {
     return r;
 }
 
-// fp32 x8 -> fp16 hi (round toward zero, cannot overflow to inf) and fp16 lo = fp16(z - hi)
+// fp32 x8 -> fp16 hi (round toward zero, cannot overflow to inf) and fp16 lo = fp16(z - hi).
+// (Writing the residual with v_fma_mixlo_f16 / v_fma_mixhi_f16 saves one instruction per pair, but with a single
+// wave per SIMD it produced wrong residuals on gfx950: the half-register writes stay out of this kernel.)
 __device__ __forceinline__ void split_hi_lo(const f32x16& acc, int base, half8& hi, half8& lo) {
     u32x4 h, l;
 #pragma unroll
@@ -618,7 +620,7 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     const int64_t rounds = (d.T + resident - 1) / resident;
     int64_t grid = (d.T + rounds - 1) / rounds;
     if (mode == 3) {
-        if (d.T > resident) return hipErrorInvalidConfiguration;   // only reachable through the tuning overrides
+        if (d.T > 0x7fffffff) return hipErrorInvalidConfiguration;   // only reachable through the tuning overrides
         grid = d.T;
     }
     hipLaunchKernelGGL(v.fn, dim3((unsigned)grid), dim3(nt), v.lds, stream, d, d.clip);
