@@ -26,6 +26,29 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// Eight fp16 values of one column of a row-major fp16 matrix in LDS, rows r0..r0+3 and r0+gap..r0+gap+3, for every
+// lane: two transposing LDS reads (ds_read_b64_tr_b16).  Within each block of 16 lanes, lane s supplies the address
+// of a 64-bit chunk and lane i receives element i%4 of the chunks supplied by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4
+// (measured on gfx950).  So lane s points at row r0 + s/4, columns col0 + 4(s%4).., and lane i ends up with rows
+// r0..r0+3 of column col0 + i.  `lane16` = lane % 16; `col0` is the first column of the lane's 16-lane block.
+typedef short short4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ half8 lds_column8(const _Float16* m, int pitch, int r0, int gap, int col0, int lane16) {
+    const _Float16* a0 = m + (r0 + (lane16 >> 2)) * pitch + col0 + 4 * (lane16 & 3);
+    typedef short4v __attribute__((address_space(3))) * lds_ptr;
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(a0));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(a0 + gap * pitch));
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    const short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(half8, v);
+}
+
+// (a << sh) + b in one instruction (the compiler otherwise re-associates the nibble chain into more operations)
+__device__ __forceinline__ uint32_t lshl_add(uint32_t a, int sh, uint32_t b) {
+    uint32_t r;
+    asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "n"(sh), "v"(b));
+    return r;
+}
+
 constexpr int KV_D = 128;
 constexpr int KV_WAVES = 4;
 constexpr int KV_NT = 64 * KV_WAVES;
@@ -57,49 +80,63 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
     uint8_t* stage_all = smem + KV_FRAG_BYTES;                                // loop only (reuses Pflat's space)
 
     const int tid = threadIdx.x;
-    const int l = tid & 63, w = tid >> 6, c = l & 31, h = l >> 5;
+    const int l = tid & 63, c = l & 31, h = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: block indices and base addresses stay scalar
     const int head = blockIdx.y;
     const _Float16* Ph = p.P + (size_t)(p.Hp == 1 ? 0 : head) * KV_D * KV_D;
     const int64_t nblk = (p.T + KV_TOK - 1) / KV_TOK;
     const int64_t bstep = (int64_t)gridDim.x * KV_WAVES;
 
-    auto row_ptr = [&](int64_t blk) {
-        int64_t tok = blk * KV_TOK + c;
-        if (tok >= p.T) tok = p.T - 1;                      // lanes past the end re-read the last token and later store its (identical) results onto it
-        return reinterpret_cast<const u32x4*>(p.kv + (tok * p.H + head) * KV_D);
+    // Group (token, head) addressing.  Block `blk` starts at group blk * 32 * H + head (scalar); a lane adds the offset
+    // of its token, r tokens further on.  Tokens past the end are clamped to the last one: such lanes re-read its row
+    // and later store its (identical) results onto it, so no access needs a branch.
+    auto first_group = [&](int64_t blk) { return blk * KV_TOK * p.H + head; };
+    auto group_ofs = [&](int64_t blk, int r) -> uint32_t {
+        const int64_t left = p.T - 1 - blk * KV_TOK;                       // scalar
+        const int rem = left < KV_TOK - 1 ? (int)left : KV_TOK - 1;
+        return (uint32_t)((r < rem ? r : rem) * p.H);
     };
     auto issue = [&](int64_t blk, u32x4 (&r)[KV_KB]) {
-        const u32x4* row = row_ptr(blk < nblk ? blk : nblk - 1);
+        const int64_t b = blk < nblk ? blk : nblk - 1;
+        const u32x4* row = reinterpret_cast<const u32x4*>(p.kv + first_group(b) * KV_D) + (size_t)group_ofs(b, c) * (KV_D / 8);
 #pragma unroll
         for (int kb = 0; kb < KV_KB; ++kb) r[kb] = row[2 * kb + h];   // cached: a 128-byte line is shared by 4 of these loads
     };
 
-    // ---- the first rows are requested before the transform matrix
     int64_t blk = (int64_t)blockIdx.x * KV_WAVES + w;
     u32x4 cur[KV_KB], nxt[KV_KB];
-    issue(blk, cur);
 
     // ---- P_h: coalesced loads -> LDS (padded pitch) -> A fragments: lane (c, h) of fragment (mt, kb) holds
-    // P_h[16kb + 8h + s][32mt + c], s = 0..7.  Two passes of 64 rows keep the LDS footprint at 3 workgroups per CU.
+    // P_h[16kb + 8h + s][32mt + c], s = 0..7.  The LDS copy is made in two passes of 64 rows (3 workgroups per CU), but
+    // all of P_h is requested up front, and the first token rows only once it has arrived.  A CU's vector memory pipe
+    // returns data in request order: if the workgroups that start first queued their rows (HBM) at once, the P_h
+    // requests (L2) of the workgroups that start a little later on the same CU would wait behind them for microseconds,
+    // and those workgroups would end the kernel late (measured: 11 us to build the fragments instead of 3).
+    constexpr int CH = KV_FLAT_ROWS * KV_D / 8;   // 1024 chunks of 16 bytes per pass, 4 per thread
+    u32x4 v[2][CH / KV_NT];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass)
+#pragma unroll
+        for (int k = 0; k < CH / KV_NT; ++k) v[pass][k] = reinterpret_cast<const u32x4*>(Ph)[pass * CH + tid + k * KV_NT];
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
-        constexpr int CH = KV_FLAT_ROWS * KV_D / 8;   // 1024 chunks of 16 bytes, 4 per thread
-        u32x4 v[CH / KV_NT];
-#pragma unroll
-        for (int k = 0; k < CH / KV_NT; ++k) v[k] = reinterpret_cast<const u32x4*>(Ph)[pass * CH + tid + k * KV_NT];
         if (pass > 0) __syncthreads();   // previous pass fully consumed
 #pragma unroll
         for (int k = 0; k < CH / KV_NT; ++k) {
             const int q = tid + k * KV_NT, r = q >> 4, cc = q & 15;
-            *reinterpret_cast<u32x4*>(Pflat + r * (KV_D + 8) + cc * 8) = v[k];
+            *reinterpret_cast<u32x4*>(Pflat + r * (KV_D + 8) + cc * 8) = v[pass][k];
+        }
+        if (pass == 1) {   // all of P_h has arrived: only now request the first token rows (see above)
+            __builtin_amdgcn_sched_barrier(0);
+            issue(blk, cur);
+            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
         for (int e = tid; e < KV_MT * (KV_KB / 2) * 64; e += KV_NT) {
             const int ln = e & 63, kbl = (e >> 6) % (KV_KB / 2), mt = (e >> 6) / (KV_KB / 2);
             const int cc = ln & 31, hh = ln >> 5;
-            half8 f;
-#pragma unroll
-            for (int s = 0; s < 8; ++s) f[s] = Pflat[(16 * kbl + 8 * hh + s) * (KV_D + 8) + 32 * mt + cc];
+            // e % 64 is the lane, so whole 16-lane blocks cooperate in the transposing reads
+            const half8 f = lds_column8(Pflat, KV_D + 8, 16 * kbl + 8 * hh, 4, 32 * mt + (cc & 16), ln & 15);
             *reinterpret_cast<half8*>(&Pf[(mt * KV_KB + pass * (KV_KB / 2) + kbl) * 64 + ln]) = f;
         }
     }
@@ -132,9 +169,9 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
 #pragma unroll
         for (int mt = 0; mt < KV_MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                mx = __builtin_fmaxf(mx, __builtin_fmaxf(acc[mt][r], acc[mt][r + 1]));
-                mn = __builtin_fminf(mn, __builtin_fminf(acc[mt][r], acc[mt][r + 1]));
+            for (int r = 0; r < 16; r += 2) {   // running value first: each pair folds into one v_max3 / v_min3
+                mx = __builtin_fmaxf(__builtin_fmaxf(mx, acc[mt][r]), acc[mt][r + 1]);
+                mn = __builtin_fminf(__builtin_fminf(mn, acc[mt][r]), acc[mt][r + 1]);
             }
         mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
         mn = __builtin_fminf(mn, __shfl_xor(mn, 32));
@@ -161,7 +198,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
                     const float yc = __builtin_amdgcn_fmed3f(acc[mt][4 * g + k], lim_lo, lim_hi);
                     bits[k] = __builtin_bit_cast(uint32_t, __builtin_fmaf(yc, inv, magic));
                 }
-                const uint32_t pk = (((bits[3] << 4) + bits[2]) << 8) + ((bits[1] << 4) + bits[0]);
+                const uint32_t pk = lshl_add(lshl_add(bits[3], 4, bits[2]), 8, lshl_add(bits[1], 4, bits[0]));
                 const int dp = 32 * mt + 8 * g + 4 * h;   // first of 4 consecutive output channels
                 *reinterpret_cast<uint16_t*>(srow + (dp >> 1)) = (uint16_t)pk;
             }
@@ -170,19 +207,17 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         // 32 rows x 64 bytes: lane -> (row l/4 + 16k, 16-byte chunk l%4).  Rows past the end hold a copy of the last
         // token's row (their lanes re-read its input), so they are stored onto it: same bytes, no branch.
+        const int64_t g0 = first_group(blk);
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const int r = (l >> 2) + 16 * k, ch = l & 3;
-            int64_t tk = blk * KV_TOK + r;
-            if (tk >= p.T) tk = p.T - 1;
             const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * KV_STAGE_PITCH + 16 * ch);
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.out_codes + (tk * p.H + head) * (KV_D / 2) + 16 * ch));
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.out_codes + g0 * (KV_D / 2)) + (size_t)group_ofs(blk, r) * (KV_D / 32) + ch);
         }
-        {
-            int64_t tok = blk * KV_TOK + c;
-            if (tok >= p.T) tok = p.T - 1;
-            p.out_scales[tok * p.H + head] = sh;           // both half-waves hold the same step and zero point
-            p.out_zeros[tok * p.H + head] = (_Float16)z;
+        if (h == 0) {   // both half-waves hold the same step and zero point: one of them stores
+            const size_t go = group_ofs(blk, c);
+            (p.out_scales + g0)[go] = sh;
+            (p.out_zeros + g0)[go] = (_Float16)z;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();   // staged rows are consumed before the next step overwrites them
