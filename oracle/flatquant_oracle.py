@@ -22,6 +22,11 @@ What each function follows
 * kv_transform                 : Sec. 3.2 "Self-Attention": a dense per-head
   matrix P_h applied head by head (not decomposed).
 * dequantize                   : Sec. 2.1, s * q (symmetric) or s * (q - z).
+* inverse_transpose / weight_transform / weight_transform_quant /
+  quantized_linear             : the right factor of Eq. (2),
+  Q(P1^-1 x_1 W~ x_2 (P2^-1)^T), i.e. every weight row times (P1 (x) P2)^-T,
+  with per-output-channel symmetric INT4 (Sec. 4.1 "Quantization") and the
+  product of the two de-quantized factors that replaces X W^T (Eq. (1)).
 
 Conventions fixed where the paper is silent (all listed in the design notes):
 row-major reshape (channel c = i * n2 + j); signed grid [-8, 7] with step
@@ -213,6 +218,46 @@ def dequantize(codes_packed, scales_fp16, zeros=None) -> np.ndarray:
 # --------------------------------------------------------------------------
 # Closed forms of the paper's cost analysis (App. "Overhead Analysis")
 # --------------------------------------------------------------------------
+# --------------------------------------------------------------------------
+# Right factor of Eq. (2): the offline weight side
+# --------------------------------------------------------------------------
+def inverse_transpose(P) -> np.ndarray:
+    """(P^-1)^T in fp64 (library LU inverse as the one step)."""
+    return np.linalg.inv(as_f64(P)).T
+
+
+def weight_transform(W, P1, P2) -> np.ndarray:
+    """W [m, n] -> (P^-1 W^T)^T = W (P1 (x) P2)^-T, the weights that pair with
+    X P in Eq. (1): the inverse of the dense Kronecker matrix is taken as it
+    stands (no use of the factor structure)."""
+    P = kron_dense(P1, P2)
+    return as_f64(W) @ np.linalg.inv(P).T
+
+
+def weight_transform_factored(W, A1, A2) -> np.ndarray:
+    """Eq. (2), right factor, as printed: for every output channel o,
+    A1^T W~_o A2 with A1^T = P1^-1 and A2 = (P2^-1)^T, W~_o the row-major
+    n1 x n2 reshape of row o.  A1, A2 are passed in (e.g. fp16-rounded)."""
+    W = as_f64(W)
+    A1, A2 = as_f64(A1), as_f64(A2)
+    n1, n2 = A1.shape[0], A2.shape[0]
+    Wt = W.reshape(W.shape[0], n1, n2)
+    return np.einsum("ia,oij,jb->oab", A1, Wt, A2).reshape(W.shape[0], n1 * n2)
+
+
+def weight_transform_quant(W, A1, A2, clip_w):
+    """Per-output-channel symmetric INT4 of the transformed weights, with the
+    weight clipping ratio alpha_w (scalar or one per output channel)."""
+    y = weight_transform_factored(W, A1, A2)
+    q, s, u = quantize_sym_int4(y, clip_w)
+    return {"codes": pack_nibbles(q), "scales": s, "q": q, "u": u, "y": y}
+
+
+def quantized_linear(codes_x, scales_x, codes_w, scales_w) -> np.ndarray:
+    """deq(Q(XP)) deq(Q(P^-1 W^T)): [T, n/2] x [m, n/2] packed codes -> [T, m] fp64."""
+    return dequantize(codes_x, scales_x) @ dequantize(codes_w, scales_w).T
+
+
 def choose_factors(n: int):
     """argmin (n1 + n2) s.t. n1 * n2 = n, n1 <= n2  (Sec. 3.1)."""
     best = None

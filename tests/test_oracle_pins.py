@@ -348,3 +348,80 @@ def test_synthetic_recipes_are_deterministic_and_shaped():
     assert np.all(np.isfinite(a.x.astype(np.float32)))
     d = synth.decode_7b(8, wide=True)
     assert (d.n1, d.n2, d.n) == (86, 128, 11008)
+
+
+# ---- right factor of Eq. (2): the offline weight side -------------------------
+def _invertible(r, n, noise=0.2):
+    return (np.eye(n) + noise * r.standard_normal((n, n))).astype(np.float16)
+
+
+def test_weight_side_keeps_the_layer_output_eq1():
+    """Eq. (1): (X P)(P^-1 W^T) = X W^T.  The oracle's transformed weights, multiplied with the transformed
+    activations, must give back the plain layer output; brute-force exact rationals on a tiny case."""
+    r = rng(601)
+    n1, n2, T, m = 2, 3, 2, 3
+    P1 = np.array([[2, 1], [1, 1]], dtype=np.float16)              # unimodular: exact integer inverses
+    P2 = np.array([[1, 1, 0], [0, 1, 1], [0, 0, 1]], dtype=np.float16)
+    X = r.integers(-4, 5, size=(T, n1 * n2)).astype(np.float16)
+    W = r.integers(-4, 5, size=(m, n1 * n2)).astype(np.float16)
+    Wt = fo.weight_transform(W, P1, P2)
+    Y = fo.affine_transform(X, P1, P2) @ Wt.T
+    for t in range(T):
+        for o in range(m):
+            exact = sum(frac(X[t, c]) * frac(W[o, c]) for c in range(n1 * n2))
+            assert abs(Y[t, o] - float(exact)) < 1e-9
+    # a transposed or un-inverted factor must not pass (orientation pin)
+    wrong = fo.weight_transform_factored(W, np.linalg.inv(P1.astype(np.float64)), np.linalg.inv(P2.astype(np.float64)))
+    assert np.abs(fo.affine_transform(X, P1, P2) @ wrong.T - X.astype(np.float64) @ W.astype(np.float64).T).max() > 0.5
+
+
+@pytest.mark.parametrize("n1,n2", [(1, 4), (3, 5), (8, 8), (16, 4)])
+def test_weight_side_factored_form_equals_dense_inverse(n1, n2):
+    """(P1 (x) P2)^-1 = P1^-1 (x) P2^-1 (textbook): the factored right factor of Eq. (2) with A1 = P1^-T,
+    A2 = P2^-T must equal the weights obtained from the dense inverse."""
+    r = rng(610 + n1 * 31 + n2)
+    P1, P2 = _invertible(r, n1), _invertible(r, n2)
+    W = rand_fp16(r, (7, n1 * n2))
+    dense = fo.weight_transform(W, P1, P2)
+    fact = fo.weight_transform_factored(W, fo.inverse_transpose(P1), fo.inverse_transpose(P2))
+    assert np.allclose(dense, fact, rtol=1e-9, atol=1e-9)
+    # inverse_transpose against the defining property, not against itself
+    A1 = fo.inverse_transpose(P1)
+    assert np.allclose(A1.T @ P1.astype(np.float64), np.eye(n1), atol=1e-10)
+
+
+def test_weight_side_with_orthogonal_factors_is_the_activation_transform():
+    """For orthogonal P (normalised Hadamard factors) P^-T = P: weights and activations get the same transform."""
+    H = np.array([[1.0]])
+    for _ in range(3):
+        H = np.block([[H, H], [H, -H]])
+    P1 = (H / np.sqrt(8)).astype(np.float64)     # 8 x 8, not exactly representable in fp16: keep fp64
+    H2 = np.block([[H, H], [H, -H]])
+    P2 = (H2 / 4.0).astype(np.float16)           # 16 x 16, entries +-1/4 exact
+    r = rng(620)
+    W = rand_fp16(r, (5, 128))
+    assert np.allclose(fo.weight_transform(W, P1, P2), fo.affine_transform(W, P1, P2), atol=1e-12)
+
+
+def test_quantized_layer_error_is_within_the_rounding_bound():
+    """With alpha = 1 nothing clips, so |x^ - x'| <= s_x / 2 and |w^ - w'| <= s_w / 2 element-wise and
+    |y^ - y| <= ||x'||_1 s_w / 2 + ||w'||_1 s_x / 2 + n s_x s_w / 4 for every output: a rigorous bound that a wrong
+    scale, a wrong pairing of transformed factors or a wrong de-quantization breaks."""
+    r = rng(630)
+    n1, n2, T, m = 8, 16, 12, 9
+    P1, P2 = _invertible(r, n1, 0.1), _invertible(r, n2, 0.1)
+    X = rand_fp16(r, (T, n1 * n2), 2.0)
+    X[:, 5] *= 30
+    W = rand_fp16(r, (m, n1 * n2), 0.05)
+    ax = fo.transform_quant(X, P1, P2, 1.0)
+    aw = fo.weight_transform_quant(W, fo.inverse_transpose(P1), fo.inverse_transpose(P2), 1.0)
+    Yq = fo.quantized_linear(ax["codes"], ax["scales"], aw["codes"], aw["scales"])
+    Y = X.astype(np.float64) @ W.astype(np.float64).T
+    sx, sw = fo.as_f64(ax["scales"]), fo.as_f64(aw["scales"])
+    bound = (np.abs(ax["y"]).sum(1)[:, None] * sw[None, :] / 2 + np.abs(aw["y"]).sum(1)[None, :] * sx[:, None] / 2
+             + n1 * n2 * sx[:, None] * sw[None, :] / 4)
+    assert np.all(np.abs(Yq - Y) <= bound * (1 + 1e-9) + 1e-9)
+    assert np.abs(Yq - Y).max() > 0          # it is a quantized product, not the exact one
+    # per-output-channel steps: a row's codes do not depend on the other rows
+    one = fo.weight_transform_quant(W[3:4], fo.inverse_transpose(P1), fo.inverse_transpose(P2), 1.0)
+    assert np.array_equal(one["codes"][0], aw["codes"][3]) and one["scales"][0] == aw["scales"][3]
