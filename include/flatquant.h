@@ -86,6 +86,22 @@ fq_status flatquant_kv_transform_quant(const void* kv, const void* P, int Hp, fl
                                        void* stream);
 
 /*
+ * Weight side of the same layer (Eq. (2), right factor; Sec. 4.1 "Quantization": per-channel symmetric weights):
+ *     Q( P1^-1 x_1 W~ x_2 (P2^-1)^T )   ==   Q( W (P1 (x) P2)^-T ),   one step per output channel.
+ * Row o of W (width n = n1*n2, reshaped row-major to n1 x n2) becomes A1^T W~_o A2 with A1 = (P1^-1)^T and
+ * A2 = (P2^-1)^T, then is quantized like a token row: this is flatquant_transform_quant applied to the weight matrix
+ * with the inverse-transposed factors (fq_inverse_transpose builds them on the host), `m` output channels in the role
+ * of tokens and the weight clipping ratio(s) in `clip`.  Run once, offline; layouts, alignment and errors as above.
+ *   w          fp16 [m, n], row stride w_stride halves.      A1 fp16 [n1, n1], A2 fp16 [n2, n2] row-major.
+ *   out_codes  u8 [m, n/2];  out_scales fp16 [m] (one step per output channel).
+ * The product of flatquant_dequant(activation codes) and flatquant_dequant(weight codes)^T replaces X W^T (Eq. (1)).
+ */
+fq_status flatquant_weight_transform_quant(const void* w, const void* A1, const void* A2,
+                                           const float* clip, int clip_mode,
+                                           int64_t m, int n1, int n2, int64_t w_stride,
+                                           uint8_t* out_codes, void* out_scales, void* stream);
+
+/*
  * De-quantization check helper (Sec. 2.1: W^ = s * Pi(W / s)).
  *   zeros == NULL : out[r, c] = s[r] * q[r, c]            (signed nibbles)
  *   zeros != NULL : out[r, c] = s[r] * (q[r, c] - z[r])   (unsigned nibbles)
@@ -111,6 +127,12 @@ int fq_supported(int n1, int n2);
 /* The paper's factor rule (Sec. 3.1): argmin (n1 + n2) s.t. n1*n2 == n, n1 <= n2.
  * n < 1 leaves the outputs untouched and returns FQ_INVALID_ARG.  Host pointers. */
 fq_status fq_choose_factors(int64_t n, int* n1, int* n2);
+
+/* Host helper for the weight side: out = fp16( (P^-1)^T ) for a square fp16 matrix P [n, n] (host pointers, row-major,
+ * 1 <= n <= 256), inverted in fp64 by Gauss-Jordan elimination with partial pivoting and rounded once.  If
+ * `max_residual` is not NULL it receives max |P^T out - I| of the rounded result, in fp64.  Returns FQ_INVALID_ARG
+ * for null pointers, n out of range or a singular matrix (a pivot below 1e-12 times the largest entry). */
+fq_status fq_inverse_transpose(const void* P, int n, void* out, double* max_residual);
 
 /* On-chip footprint test of App. "Detailed Design of Kernel Fusion": returns 1
  * when (n1*n1 + 2*n1*n2)*2 < m and (n2*n2 + 2*n1*n2)*2 < m for m bytes of

@@ -18,6 +18,7 @@ FQ_OK, FQ_INVALID_ARG, FQ_UNSUPPORTED_SHAPE, FQ_MISALIGNED, FQ_LAUNCH_FAILED = r
 
 EXPORTS = (
     "flatquant_transform_quant", "flatquant_kv_transform_quant", "flatquant_dequant", "flatquant_stream_probe",
+    "flatquant_weight_transform_quant", "fq_inverse_transpose",
     "fq_supported", "fq_choose_factors", "fq_default_design_fits", "fq_lds_bytes",
     "fq_status_string", "fq_last_hip_error", "fq_abi_version",
 )
@@ -47,6 +48,10 @@ def lib() -> ctypes.CDLL:
         L.flatquant_kv_transform_quant.restype = i32
         L.flatquant_dequant.argtypes = [vp, vp, vp, i64, i32, vp, vp]
         L.flatquant_dequant.restype = i32
+        L.flatquant_weight_transform_quant.argtypes = L.flatquant_transform_quant.argtypes
+        L.flatquant_weight_transform_quant.restype = i32
+        L.fq_inverse_transpose.argtypes = [vp, i32, vp, ctypes.POINTER(ctypes.c_double)]
+        L.fq_inverse_transpose.restype = i32
         L.flatquant_stream_probe.argtypes = [vp, i64, i32, i64, vp, vp]
         L.flatquant_stream_probe.restype = i32
         L.fq_supported.argtypes = [i32, i32]
@@ -114,6 +119,30 @@ def flatquant_dequant(codes, scales, zeros, rows: int, n: int, out, stream=None,
     if check and st != FQ_OK:
         raise FlatQuantError(st, "flatquant_dequant")
     return st
+
+
+def flatquant_weight_transform_quant(w, A1, A2, clip, clip_mode: int, m: int, n1: int, n2: int, w_stride: int,
+                                     out_codes, out_scales, stream=None, check: bool = True) -> int:
+    st = lib().flatquant_weight_transform_quant(_ptr(w), _ptr(A1), _ptr(A2), _ptr(clip), int(clip_mode), int(m), int(n1),
+                                                int(n2), int(w_stride), _ptr(out_codes), _ptr(out_scales), _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_weight_transform_quant")
+    return st
+
+
+def fq_inverse_transpose(P):
+    """Host helper: fp16 [n, n] numpy array -> (fp16 (P^-1)^T, max |P^T out - I|).  Raises on a singular matrix."""
+    import numpy as np
+    P = np.ascontiguousarray(P, dtype=np.float16)
+    n = P.shape[0]
+    if P.ndim != 2 or P.shape != (n, n):
+        raise ValueError("fq_inverse_transpose expects a square matrix")
+    out = np.empty((n, n), dtype=np.float16)
+    res = ctypes.c_double(0.0)
+    st = lib().fq_inverse_transpose(P.ctypes.data, n, out.ctypes.data, ctypes.byref(res))
+    if st != FQ_OK:
+        raise FlatQuantError(st, "fq_inverse_transpose")
+    return out, res.value
 
 
 def flatquant_stream_probe(x, T: int, n: int, x_stride: int, out, stream=None, check: bool = True) -> int:

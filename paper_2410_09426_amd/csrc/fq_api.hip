@@ -2,6 +2,10 @@
 #include "../../include/flatquant.h"
 #include "fq_internal.h"
 
+#include <cmath>
+#include <utility>
+#include <vector>
+
 #include <cstdlib>
 
 namespace fq {
@@ -68,6 +72,13 @@ fq_status flatquant_transform_quant(const void* x, const void* P1, const void* P
     return fq::finish(fq::tq_launch(a, static_cast<hipStream_t>(stream)));
 }
 
+fq_status flatquant_weight_transform_quant(const void* w, const void* A1, const void* A2, const float* clip, int clip_mode,
+                                           int64_t m, int n1, int n2, int64_t w_stride, uint8_t* out_codes,
+                                           void* out_scales, void* stream) {
+    // the right factor of Eq. (2) is the left factor's operation on the rows of W with inverse-transposed matrices
+    return flatquant_transform_quant(w, A1, A2, clip, clip_mode, m, n1, n2, w_stride, out_codes, out_scales, stream);
+}
+
 fq_status flatquant_kv_transform_quant(const void* kv, const void* P, int Hp, float clip, int64_t T, int H, int D,
                                        uint8_t* out_codes, void* out_scales, void* out_zeros, void* stream) {
     if (T < 0 || H < 1 || D < 1 || !(clip > 0.0f)) return FQ_INVALID_ARG;
@@ -120,6 +131,55 @@ fq_status fq_choose_factors(int64_t n, int* n1, int* n2) {
         if (n % d == 0) best = d;
     *n1 = (int)best;
     *n2 = (int)(n / best);
+    return FQ_OK;
+}
+
+fq_status fq_inverse_transpose(const void* P, int n, void* out, double* max_residual) {
+    if (!P || !out || n < 1 || n > 256) return FQ_INVALID_ARG;
+    const _Float16* src = static_cast<const _Float16*>(P);
+    _Float16* dst = static_cast<_Float16*>(out);
+    std::vector<double> a((size_t)n * 2 * n);   // [P | I], reduced to [I | P^-1]
+    double big = 0.0;
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j) {
+            const double v = (double)src[(size_t)i * n + j];
+            a[(size_t)i * 2 * n + j] = v;
+            a[(size_t)i * 2 * n + n + j] = (i == j) ? 1.0 : 0.0;
+            big = std::fmax(big, std::fabs(v));
+        }
+    if (!(big > 0.0) || !std::isfinite(big)) return FQ_INVALID_ARG;
+    for (int col = 0; col < n; ++col) {
+        int piv = col;
+        for (int r = col + 1; r < n; ++r)
+            if (std::fabs(a[(size_t)r * 2 * n + col]) > std::fabs(a[(size_t)piv * 2 * n + col])) piv = r;
+        if (!(std::fabs(a[(size_t)piv * 2 * n + col]) > 1e-12 * big)) return FQ_INVALID_ARG;
+        if (piv != col)
+            for (int j = 0; j < 2 * n; ++j) std::swap(a[(size_t)piv * 2 * n + j], a[(size_t)col * 2 * n + j]);
+        const double d = 1.0 / a[(size_t)col * 2 * n + col];
+        for (int j = 0; j < 2 * n; ++j) a[(size_t)col * 2 * n + j] *= d;
+        for (int r = 0; r < n; ++r) {
+            if (r == col) continue;
+            const double f = a[(size_t)r * 2 * n + col];
+            if (f == 0.0) continue;
+            for (int j = 0; j < 2 * n; ++j) a[(size_t)r * 2 * n + j] -= f * a[(size_t)col * 2 * n + j];
+        }
+    }
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j) {
+            const double v = a[(size_t)j * 2 * n + n + i];   // transpose of the inverse
+            if (!(std::fabs(v) <= 65504.0)) return FQ_INVALID_ARG;
+            dst[(size_t)i * n + j] = (_Float16)v;
+        }
+    if (max_residual) {
+        double worst = 0.0;
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) {
+                double acc = 0.0;   // (P^T out)[i][j] = sum_k P[k][i] out[k][j]
+                for (int k = 0; k < n; ++k) acc += (double)src[(size_t)k * n + i] * (double)dst[(size_t)k * n + j];
+                worst = std::fmax(worst, std::fabs(acc - (i == j ? 1.0 : 0.0)));
+            }
+        *max_residual = worst;
+    }
     return FQ_OK;
 }
 

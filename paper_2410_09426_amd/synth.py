@@ -162,3 +162,17 @@ def generic(seed: int, T: int, n1: int, n2: int, *, sigma: float = 0.05, clip_mo
     P2 = near_identity(r, n2, sigma)
     clip = sigmoid_clip(r, T) if clip_mode == 1 else np.array([0.9], dtype=np.float32)
     return ActCase(f"generic_{n1}x{n2}_T{T}", T, n1, n2, x, P1, P2, clip, clip_mode)
+
+
+def weights(config_index: int, m: int, n: int, *, sigma: float = 0.02, heavy_frac: float = 0.002) -> np.ndarray:
+    """[m, n] fp16 weight matrix of a linear layer: N(0, sigma^2) with a few heavier input channels (x8)."""
+    r = _rng(config_index, 7)
+    w = r.standard_normal((m, n), dtype=np.float32) * np.float32(sigma)
+    k = max(1, int(round(heavy_frac * n)))
+    w[:, r.choice(n, size=k, replace=False)] *= np.float32(8.0)
+    return w.astype(np.float16)
+
+
+def weight_clip(config_index: int, m: int) -> np.ndarray:
+    """Per-output-channel weight clipping ratios in (0.85, 1) (fp32 [m])."""
+    return _rng(config_index, 8).uniform(0.85, 1.0, size=m).astype(np.float32)

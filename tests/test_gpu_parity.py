@@ -241,3 +241,53 @@ def test_stream_probe_moves_every_byte_once(T, n, pad):
     v = x[:, :n]
     want = v[:, :q] ^ v[:, q:2 * q] ^ v[:, 2 * q:3 * q] ^ v[:, 3 * q:]
     assert np.array_equal(got[64:-64].view(np.uint16).reshape(T, q), want)
+
+
+# ---- weight side of Eq. (2) and the whole quantized layer ----------------------------------------------------------
+def _layer_case(T, m, n1, n2, config_index, seed):
+    c = synth.generic(seed, T, n1, n2, sigma=0.05, clip_mode=1)
+    W = synth.weights(config_index, m, n1 * n2)
+    cw = synth.weight_clip(config_index, m)
+    A1, r1 = fq.fq_inverse_transpose(c.P1)
+    A2, r2 = fq.fq_inverse_transpose(c.P2)
+    print(f"[layer] T={T} m={m} {n1}x{n2}: inverse residuals {r1:.2e} {r2:.2e}", flush=True)
+    return c, W, cw, A1, A2
+
+
+@pytest.mark.parametrize("T,m,n1,n2", [(96, 300, 64, 64), (40, 130, 32, 64), (33, 70, 86, 128)])
+def test_weight_side_parity_and_quantized_layer(T, m, n1, n2):
+    """Right factor of Eq. (2) through the C ABI against the oracle (same fp16 inverse-transposed factors on both
+    sides), then the product of the two de-quantized factors against X W^T."""
+    n = n1 * n2
+    c, W, cw, A1, A2 = _layer_case(T, m, n1, n2, 9, 700 + n1)
+    Wd, A1d, A2d, cwd = dev(W), dev(A1), dev(A2), dev(cw)
+    wcodes = torch.full((m, n // 2), 0xCD, dtype=torch.uint8, device="cuda")
+    wsc = torch.full((m,), -1.0, dtype=torch.float16, device="cuda")
+    fq.flatquant_weight_transform_quant(Wd, A1d, A2d, cwd, 1, m, n1, n2, n, wcodes, wsc, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    yw = fo.weight_transform_factored(W, A1, A2)
+    rep = parity.check_sym(yw, cw, wcodes.cpu().numpy(), wsc.cpu().numpy().view(np.float16))
+    print(f"[parity] weight side {n1}x{n2}: {rep}", flush=True)
+    assert rep["band_flips"] <= max(4, rep["in_band"])
+
+    # activation side, then the layer: deq(Q(XP)) deq(Q(P^-1 W^T)) vs X W^T
+    xcodes, xsc, xcodes_d, xsc_d = run_tq(dev(c.x), dev(c.P1), dev(c.P2), dev(c.clip), 1, n1, n2)
+    xq = run_dequant(xcodes_d, xsc_d, None, T, n).astype(np.float64)
+    wq = run_dequant(wcodes, wsc, None, m, n).astype(np.float64)
+    Yq = xq @ wq.T
+    Y = c.x.astype(np.float64) @ W.astype(np.float64).T
+    # oracle's quantized layer from the oracle's own codes: the two must agree up to the in-band code differences
+    ox = fo.transform_quant(c.x, c.P1, c.P2, c.clip)
+    ow = fo.weight_transform_quant(W, A1, A2, cw)
+    Yo = fo.quantized_linear(ox["codes"], ox["scales"], ow["codes"], ow["scales"])
+    sx, sw = fo.as_f64(ox["scales"]), fo.as_f64(ow["scales"])
+    flips_x = (fo.unpack_nibbles(xcodes, True) != ox["q"]).sum(1)
+    flips_w = (fo.unpack_nibbles(wcodes.cpu().numpy(), True) != ow["q"]).sum(1)
+    # a flipped code moves one factor by one step: |dY| <= flips_x s_x max|w^| + flips_w s_w max|x^| (+ product term)
+    slack = (flips_x[:, None] * sx[:, None] * 8 * sw[None, :] + flips_w[None, :] * sw[None, :] * 8 * sx[:, None]) + 1e-6 * np.abs(Yo) + 1e-9
+    assert np.all(np.abs(Yq - Yo) <= slack), float(np.abs(Yq - Yo).max())
+    # how good W4A4 is with these untrained, random transforms is not a property of the kernels: reported only
+    rel, rel_o = np.linalg.norm(Yq - Y) / np.linalg.norm(Y), np.linalg.norm(Yo - Y) / np.linalg.norm(Y)
+    print(f"[layer] {n1}x{n2}: relative error of the W4A4 layer output {rel:.4f} (oracle's codes: {rel_o:.4f}); "
+          f"code flips x {int(flips_x.sum())} w {int(flips_w.sum())}", flush=True)
+    assert abs(rel - rel_o) <= 1e-3 * max(rel_o, 1e-6) + 1e-6 * (int(flips_x.sum()) + int(flips_w.sum()) + 1)

@@ -101,3 +101,28 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(fq, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libflatquant.so"))
     with pytest.raises(FileNotFoundError):
         fq.lib()
+
+
+def test_inverse_transpose_helper_against_numpy():
+    """Host Gauss-Jordan of the library against numpy's LU inverse (an independent routine) and the defining property."""
+    import numpy as np
+    r = np.random.Generator(np.random.PCG64(4242))
+    for n in (1, 2, 7, 64, 128, 256):
+        P = (np.eye(n) + 0.05 * r.standard_normal((n, n))).astype(np.float16)
+        out, res = fq.fq_inverse_transpose(P)
+        want = np.linalg.inv(P.astype(np.float64)).T
+        assert out.dtype == np.float16 and out.shape == (n, n)
+        assert np.array_equal(out, want.astype(np.float16)) or np.abs(out.astype(np.float64) - want).max() <= 2.0 ** -11 * np.abs(want).max()
+        assert res <= 2.0 ** -10 * n * np.abs(want).max() * np.abs(P.astype(np.float64)).max()
+        assert abs(res - np.abs(P.astype(np.float64).T @ out.astype(np.float64) - np.eye(n)).max()) < 1e-12
+    # a matrix that needs row exchanges
+    P = np.array([[0, 1, 0], [0, 0, 2], [4, 0, 0]], dtype=np.float16)
+    out, res = fq.fq_inverse_transpose(P)
+    assert np.array_equal(out, np.linalg.inv(P.astype(np.float64)).T.astype(np.float16)) and res == 0.0
+    with pytest.raises(fq.FlatQuantError):
+        fq.fq_inverse_transpose(np.ones((4, 4), dtype=np.float16))       # singular
+    with pytest.raises(fq.FlatQuantError):
+        fq.fq_inverse_transpose(np.zeros((3, 3), dtype=np.float16))
+    assert fq.lib().fq_inverse_transpose(None, 4, None, None) == fq.FQ_INVALID_ARG
+    assert fq.flatquant_weight_transform_quant(None, None, None, None, 0, 0, 64, 64, 4096, None, None, check=False) == fq.FQ_OK
+    assert fq.flatquant_weight_transform_quant(None, None, None, None, 0, 5, 64, 64, 4096, None, None, check=False) == fq.FQ_INVALID_ARG
