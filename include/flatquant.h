@@ -50,6 +50,9 @@ enum {
  *              Alignment: 4 bytes (base and row pitch, i.e. x_stride even).
  *   P1         fp16 [n1, n1] row-major, NOT transposed (the kernel applies P1^T).
  *   P2         fp16 [n2, n2] row-major.
+ *              Either may be NULL and then stands for the identity: the one-sided transforms of Sec. 3.2, e.g. the
+ *              online part of P_o once its per-head factor is fused into the value projection (n1 = heads, n2 =
+ *              head_dim, P2 = NULL).  Both NULL gives plain per-token INT4 quantization of x.
  *   clip       fp32; clip_mode 0: one value shared by all tokens (the paper's
  *              layer-wise threshold); clip_mode 1: T values, one per token.
  *              Values are the thresholds after the sigmoid, expected in (0, 1].

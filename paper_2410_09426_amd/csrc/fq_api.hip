@@ -54,7 +54,7 @@ fq_status flatquant_transform_quant(const void* x, const void* P1, const void* P
     if (n % 2 != 0 || x_stride < n) return FQ_INVALID_ARG;
     if (!fq::tq_supported(n1, n2)) return FQ_UNSUPPORTED_SHAPE;
     if (T == 0) return FQ_OK;
-    if (!x || !P1 || !P2 || !clip || !out_codes || !out_scales) return FQ_INVALID_ARG;
+    if (!x || !clip || !out_codes || !out_scales) return FQ_INVALID_ARG;   // P1 / P2 may be null: identity
     if ((reinterpret_cast<uintptr_t>(x) & 3) || (x_stride & 1) || (reinterpret_cast<uintptr_t>(P1) & 1) ||
         (reinterpret_cast<uintptr_t>(P2) & 1) || (reinterpret_cast<uintptr_t>(clip) & 3) ||
         (reinterpret_cast<uintptr_t>(out_scales) & 1))

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(64 * B) void tq_kernel(TqDev p) {
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             const int j = 16 * kb + 8 * h + s;
-            p2f[kb][s] = (j < n2 && jp < n2) ? p.P2[j * n2 + jp] : (_Float16)0;
+            p2f[kb][s] = (j < n2 && jp < n2) ? (p.P2 ? p.P2[j * n2 + jp] : (_Float16)(j == jp ? 1.0f : 0.0f)) : (_Float16)0;
         }
     }
     // ---- one-off: P1 as B-operand fragments of the second contraction (lane <-> i'),
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(64 * B) void tq_kernel(TqDev p) {
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
                 const int i = 32 * (kk >> 1) + 8 * (2 * (kk & 1) + (s >> 2)) + 4 * hh + (s & 3);
-                f[s] = (i < n1 && ip < n1) ? p.P1[i * n1 + ip] : (_Float16)0;
+                f[s] = (i < n1 && ip < n1) ? (p.P1 ? p.P1[i * n1 + ip] : (_Float16)(i == ip ? 1.0f : 0.0f)) : (_Float16)0;
             }
             *reinterpret_cast<half8*>(&P1s[e]) = f;
         }
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(64 * B) void tq_kernel(TqDev p) {
 #pragma unroll
                 for (int s = 0; s < 8; ++s) {
                     const int i = 32 * (kk >> 1) + 8 * (2 * (kk & 1) + (s >> 2)) + 4 * h + (s & 3);
-                    p1f[It][kk][s] = (i < n1 && ip < n1) ? p.P1[i * n1 + ip] : (_Float16)0;
+                    p1f[It][kk][s] = (i < n1 && ip < n1) ? (p.P1 ? p.P1[i * n1 + ip] : (_Float16)(i == ip ? 1.0f : 0.0f)) : (_Float16)0;
                 }
             }
     }

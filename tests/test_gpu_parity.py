@@ -291,3 +291,22 @@ def test_weight_side_parity_and_quantized_layer(T, m, n1, n2):
     print(f"[layer] {n1}x{n2}: relative error of the W4A4 layer output {rel:.4f} (oracle's codes: {rel_o:.4f}); "
           f"code flips x {int(flips_x.sum())} w {int(flips_w.sum())}", flush=True)
     assert abs(rel - rel_o) <= 1e-3 * max(rel_o, 1e-6) + 1e-6 * (int(flips_x.sum()) + int(flips_w.sum()) + 1)
+
+
+# ---- one-sided transforms (a factor left out = identity) ------------------------------------------------------------
+@pytest.mark.parametrize("n1,n2,T,which", [(32, 128, 200, "P1 only"), (32, 128, 3000, "P1 only"), (64, 64, 2048, "P1 only"),
+                                           (64, 64, 70, "P2 only"), (86, 128, 37, "P2 only"), (64, 64, 50, "none"),
+                                           (33, 34, 21, "P1 only"), (6, 10, 9, "P2 only")])
+def test_one_sided_transforms(n1, n2, T, which):
+    """P_o's online part is the left factor alone (heads x heads, Sec. 3.2): a null factor must act as the identity."""
+    c = synth.generic(800 + n1 + n2, T, n1, n2)
+    use1, use2 = which in ("P1 only",), which in ("P2 only",)
+    P1 = c.P1 if use1 else np.eye(n1, dtype=np.float16)
+    P2 = c.P2 if use2 else np.eye(n2, dtype=np.float16)
+    print(f"[case] one-sided {which} {n1}x{n2} T={T}", flush=True)
+    codes, scales, _, _ = run_tq(dev(c.x), dev(c.P1) if use1 else None, dev(c.P2) if use2 else None, dev(c.clip), c.clip_mode, n1, n2)
+    rows = subset_rows(T, 200, 31)
+    y = fo.affine_transform(c.x[rows], P1, P2)
+    rep = parity.check_sym(y, c.clip[rows], codes[rows], scales[rows], rows=rows)
+    print(f"[parity] one-sided {which}: {rep}", flush=True)
+    assert rep["band_flips"] <= max(4, rep["in_band"])
