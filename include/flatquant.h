@@ -89,6 +89,16 @@ fq_status flatquant_kv_transform_quant(const void* kv, const void* P, int Hp, fl
                                        void* stream);
 
 /*
+ * Per-head transform with fp16 output (Sec. 3.2 "Self-Attention": P_h acts head by head and is not decomposed;
+ * queries stay in FP16).  out[t, h, :] = fp16( x[t, h, :] P_h ), fp32 accumulation, one rounding.  With the key cache
+ * stored as Q(K P_h) the scores are kept by feeding the queries through this call with P = (P_h^-1)^T
+ * (fq_inverse_transpose, head by head).
+ *   x, out  fp16 [T, H, D] contiguous, 16-byte aligned, not overlapping.  D must be 128.
+ *   P       fp16 [Hp, D, D] row-major, Hp == 1 or Hp == H.
+ */
+fq_status flatquant_head_transform(const void* x, const void* P, int Hp, int64_t T, int H, int D, void* out, void* stream);
+
+/*
  * Weight side of the same layer (Eq. (2), right factor; Sec. 4.1 "Quantization": per-channel symmetric weights):
  *     Q( P1^-1 x_1 W~ x_2 (P2^-1)^T )   ==   Q( W (P1 (x) P2)^-T ),   one step per output channel.
  * Row o of W (width n = n1*n2, reshaped row-major to n1 x n2) becomes A1^T W~_o A2 with A1 = (P1^-1)^T and

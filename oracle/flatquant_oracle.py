@@ -162,6 +162,12 @@ def kv_transform(kv, P) -> np.ndarray:
     return y
 
 
+def head_transform_fp16(x, P) -> np.ndarray:
+    """Transform only, kept in FP16 (Sec. 3.2: queries are not quantized):
+    fp16(x[t, h, :] P_h), one rounding of the fp64 product."""
+    return round_to_fp16(kv_transform(x, P))
+
+
 def kv_scale_zero(y, clip):
     """Per group (last axis): mx = max(y, 0), mn = min(y, 0) scaled by alpha;
     step s = fp16((mx - mn) / 15); zero point z = round(-mn / s) in [0, 15].

@@ -101,6 +101,25 @@ fq_status flatquant_kv_transform_quant(const void* kv, const void* P, int Hp, fl
     return fq::finish(fq::kv_launch(a, static_cast<hipStream_t>(stream)));
 }
 
+fq_status flatquant_head_transform(const void* x, const void* P, int Hp, int64_t T, int H, int D, void* out, void* stream) {
+    if (T < 0 || H < 1 || D < 1) return FQ_INVALID_ARG;
+    if (Hp != 1 && Hp != H) return FQ_INVALID_ARG;
+    if (D != 128 || H > 65535) return FQ_UNSUPPORTED_SHAPE;
+    if (T == 0) return FQ_OK;
+    if (!x || !P || !out) return FQ_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(out) & 15) || (reinterpret_cast<uintptr_t>(P) & 1))
+        return FQ_MISALIGNED;
+    const int64_t bytes = T * H * D * 2;
+    if (fq::overlap(x, bytes, out, bytes)) return FQ_INVALID_ARG;
+    fq::KvArgs a;
+    a.kv = static_cast<const _Float16*>(x);
+    a.P = static_cast<const _Float16*>(P);
+    a.Hp = Hp; a.clip = 1.0f; a.T = T; a.H = H; a.D = D;
+    a.out_codes = static_cast<uint8_t*>(out); a.out_scales = nullptr; a.out_zeros = nullptr;
+    a.fp16_out = true;
+    return fq::finish(fq::kv_launch(a, static_cast<hipStream_t>(stream)));
+}
+
 fq_status flatquant_dequant(const uint8_t* codes, const void* scales, const void* zeros, int64_t rows, int n, float* out,
                             void* stream) {
     if (rows < 0 || n < 2 || (n & 1)) return FQ_INVALID_ARG;

@@ -61,6 +61,7 @@ struct KvArgs {
     uint8_t* out_codes;
     _Float16* out_scales;
     _Float16* out_zeros;
+    bool fp16_out = false;   // transform only: out_codes points at an fp16 [T, H, D] tensor, no steps / zero points
 };
 hipError_t kv_launch(const KvArgs& a, hipStream_t stream);
 

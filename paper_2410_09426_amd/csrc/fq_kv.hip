@@ -61,6 +61,10 @@ constexpr int KV_FLAT_ROWS = KV_D / 2;                        // P_h is re-laid 
 constexpr int KV_FLAT_BYTES = KV_FLAT_ROWS * (KV_D + 8) * 2;  // row-major, padded pitch, while fragments are built
 constexpr int KV_STAGE_BYTES = KV_WAVES * 32 * KV_STAGE_PITCH;
 constexpr int KV_LDS_BYTES = KV_FRAG_BYTES + (KV_FLAT_BYTES > KV_STAGE_BYTES ? KV_FLAT_BYTES : KV_STAGE_BYTES);
+// transform-only mode (fp16 out): the staged rows are 256 bytes wide
+constexpr int KV_OUT_PITCH = 2 * KV_D + 16;
+constexpr int KV_OUT_STAGE_BYTES = KV_WAVES * 32 * KV_OUT_PITCH;
+constexpr int KV_OUT_LDS_BYTES = KV_FRAG_BYTES + (KV_FLAT_BYTES > KV_OUT_STAGE_BYTES ? KV_FLAT_BYTES : KV_OUT_STAGE_BYTES);
 
 struct KvDev {
     const _Float16* kv;
@@ -73,6 +77,9 @@ struct KvDev {
     float clip;
 };
 
+// QUANT: asymmetric INT4 codes + step + zero point per group.  !QUANT: the transformed rows themselves, rounded to
+// fp16 (p.out_codes then points at an fp16 [T, H, D] tensor): the query side of a transformed key cache.
+template <bool QUANT>
 __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void kv_kernel(KvDev p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     u32x4* Pf = reinterpret_cast<u32x4*>(smem);                               // fragment table
@@ -142,7 +149,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
     }
     __syncthreads();   // fragments ready; the flat copy's space becomes the stage buffers
 
-    uint8_t* stage = stage_all + w * 32 * KV_STAGE_PITCH;
+    uint8_t* stage = stage_all + w * 32 * (QUANT ? KV_STAGE_PITCH : KV_OUT_PITCH);
     const float clip = p.clip;
 
     // one step: 32 tokens whose rows are in `rows`; the rows of the next step are requested into `far`
@@ -163,6 +170,32 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
                 const half8 a = *reinterpret_cast<const half8*>(&Pf[(mt * KV_KB + kb) * 64 + l]);
                 acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[mt], 0, 0, 0);
             }
+        }
+        if constexpr (!QUANT) {
+            // fp16 rows: a lane holds runs of 4 consecutive channels of its token -> 8-byte LDS writes, then whole
+            // 256-byte rows leave with 16-byte stores (lane -> row l/16 + 4k, chunk l%16)
+            typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+            uint8_t* srow = stage + c * KV_OUT_PITCH;
+#pragma unroll
+            for (int mt = 0; mt < KV_MT; ++mt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const half4 v = {(_Float16)acc[mt][4 * g], (_Float16)acc[mt][4 * g + 1], (_Float16)acc[mt][4 * g + 2], (_Float16)acc[mt][4 * g + 3]};
+                    *reinterpret_cast<half4*>(srow + 2 * (32 * mt + 8 * g + 4 * h)) = v;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int64_t g0 = first_group(blk);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int r = (l >> 4) + 4 * k, ch = l & 15;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * KV_OUT_PITCH + 16 * ch);
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.out_codes + g0 * (2 * KV_D)) + (size_t)group_ofs(blk, r) * (KV_D / 8) + ch);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            return;
         }
         // ---- group range (always containing 0): in-lane over 64 values, then the other half-wave's 64
         float mx = 0.0f, mn = 0.0f;
@@ -231,13 +264,15 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
     }
 }
 
-hipError_t kv_launch(const KvArgs& a, hipStream_t stream) {
+template <bool QUANT>
+static hipError_t kv_launch_mode(const KvArgs& a, hipStream_t stream) {
+    constexpr int LDS = QUANT ? KV_LDS_BYTES : KV_OUT_LDS_BYTES;
     static int wg_per_cu = 0;   // computed once per process (benign race: same value)
     if (wg_per_cu == 0) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kv_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, KV_LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kv_kernel<QUANT>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         if (e != hipSuccess) return e;
         int nb = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kv_kernel, KV_NT, KV_LDS_BYTES);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kv_kernel<QUANT>, KV_NT, LDS);
         if (e != hipSuccess) return e;
         if (nb < 1) return hipErrorLaunchOutOfResources;
         wg_per_cu = nb;
@@ -254,8 +289,12 @@ hipError_t kv_launch(const KvArgs& a, hipStream_t stream) {
     KvDev d;
     d.kv = a.kv; d.P = a.P; d.out_codes = a.out_codes; d.out_scales = a.out_scales; d.out_zeros = a.out_zeros;
     d.T = a.T; d.H = a.H; d.Hp = a.Hp; d.clip = a.clip;
-    hipLaunchKernelGGL(kv_kernel, dim3((unsigned)gx, (unsigned)a.H), dim3(KV_NT), KV_LDS_BYTES, stream, d);
+    hipLaunchKernelGGL(kv_kernel<QUANT>, dim3((unsigned)gx, (unsigned)a.H), dim3(KV_NT), LDS, stream, d);
     return hipGetLastError();
+}
+
+hipError_t kv_launch(const KvArgs& a, hipStream_t stream) {
+    return a.fp16_out ? kv_launch_mode<false>(a, stream) : kv_launch_mode<true>(a, stream);
 }
 
 }  // namespace fq

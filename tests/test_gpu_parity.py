@@ -310,3 +310,31 @@ def test_one_sided_transforms(n1, n2, T, which):
     rep = parity.check_sym(y, c.clip[rows], codes[rows], scales[rows], rows=rows)
     print(f"[parity] one-sided {which}: {rep}", flush=True)
     assert rep["band_flips"] <= max(4, rep["in_band"])
+
+
+@pytest.mark.parametrize("T,H,shared", [(4096, 8, False), (1, 8, False), (77, 3, False), (200, 8, True)])
+def test_head_transform_fp16_out(T, H, shared):
+    """Query side of a transformed key cache: fp16(x P_h) against the oracle's single rounding of the fp64 product.
+    Tolerance from the arithmetic: fp32 accumulation of 128 exact fp16 products (<= 128 * 2^-24 of the sum of their
+    magnitudes) plus one fp16 rounding (2^-11 relative, + 2^-25 in the subnormal range)."""
+    D = 128
+    c = synth.kv_cache(T, H, D)
+    Pq = np.stack([fq.fq_inverse_transpose(c.P[h])[0] for h in range(H)])
+    if shared:
+        Pq = Pq[:1]
+    xd, Pd = dev(c.k), dev(Pq)
+    out = torch.full((T * H * D + 64,), float("nan"), dtype=torch.float16, device="cuda")
+    fq.flatquant_head_transform(xd, Pd, Pq.shape[0], T, H, D, out, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    got = out.cpu().view(torch.int16).numpy().view(np.float16)
+    assert np.all(np.isnan(got[T * H * D:]))
+    got = got[:T * H * D].reshape(T, H, D).astype(np.float64)
+    rows = subset_rows(T, 256, 41)
+    y = fo.kv_transform(c.k[rows], Pq)
+    mag = np.einsum("thd,hde->the", np.abs(c.k[rows].astype(np.float64)), np.abs(np.broadcast_to(Pq, (H, D, D)).astype(np.float64)))
+    tol = 2.0 ** -11 * np.abs(y) * (1 + 2.0 ** -10) + 128 * 2.0 ** -24 * mag + 2.0 ** -25
+    err = np.abs(got[rows] - y)
+    assert np.all(err <= tol), float((err / tol).max())
+    exact = (got[rows] == fo.head_transform_fp16(c.k[rows], Pq).astype(np.float64)).mean()
+    print(f"[parity] head transform T={T} H={H}: max err/tol {float((err / tol).max()):.3f}, identical to the oracle's fp16 in {exact * 100:.2f} % of elements", flush=True)
+    assert exact > 0.97

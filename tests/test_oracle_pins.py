@@ -425,3 +425,19 @@ def test_quantized_layer_error_is_within_the_rounding_bound():
     # per-output-channel steps: a row's codes do not depend on the other rows
     one = fo.weight_transform_quant(W[3:4], fo.inverse_transpose(P1), fo.inverse_transpose(P2), 1.0)
     assert np.array_equal(one["codes"][0], aw["codes"][3]) and one["scales"][0] == aw["scales"][3]
+
+
+def test_query_side_transform_keeps_attention_scores():
+    """Sec. 3.2: with keys stored as K P_h, queries through (P_h^-1)^T leave Q K^T unchanged (textbook identity,
+    checked head by head against the untransformed scores); also pins kv_transform's head indexing."""
+    r = rng(640)
+    T, H, D = 5, 3, 8
+    Q, K = rand_fp16(r, (T, H, D)), rand_fp16(r, (T, H, D))
+    P = np.stack([_invertible(r, D) for _ in range(H)])
+    Pq = np.stack([fo.inverse_transpose(P[h]) for h in range(H)])
+    Kt, Qt = fo.kv_transform(K, P), fo.kv_transform(Q, Pq)
+    for h in range(H):
+        want = Q[:, h, :].astype(np.float64) @ K[:, h, :].astype(np.float64).T
+        assert np.allclose(Qt[:, h, :] @ Kt[:, h, :].T, want, atol=1e-9)
+    out = fo.head_transform_fp16(Q, Pq)
+    assert out.dtype == np.float16 and np.all(np.abs(out.astype(np.float64) - Qt) <= 2.0 ** -11 * np.abs(Qt) + 2.0 ** -25)
