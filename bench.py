@@ -153,7 +153,7 @@ def main() -> int:
     if not args.no_extras:
         extras = {}
 
-        def time_shape(name, Tn, a, b, steps, warmup, cold_sets=1):
+        def time_shape(name, Tn, a, b, steps, warmup, cold_sets=1, use_p1=True, use_p2=True):
             nn = a * b
             g = torch.Generator(device="cuda").manual_seed(1234 + nn)
             col = torch.ones(nn, device="cuda")
@@ -175,7 +175,7 @@ def main() -> int:
 
             def st(i):
                 k = i % cold_sets
-                fq.flatquant_transform_quant(xsets[k], p1, p2, cl, 1, Tn, a, b, nn, oc[k], os_[k], stream=stream)
+                fq.flatquant_transform_quant(xsets[k], p1 if use_p1 else None, p2 if use_p2 else None, cl, 1, Tn, a, b, nn, oc[k], os_[k], stream=stream)
             ms = float(np.median([time_region(st, steps, warmup if r == 0 else 1)[0] for r in range(5)]))   # median of 5 repetitions
             by = Tn * alg_bytes_per_token(nn)
             pad32 = 32 * ((a + 31) // 32)
@@ -189,6 +189,8 @@ def main() -> int:
         time_shape("decode_4096", 64, 64, 64, 500, 50)
         time_shape("decode_11008", 64, 86, 128, 500, 50)
         time_shape("prefill_70b_8192", 16384, 64, 128, 20, 4, cold_sets=4)
+        # online part of P_o for LLaMA-2-7B: 32 heads x 128, left factor only (the per-head factor is fused offline)
+        time_shape("p_o_left_only_32x128", 2048, 32, 128, 200, 20, cold_sets=60, use_p2=False)
         if not args.no_wide:
             time_shape("prefill_70b_28672", 16384, 112, 256, 5, 1, cold_sets=1)
 
@@ -208,7 +210,16 @@ def main() -> int:
         by = Tk * H * (2 * D + D // 2 + 4)
         extras["kv_cache"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms * 1e3, "groups_per_s": Tk * H / (ms * 1e-3),
                               "gbs": by / (ms * 1e-3) / 1e9, "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
-        del kvsets, kc, ks, kz
+        # query side: per-head transform, fp16 out (same tensors, 2 x 2D bytes per group)
+        qo = [torch.empty((Tk, H, D), dtype=torch.float16, device="cuda") for _ in range(4)]
+
+        def st_q(i):
+            fq.flatquant_head_transform(kvsets[i % 8], Pk, H, Tk, H, D, qo[i % 4], stream=stream)
+        ms = float(np.median([time_region(st_q, 40, 8 if r == 0 else 1)[0] for r in range(5)]))
+        by = Tk * H * 4 * D
+        extras["head_transform_fp16"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms * 1e3, "gbs": by / (ms * 1e-3) / 1e9,
+                                         "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del kvsets, kc, ks, kz, qo
         out["extras"] = extras
 
     # ------------------------------------------------------------------ CPU oracle: baseline timing + parity of the timed buffers

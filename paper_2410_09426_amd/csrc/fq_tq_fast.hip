@@ -85,17 +85,6 @@ __device__ __forceinline__ void split_hi_lo(const f32x16& acc, int base, half8& 
     lo = __builtin_bit_cast(half8, l);
 }
 
-// Elements f0 .. f0+NH-1 of a flat, row-major n x n identity matrix as packed fp16 (element idx is 1 iff idx % (n+1) == 0):
-// what the staging loads put in place of a transform that the caller left out (null pointer).
-template <typename V>
-__device__ __forceinline__ V identity_chunk(int f0, int n) {
-    constexpr int NH = sizeof(V) / 2;
-    _Float16 e[NH];
-#pragma unroll
-    for (int k = 0; k < NH; ++k) e[k] = ((f0 + k) % (n + 1) == 0) ? (_Float16)1.0f : (_Float16)0.0f;
-    return __builtin_bit_cast(V, e);
-}
-
 // (a << sh) + b in one instruction (the compiler otherwise re-associates the nibble chain into more operations)
 __device__ __forceinline__ uint32_t lshl_add(uint32_t a, int sh, uint32_t b) {
     uint32_t r;
@@ -185,9 +174,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
                 for (int k = 0; k < BATCH; ++k) {
                     const int idx = base + k * NT + tid;
-                    const int ic = idx < count ? idx : count - 1;
-                    if (p.P1) v[k] = src[ic];
-                    else v[k] = identity_chunk<decltype(*src + 0)>(ic * (int)(sizeof(v[k]) / 2), n1);
+                    v[k] = src[idx < count ? idx : count - 1];
                 }
                 if (base == 0) {
                     __builtin_amdgcn_sched_barrier(0);
@@ -204,7 +191,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         if ((reinterpret_cast<uintptr_t>(p.P1) & 15) == 0) {   // bulk in 16-byte chunks, then up to 7 single elements
             const int done = n1sq & ~7;
             const int ti = done + tid < n1sq ? done + tid : n1sq - 1;
-            const _Float16 tail = p.P1 ? p.P1[ti] : (_Float16)(ti % (n1 + 1) == 0 ? 1.0f : 0.0f);
+            const _Float16 tail = p.P1[ti];
             copy_batched(reinterpret_cast<u32x4*>(P1flat), reinterpret_cast<const u32x4*>(p.P1), n1sq >> 3);
             if (done + tid < n1sq) P1flat[ti] = tail;
         } else {   // only 4-byte aligned: pairs, plus a last odd element
@@ -221,10 +208,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         const u32x4* src = reinterpret_cast<const u32x4*>(p.P2) + pass * CH;
         u32x4 v2[CH / NT];
 #pragma unroll
-        for (int k = 0; k < CH / NT; ++k) {
-            if (p.P2) v2[k] = src[tid + k * NT];
-            else v2[k] = identity_chunk<u32x4>((pass * CH + tid + k * NT) * 8, N2);
-        }
+        for (int k = 0; k < CH / NT; ++k) v2[k] = src[tid + k * NT];
         if (pass == 0) {
             // P1's loads queue behind P2's: one latency for both.  The second token row is requested behind them, so
             // it is in flight during the whole prologue without delaying the transforms (loads return in order).
@@ -573,6 +557,7 @@ static Variant variant(int A, int B, bool full1, int mode) {
 
 bool tq_fast_applicable(const TqDev& d) {
     if (d.n2 % 32 != 0 || !d.vec8 || !d.out_vec16) return false;
+    if (!d.P1 || !d.P2) return false;   // a left-out factor (identity) is handled by the general kernel only
     if (reinterpret_cast<uintptr_t>(d.P2) & 15) return false;
     const int n1sq = d.n1 * d.n1;
     const uintptr_t a1 = reinterpret_cast<uintptr_t>(d.P1);
