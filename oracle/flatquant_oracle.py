@@ -27,6 +27,9 @@ What each function follows
   Q(P1^-1 x_1 W~ x_2 (P2^-1)^T), i.e. every weight row times (P1 (x) P2)^-T,
   with per-output-channel symmetric INT4 (Sec. 4.1 "Quantization") and the
   product of the two de-quantized factors that replaces X W^T (Eq. (1)).
+* w4a4_gemm                    : the same product computed the way low-bit
+  hardware does it (Sec. 3.2, Sec. 3.3): integer dot products of the codes,
+  scaled by the activation step of the row and the weight step of the column.
 
 Conventions fixed where the paper is silent (all listed in the design notes):
 row-major reshape (channel c = i * n2 + j); signed grid [-8, 7] with step
@@ -262,6 +265,17 @@ def weight_transform_quant(W, A1, A2, clip_w):
 def quantized_linear(codes_x, scales_x, codes_w, scales_w) -> np.ndarray:
     """deq(Q(XP)) deq(Q(P^-1 W^T)): [T, n/2] x [m, n/2] packed codes -> [T, m] fp64."""
     return dequantize(codes_x, scales_x) @ dequantize(codes_w, scales_w).T
+
+
+def w4a4_gemm(codes_x, scales_x, codes_w, scales_w):
+    """The low-bit matrix multiplication that consumes the two quantized factors of Eq. (2) (Sec. 3.2: "low-bit
+    matrix multiplications for all linear layers"): exact integer dot products of the 4-bit codes, then the two
+    steps.  Returns (acc int64 [T, m], y fp64 [T, m], y rounded once to fp16)."""
+    qx = unpack_nibbles(codes_x, signed=True).astype(np.int64)
+    qw = unpack_nibbles(codes_w, signed=True).astype(np.int64)
+    acc = qx @ qw.T
+    y = acc.astype(np.float64) * as_f64(scales_x).reshape(-1, 1) * as_f64(scales_w).reshape(1, -1)
+    return acc, y, round_to_fp16(y)
 
 
 def choose_factors(n: int):

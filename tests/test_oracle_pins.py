@@ -441,3 +441,28 @@ def test_query_side_transform_keeps_attention_scores():
         assert np.allclose(Qt[:, h, :] @ Kt[:, h, :].T, want, atol=1e-9)
     out = fo.head_transform_fp16(Q, Pq)
     assert out.dtype == np.float16 and np.all(np.abs(out.astype(np.float64) - Qt) <= 2.0 ** -11 * np.abs(Qt) + 2.0 ** -25)
+
+
+def test_w4a4_gemm_is_the_product_of_the_dequantized_factors():
+    """Integer dot products of codes times the two steps must equal deq(x) deq(w)^T (a different route through the
+    oracle: de-quantize first, multiply in floating point), and a brute-force loop over a tiny case with hand-set
+    codes pins nibble order and signedness."""
+    r = rng(650)
+    T, m, n = 7, 5, 64
+    qx = r.integers(-8, 8, size=(T, n)).astype(np.int8)
+    qw = r.integers(-8, 8, size=(m, n)).astype(np.int8)
+    sx = (r.uniform(0.01, 3.0, size=T)).astype(np.float16)
+    sw = (r.uniform(0.001, 0.1, size=m)).astype(np.float16)
+    cx, cw = fo.pack_nibbles(qx), fo.pack_nibbles(qw)
+    acc, y, y16 = fo.w4a4_gemm(cx, sx, cw, sw)
+    for t in range(T):
+        for o in range(m):
+            want = sum(int(qx[t, k]) * int(qw[o, k]) for k in range(n))
+            assert acc[t, o] == want
+            assert y[t, o] == pytest.approx(want * float(sx[t]) * float(sw[o]), rel=1e-15)
+    assert np.allclose(y, fo.quantized_linear(cx, sx, cw, sw), rtol=1e-12, atol=1e-300)
+    assert y16.dtype == np.float16 and np.all(np.abs(y16.astype(np.float64) - y) <= 2.0 ** -11 * np.abs(y) + 2.0 ** -25)
+    # hand-set bytes: 0x7F = codes (-1, 7), 0x80 = (0, -8)
+    one = fo.w4a4_gemm(np.array([[0x7F, 0x80]], dtype=np.uint8), np.array([2.0], dtype=np.float16),
+                       np.array([[0x21, 0x3F]], dtype=np.uint8), np.array([0.5], dtype=np.float16))
+    assert one[0][0, 0] == (-1) * 1 + 7 * 2 + 0 * (-1) + (-8) * 3 and one[1][0, 0] == -11.0
