@@ -115,6 +115,19 @@ fq_status flatquant_weight_transform_quant(const void* w, const void* A1, const 
                                            uint8_t* out_codes, void* out_scales, void* stream);
 
 /*
+ * W4A4 matrix product of the two quantized factors (Sec. 3.2: low-bit matrix multiplications for all linear layers;
+ * Eq. (1)-(2)):   out[t, o] = fp16( s_x[t] * s_w[o] * sum_k q_x[t, k] * q_w[o, k] ),
+ * exact integer accumulation (int8 MFMA on the widened codes), two fp32 multiplications, one rounding to fp16.
+ *   x_codes  u8 [T, n/2], x_scales fp16 [T]   : outputs of flatquant_transform_quant
+ *   w_codes  u8 [m, n/2], w_scales fp16 [m]   : outputs of flatquant_weight_transform_quant
+ *   out      fp16 [T, m], row t at out + t*out_stride halves, out_stride >= m.
+ * n must be a multiple of 256 (and <= 131072); code tensors 16-byte aligned.  T == 0 or m == 0 returns FQ_OK.
+ * Values beyond the fp16 range come out as infinities.
+ */
+fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, const uint8_t* w_codes, const void* w_scales,
+                              int64_t T, int m, int n, void* out, int64_t out_stride, void* stream);
+
+/*
  * De-quantization check helper (Sec. 2.1: W^ = s * Pi(W / s)).
  *   zeros == NULL : out[r, c] = s[r] * q[r, c]            (signed nibbles)
  *   zeros != NULL : out[r, c] = s[r] * (q[r, c] - z[r])   (unsigned nibbles)

@@ -18,7 +18,7 @@ FQ_OK, FQ_INVALID_ARG, FQ_UNSUPPORTED_SHAPE, FQ_MISALIGNED, FQ_LAUNCH_FAILED = r
 
 EXPORTS = (
     "flatquant_transform_quant", "flatquant_kv_transform_quant", "flatquant_dequant", "flatquant_stream_probe",
-    "flatquant_weight_transform_quant", "fq_inverse_transpose", "flatquant_head_transform",
+    "flatquant_weight_transform_quant", "fq_inverse_transpose", "flatquant_head_transform", "flatquant_w4a4_gemm",
     "fq_supported", "fq_choose_factors", "fq_default_design_fits", "fq_lds_bytes",
     "fq_status_string", "fq_last_hip_error", "fq_abi_version",
 )
@@ -50,6 +50,8 @@ def lib() -> ctypes.CDLL:
         L.flatquant_dequant.restype = i32
         L.flatquant_weight_transform_quant.argtypes = L.flatquant_transform_quant.argtypes
         L.flatquant_weight_transform_quant.restype = i32
+        L.flatquant_w4a4_gemm.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, i64, vp]
+        L.flatquant_w4a4_gemm.restype = i32
         L.flatquant_head_transform.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp]
         L.flatquant_head_transform.restype = i32
         L.fq_inverse_transpose.argtypes = [vp, i32, vp, ctypes.POINTER(ctypes.c_double)]
@@ -129,6 +131,15 @@ def flatquant_weight_transform_quant(w, A1, A2, clip, clip_mode: int, m: int, n1
                                                 int(n2), int(w_stride), _ptr(out_codes), _ptr(out_scales), _stream(stream))
     if check and st != FQ_OK:
         raise FlatQuantError(st, "flatquant_weight_transform_quant")
+    return st
+
+
+def flatquant_w4a4_gemm(x_codes, x_scales, w_codes, w_scales, T: int, m: int, n: int, out, out_stride: int,
+                        stream=None, check: bool = True) -> int:
+    st = lib().flatquant_w4a4_gemm(_ptr(x_codes), _ptr(x_scales), _ptr(w_codes), _ptr(w_scales), int(T), int(m), int(n),
+                                   _ptr(out), int(out_stride), _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_w4a4_gemm")
     return st
 
 

@@ -1,0 +1,163 @@
+// W4A4 matrix product for gfx950: out[t, o] = fp16( s_x[t] s_w[o] sum_k q_x[t, k] q_w[o, k] ), the low-bit matrix
+// multiplication that consumes the two quantized factors of Eq. (2) (Sec. 3.2: low-bit matrix multiplications for all
+// linear layers; Sec. 3.3: the transform + quantization kernel feeds an INT4 GEMM).
+//
+// Both operands arrive as packed 4-bit two's-complement codes, K contiguous (activations [T, n/2], weights [m, n/2]),
+// which is the operand order of an MFMA for C = A B^T.  The codes are widened to int8 on the fly without a sign
+// extension: for a packed dword w, (w << 4) & 0xF0F0F0F0 holds 16 q of the even channels and w & 0xF0F0F0F0 holds 16 q
+// of the odd channels, as signed bytes.  Both operands are widened the same way, so the K order inside an MFMA is
+// the same permutation for both and every product carries a factor 256 that the epilogue divides out exactly.
+// v_mfma_i32_32x32x32_i8 accumulates in int32 (|sum| <= 128 * 128 * n, n <= 131072).
+//
+// Workgroup: 4 waves, C tile 128 tokens x 128 output channels, each wave 64 x 64 (2 x 2 MFMA tiles).  K advances by
+// 256 codes (128 bytes = one cache line per row) per iteration through double-buffered LDS tiles; the next tiles are
+// requested into registers before the MFMAs of the current ones, one barrier per iteration.
+#include "fq_internal.h"
+
+namespace fq {
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int GT = 128;               // tile edge, tokens and output channels
+constexpr int GKB = 128;              // packed bytes of K per row and iteration (256 codes)
+constexpr int GPITCH = GKB + 16;      // LDS row pitch: 16-byte operand reads of 32 consecutive rows fall on distinct banks
+constexpr int G_NT = 256;
+constexpr int G_TILE_BYTES = GT * GPITCH;
+constexpr int G_LDS_BYTES = 4 * G_TILE_BYTES;   // A and B, two buffers each
+
+struct GemmDev {
+    const uint8_t* xc;
+    const _Float16* xs;
+    const uint8_t* wc;
+    const _Float16* ws;
+    _Float16* out;
+    int64_t T;
+    int64_t out_stride;
+    int m, n;
+};
+
+// two k-steps of MFMA operands from 16 packed bytes
+__device__ __forceinline__ void widen(const u32x4 w, i32x4& s0, i32x4& s1) {
+    constexpr unsigned M = 0xF0F0F0F0u;
+    s0 = i32x4{(int)((w[0] << 4) & M), (int)(w[0] & M), (int)((w[1] << 4) & M), (int)(w[1] & M)};
+    s1 = i32x4{(int)((w[2] << 4) & M), (int)(w[2] & M), (int)((w[3] << 4) & M), (int)(w[3] & M)};
+}
+
+__global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void w4a4_kernel(GemmDev p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int l = tid & 63, c = l & 31, h = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w & 1, wn = w >> 1;
+    const int64_t t0 = (int64_t)blockIdx.x * GT;
+    const int o0 = blockIdx.y * GT;
+    const int64_t kbytes = p.n / 2;
+    const int nk = p.n / (2 * GKB);
+
+    // tile loads: chunk q = tid + 256 k -> row q / 8, 16-byte chunk q % 8; rows past the end re-read the last row
+    const u32x4* asrc[4];
+    const u32x4* bsrc[4];
+    int ldst[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int q = tid + G_NT * k, row = q >> 3, ch = q & 7;
+        int64_t tr = t0 + row;
+        if (tr >= p.T) tr = p.T - 1;
+        int orow = o0 + row;
+        if (orow >= p.m) orow = p.m - 1;
+        asrc[k] = reinterpret_cast<const u32x4*>(p.xc + tr * kbytes) + ch;
+        bsrc[k] = reinterpret_cast<const u32x4*>(p.wc + (int64_t)orow * kbytes) + ch;
+        ldst[k] = row * GPITCH + ch * 16;
+    }
+    u32x4 ra[4], rb[4];
+    auto issue = [&](int it) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            ra[k] = asrc[k][it * (GKB / 16)];
+            rb[k] = bsrc[k][it * (GKB / 16)];
+        }
+    };
+    auto commit = [&](int buf) {
+        unsigned char* A = smem + buf * G_TILE_BYTES;
+        unsigned char* B = smem + (2 + buf) * G_TILE_BYTES;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            *reinterpret_cast<u32x4*>(A + ldst[k]) = ra[k];
+            *reinterpret_cast<u32x4*>(B + ldst[k]) = rb[k];
+        }
+    };
+
+    i32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    issue(0);
+    commit(0);
+    __syncthreads();
+    const int aoff = (64 * wm + c) * GPITCH + 16 * h;
+    const int boff = (64 * wn + c) * GPITCH + 16 * h;
+    for (int it = 0; it < nk; ++it) {
+        const int buf = it & 1;
+        if (it + 1 < nk) issue(it + 1);
+        const unsigned char* A = smem + buf * G_TILE_BYTES + aoff;
+        const unsigned char* B = smem + (2 + buf) * G_TILE_BYTES + boff;
+#pragma unroll
+        for (int kp = 0; kp < 4; ++kp) {
+            i32x4 a[2][2], b[2][2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                widen(*reinterpret_cast<const u32x4*>(A + 32 * i * GPITCH + 32 * kp), a[i][0], a[i][1]);
+                widen(*reinterpret_cast<const u32x4*>(B + 32 * i * GPITCH + 32 * kp), b[i][0], b[i][1]);
+            }
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][s], b[j][s], acc[i][j], 0, 0, 0);
+        }
+        if (it + 1 < nk) commit(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: lane <-> output channel, register r <-> token 8(r/4) + 4h + r%4 of the tile
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int o = o0 + 64 * wn + 32 * j + c;
+        const float sw = (o < p.m) ? (float)p.ws[o] : 0.0f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t t = t0 + 64 * wm + 32 * i + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (t < p.T && o < p.m) {
+                    const float sx = (float)p.xs[t];
+                    p.out[t * p.out_stride + o] = (_Float16)((float)(acc[i][j][r] >> 8) * sx * sw);   // sums are multiples of 256
+                }
+            }
+    }
+}
+
+hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
+    static bool configured = false;   // benign race: same call, same values
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(w4a4_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, G_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    GemmDev d;
+    d.xc = a.x_codes; d.xs = a.x_scales; d.wc = a.w_codes; d.ws = a.w_scales; d.out = a.out;
+    d.T = a.T; d.out_stride = a.out_stride; d.m = a.m; d.n = a.n;
+    const dim3 grid((unsigned)((a.T + GT - 1) / GT), (unsigned)((a.m + GT - 1) / GT));
+    hipLaunchKernelGGL(w4a4_kernel, grid, dim3(G_NT), G_LDS_BYTES, stream, d);
+    return hipGetLastError();
+}
+
+}  // namespace fq

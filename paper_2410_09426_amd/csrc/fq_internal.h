@@ -68,6 +68,19 @@ hipError_t kv_launch(const KvArgs& a, hipStream_t stream);
 hipError_t dequant_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,
                           int64_t rows, int n, float* out, hipStream_t stream);
 
+struct GemmArgs {
+    const uint8_t* x_codes;
+    const _Float16* x_scales;
+    const uint8_t* w_codes;
+    const _Float16* w_scales;
+    _Float16* out;
+    int64_t T;
+    int64_t out_stride;
+    int m, n;
+};
+// W4A4 matrix product of the two quantized factors (fq_gemm.hip).
+hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream);
+
 // Copy-like probe with the activation kernel's traffic (fq_probe.hip).
 hipError_t stream_probe_launch(const void* x, int64_t T, int n, int64_t x_stride, uint8_t* out, hipStream_t stream);
 

@@ -338,3 +338,35 @@ def test_head_transform_fp16_out(T, H, shared):
     exact = (got[rows] == fo.head_transform_fp16(c.k[rows], Pq).astype(np.float64)).mean()
     print(f"[parity] head transform T={T} H={H}: max err/tol {float((err / tol).max()):.3f}, identical to the oracle's fp16 in {exact * 100:.2f} % of elements", flush=True)
     assert exact > 0.97
+
+
+# ---- W4A4 matrix product ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("T,m,n,pad", [(300, 260, 512, 0), (128, 128, 256, 0), (1, 1, 256, 0), (2048, 384, 4096, 0), (77, 200, 11008, 24)])
+def test_w4a4_gemm(T, m, n, pad):
+    """Integer accumulation is exact, so the only freedom is the final rounding: two fp32 multiplications and one fp16
+    rounding against the oracle's single rounding of the fp64 value (2^-11 relative + two fp32 roundings)."""
+    r = np.random.Generator(np.random.PCG64(900 + T + m + n))
+    cx = r.integers(0, 256, size=(T, n // 2), dtype=np.uint8)
+    cw = r.integers(0, 256, size=(m, n // 2), dtype=np.uint8)
+    cx[0, :] = 0x88      # every code -8: the largest magnitude sums
+    cw[0, :] = 0x88
+    sx = r.uniform(0.01, 4.0, size=T).astype(np.float16)
+    sw = r.uniform(0.001, 0.2 * 256 / n, size=m).astype(np.float16)     # keeps 64 n s_x s_w inside the fp16 range
+    print(f"[case] w4a4 T={T} m={m} n={n}", flush=True)
+    out = torch.full((64 + T * (m + pad) + 64,), float("nan"), dtype=torch.float16, device="cuda")
+    fq.flatquant_w4a4_gemm(dev(cx), dev(sx), dev(cw), dev(sw), T, m, n, out[64:], m + pad, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    got = out.cpu().view(torch.int16).numpy().view(np.float16)
+    assert np.all(np.isnan(got[:64])) and np.all(np.isnan(got[64 + (T - 1) * (m + pad) + m:]))
+    body = got[64:64 + T * (m + pad)].reshape(T, m + pad)
+    if pad:
+        assert np.all(np.isnan(body[:, m:]))
+    dev_y = body[:, :m].astype(np.float64)
+    acc, y, y16 = fo.w4a4_gemm(cx, sx, cw, sw)
+    assert acc[0, 0] == 64 * n
+    tol = 2.0 ** -11 * np.abs(y) * (1 + 2.0 ** -9) + 2.0 ** -25
+    err = np.abs(dev_y - y)
+    assert np.all(err <= tol), float((err / tol).max())
+    same = float((body[:, :m] == y16).mean())
+    print(f"[parity] w4a4 T={T} m={m} n={n}: max err/tol {float((err / tol).max()):.3f}, identical to the oracle's fp16 in {same * 100:.3f} %", flush=True)
+    assert same > 0.99
