@@ -9,7 +9,8 @@
 // the same permutation for both and every product carries a factor 256 that the epilogue divides out exactly.
 // v_mfma_i32_32x32x32_i8 accumulates in int32 (|sum| <= 128 * 128 * n, n <= 131072).
 //
-// Workgroup: 4 waves, C tile 128 tokens x 128 output channels, each wave 64 x 64 (2 x 2 MFMA tiles).  K advances by
+// Workgroup: 4 waves, C tile 128 tokens x 128 output channels, each wave 64 x 64 (2 x 2 MFMA tiles; the weights are
+// the MFMA's first operand so that a lane ends up with runs of 4 consecutive output channels of one token).  K advances by
 // 256 codes (128 bytes = one cache line per row) per iteration through double-buffered LDS tiles; the next tiles are
 // requested into registers before the MFMAs of the current ones, one barrier per iteration.
 #include "fq_internal.h"
@@ -21,11 +22,14 @@ typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int GT = 128;               // tile edge, tokens and output channels
-constexpr int GKB = 128;              // packed bytes of K per row and iteration (256 codes)
+#ifndef FQ_GKB
+#define FQ_GKB 128
+#endif
+constexpr int GKB = FQ_GKB;              // packed bytes of K per row and iteration (256 codes)
 constexpr int GPITCH = GKB + 16;      // LDS row pitch: 16-byte operand reads of 32 consecutive rows fall on distinct banks
 constexpr int G_NT = 256;
 constexpr int G_TILE_BYTES = GT * GPITCH;
-constexpr int G_LDS_BYTES = 4 * G_TILE_BYTES;   // A and B, two buffers each
+constexpr int G_LDS_BYTES = 4 * G_TILE_BYTES + GT * 4;   // A and B, two buffers each, + the weight steps of the tile
 
 struct GemmDev {
     const uint8_t* xc;
@@ -56,13 +60,14 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     const int64_t kbytes = p.n / 2;
     const int nk = p.n / (2 * GKB);
 
-    // tile loads: chunk q = tid + 256 k -> row q / 8, 16-byte chunk q % 8; rows past the end re-read the last row
-    const u32x4* asrc[4];
-    const u32x4* bsrc[4];
-    int ldst[4];
+    // tile loads: chunk q = tid + 256 k -> row q / CPR, 16-byte chunk q % CPR; rows past the end re-read the last row
+    constexpr int CPR = GKB / 16, NLD = GT * CPR / G_NT;
+    const u32x4* asrc[NLD];
+    const u32x4* bsrc[NLD];
+    int ldst[NLD];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int q = tid + G_NT * k, row = q >> 3, ch = q & 7;
+    for (int k = 0; k < NLD; ++k) {
+        const int q = tid + G_NT * k, row = q / CPR, ch = q % CPR;
         int64_t tr = t0 + row;
         if (tr >= p.T) tr = p.T - 1;
         int orow = o0 + row;
@@ -71,10 +76,10 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
         bsrc[k] = reinterpret_cast<const u32x4*>(p.wc + (int64_t)orow * kbytes) + ch;
         ldst[k] = row * GPITCH + ch * 16;
     }
-    u32x4 ra[4], rb[4];
+    u32x4 ra[NLD], rb[NLD];
     auto issue = [&](int it) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < NLD; ++k) {
             ra[k] = asrc[k][it * (GKB / 16)];
             rb[k] = bsrc[k][it * (GKB / 16)];
         }
@@ -83,7 +88,7 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
         unsigned char* A = smem + buf * G_TILE_BYTES;
         unsigned char* B = smem + (2 + buf) * G_TILE_BYTES;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < NLD; ++k) {
             *reinterpret_cast<u32x4*>(A + ldst[k]) = ra[k];
             *reinterpret_cast<u32x4*>(B + ldst[k]) = rb[k];
         }
@@ -97,6 +102,10 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
+    if (tid < GT) {
+        const int o = o0 + tid;
+        reinterpret_cast<float*>(smem + 4 * G_TILE_BYTES)[tid] = (o < p.m) ? (float)p.ws[o] : 0.0f;
+    }
     issue(0);
     commit(0);
     __syncthreads();
@@ -108,7 +117,7 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
         const unsigned char* A = smem + buf * G_TILE_BYTES + aoff;
         const unsigned char* B = smem + (2 + buf) * G_TILE_BYTES + boff;
 #pragma unroll
-        for (int kp = 0; kp < 4; ++kp) {
+        for (int kp = 0; kp < GKB / 32; ++kp) {
             i32x4 a[2][2], b[2][2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
@@ -121,27 +130,53 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][s], b[j][s], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[j][s], a[i][s], acc[i][j], 0, 0, 0);
         }
         if (it + 1 < nk) commit(buf ^ 1);
         __syncthreads();
     }
 
-    // epilogue: lane <-> output channel, register r <-> token 8(r/4) + 4h + r%4 of the tile
+    // epilogue.  The weights are the MFMA's first operand, so in acc[i][j] a lane holds, for token 64 wm + 32 i + c,
+    // the output channels 64 wn + 32 j + 8 (r / 4) + 4 h + r % 4: runs of 4 consecutive channels.  They are scaled,
+    // rounded to fp16 and staged in LDS (the K tiles are dead by now) as a [128 tokens][128 channels] tile, which then
+    // leaves in whole 16-byte pieces.  Every sum is a multiple of 256 (both operands carry a factor 16).
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    constexpr int OPITCH = 2 * GT + 16;
+    unsigned char* otile = smem;
+    float* sws = reinterpret_cast<float*>(smem + 4 * G_TILE_BYTES);          // [128] weight steps of this tile
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int o = o0 + 64 * wn + 32 * j + c;
-        const float sw = (o < p.m) ? (float)p.ws[o] : 0.0f;
+    for (int i = 0; i < 2; ++i) {
+        const int64_t t = t0 + 64 * wm + 32 * i + c;
+        const float sx = (float)p.xs[t < p.T ? t : p.T - 1];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t t = t0 + 64 * wm + 32 * i + 8 * (r >> 2) + 4 * h + (r & 3);
-                if (t < p.T && o < p.m) {
-                    const float sx = (float)p.xs[t];
-                    p.out[t * p.out_stride + o] = (_Float16)((float)(acc[i][j][r] >> 8) * sx * sw);   // sums are multiples of 256
-                }
+            for (int g = 0; g < 4; ++g) {
+                const int oc = 64 * wn + 32 * j + 8 * g + 4 * h;
+                const float4 sw = *reinterpret_cast<const float4*>(sws + oc);
+                const half4 v = {(_Float16)((float)(acc[i][j][4 * g] >> 8) * sx * sw.x), (_Float16)((float)(acc[i][j][4 * g + 1] >> 8) * sx * sw.y),
+                                 (_Float16)((float)(acc[i][j][4 * g + 2] >> 8) * sx * sw.z), (_Float16)((float)(acc[i][j][4 * g + 3] >> 8) * sx * sw.w)};
+                *reinterpret_cast<half4*>(otile + (64 * wm + 32 * i + c) * OPITCH + 2 * oc) = v;
             }
+    }
+    __syncthreads();
+    const bool wide = ((reinterpret_cast<uintptr_t>(p.out) & 15) == 0) && (p.out_stride % 8 == 0);
+#pragma unroll
+    for (int k = 0; k < GT * 16 / G_NT; ++k) {
+        const int q = tid + G_NT * k, row = q >> 4, ch = q & 15;
+        const int64_t t = t0 + row;
+        const int o = o0 + 8 * ch;
+        if (t < p.T && o < p.m) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(otile + row * OPITCH + 16 * ch);
+            _Float16* dst = p.out + t * p.out_stride + o;
+            if (wide && o + 8 <= p.m) {
+                *reinterpret_cast<u32x4*>(dst) = v;
+            } else {
+                const _Float16* e = reinterpret_cast<const _Float16*>(&v);
+                for (int x = 0; x < 8; ++x)
+                    if (o + x < p.m) dst[x] = e[x];
+            }
+        }
     }
 }
 
