@@ -180,6 +180,91 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     }
 }
 
+// ---- few tokens (decode): the weights are read once and the kernel is bound by that stream.  A workgroup owns 32
+// output channels for all (<= 64) tokens; its 4 waves split K in interleaved units of 64 codes, each wave feeding
+// the MFMA straight from global memory (lane <-> weight row / token row, 16 bytes = two K steps), and the four partial
+// accumulators are added through LDS.
+template <int NTT>   // token tiles of 32
+__global__ __launch_bounds__(G_NT) void w4a4_decode_kernel(GemmDev p) {
+    __shared__ __attribute__((aligned(16))) i32x4 part[4 * NTT * 4 * 64];
+    const int tid = threadIdx.x;
+    const int l = tid & 63, c = l & 31, h = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int o0 = blockIdx.x * 32;
+    const int64_t kbytes = p.n / 2;
+    const int units = p.n / 64 / 4;            // units of 64 codes (32 bytes per row) per wave
+    int orow = o0 + c;
+    if (orow >= p.m) orow = p.m - 1;
+    const u32x4* wsrc = reinterpret_cast<const u32x4*>(p.wc + (int64_t)orow * kbytes) + 2 * w + h;
+    const u32x4* xsrc[NTT];
+#pragma unroll
+    for (int i = 0; i < NTT; ++i) {
+        int64_t t = 32 * i + c;
+        if (t >= p.T) t = p.T - 1;
+        xsrc[i] = reinterpret_cast<const u32x4*>(p.xc + t * kbytes) + 2 * w + h;
+    }
+    i32x16 acc[NTT];
+#pragma unroll
+    for (int i = 0; i < NTT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    constexpr int BATCH = 8;                   // units in flight per wave (the tail of a batch re-reads the last unit)
+    for (int u0 = 0; u0 < units; u0 += BATCH) {
+        u32x4 wv[BATCH], xv[BATCH][NTT];
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            const int u = (u0 + b < units) ? u0 + b : units - 1;
+            wv[b] = __builtin_nontemporal_load(wsrc + 8 * u);     // unit u of this wave: chunks 8u + 2w + h
+#pragma unroll
+            for (int i = 0; i < NTT; ++i) xv[b][i] = xsrc[i][8 * u];
+        }
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            if (u0 + b < units) {
+                i32x4 ws0, ws1;
+                widen(wv[b], ws0, ws1);
+#pragma unroll
+                for (int i = 0; i < NTT; ++i) {
+                    i32x4 xs0, xs1;
+                    widen(xv[b][i], xs0, xs1);
+                    acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws0, xs0, acc[i], 0, 0, 0);
+                    acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws1, xs1, acc[i], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // partial sums -> LDS as [wave][tile][quad g][lane] x 4 ints, then 4-way add, scale, round, 8-byte stores
+#pragma unroll
+    for (int i = 0; i < NTT; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            part[((w * NTT + i) * 4 + g) * 64 + l] = i32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
+    __syncthreads();
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    const bool wide = ((reinterpret_cast<uintptr_t>(p.out) & 7) == 0) && (p.out_stride % 4 == 0);
+    for (int e = tid; e < NTT * 4 * 64; e += G_NT) {
+        const int el = e & 63, g = (e >> 6) & 3, i = e >> 8;
+        i32x4 sum = part[e];
+#pragma unroll
+        for (int ww = 1; ww < 4; ++ww) sum += part[ww * NTT * 4 * 64 + e];
+        const int64_t t = 32 * i + (el & 31);
+        const int o = o0 + 8 * g + 4 * (el >> 5);
+        if (t < p.T && o < p.m) {
+            const float sx = (float)p.xs[t];
+            _Float16 v[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) v[x] = (_Float16)((float)(sum[x] >> 8) * sx * (float)p.ws[o + x < p.m ? o + x : p.m - 1]);
+            _Float16* dst = p.out + t * p.out_stride + o;
+            if (wide && o + 4 <= p.m) {
+                *reinterpret_cast<half4*>(dst) = half4{v[0], v[1], v[2], v[3]};
+            } else {
+                for (int x = 0; x < 4; ++x)
+                    if (o + x < p.m) dst[x] = v[x];
+            }
+        }
+    }
+}
+
 hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
     static bool configured = false;   // benign race: same call, same values
     if (!configured) {
@@ -190,6 +275,12 @@ hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
     GemmDev d;
     d.xc = a.x_codes; d.xs = a.x_scales; d.wc = a.w_codes; d.ws = a.w_scales; d.out = a.out;
     d.T = a.T; d.out_stride = a.out_stride; d.m = a.m; d.n = a.n;
+    if (a.T <= 64 && env_int("FLATQUANT_GEMM_TILED", 0) == 0) {   // decode: one pass over the weights, K split inside a workgroup
+        const dim3 grid((unsigned)((a.m + 31) / 32));
+        if (a.T <= 32) hipLaunchKernelGGL(w4a4_decode_kernel<1>, grid, dim3(G_NT), 0, stream, d);
+        else hipLaunchKernelGGL(w4a4_decode_kernel<2>, grid, dim3(G_NT), 0, stream, d);
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)((a.T + GT - 1) / GT), (unsigned)((a.m + GT - 1) / GT));
     hipLaunchKernelGGL(w4a4_kernel, grid, dim3(G_NT), G_LDS_BYTES, stream, d);
     return hipGetLastError();
