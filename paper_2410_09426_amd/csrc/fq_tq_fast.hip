@@ -144,14 +144,29 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     auto issue = [&](int64_t t, u32x4 (&pre)[NPRE]) {
         const u32x4* src = reinterpret_cast<const u32x4*>(p.x + t * p.x_stride) + tid;
 #pragma unroll
-        for (int k = 0; k < NPRE; ++k)
-            if (FULL1 || xrow0 + RSTEP * k < n1) pre[k] = __builtin_nontemporal_load(src + k * NT);
+        for (int k = 0; k < NPRE; ++k) {
+            int off = k * NT;
+            if constexpr (!FULL1) {
+                // Rows past n1 (only possible in the last row tile): a request whose rows all lie past n1 is left out
+                // (same decision for every thread); in a request that straddles n1 the rows past it re-read row
+                // n1 - 1, so there is no per-lane branch.  Their products meet all-zero rows of the P1 fragments, so
+                // whatever they hold (finite) drops out.
+                if (RSTEP * k >= 32 * (A - 1) && RSTEP * k >= n1) continue;   // first test at compile time: last row tile only
+                if (RSTEP * (k + 1) > 32 * (A - 1)) {
+                    const int over = xrow0 + RSTEP * k - (n1 - 1);
+                    off -= (over > 0 ? over : 0) * CPR;
+                }
+            }
+            pre[k] = __builtin_nontemporal_load(src + off);
+        }
     };
     auto commit = [&](const u32x4 (&pre)[NPRE], int buf = 0) {
         _Float16* Xt = Xs + buf * (L::XS_BYTES / 2);
 #pragma unroll
-        for (int k = 0; k < NPRE; ++k)
-            if (FULL1 || xrow0 + RSTEP * k < n1) *reinterpret_cast<u32x4*>(Xt + xbase + RSTEP * k * PITCH) = pre[k];
+        for (int k = 0; k < NPRE; ++k) {
+            if (!FULL1 && RSTEP * k >= 32 * (A - 1) && RSTEP * k >= n1) continue;   // never requested: those tile rows stay zero
+            *reinterpret_cast<u32x4*>(Xt + xbase + RSTEP * k * PITCH) = pre[k];
+        }
     };
 
     // ---- the first token row of this workgroup is requested before anything else
@@ -271,10 +286,11 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     }
     // [phase:fragments built]
     __syncthreads();   // staging area is free: it becomes the token tile
-    if constexpr (!FULL1) {   // rows n1 .. 32A-1 of the tile are never loaded: make them exact zeros once
+    if constexpr (!FULL1) {   // tile rows that are never written (whole requests past n1) must be exact zeros
         for (int bf = 0; bf < NBUF; ++bf)
             for (int q = tid; q < (32 * A - n1) * (PITCH / 8); q += NT)
                 reinterpret_cast<u32x4*>(Xs + bf * (L::XS_BYTES / 2) + n1 * PITCH)[q] = u32x4{0u, 0u, 0u, 0u};
+        __syncthreads();
     }
     commit(pre0);
     __syncthreads();   // [phase:first tile in LDS]
@@ -378,7 +394,6 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     auto quant_unit = [&](const f32x16 (&acc2)[SPW][A], const Step& st, int buf, int u) {
         const int q = u / (4 * A), It = (u / 4) % A, g = u % 4;
         uint8_t* stg = stage + buf * L::STAGE_BYTES;
-        const int ip = 32 * It + c;
         uint32_t bits[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -387,8 +402,8 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         }
         const uint32_t pk = lshl_add(lshl_add(bits[3], 4, bits[2]), 8, lshl_add(bits[1], 4, bits[0])) ^ 0x8888u;
         // byte offset of channel (ip, jp) / 2 with ip = 32 It + c, jp = 32 (w SPW + q) + 8 g + 4 h: lane part + constant
-        if (FULL1 || It < A - 1 || ip < n1)
-            *reinterpret_cast<uint16_t*>(stg + stage_lane + (32 * It * N2 + 32 * q + 8 * g) / 2) = (uint16_t)pk;
+        // rows past n1 land in the unused tail of the stage buffer (it holds 32 A rows): no branch around the write
+        *reinterpret_cast<uint16_t*>(stg + stage_lane + (32 * It * N2 + 32 * q + 8 * g) / 2) = (uint16_t)pk;
     };
     auto quant_to_stage = [&](const f32x16 (&acc2)[SPW][A], float m, float clipv, int buf) -> _Float16 {
         const Step st = make_step(m, clipv);
