@@ -40,7 +40,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the path shards over tokens without any exchange "
-              "(see DESIGN.md), so no multi-GPU figure is produced. Use --gpus 1.", file=sys.stderr)
+              "so no multi-GPU figure is produced. Use --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np
