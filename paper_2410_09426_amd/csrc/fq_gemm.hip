@@ -116,13 +116,29 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
         if (it + 1 < nk) issue(it + 1);
         const unsigned char* A = smem + buf * G_TILE_BYTES + aoff;
         const unsigned char* B = smem + (2 + buf) * G_TILE_BYTES + boff;
+        // the packed operands of K step pair kp + 1 are read from LDS while pair kp goes through the MFMAs
+        constexpr int NKP = GKB / 32;
+        u32x4 pa[2][2], pb[2][2];
 #pragma unroll
-        for (int kp = 0; kp < GKB / 32; ++kp) {
+        for (int i = 0; i < 2; ++i) {
+            pa[0][i] = *reinterpret_cast<const u32x4*>(A + 32 * i * GPITCH);
+            pb[0][i] = *reinterpret_cast<const u32x4*>(B + 32 * i * GPITCH);
+        }
+#pragma unroll
+        for (int kp = 0; kp < NKP; ++kp) {
+            if (kp + 1 < NKP) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    pa[(kp + 1) & 1][i] = *reinterpret_cast<const u32x4*>(A + 32 * i * GPITCH + 32 * (kp + 1));
+                    pb[(kp + 1) & 1][i] = *reinterpret_cast<const u32x4*>(B + 32 * i * GPITCH + 32 * (kp + 1));
+                }
+                __builtin_amdgcn_sched_barrier(0);   // keep these reads ahead of the arithmetic on pair kp
+            }
             i32x4 a[2][2], b[2][2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                widen(*reinterpret_cast<const u32x4*>(A + 32 * i * GPITCH + 32 * kp), a[i][0], a[i][1]);
-                widen(*reinterpret_cast<const u32x4*>(B + 32 * i * GPITCH + 32 * kp), b[i][0], b[i][1]);
+                widen(pa[kp & 1][i], a[i][0], a[i][1]);
+                widen(pb[kp & 1][i], b[i][0], b[i][1]);
             }
 #pragma unroll
             for (int s = 0; s < 2; ++s)
