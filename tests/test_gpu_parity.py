@@ -146,6 +146,23 @@ def test_degenerate_rows_and_small_magnitudes():
     assert not codes[3].any() and float(scales[3]) == 0.0
 
 
+def test_large_magnitudes_near_the_fp16_range():
+    """The result is defined while x, the intermediate X~ P2 (kept as fp16 hi + lo) and Y stay finite in fp16 range.
+    Rows built to come close to that edge (|x| = 30000 everywhere, signs chosen so that the sums against the
+    near-identity P2 stay below 65504) must still match the oracle."""
+    for n1, n2 in ((64, 64), (86, 128)):
+        c = synth.generic(81 + n1, 24, n1, n2, massive_tokens=())
+        r = np.random.Generator(np.random.PCG64(4))
+        sign = r.choice(np.array([-1.0, 1.0], dtype=np.float32), size=(6, c.n))
+        unit = np.einsum("tij,jk->tik", sign.astype(np.float64).reshape(6, n1, n2), c.P2.astype(np.float64))
+        amp = 60000.0 / np.abs(unit).reshape(6, -1).max(axis=1)             # per row: the largest |X~ P2| entry becomes ~60000
+        c.x[:6] = (amp[:, None] * sign).astype(np.float16)
+        z = np.einsum("tij,jk->tik", c.x[:6].astype(np.float64).reshape(6, n1, n2), c.P2.astype(np.float64))
+        assert 55000 < np.abs(z).max() < 65504                              # inside the contract, and near its edge
+        rep, codes, scales = check_case(c, with_dequant=False, label="near the fp16 range")
+        assert np.all(np.isfinite(scales.astype(np.float32)))
+
+
 def test_power_of_two_scaling_keeps_codes():
     c = synth.generic(80, 48, 64, 64, massive_tokens=())
     _, codes, scales = check_case(c)
