@@ -70,8 +70,9 @@ __device__ __forceinline__ float sub_half(float z, unsigned int packed) {
 }
 
 // fp32 x8 -> fp16 hi (round toward zero, cannot overflow to inf) and fp16 lo = fp16(z - hi).
-// (Writing the residual with v_fma_mixlo_f16 / v_fma_mixhi_f16 saves one instruction per pair, but with a single
-// wave per SIMD it produced wrong residuals on gfx950: the half-register writes stay out of this kernel.)
+// (Writing the residual with v_fma_mixlo_f16 / v_fma_mixhi_f16 saves one instruction per pair, but the two
+// half-register writes need a wait state between them on gfx950 (without it, a single wave per SIMD gets wrong
+// residuals), and with the wait states the kernel measured slower than this form.)
 __device__ __forceinline__ void split_hi_lo(const f32x16& acc, int base, half8& hi, half8& lo) {
     u32x4 h, l;
 #pragma unroll
