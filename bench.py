@@ -274,7 +274,7 @@ def main() -> int:
         P = fo.kron_dense(c.P1, c.P2)
         t_kron = time.perf_counter() - t0
         reps, t_run = 0, 0.0
-        while reps < 3 or (t_run < 10.0 and reps < 12):
+        while reps < 3 or (t_run < 10.0 and reps < 400):
             t0 = time.perf_counter()
             res = fo.transform_quant(c.x, c.P1, c.P2, c.clip, P=P)
             t_run += time.perf_counter() - t0
