@@ -111,7 +111,9 @@ __device__ __forceinline__ half8 lds_column8(const _Float16* m, int pitch, int r
 
 // KIND 0: persistent loop, one token per step; 1: persistent loop, software-pipelined over tokens;
 // 2: one token per workgroup (small T: every token gets its own workgroup, all resident at once, 4 waves per SIMD)
-template <int A, int B, int SPW, bool FULL1, int KIND>
+// ID2: the second factor is left out (identity): only the contraction over axis 1 runs, its operand gathered from the
+// token tile in LDS with transposing reads (the tile holds exact fp16, so there is no hi / lo split).
+template <int A, int B, int SPW, bool FULL1, int KIND, bool ID2 = false>
 __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(KIND == 2 ? 4 : 2))) void tq_fast_kernel(TqDev p, const float* __restrict__ clip) {
     static_assert(B % SPW == 0 && 16 % SPW == 0, "slabs per wave must divide the slab count and 16");
     constexpr bool PIPE = (KIND == 1), ONE = (KIND == 2);
@@ -216,15 +218,17 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
             if ((n1sq & 1) && tid == 0) P1flat[n1sq - 1] = tail;
         }
     };
-    half8 p2f[SPW][KB2];
+    half8 p2f[ID2 ? 1 : SPW][ID2 ? 1 : KB2];
     half8 p1f[P1LDS ? 1 : A][P1LDS ? 1 : KB1];
 #pragma unroll
-    for (int pass = 0; pass < L::P2PASSES; ++pass) {
+    for (int pass = 0; pass < (ID2 ? 1 : L::P2PASSES); ++pass) {
         constexpr int CH = L::P2ROWS * N2 / 8;
         const u32x4* src = reinterpret_cast<const u32x4*>(p.P2) + pass * CH;
         u32x4 v2[CH / NT];
+        if constexpr (!ID2) {
 #pragma unroll
-        for (int k = 0; k < CH / NT; ++k) v2[k] = src[tid + k * NT];
+            for (int k = 0; k < CH / NT; ++k) v2[k] = src[tid + k * NT];
+        }
         if (pass == 0) {
             // P1's loads queue behind P2's: one latency for both.  The second token row is requested behind them, so
             // it is in flight during the whole prologue without delaying the transforms (loads return in order).
@@ -234,15 +238,19 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
             });
         }
         else __syncthreads();               // previous pass fully consumed
+        if constexpr (!ID2) {
 #pragma unroll
-        for (int k = 0; k < CH / NT; ++k) reinterpret_cast<u32x4*>(P2flat)[tid + k * NT] = v2[k];
+            for (int k = 0; k < CH / NT; ++k) reinterpret_cast<u32x4*>(P2flat)[tid + k * NT] = v2[k];
+        }
         __syncthreads();   // [phase:transforms staged]
         // B-operand fragments of this wave's slab: lane (c, h) holds P2[16kb + 8h + s][32w + c], s = 0..7
+        if constexpr (!ID2) {
 #pragma unroll
-        for (int kb = pass * (L::P2ROWS / 16); kb < (pass + 1) * (L::P2ROWS / 16); ++kb)
+            for (int kb = pass * (L::P2ROWS / 16); kb < (pass + 1) * (L::P2ROWS / 16); ++kb)
 #pragma unroll
-            for (int q = 0; q < SPW; ++q)
-                p2f[q][kb] = lds_column8(P2flat, N2, 16 * kb - pass * L::P2ROWS + 8 * h, 4, 32 * (w * SPW + q) + (c & 16), l & 15);
+                for (int q = 0; q < SPW; ++q)
+                    p2f[q][kb] = lds_column8(P2flat, N2, 16 * kb - pass * L::P2ROWS + 8 * h, 4, 32 * (w * SPW + q) + (c & 16), l & 15);
+        }
         if (pass == 0) {
             // P1 fragments, gathered with the k-permutation of the first contraction's accumulator layout:
             // K block kk, slot s, half-wave h  <->  i = 32(kk/2) + 8(2(kk%2) + s/4) + 4h + s%4
@@ -308,6 +316,23 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
             for (int It = 0; It < A; ++It)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc2[q][It][r] = 0.0f;
+        if constexpr (ID2) {
+            // Z = X~: lane (c, h) takes, for K block kk, the 8 tile rows of the accumulator-layout permutation in its
+            // own column, i.e. the same gather as for the P1 fragments, straight from the token tile
+            static_assert(!P1LDS, "left-factor-only variant keeps the P1 fragments in registers");
+#pragma unroll
+            for (int q = 0; q < SPW; ++q)
+#pragma unroll
+                for (int kk = 0; kk < KB1; ++kk)
+                    if (FULL1 || 16 * kk < n1) {
+                        const half8 z = lds_column8(Xt, PITCH, 32 * (kk >> 1) + 16 * (kk & 1) + 4 * h, 8, 32 * (w * SPW + q) + (c & 16), l & 15);
+#pragma unroll
+                        for (int It = 0; It < A; ++It) acc2[q][It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(z, p1f[It][kk], acc2[q][It], 0, 0, 0);
+                    }
+#pragma unroll
+            for (int slot = 0; slot < NSLOT; ++slot) side(slot);
+            return;
+        }
         // row tiles of X~ go through the first contraction in pairs so that consecutive MFMAs are independent
 #pragma unroll
         for (int q = 0; q < SPW; ++q)
@@ -573,7 +598,10 @@ static Variant variant(int A, int B, bool full1, int mode) {
 
 bool tq_fast_applicable(const TqDev& d) {
     if (d.n2 % 32 != 0 || !d.vec8 || !d.out_vec16) return false;
-    if (!d.P1 || !d.P2) return false;   // a left-out factor (identity) is handled by the general kernel only
+    // a left-out factor (identity): only the left-factor-only case of 128-wide rows (P_o: heads x head_dim) has
+    // specialised kernels; everything else with a null factor goes to the general kernel
+    if (!d.P1) return false;
+    if (!d.P2 && !(d.n2 == 128 && (d.n1 == 32 || d.n1 == 64))) return false;
     if (reinterpret_cast<uintptr_t>(d.P2) & 15) return false;
     const int n1sq = d.n1 * d.n1;
     const uintptr_t a1 = reinterpret_cast<uintptr_t>(d.P1);
@@ -612,6 +640,47 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
         occ = slot;
         return hipSuccess;
     };
+    if (!d.P2) {   // left factor only (n1 = 32 or 64, n2 = 128): loop-free kernel while every token gets a resident workgroup
+        const bool two = (A == 2);
+        static int occ_id2[2][2];
+        auto kern = [&](int one) -> Variant {
+            if (two) return one ? Variant{&tq_fast_kernel<2, 4, 1, true, 2, true>, FastLds<2, 4>::TOTAL} : Variant{&tq_fast_kernel<2, 4, 1, true, 0, true>, FastLds<2, 4>::TOTAL};
+            return one ? Variant{&tq_fast_kernel<1, 4, 1, true, 2, true>, FastLds<1, 4>::TOTAL} : Variant{&tq_fast_kernel<1, 4, 1, true, 0, true>, FastLds<1, 4>::TOTAL};
+        };
+        auto occ_of = [&](int one, int& occ) -> hipError_t {
+            int& slot = occ_id2[two][one];
+            if (slot == 0) {
+                const Variant v = kern(one);
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.fn), hipFuncAttributeMaxDynamicSharedMemorySize, v.lds);
+                if (e != hipSuccess) return e;
+                int nb = 0;
+                e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, v.fn, 256, v.lds);
+                if (e != hipSuccess) return e;
+                if (nb < 1) return hipErrorLaunchOutOfResources;
+                slot = nb;
+            }
+            occ = slot;
+            return hipSuccess;
+        };
+        int occ1 = 0, occ0 = 0;
+        hipError_t e = occ_of(1, occ1);
+        if (e != hipSuccess) return e;
+        int one = (d.T <= (int64_t)cu_count() * occ1) ? 1 : 0;
+        const int force = env_int("FLATQUANT_MODE", -1);
+        if (force == 0) one = 0;
+        if (force == 3 && d.T <= 0x7fffffff) one = 1;
+        const Variant v = kern(one);
+        int64_t grid = d.T;
+        if (!one) {
+            e = occ_of(0, occ0);
+            if (e != hipSuccess) return e;
+            const int64_t resident = (int64_t)cu_count() * occ0;
+            const int64_t rounds = (d.T + resident - 1) / resident;
+            grid = (d.T + rounds - 1) / rounds;
+        }
+        hipLaunchKernelGGL(v.fn, dim3((unsigned)grid), dim3(256), v.lds, stream, d, d.clip);
+        return hipGetLastError();
+    }
     int mode = (A <= 2) ? 2 : 0;
     if (A <= 2 && B == 2 && d.T >= 32768) mode = 1;
     if (A <= 2 && B <= 2) {

@@ -312,6 +312,7 @@ def test_weight_side_parity_and_quantized_layer(T, m, n1, n2):
 
 # ---- one-sided transforms (a factor left out = identity) ------------------------------------------------------------
 @pytest.mark.parametrize("n1,n2,T,which", [(32, 128, 200, "P1 only"), (32, 128, 3000, "P1 only"), (64, 64, 2048, "P1 only"),
+                                           (64, 128, 2500, "P1 only"), (64, 128, 129, "P1 only"), (32, 128, 1, "P1 only"),
                                            (64, 64, 70, "P2 only"), (86, 128, 37, "P2 only"), (64, 64, 50, "none"),
                                            (33, 34, 21, "P1 only"), (6, 10, 9, "P2 only")])
 def test_one_sided_transforms(n1, n2, T, which):
