@@ -282,6 +282,15 @@ def main() -> int:
         out["cpu_baseline"] = {"value": T * reps / t_run, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
                                "sample": f"all {T} tokens of the headline workload, {reps} passes of the fp64 dense-Kronecker oracle "
                                          f"(numpy); building the {n}x{n} matrix once took {t_kron:.2f} s and is not in the rate"}
+        # a second CPU line: the same oracle through the factored form of Eq. (2) (two small contractions per token)
+        reps_f, t_f = 0, 0.0
+        while reps_f < 2 or (t_f < 5.0 and reps_f < 400):
+            t0 = time.perf_counter()
+            yf = fo.affine_transform_factored(c.x, c.P1, c.P2)
+            fo.quantize_sym_int4(yf, c.clip)
+            t_f += time.perf_counter() - t0
+            reps_f += 1
+        out["detail"]["cpu_oracle_factored_form_tokens_per_s"] = T * reps_f / t_f
         rep = parity.check_sym(res["y"], c.clip, codes[0].cpu().numpy(),
                                scales[0].cpu().view(torch.int16).numpy().view(np.float16))
         out["detail"]["parity_on_timed_buffers"] = rep

@@ -81,6 +81,16 @@ def affine_transform(x, P1, P2, P=None) -> np.ndarray:
     return x @ P
 
 
+def affine_transform_factored(x, P1, P2) -> np.ndarray:
+    """The same product in the factored form of Eq. (2), as printed: for every token, P1^T X~ P2 with X~ the
+    row-major n1 x n2 reshape (two small contractions instead of one n x n product)."""
+    x = as_f64(x)
+    P1, P2 = as_f64(P1), as_f64(P2)
+    n1, n2 = P1.shape[0], P2.shape[0]
+    Xt = x.reshape(x.shape[0], n1, n2)
+    return np.matmul(P1.T, np.matmul(Xt, P2)).reshape(x.shape[0], n1 * n2)
+
+
 # --------------------------------------------------------------------------
 # Sec. 2.1 / 3.1 / 4.1: per-token symmetric INT4 with a clipping ratio
 # --------------------------------------------------------------------------

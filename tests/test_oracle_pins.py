@@ -99,6 +99,16 @@ def test_kron_identity_bruteforce(n1, n2):
     np.testing.assert_allclose(y, yf, rtol=1e-12, atol=1e-12)
 
 
+def test_factored_form_of_eq2_equals_the_dense_product():
+    """vec(V)(P1 (x) P2) = vec(P1^T V P2) (the vectorisation identity the paper recalls in Sec. 3.1): the oracle's
+    factored route and its dense route are two different computations of the same numbers."""
+    r = rng(77)
+    for n1, n2 in [(1, 6), (5, 3), (16, 16), (8, 32)]:
+        x = rand_fp16(r, (9, n1 * n2), 3.0)
+        P1, P2 = rand_fp16(r, (n1, n1)), rand_fp16(r, (n2, n2))
+        assert np.allclose(fo.affine_transform_factored(x, P1, P2), fo.affine_transform(x, P1, P2), rtol=1e-12, atol=1e-12)
+
+
 def test_kron_hand_worked_and_transpose_matters():
     g = read_golden("hand_worked.txt")
     P1 = np.array([[1, 2], [3, 4]], dtype=np.float16)
