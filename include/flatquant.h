@@ -121,7 +121,7 @@ fq_status flatquant_weight_transform_quant(const void* w, const void* A1, const 
  *   x_codes  u8 [T, n/2], x_scales fp16 [T]   : outputs of flatquant_transform_quant
  *   w_codes  u8 [m, n/2], w_scales fp16 [m]   : outputs of flatquant_weight_transform_quant
  *   out      fp16 [T, m], row t at out + t*out_stride halves, out_stride >= m.
- * n must be a multiple of 256 (and <= 131072); code tensors 16-byte aligned.  T == 0 or m == 0 returns FQ_OK.
+ * n must be a multiple of 256 (and <= 65536, so that the int32 sums cannot overflow); code tensors 16-byte aligned.  T == 0 or m == 0 returns FQ_OK.
  * Values beyond the fp16 range come out as infinities.
  */
 fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, const uint8_t* w_codes, const void* w_scales,

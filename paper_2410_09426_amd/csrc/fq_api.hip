@@ -123,7 +123,7 @@ fq_status flatquant_head_transform(const void* x, const void* P, int Hp, int64_t
 fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, const uint8_t* w_codes, const void* w_scales,
                               int64_t T, int m, int n, void* out, int64_t out_stride, void* stream) {
     if (T < 0 || m < 0 || n < 1 || out_stride < m) return FQ_INVALID_ARG;
-    if (n % 256 != 0 || n > 131072) return FQ_UNSUPPORTED_SHAPE;
+    if (n % 256 != 0 || n > 65536) return FQ_UNSUPPORTED_SHAPE;
     if (T == 0 || m == 0) return FQ_OK;
     if (!x_codes || !x_scales || !w_codes || !w_scales || !out) return FQ_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(x_codes) & 15) || (reinterpret_cast<uintptr_t>(w_codes) & 15) ||

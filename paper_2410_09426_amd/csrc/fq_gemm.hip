@@ -7,7 +7,7 @@
 // extension: for a packed dword w, (w << 4) & 0xF0F0F0F0 holds 16 q of the even channels and w & 0xF0F0F0F0 holds 16 q
 // of the odd channels, as signed bytes.  Both operands are widened the same way, so the K order inside an MFMA is
 // the same permutation for both and every product carries a factor 256 that the epilogue divides out exactly.
-// v_mfma_i32_32x32x32_i8 accumulates in int32 (|sum| <= 128 * 128 * n, n <= 131072).
+// v_mfma_i32_32x32x32_i8 accumulates in int32 (|sum| <= 128 * 128 * n < 2^31 for n <= 65536).
 //
 // Workgroup: 4 waves, C tile 128 tokens x 128 output channels, each wave 64 x 64 (2 x 2 MFMA tiles; the weights are
 // the MFMA's first operand so that a lane ends up with runs of 4 consecutive output channels of one token).  K advances by

@@ -89,6 +89,17 @@ def test_argument_validation_without_a_device():
     assert fq.flatquant_stream_probe(A + 2, 4, 4096, 4096, A + 0x400000, check=False) == fq.FQ_MISALIGNED
     assert fq.flatquant_stream_probe(None, 4, 4096, 4096, A + 0x400000, check=False) == fq.FQ_INVALID_ARG
 
+    gm = lambda **k: fq.flatquant_w4a4_gemm(**{**dict(x_codes=A, x_scales=A + 0x100000, w_codes=A + 0x200000, w_scales=A + 0x300000, T=4, m=8,
+                                                     n=512, out=A + 0x400000, out_stride=8, check=False), **k})
+    assert gm(T=0) == fq.FQ_OK and gm(m=0, out_stride=0) == fq.FQ_OK
+    assert gm(n=500) == fq.FQ_UNSUPPORTED_SHAPE and gm(n=65536 + 256) == fq.FQ_UNSUPPORTED_SHAPE
+    assert gm(out_stride=7) == fq.FQ_INVALID_ARG and gm(out=None) == fq.FQ_INVALID_ARG
+    assert gm(x_codes=A + 8) == fq.FQ_MISALIGNED
+    assert gm(out=A + 0x200000) == fq.FQ_INVALID_ARG          # output overlaps the weight codes
+    ht = lambda **k: fq.flatquant_head_transform(**{**dict(x=A, P=A + 0x100000, Hp=8, T=4, H=8, D=128, out=A + 0x400000, check=False), **k})
+    assert ht(T=0) == fq.FQ_OK and ht(D=64) == fq.FQ_UNSUPPORTED_SHAPE and ht(Hp=3) == fq.FQ_INVALID_ARG
+    assert ht(out=A) == fq.FQ_INVALID_ARG and ht(x=A + 4) == fq.FQ_MISALIGNED
+
     dq = lambda **k: fq.flatquant_dequant(**{**dict(codes=A, scales=A + 0x100000, zeros=None, rows=4, n=64, out=A + 0x200000, check=False), **k})
     assert dq(rows=0) == fq.FQ_OK
     assert dq(n=63) == fq.FQ_INVALID_ARG
