@@ -281,6 +281,138 @@ __global__ __launch_bounds__(G_NT) void w4a4_decode_kernel(GemmDev p) {
     }
 }
 
+// ---- few tokens, second form: the activation codes go through LDS.  In the kernel above every wave gathers 16 bytes
+// per token row per load (a quarter of a cache line from 32 rows at once), which costs more than the weight stream
+// itself once there are more than a few tokens.  Here the workgroup copies the token rows, 1 KB of K at a time, with
+// whole-row loads into an LDS tile; the waves split each 1 KB slice four ways, read their activation operands from the
+// tile and their weight rows from global memory.  The next slice is requested before the current one is multiplied.
+constexpr int DSB = 1024;            // packed bytes of K per token row and pass (2048 codes)
+constexpr int DPITCH = DSB + 16;     // 16-byte operand reads of 32 consecutive rows fall on distinct banks
+template <int NTT>
+__global__ __launch_bounds__(G_NT) void w4a4_decode_lds_kernel(GemmDev p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int R = 32 * NTT;
+    constexpr int NLD = R * (DSB / 16) / G_NT;
+    const int tid = threadIdx.x;
+    const int l = tid & 63, c = l & 31, h = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int o0 = blockIdx.x * 32;
+    const int kbytes = p.n / 2;
+    const int npass = (kbytes + DSB - 1) / DSB;
+    int orow = o0 + c;
+    if (orow >= p.m) orow = p.m - 1;
+    const unsigned char* wrow = p.wc + (int64_t)orow * kbytes + 16 * h;
+
+    i32x16 acc[NTT];
+#pragma unroll
+    for (int i = 0; i < NTT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+
+    u32x4 tl[NLD];
+    // slice `ps`: `bytes` per row (a multiple of 128), `bytes / 16` chunks per row; chunk q of the tile = row q / cpr
+    auto slice_bytes = [&](int ps) { const int left = kbytes - ps * DSB; return left < DSB ? left : DSB; };
+    auto issue_tile = [&](int ps) {
+        const int cpr = slice_bytes(ps) >> 4;
+#pragma unroll
+        for (int k = 0; k < NLD; ++k) {
+            const int q = tid + G_NT * k;
+            int row = q / cpr;
+            const int ch = q - row * cpr;
+            if (row > R - 1) row = R - 1;            // chunks past the tile (short last slice) re-read its last row
+            int64_t t = row;
+            if (t >= p.T) t = p.T - 1;
+            tl[k] = *reinterpret_cast<const u32x4*>(p.xc + t * kbytes + ps * DSB + ch * 16);
+        }
+    };
+    auto commit_tile = [&](int ps) {
+        const int cpr = slice_bytes(ps) >> 4;
+#pragma unroll
+        for (int k = 0; k < NLD; ++k) {
+            const int q = tid + G_NT * k;
+            const int row = q / cpr, ch = q - row * cpr;
+            if (row < R) *reinterpret_cast<u32x4*>(smem + row * DPITCH + ch * 16) = tl[k];
+        }
+    };
+    auto issue_w = [&](int ps, u32x4 (&wv)[8]) {
+        const int per_wave = slice_bytes(ps) >> 2;   // a multiple of 32: units of 64 codes
+        const int nu = per_wave >> 5;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int uu = u < nu ? u : nu - 1;
+            wv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow + ps * DSB + w * per_wave + 32 * uu));
+        }
+    };
+    auto compute = [&](int ps, const u32x4 (&wv)[8]) {
+        const int per_wave = slice_bytes(ps) >> 2;
+        const int nu = per_wave >> 5;
+        const unsigned char* xr = smem + c * DPITCH + w * per_wave + 16 * h;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (u < nu) {
+                i32x4 ws0, ws1;
+                widen(wv[u], ws0, ws1);
+#pragma unroll
+                for (int i = 0; i < NTT; ++i) {
+                    i32x4 xs0, xs1;
+                    widen(*reinterpret_cast<const u32x4*>(xr + 32 * i * DPITCH + 32 * u), xs0, xs1);
+                    acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws0, xs0, acc[i], 0, 0, 0);
+                    acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws1, xs1, acc[i], 0, 0, 0);
+                }
+            }
+    };
+    u32x4 wv0[8], wv1[8];
+    issue_tile(0);
+    issue_w(0, wv0);
+    commit_tile(0);
+    __syncthreads();
+    for (int ps = 0; ps < npass; ps += 2) {
+        if (ps + 1 < npass) { issue_tile(ps + 1); issue_w(ps + 1, wv1); }
+        compute(ps, wv0);
+        __syncthreads();                       // every wave is done with the tile
+        if (ps + 1 >= npass) break;
+        commit_tile(ps + 1);
+        __syncthreads();
+        if (ps + 2 < npass) { issue_tile(ps + 2); issue_w(ps + 2, wv0); }
+        compute(ps + 1, wv1);
+        __syncthreads();
+        if (ps + 2 >= npass) break;
+        commit_tile(ps + 2);
+        __syncthreads();
+    }
+    // partial sums -> LDS (the tile is dead) as [wave][tile][quad g][lane] x 4 ints, then 4-way add, scale, round, 8-byte stores
+    i32x4* part = reinterpret_cast<i32x4*>(smem);
+#pragma unroll
+    for (int i = 0; i < NTT; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            part[((w * NTT + i) * 4 + g) * 64 + l] = i32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
+    __syncthreads();
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    const bool wide = ((reinterpret_cast<uintptr_t>(p.out) & 7) == 0) && (p.out_stride % 4 == 0);
+    for (int e = tid; e < NTT * 4 * 64; e += G_NT) {
+        const int el = e & 63, g = (e >> 6) & 3, i = e >> 8;
+        i32x4 sum = part[e];
+#pragma unroll
+        for (int ww = 1; ww < 4; ++ww) sum += part[ww * NTT * 4 * 64 + e];
+        const int64_t t = 32 * i + (el & 31);
+        const int o = o0 + 8 * g + 4 * (el >> 5);
+        if (t < p.T && o < p.m) {
+            const float sx = (float)p.xs[t];
+            _Float16 v[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) v[x] = (_Float16)((float)(sum[x] >> 8) * sx * (float)p.ws[o + x < p.m ? o + x : p.m - 1]);
+            _Float16* dst = p.out + t * p.out_stride + o;
+            if (wide && o + 4 <= p.m) {
+                *reinterpret_cast<half4*>(dst) = half4{v[0], v[1], v[2], v[3]};
+            } else {
+                for (int x = 0; x < 4; ++x)
+                    if (o + x < p.m) dst[x] = v[x];
+            }
+        }
+    }
+}
+
 hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
     static bool configured = false;   // benign race: same call, same values
     if (!configured) {
@@ -293,6 +425,21 @@ hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
     d.T = a.T; d.out_stride = a.out_stride; d.m = a.m; d.n = a.n;
     if (a.T <= 64 && env_int("FLATQUANT_GEMM_TILED", 0) == 0) {   // decode: one pass over the weights, K split inside a workgroup
         const dim3 grid((unsigned)((a.m + 31) / 32));
+        // more than a few tokens: activation codes through LDS (FLATQUANT_GEMM_DECODE = 0 / 1 forces one form)
+        const int form = env_int("FLATQUANT_GEMM_DECODE", a.T > 8 ? 1 : 0);
+        if (form == 1) {
+            static bool conf2 = false;   // benign race: same calls, same values
+            if (!conf2) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(w4a4_decode_lds_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, 32 * DPITCH);
+                if (e != hipSuccess) return e;
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(w4a4_decode_lds_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * DPITCH);
+                if (e != hipSuccess) return e;
+                conf2 = true;
+            }
+            if (a.T <= 32) hipLaunchKernelGGL(w4a4_decode_lds_kernel<1>, grid, dim3(G_NT), 32 * DPITCH, stream, d);
+            else hipLaunchKernelGGL(w4a4_decode_lds_kernel<2>, grid, dim3(G_NT), 64 * DPITCH, stream, d);
+            return hipGetLastError();
+        }
         if (a.T <= 32) hipLaunchKernelGGL(w4a4_decode_kernel<1>, grid, dim3(G_NT), 0, stream, d);
         else hipLaunchKernelGGL(w4a4_decode_kernel<2>, grid, dim3(G_NT), 0, stream, d);
         return hipGetLastError();

@@ -360,7 +360,8 @@ def test_head_transform_fp16_out(T, H, shared):
 
 # ---- W4A4 matrix product ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("T,m,n,pad", [(300, 260, 512, 0), (128, 128, 256, 0), (1, 1, 256, 0), (2048, 384, 4096, 0), (77, 200, 11008, 24),
-                                       (64, 4096, 4096, 0), (33, 100, 512, 0), (17, 4099, 11008, 5), (32, 64, 256, 0), (65, 96, 768, 0)])
+                                       (64, 4096, 4096, 0), (33, 100, 512, 0), (17, 4099, 11008, 5), (32, 64, 256, 0), (65, 96, 768, 0),
+                                       (9, 40, 2304, 0), (64, 33, 11008, 0), (8, 64, 4096, 0)])
 def test_w4a4_gemm(T, m, n, pad):
     """Integer accumulation is exact, so the only freedom is the final rounding: two fp32 multiplications and one fp16
     rounding against the oracle's single rounding of the fp64 value (2^-11 relative + two fp32 roundings)."""
