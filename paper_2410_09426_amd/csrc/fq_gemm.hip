@@ -361,20 +361,24 @@ __global__ __launch_bounds__(G_NT) void w4a4_decode_lds_kernel(GemmDev p) {
                 }
             }
     };
+    // Weight rows (the HBM stream) are requested two slices ahead, the token tile (L2-resident) one slice ahead.
     u32x4 wv0[8], wv1[8];
     issue_tile(0);
     issue_w(0, wv0);
+    if (npass > 1) issue_w(1, wv1);
     commit_tile(0);
     __syncthreads();
     for (int ps = 0; ps < npass; ps += 2) {
-        if (ps + 1 < npass) { issue_tile(ps + 1); issue_w(ps + 1, wv1); }
+        if (ps + 1 < npass) issue_tile(ps + 1);
         compute(ps, wv0);
+        if (ps + 2 < npass) issue_w(ps + 2, wv0);
         __syncthreads();                       // every wave is done with the tile
         if (ps + 1 >= npass) break;
         commit_tile(ps + 1);
         __syncthreads();
-        if (ps + 2 < npass) { issue_tile(ps + 2); issue_w(ps + 2, wv0); }
+        if (ps + 2 < npass) issue_tile(ps + 2);
         compute(ps + 1, wv1);
+        if (ps + 3 < npass) issue_w(ps + 3, wv1);
         __syncthreads();
         if (ps + 2 >= npass) break;
         commit_tile(ps + 2);
