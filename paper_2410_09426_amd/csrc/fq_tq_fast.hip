@@ -30,7 +30,10 @@ struct FastLds {
     static constexpr int N2 = 32 * B;
     static constexpr int PITCH = N2 + kLdsPad;                       // halves per row of the token tile
     static constexpr int XS_BYTES = 32 * A * PITCH * 2;
-    static constexpr int STAGE_BYTES = 512 * A * B;                  // packed codes of one token
+    // packed codes of one token, one row of X~ (N2 / 2 bytes) per line; 16 bytes of padding per line spread the
+    // 2-byte writes of 32 lanes (one line each) over the banks instead of piling them on two
+    static constexpr int SPITCH = N2 / 2 + 16;
+    static constexpr int STAGE_BYTES = 32 * A * SPITCH;
     static constexpr int BODY_BYTES = NBUF * (XS_BYTES + STAGE_BYTES) + 64;   // + one absmax float per wave and buffer
     static constexpr int P2ROWS = (B <= 4) ? N2 : N2 / 2;            // rows of P2 staged per pass
     static constexpr int P2PASSES = N2 / P2ROWS;
@@ -403,7 +406,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     // ---- step from the absmax; clamp, round, pack into stage buffer `buf`.  fma against 1.5 * 2^23 + 8 leaves
     // code + 8 (0..15) in the low mantissa bits with zeros above up to bit 21, so four results chain with shift-adds
     // and one xor turns offset-binary nibbles into two's complement ones.
-    const int stage_lane = (c * N2 + 32 * w * SPW + 4 * h) >> 1;   // this lane's byte offset inside a staged code row
+    const int stage_lane = c * L::SPITCH + ((32 * w * SPW + 4 * h) >> 1);   // this lane's byte offset inside the staged codes
     struct Step { _Float16 sh; float inv, lim_lo, lim_hi; };
     auto make_step = [&](float m, float clipv) {
         Step st;
@@ -429,7 +432,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         const uint32_t pk = lshl_add(lshl_add(bits[3], 4, bits[2]), 8, lshl_add(bits[1], 4, bits[0])) ^ 0x8888u;
         // byte offset of channel (ip, jp) / 2 with ip = 32 It + c, jp = 32 (w SPW + q) + 8 g + 4 h: lane part + constant
         // rows past n1 land in the unused tail of the stage buffer (it holds 32 A rows): no branch around the write
-        *reinterpret_cast<uint16_t*>(stg + stage_lane + (32 * It * N2 + 32 * q + 8 * g) / 2) = (uint16_t)pk;
+        *reinterpret_cast<uint16_t*>(stg + stage_lane + 32 * It * L::SPITCH + (32 * q + 8 * g) / 2) = (uint16_t)pk;
     };
     auto quant_to_stage = [&](const f32x16 (&acc2)[SPW][A], float m, float clipv, int buf) -> _Float16 {
         const Step st = make_step(m, clipv);
@@ -446,10 +449,13 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         constexpr int NQ_FULL = 32 * A * B;   // 16-byte units of one code row when n1 = 32A
         if constexpr (FULL1 && NQ_FULL % NT == 0) {
 #pragma unroll
-            for (int k = 0; k < NQ_FULL / NT; ++k) __builtin_nontemporal_store(stg[tid + k * NT], dst + tid + k * NT);
+            for (int k = 0; k < NQ_FULL / NT; ++k) {
+                const int q = tid + k * NT;            // unit q = 16-byte chunk q % B of line q / B
+                __builtin_nontemporal_store(stg[(q / B) * (B + 1) + q % B], dst + q);
+            }
         } else {
             const int nq = n1 * B;
-            for (int q = tid; q < nq; q += NT) __builtin_nontemporal_store(stg[q], dst + q);
+            for (int q = tid; q < nq; q += NT) __builtin_nontemporal_store(stg[(q / B) * (B + 1) + q % B], dst + q);
         }
         p.out_scales[t] = sh;   // every lane writes the same two bytes: cheaper than a branch around the store
     };
