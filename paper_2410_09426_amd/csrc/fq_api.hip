@@ -13,15 +13,35 @@ namespace fq {
 static thread_local int g_last_hip_error = 0;
 
 int cu_count() {
-    static int cached[64];
+    static std::atomic<int> cached[kMaxDevices];
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
+}
+
+hipError_t kernel_occupancy(const void* fn, int threads, int lds, OccCache& cache, int& wg_per_cu) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::atomic<int>* slot = (dev >= 0 && dev < kMaxDevices) ? &cache.per_device[dev] : nullptr;
+    int v = slot ? slot->load(std::memory_order_acquire) : 0;
+    if (v == 0) {
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        int nb = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, threads, lds);
+        if (e != hipSuccess) return e;
+        if (nb < 1) return hipErrorLaunchOutOfResources;
+        v = nb;
+        if (slot) slot->store(v, std::memory_order_release);
+    }
+    wg_per_cu = v;
+    return hipSuccess;
 }
 
 int env_int(const char* name, int dflt) {

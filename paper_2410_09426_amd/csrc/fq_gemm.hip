@@ -418,12 +418,7 @@ __global__ __launch_bounds__(G_NT) void w4a4_decode_lds_kernel(GemmDev p) {
 }
 
 hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
-    static bool configured = false;   // benign race: same call, same values
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(w4a4_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, G_LDS_BYTES);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    int unused = 0;
     GemmDev d;
     d.xc = a.x_codes; d.xs = a.x_scales; d.wc = a.w_codes; d.ws = a.w_scales; d.out = a.out;
     d.T = a.T; d.out_stride = a.out_stride; d.m = a.m; d.n = a.n;
@@ -432,14 +427,10 @@ hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
         // more than a few tokens: activation codes through LDS (FLATQUANT_GEMM_DECODE = 0 / 1 forces one form)
         const int form = env_int("FLATQUANT_GEMM_DECODE", a.T > 8 ? 1 : 0);
         if (form == 1) {
-            static bool conf2 = false;   // benign race: same calls, same values
-            if (!conf2) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(w4a4_decode_lds_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, 32 * DPITCH);
-                if (e != hipSuccess) return e;
-                e = hipFuncSetAttribute(reinterpret_cast<const void*>(w4a4_decode_lds_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * DPITCH);
-                if (e != hipSuccess) return e;
-                conf2 = true;
-            }
+            static OccCache c1, c2;
+            hipError_t e = (a.T <= 32) ? kernel_occupancy(reinterpret_cast<const void*>(w4a4_decode_lds_kernel<1>), G_NT, 32 * DPITCH, c1, unused)
+                                       : kernel_occupancy(reinterpret_cast<const void*>(w4a4_decode_lds_kernel<2>), G_NT, 64 * DPITCH, c2, unused);
+            if (e != hipSuccess) return e;
             if (a.T <= 32) hipLaunchKernelGGL(w4a4_decode_lds_kernel<1>, grid, dim3(G_NT), 32 * DPITCH, stream, d);
             else hipLaunchKernelGGL(w4a4_decode_lds_kernel<2>, grid, dim3(G_NT), 64 * DPITCH, stream, d);
             return hipGetLastError();
@@ -447,6 +438,11 @@ hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
         if (a.T <= 32) hipLaunchKernelGGL(w4a4_decode_kernel<1>, grid, dim3(G_NT), 0, stream, d);
         else hipLaunchKernelGGL(w4a4_decode_kernel<2>, grid, dim3(G_NT), 0, stream, d);
         return hipGetLastError();
+    }
+    static OccCache ct;
+    {
+        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_kernel), G_NT, G_LDS_BYTES, ct, unused);
+        if (e != hipSuccess) return e;
     }
     const dim3 grid((unsigned)((a.T + GT - 1) / GT), (unsigned)((a.m + GT - 1) / GT));
     hipLaunchKernelGGL(w4a4_kernel, grid, dim3(G_NT), G_LDS_BYTES, stream, d);

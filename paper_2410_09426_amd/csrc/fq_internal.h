@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace fq {
 
 constexpr int kTile = 32;          // MFMA tile edge (v_mfma_f32_32x32x16_f16)
@@ -83,6 +85,15 @@ hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream);
 
 // Copy-like probe with the activation kernel's traffic (fq_probe.hip).
 hipError_t stream_probe_launch(const void* x, int64_t T, int n, int64_t x_stride, uint8_t* out, hipStream_t stream);
+
+// Launch facts of one kernel, cached per device: the first call on a device raises the kernel's dynamic-LDS limit to
+// `lds` bytes and asks the runtime how many workgroups of `threads` threads fit on a CU.  Concurrent first calls
+// compute the same value; devices past the table are served without caching.
+constexpr int kMaxDevices = 64;
+struct OccCache {
+    std::atomic<int> per_device[kMaxDevices];
+};
+hipError_t kernel_occupancy(const void* fn, int threads, int lds, OccCache& cache, int& wg_per_cu);
 
 // Number of compute units of the current device (cached per device).
 int cu_count();

@@ -267,17 +267,12 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
 template <bool QUANT>
 static hipError_t kv_launch_mode(const KvArgs& a, hipStream_t stream) {
     constexpr int LDS = QUANT ? KV_LDS_BYTES : KV_OUT_LDS_BYTES;
-    static int wg_per_cu = 0;   // computed once per process (benign race: same value)
-    if (wg_per_cu == 0) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kv_kernel<QUANT>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    static OccCache occ_cache;
+    int occ = 0;
+    {
+        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(kv_kernel<QUANT>), KV_NT, LDS, occ_cache, occ);
         if (e != hipSuccess) return e;
-        int nb = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kv_kernel<QUANT>, KV_NT, LDS);
-        if (e != hipSuccess) return e;
-        if (nb < 1) return hipErrorLaunchOutOfResources;
-        wg_per_cu = nb;
     }
-    int occ = wg_per_cu;
     const int cap = env_int("FLATQUANT_KV_WG_PER_CU", 0);
     if (cap > 0 && cap < occ) occ = cap;
     const int64_t nblk = (a.T + KV_TOK - 1) / KV_TOK;

@@ -629,44 +629,21 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     // wherever it fits; very long 64-wide streams sustain ~10 % more with one wave per token; and when every token can
     // have its own resident workgroup (4 waves per SIMD) the loop-free kernel is ~10 % faster still.
     // FLATQUANT_MODE overrides the choice for tuning and tests.
-    static int wg_per_cu[4][8][2][4];   // per-variant occupancy, computed once per process (benign race: same value)
+    static OccCache occ_cache[4][8][2][4];   // per variant and device
     auto occupancy = [&](int mode, int& occ) -> hipError_t {
-        int& slot = wg_per_cu[A - 1][B - 1][full1][mode];
-        if (slot == 0) {
-            const Variant v = variant(A, B, full1, mode);
-            const int nt = 64 * (B / (mode == 1 ? 2 : 1));
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.fn), hipFuncAttributeMaxDynamicSharedMemorySize, v.lds);
-            if (e != hipSuccess) return e;
-            int nb = 0;
-            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, v.fn, nt, v.lds);
-            if (e != hipSuccess) return e;
-            if (nb < 1) return hipErrorLaunchOutOfResources;
-            slot = nb;
-        }
-        occ = slot;
-        return hipSuccess;
+        const Variant v = variant(A, B, full1, mode);
+        return kernel_occupancy(reinterpret_cast<const void*>(v.fn), 64 * (B / (mode == 1 ? 2 : 1)), v.lds, occ_cache[A - 1][B - 1][full1][mode], occ);
     };
     if (!d.P2) {   // left factor only (n1 = 32 or 64, n2 = 128): loop-free kernel while every token gets a resident workgroup
         const bool two = (A == 2);
-        static int occ_id2[2][2];
+        static OccCache occ_id2[2][2];
         auto kern = [&](int one) -> Variant {
             if (two) return one ? Variant{&tq_fast_kernel<2, 4, 1, true, 2, true>, FastLds<2, 4>::TOTAL} : Variant{&tq_fast_kernel<2, 4, 1, true, 0, true>, FastLds<2, 4>::TOTAL};
             return one ? Variant{&tq_fast_kernel<1, 4, 1, true, 2, true>, FastLds<1, 4>::TOTAL} : Variant{&tq_fast_kernel<1, 4, 1, true, 0, true>, FastLds<1, 4>::TOTAL};
         };
         auto occ_of = [&](int one, int& occ) -> hipError_t {
-            int& slot = occ_id2[two][one];
-            if (slot == 0) {
-                const Variant v = kern(one);
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.fn), hipFuncAttributeMaxDynamicSharedMemorySize, v.lds);
-                if (e != hipSuccess) return e;
-                int nb = 0;
-                e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, v.fn, 256, v.lds);
-                if (e != hipSuccess) return e;
-                if (nb < 1) return hipErrorLaunchOutOfResources;
-                slot = nb;
-            }
-            occ = slot;
-            return hipSuccess;
+            const Variant v = kern(one);
+            return kernel_occupancy(reinterpret_cast<const void*>(v.fn), 256, v.lds, occ_id2[two][one], occ);
         };
         int occ1 = 0, occ0 = 0;
         hipError_t e = occ_of(1, occ1);

@@ -321,18 +321,11 @@ hipError_t tq_launch(const TqArgs& a, hipStream_t stream) {
     // FLATQUANT_FORCE_GENERIC=1 keeps the general kernel testable on shapes the specialised ones would take
     if (tq_fast_applicable(d) && env_int("FLATQUANT_FORCE_GENERIC", 0) == 0) return tq_fast_launch(d, stream);
 
-    // per-variant launch facts, computed once per process (benign race: same values)
-    static int wg_per_cu[4][8];
-    int occ = wg_per_cu[A - 1][B - 1];
-    if (occ == 0) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    static OccCache occ_cache[4][8];   // per variant and device
+    int occ = 0;
+    {
+        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(fn), nt, (int)lds, occ_cache[A - 1][B - 1], occ);
         if (e != hipSuccess) return e;
-        int nb = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, nt, lds);
-        if (e != hipSuccess) return e;
-        if (nb < 1) return hipErrorLaunchOutOfResources;
-        occ = nb;
-        wg_per_cu[A - 1][B - 1] = occ;
     }
     const int cap = env_int("FLATQUANT_WG_PER_CU", 0);
     if (cap > 0 && cap < occ) occ = cap;
