@@ -349,15 +349,41 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc1[d][r] = 0.0f;
             const _Float16* arow = Xt + (32 * I0 + c) * PITCH + 8 * h;
-#pragma unroll
-            for (int kb = 0; kb < KB2; ++kb) {
+            if constexpr (A >= 3) {
+                // wide tiles: the operands of K block kb + 1 are read from LDS before the MFMAs of block kb are issued
+                // (measured: helps the 128-row tiles, costs the 64-row ones)
+                half8 anext[NI_MAX];
 #pragma unroll
                 for (int d = 0; d < NI_MAX; ++d)
-                    if (d < ni) {
-                        const half8 a = *reinterpret_cast<const half8*>(arow + d * 32 * PITCH + 16 * kb);
-                        acc1[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p2f[q][kb], acc1[d], 0, 0, 0);
+                    if (d < ni) anext[d] = *reinterpret_cast<const half8*>(arow + d * 32 * PITCH);
+#pragma unroll
+                for (int kb = 0; kb < KB2; ++kb) {
+                    half8 acur[NI_MAX];
+#pragma unroll
+                    for (int d = 0; d < NI_MAX; ++d)
+                        if (d < ni) acur[d] = anext[d];
+                    if (kb + 1 < KB2) {
+#pragma unroll
+                        for (int d = 0; d < NI_MAX; ++d)
+                            if (d < ni) anext[d] = *reinterpret_cast<const half8*>(arow + d * 32 * PITCH + 16 * (kb + 1));
+                        __builtin_amdgcn_sched_barrier(0);
                     }
-                side((q * ((A + 1) / 2) + I0 / 2) * KB2 + kb);
+#pragma unroll
+                    for (int d = 0; d < NI_MAX; ++d)
+                        if (d < ni) acc1[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(acur[d], p2f[q][kb], acc1[d], 0, 0, 0);
+                    side((q * ((A + 1) / 2) + I0 / 2) * KB2 + kb);
+                }
+            } else {
+#pragma unroll
+                for (int kb = 0; kb < KB2; ++kb) {
+#pragma unroll
+                    for (int d = 0; d < NI_MAX; ++d)
+                        if (d < ni) {
+                            const half8 a = *reinterpret_cast<const half8*>(arow + d * 32 * PITCH + 16 * kb);
+                            acc1[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p2f[q][kb], acc1[d], 0, 0, 0);
+                        }
+                    side((q * ((A + 1) / 2) + I0 / 2) * KB2 + kb);
+                }
             }
             // Y^T[slab, :] += Z^T[slab, K block] P1[K block, :], hi and lo parts of Z
 #pragma unroll
