@@ -34,7 +34,7 @@ struct FastLds {
     // 2-byte writes of 32 lanes (one line each) over the banks instead of piling them on two
     static constexpr int SPITCH = N2 / 2 + 16;
     static constexpr int STAGE_BYTES = 32 * A * SPITCH;
-    static constexpr int BODY_BYTES = NBUF * (XS_BYTES + STAGE_BYTES) + 64;   // + one absmax float per wave and buffer
+    static constexpr int BODY_BYTES = NBUF * (XS_BYTES + STAGE_BYTES) + 32 * (NBUF < 2 ? 2 : NBUF);   // + one absmax float per wave and buffer
     static constexpr int P2ROWS = (B <= 4) ? N2 : N2 / 2;            // rows of P2 staged per pass
     static constexpr int P2PASSES = N2 / P2ROWS;
     static constexpr int P1FLAT_BYTES = 32 * A * 32 * A * 2;
@@ -116,13 +116,17 @@ __device__ __forceinline__ half8 lds_column8(const _Float16* m, int pitch, int r
 // 2: one token per workgroup (small T: every token gets its own workgroup, all resident at once, 4 waves per SIMD)
 // ID2: the second factor is left out (identity): only the contraction over axis 1 runs, its operand gathered from the
 // token tile in LDS with transposing reads (the tile holds exact fp16, so there is no hi / lo split).
-template <int A, int B, int SPW, bool FULL1, int KIND, bool ID2 = false>
-__global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(KIND == 2 ? 4 : 2))) void tq_fast_kernel(TqDev p, const float* __restrict__ clip) {
+// TPW (KIND 2, one wave per token only): tokens per workgroup.  The waves of a workgroup share the staging of P1 and
+// P2 (the bytes every workgroup pulls through its CU's vector memory path on top of its tokens) and nothing else:
+// after the fragments are built each wave works on its own token, tile and staged codes, with no workgroup barrier.
+template <int A, int B, int SPW, bool FULL1, int KIND, bool ID2 = false, int TPW = 1>
+__global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_per_eu((KIND == 2 && SPW == 1) ? 4 : 2))) void tq_fast_kernel(TqDev p, const float* __restrict__ clip) {
     static_assert(B % SPW == 0 && 16 % SPW == 0, "slabs per wave must divide the slab count and 16");
+    static_assert(TPW == 1 || (KIND == 2 && B == SPW && A <= 2), "several tokens per workgroup: loop-free kernel, one wave per token");
     constexpr bool PIPE = (KIND == 1), ONE = (KIND == 2);
-    using L = FastLds<A, B, PIPE ? 2 : 1>;
-    constexpr int WPT = B / SPW;                  // waves per token = waves per workgroup
-    constexpr int NT = 64 * WPT, N2 = L::N2, PITCH = L::PITCH;
+    using L = FastLds<A, B, PIPE ? 2 : TPW>;
+    constexpr int WPT = B / SPW;                  // waves per token
+    constexpr int NT = 64 * WPT, NTA = NT * TPW, N2 = L::N2, PITCH = L::PITCH;   // threads per token, per workgroup
     constexpr int KB1 = 2 * A, KB2 = 2 * B, NPRE = 2 * A * SPW;
     constexpr int RSTEP = 16 / SPW;               // rows of X~ covered by one 16-byte chunk per thread
     constexpr int CPR = 4 * B;                    // 16-byte chunks per row of X~
@@ -130,7 +134,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // body layout: [tile 0][tile 1 if PIPE][stage 0][stage 1 if PIPE][absmax exchange: 8 floats per buffer]
-    constexpr int NBUF = PIPE ? 2 : 1;
+    constexpr int NBUF = PIPE ? 2 : TPW;
     _Float16* Xs = reinterpret_cast<_Float16*>(smem);
     uint8_t* stage = smem + NBUF * L::XS_BYTES;
     float* red = reinterpret_cast<float*>(smem + NBUF * (L::XS_BYTES + L::STAGE_BYTES));
@@ -138,8 +142,10 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     _Float16* P1flat = reinterpret_cast<_Float16*>(smem);
     _Float16* P2flat = reinterpret_cast<_Float16*>(smem + L::P1FLAT_BYTES);
 
-    const int tid = threadIdx.x;
-    const int l = tid & 63, w = tid >> 6, c = l & 31, h = l >> 5;
+    const int tida = threadIdx.x;                 // thread within the workgroup: used where all waves share work
+    const int tid = TPW > 1 ? (tida & (NT - 1)) : tida;   // thread within the token's waves
+    const int ts = TPW > 1 ? tida / NT : 0;       // token slot of this wave inside the workgroup
+    const int l = tid & 63, w = tid >> 6, c = l & 31, h = l >> 5;   // w: wave within the token
     const int n1 = FULL1 ? 32 * A : p.n1;
     const int64_t row_bytes_out = (int64_t)n1 * (N2 / 2);
 
@@ -178,8 +184,10 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     // ---- the first token row of this workgroup is requested before anything else
     constexpr bool DEEP = !ONE && (PIPE || (NPRE <= 4));   // two rows in flight per workgroup when the registers allow it
     u32x4 pre0[NPRE], pre1[DEEP ? NPRE : 1];
-    int64_t t = blockIdx.x;
+    int64_t t = (int64_t)blockIdx.x * TPW + ts;
     const int64_t G = gridDim.x;
+    const bool live = TPW == 1 || t < p.T;        // a last workgroup's spare waves redo token T - 1 and store nothing
+    if (TPW > 1 && !live) t = p.T - 1;
     issue(t, pre0);   // [phase:rows requested]
 
     // ---- stage P1 (flat, n1 x n1) and P2 (in one or two passes of rows) in LDS with coalesced loads.  All loads of
@@ -190,11 +198,11 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         const int n1sq = n1 * n1;
         auto copy_batched = [&](auto* dst, const auto* src, int count) {
             constexpr int BATCH = 8;
-            for (int base = 0; base < count; base += BATCH * NT) {
+            for (int base = 0; base < count; base += BATCH * NTA) {
                 decltype(*src + 0) v[BATCH];
 #pragma unroll
                 for (int k = 0; k < BATCH; ++k) {
-                    const int idx = base + k * NT + tid;
+                    const int idx = base + k * NTA + tida;
                     v[k] = src[idx < count ? idx : count - 1];
                 }
                 if (base == 0) {
@@ -204,21 +212,21 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
                 }
 #pragma unroll
                 for (int k = 0; k < BATCH; ++k) {
-                    const int idx = base + k * NT + tid;
+                    const int idx = base + k * NTA + tida;
                     if (idx < count) dst[idx] = v[k];
                 }
             }
         };
         if ((reinterpret_cast<uintptr_t>(p.P1) & 15) == 0) {   // bulk in 16-byte chunks, then up to 7 single elements
             const int done = n1sq & ~7;
-            const int ti = done + tid < n1sq ? done + tid : n1sq - 1;
+            const int ti = done + tida < n1sq ? done + tida : n1sq - 1;
             const _Float16 tail = p.P1[ti];
             copy_batched(reinterpret_cast<u32x4*>(P1flat), reinterpret_cast<const u32x4*>(p.P1), n1sq >> 3);
-            if (done + tid < n1sq) P1flat[ti] = tail;
+            if (done + tida < n1sq) P1flat[ti] = tail;
         } else {   // only 4-byte aligned: pairs, plus a last odd element
             const _Float16 tail = p.P1[n1sq - 1];
             copy_batched(reinterpret_cast<uint32_t*>(P1flat), reinterpret_cast<const uint32_t*>(p.P1), n1sq >> 1);
-            if ((n1sq & 1) && tid == 0) P1flat[n1sq - 1] = tail;
+            if ((n1sq & 1) && tida == 0) P1flat[n1sq - 1] = tail;
         }
     };
     half8 p2f[ID2 ? 1 : SPW][ID2 ? 1 : KB2];
@@ -227,10 +235,11 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     for (int pass = 0; pass < (ID2 ? 1 : L::P2PASSES); ++pass) {
         constexpr int CH = L::P2ROWS * N2 / 8;
         const u32x4* src = reinterpret_cast<const u32x4*>(p.P2) + pass * CH;
-        u32x4 v2[CH / NT];
+        static_assert(CH % NTA == 0, "P2 pass divides over the workgroup's threads");
+        u32x4 v2[CH / NTA];
         if constexpr (!ID2) {
 #pragma unroll
-            for (int k = 0; k < CH / NT; ++k) v2[k] = src[tid + k * NT];
+            for (int k = 0; k < CH / NTA; ++k) v2[k] = src[tida + k * NTA];
         }
         if (pass == 0) {
             // P1's loads queue behind P2's: one latency for both.  The second token row is requested behind them, so
@@ -243,7 +252,7 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
         else __syncthreads();               // previous pass fully consumed
         if constexpr (!ID2) {
 #pragma unroll
-            for (int k = 0; k < CH / NT; ++k) reinterpret_cast<u32x4*>(P2flat)[tid + k * NT] = v2[k];
+            for (int k = 0; k < CH / NTA; ++k) reinterpret_cast<u32x4*>(P2flat)[tida + k * NTA] = v2[k];
         }
         __syncthreads();   // [phase:transforms staged]
         // B-operand fragments of this wave's slab: lane (c, h) holds P2[16kb + 8h + s][32w + c], s = 0..7
@@ -300,12 +309,22 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     __syncthreads();   // staging area is free: it becomes the token tile
     if constexpr (!FULL1) {   // tile rows that are never written (whole requests past n1) must be exact zeros
         for (int bf = 0; bf < NBUF; ++bf)
-            for (int q = tid; q < (32 * A - n1) * (PITCH / 8); q += NT)
+            for (int q = tida; q < (32 * A - n1) * (PITCH / 8); q += NTA)
                 reinterpret_cast<u32x4*>(Xs + bf * (L::XS_BYTES / 2) + n1 * PITCH)[q] = u32x4{0u, 0u, 0u, 0u};
         __syncthreads();
     }
-    commit(pre0);
-    __syncthreads();   // [phase:first tile in LDS]
+    // with one wave per token the tile, the staged codes and the absmax slot of a token are touched by that wave only:
+    // LDS executes a wave's instructions in order, so program order is all that has to be kept
+    auto token_sync = [&]() {
+        if constexpr (TPW > 1) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        } else {
+            __syncthreads();
+        }
+    };
+    commit(pre0, ts);
+    token_sync();   // [phase:first tile in LDS]
 
     // ---- both contractions for the token tile in LDS buffer `buf`: acc2 = (P1^T X~ P2)^T for this wave's slabs
     // `side(slot)` is called NSLOT times at even intervals of the MFMA stream; the pipelined loop uses it to
@@ -495,13 +514,13 @@ __global__ __launch_bounds__(64 * (B / SPW)) __attribute__((amdgpu_waves_per_eu(
     if constexpr (ONE) {
         const float clipv = clip[p.clip_mode ? t : 0];
         f32x16 acc2[SPW][A];
-        gemm(0, acc2, [](int) {});   // [phase:contractions done]
-        absmax_to_lds(acc2, 0);
-        __syncthreads();             // [phase:absmax exchanged]
-        const float m = absmax_from_lds(0);
-        const _Float16 sh = quant_to_stage(acc2, m, clipv, 0);   // [phase:codes staged]
-        __syncthreads();
-        copy_out(t, 0, sh);          // [phase:token done]
+        gemm(ts, acc2, [](int) {});   // [phase:contractions done]
+        absmax_to_lds(acc2, ts);
+        token_sync();                // [phase:absmax exchanged]
+        const float m = absmax_from_lds(ts);
+        const _Float16 sh = quant_to_stage(acc2, m, clipv, ts);   // [phase:codes staged]
+        token_sync();
+        if (live) copy_out(t, ts, sh);   // [phase:token done]
     } else if constexpr (!PIPE) {
         // One token per step: the tile of token t is in LDS, `pre_next` holds (or is receiving) the row of token t + G
         // and is written to LDS once every wave is done with the current tile; the row of token t + 2G is requested
@@ -585,13 +604,20 @@ struct Variant {
 };
 
 // mode 0: one slab per wave; mode 1: two slabs per wave; mode 2: one slab per wave, software-pipelined over tokens;
-// mode 3: one slab per wave, one token per workgroup (only when every token can have a resident workgroup)
+// mode 3: one slab per wave, one token per workgroup (only when every token can have a resident workgroup);
+// mode 4 (n2 = 64): one wave per token, kTokensPerWg tokens per workgroup sharing the staged transforms, no loop
+constexpr int kTokensPerWg = 4;
 template <int A, int B>
 static Variant variant_ab(bool full1, int mode) {
     if constexpr (A <= 2 && (B == 2 || B == 4 || B == 8)) {
         if (mode == 1)
             return full1 ? Variant{&tq_fast_kernel<A, B, 2, true, 0>, FastLds<A, B>::TOTAL}
                          : Variant{&tq_fast_kernel<A, B, 2, false, 0>, FastLds<A, B>::TOTAL};
+    }
+    if constexpr (A <= 2 && B == 2) {
+        if (mode == 4)
+            return full1 ? Variant{&tq_fast_kernel<A, B, 2, true, 2, false, kTokensPerWg>, FastLds<A, B, kTokensPerWg>::TOTAL}
+                         : Variant{&tq_fast_kernel<A, B, 2, false, 2, false, kTokensPerWg>, FastLds<A, B, kTokensPerWg>::TOTAL};
     }
     if constexpr (A <= 2) {
         if (mode == 2)
@@ -653,12 +679,15 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     const bool full1 = (d.n1 % 32) == 0;
     // Kernel flavour (see variant_ab), from measurements on MI355X: the pipelined loop wins or ties the plain loop
     // wherever it fits; very long 64-wide streams sustain ~10 % more with one wave per token; and when every token can
-    // have its own resident workgroup (4 waves per SIMD) the loop-free kernel is ~10 % faster still.
+    // have its own resident workgroup (4 waves per SIMD) the loop-free kernel is ~10 % faster still.  What the
+    // loop-free kernel pays per workgroup is the staging of P1 and P2: 16 KB through the CU's vector memory path per
+    // 8 KB token at 64 x 64 (about 0.8 us of the launch at T = 2048, measured by staging from a single cache line).
     // FLATQUANT_MODE overrides the choice for tuning and tests.
-    static OccCache occ_cache[4][8][2][4];   // per variant and device
+    static OccCache occ_cache[4][8][2][5];   // per variant and device
     auto occupancy = [&](int mode, int& occ) -> hipError_t {
         const Variant v = variant(A, B, full1, mode);
-        return kernel_occupancy(reinterpret_cast<const void*>(v.fn), 64 * (B / (mode == 1 ? 2 : 1)), v.lds, occ_cache[A - 1][B - 1][full1][mode], occ);
+        const int threads = mode == 4 ? 64 * kTokensPerWg : 64 * (B / (mode == 1 ? 2 : 1));
+        return kernel_occupancy(reinterpret_cast<const void*>(v.fn), threads, v.lds, occ_cache[A - 1][B - 1][full1][mode], occ);
     };
     if (!d.P2) {   // left factor only (n1 = 32 or 64, n2 = 128): loop-free kernel while every token gets a resident workgroup
         const bool two = (A == 2);
@@ -697,12 +726,17 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
         hipError_t e = occupancy(3, occ3);
         if (e != hipSuccess) return e;
         if (d.T <= (int64_t)cu_count() * occ3) mode = 3;
+        // past that, and up to where the wave-per-token loop takes over, 64-wide rows do best without a loop as well:
+        // workgroups of kTokensPerWg single-wave tokens, handed out by the hardware as earlier ones retire
+        // (measured at T = 3072 .. 16384: 3 - 8 % over the pipelined loop)
+        else if (B == 2 && d.T < 32768) mode = 4;
     }
     const int mode_env = env_int("FLATQUANT_MODE", -1);
-    if (mode_env == 0 || (mode_env == 1 && A <= 2 && (B == 2 || B == 4 || B == 8)) || (mode_env == 2 && A <= 2) || (mode_env == 3 && A <= 2)) mode = mode_env;
+    if (mode_env == 0 || (mode_env == 1 && A <= 2 && (B == 2 || B == 4 || B == 8)) || (mode_env == 2 && A <= 2) || (mode_env == 3 && A <= 2) ||
+        (mode_env == 4 && A <= 2 && B == 2)) mode = mode_env;
     const int spw = (mode == 1) ? 2 : 1;
     const Variant v = variant(A, B, full1, mode);
-    const int nt = 64 * (B / spw);
+    const int nt = mode == 4 ? 64 * kTokensPerWg : 64 * (B / spw);
     int occ = 0;
     {
         hipError_t e = occupancy(mode, occ);
@@ -714,9 +748,9 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     const int64_t resident = (int64_t)cu_count() * occ;
     const int64_t rounds = (d.T + resident - 1) / resident;
     int64_t grid = (d.T + rounds - 1) / rounds;
-    if (mode == 3) {
+    if (mode >= 3) {
         if (d.T > 0x7fffffff) return hipErrorInvalidConfiguration;   // only reachable through the tuning overrides
-        grid = d.T;
+        grid = mode == 4 ? (d.T + kTokensPerWg - 1) / kTokensPerWg : d.T;
     }
     hipLaunchKernelGGL(v.fn, dim3((unsigned)grid), dim3(nt), v.lds, stream, d, d.clip);
     return hipGetLastError();

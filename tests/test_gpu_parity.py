@@ -61,6 +61,7 @@ def test_prefill_7b_full():
 def test_prefill_7b_forced_persistent_loop(monkeypatch):
     # one workgroup per CU: every workgroup walks 8 tokens through the prefetch / double barrier loop
     monkeypatch.setenv("FLATQUANT_WG_PER_CU", "1")
+    monkeypatch.setenv("FLATQUANT_MODE", "2")
     c = synth.prefill_7b(2048 + 37)
     check_case(c, rows=subset_rows(c.T, 300, 5, must=(0, 255, 256, 257, 2047, 2048)), with_dequant=False, label="wg_per_cu=1")
 
@@ -73,10 +74,10 @@ def test_general_kernel_on_aligned_shapes(monkeypatch):
     check_case(synth.decode_7b(64, wide=True), with_dequant=False, label="general kernel")
 
 
-@pytest.mark.parametrize("mode", ["0", "1", "2", "3"])
+@pytest.mark.parametrize("mode", ["0", "1", "2", "3", "4"])
 def test_every_kernel_flavour(monkeypatch, mode):
-    # 0: one slab per wave; 1: two slabs per wave; 2: software-pipelined loop; 3: one token per workgroup
-    # (the library picks one by shape and T)
+    # 0: one slab per wave; 1: two slabs per wave; 2: software-pipelined loop; 3: one token per workgroup;
+    # 4: one wave per token, several tokens per workgroup (the library picks one by shape and T)
     monkeypatch.setenv("FLATQUANT_MODE", mode)
     c = synth.prefill_7b(1024 + 3)
     check_case(c, rows=subset_rows(c.T, 150, 11, must=(0, 1, 1023, 1024)), with_dequant=False, label=f"mode {mode}")
@@ -84,6 +85,14 @@ def test_every_kernel_flavour(monkeypatch, mode):
     check_case(c, rows=subset_rows(c.T, 80, 12), with_dequant=False, label=f"mode {mode}")
     c = synth.generic(95 + int(mode), 40, 32, 64)
     check_case(c, with_dequant=False, label=f"mode {mode}")
+    for T, n1 in ((1, 64), (6, 50), (9, 17)):   # fewer tokens than a workgroup holds, ragged n1
+        check_case(synth.generic(195 + int(mode) + T, T, n1, 64), with_dequant=False, label=f"mode {mode}")
+
+
+def test_mid_length_stream_uses_multi_token_workgroups():
+    # more tokens than resident single-token workgroups, fewer than the wave-per-token loop wants; T % 4 = 3
+    c = synth.prefill_7b(4096 + 3)
+    check_case(c, rows=subset_rows(c.T, 200, 14, must=(0, 3, 4, 4095, 4096, 4097, 4098)), with_dequant=False, label="2048 < T < 32768")
 
 
 def test_long_stream_uses_wave_per_token_path():
