@@ -14,11 +14,16 @@ What each function follows
   Sec. 4.1 "Quantization" (per-token symmetric for activations) and Sec. 3.1
   "Learnable Clipping Thresholds" (alpha in (0, 1], applied after the
   transform, shrinking the range that the grid covers).
-* kv_quantize_asym_int4        : Sec. 4.1 "Quantization" and App. "KV Cache
-  Quantization": group-wise asymmetric INT4, group = head_dim.  The paper
+* kv_quantize_asym(_int4)      : Sec. 4.1 "Quantization" and App. "KV Cache
+  Quantization": group-wise asymmetric b-bit codes (b = 4 in the main results,
+  b = 2 and 3 in the appendix tables on key / value bit widths), group =
+  head_dim, on the unsigned grid {0 .. 2^b - 1} of Sec. 2.1.  The paper
   prints no formula for the asymmetric grid; the textbook min/max affine grid
   that contains zero is used.  PARITY UNPINNED by the paper for this function;
   it is pinned by invariants in the CPU tests.
+* pack_bits / unpack_bits      : storage of b-bit codes (not fixed by the
+  paper): code k of a group sits at bits [b k, b k + b) of the group's bytes
+  read as one little-endian integer; for b = 4 this is pack_nibbles.
 * kv_transform                 : Sec. 3.2 "Self-Attention": a dense per-head
   matrix P_h applied head by head (not decomposed).
 * dequantize                   : Sec. 2.1, s * q (symmetric) or s * (q - z).
@@ -181,19 +186,20 @@ def head_transform_fp16(x, P) -> np.ndarray:
     return round_to_fp16(kv_transform(x, P))
 
 
-def kv_scale_zero(y, clip):
+def kv_scale_zero(y, clip, bits=4):
     """Per group (last axis): mx = max(y, 0), mn = min(y, 0) scaled by alpha;
-    step s = fp16((mx - mn) / 15); zero point z = round(-mn / s) in [0, 15].
-    Returns (s fp16, z int8, zf fp64 = pre-round zero point)."""
+    step s = fp16((mx - mn) / (2^b - 1)); zero point z = round(-mn / s) in
+    [0, 2^b - 1].  Returns (s fp16, z int8, zf fp64 = pre-round zero point)."""
     y = as_f64(y)
     a = float(clip)
+    qmax = (1 << int(bits)) - 1
     mx = a * np.maximum(np.max(y, axis=-1), 0.0)
     mn = a * np.minimum(np.min(y, axis=-1), 0.0)
-    s = round_to_fp16((mx - mn) / QMAX_ASYM)
+    s = round_to_fp16((mx - mn) / qmax)
     s64 = as_f64(s)
     zf = np.zeros_like(s64)
     np.divide(-mn, s64, out=zf, where=(s64 != 0))
-    z = np.clip(np.rint(zf), 0, QMAX_ASYM).astype(np.int8)
+    z = np.clip(np.rint(zf), 0, qmax).astype(np.int8)
     return s, z, zf
 
 
@@ -205,29 +211,74 @@ def kv_preround(y, scale_fp16) -> np.ndarray:
     return u
 
 
-def kv_quantize_asym_int4(y, clip, scale_fp16=None, zero=None):
-    """Returns (q uint8 in [0, 15], s fp16, z int8, u fp64, zf fp64)."""
-    s0, z0, zf = kv_scale_zero(y, clip)
+def kv_quantize_asym(y, clip, bits=4, scale_fp16=None, zero=None):
+    """Returns (q uint8 in [0, 2^b - 1], s fp16, z int8, u fp64, zf fp64)."""
+    qmax = (1 << int(bits)) - 1
+    s0, z0, zf = kv_scale_zero(y, clip, bits)
     s = s0 if scale_fp16 is None else np.asarray(scale_fp16, dtype=np.float16)
     z = z0 if zero is None else np.asarray(zero).astype(np.int8)
     u = kv_preround(y, s)
-    q = np.clip(np.rint(u) + z[..., None], 0, QMAX_ASYM).astype(np.uint8)
+    q = np.clip(np.rint(u) + z[..., None], 0, qmax).astype(np.uint8)
     return q, s, z, u, zf
 
 
-def kv_transform_quant(kv, P, clip):
+def kv_quantize_asym_int4(y, clip, scale_fp16=None, zero=None):
+    return kv_quantize_asym(y, clip, 4, scale_fp16, zero)
+
+
+def pack_bits(q, bits) -> np.ndarray:
+    """q [..., n] unsigned codes below 2^bits, n * bits a multiple of 8 ->
+    u8 [..., n * bits / 8]: code k at bits [bits k, bits k + bits) of the row
+    read as one little-endian integer."""
+    q = np.asarray(q)
+    bits = int(bits)
+    n = q.shape[-1]
+    assert (n * bits) % 8 == 0
+    assert np.all((q >= 0) & (q < (1 << bits)))
+    flat = q.reshape(-1, n)
+    out = np.zeros((flat.shape[0], n * bits // 8), dtype=np.uint8)
+    for r in range(flat.shape[0]):
+        big = 0
+        for k in range(n):
+            big |= int(flat[r, k]) << (bits * k)
+        out[r] = np.frombuffer(big.to_bytes(n * bits // 8, "little"), dtype=np.uint8)
+    return out.reshape(q.shape[:-1] + (n * bits // 8,))
+
+
+def unpack_bits(packed, bits, n) -> np.ndarray:
+    """Inverse of pack_bits: u8 [..., n * bits / 8] -> uint8 [..., n]."""
+    packed = np.asarray(packed, dtype=np.uint8)
+    bits = int(bits)
+    nb = n * bits // 8
+    assert packed.shape[-1] == nb
+    flat = packed.reshape(-1, nb)
+    out = np.zeros((flat.shape[0], n), dtype=np.uint8)
+    for r in range(flat.shape[0]):
+        big = int.from_bytes(flat[r].tobytes(), "little")
+        for k in range(n):
+            out[r, k] = (big >> (bits * k)) & ((1 << bits) - 1)
+    return out.reshape(packed.shape[:-1] + (n,))
+
+
+def kv_transform_quant(kv, P, clip, bits=4):
     y = kv_transform(kv, P)
-    q, s, z, u, zf = kv_quantize_asym_int4(y, clip)
-    return {"codes": pack_nibbles(q), "scales": s, "zeros": z, "q": q, "u": u, "y": y, "zf": zf}
+    q, s, z, u, zf = kv_quantize_asym(y, clip, bits)
+    return {"codes": pack_bits(q, bits), "scales": s, "zeros": z, "q": q, "u": u, "y": y, "zf": zf}
 
 
 # --------------------------------------------------------------------------
 # Sec. 2.1: de-quantization
 # --------------------------------------------------------------------------
-def dequantize(codes_packed, scales_fp16, zeros=None) -> np.ndarray:
-    """s * q (zeros is None: signed nibbles) or s * (q - z) (unsigned nibbles).
-    codes [..., n/2] u8, scales [...] fp16, zeros [...] -> fp64 [..., n]."""
-    q = unpack_nibbles(codes_packed, signed=zeros is None).astype(np.float64)
+def dequantize(codes_packed, scales_fp16, zeros=None, bits=4) -> np.ndarray:
+    """s * q (zeros is None: signed nibbles) or s * (q - z) (unsigned b-bit
+    codes).  codes [..., n b / 8] u8, scales [...] fp16, zeros [...] -> fp64
+    [..., n]."""
+    if bits == 4:
+        q = unpack_nibbles(codes_packed, signed=zeros is None).astype(np.float64)
+    else:
+        assert zeros is not None, "only the asymmetric grid has other widths"
+        packed = np.asarray(codes_packed)
+        q = unpack_bits(packed, bits, packed.shape[-1] * 8 // bits).astype(np.float64)
     s = as_f64(scales_fp16)[..., None]
     if zeros is not None:
         q = q - as_f64(zeros)[..., None]

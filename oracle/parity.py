@@ -75,17 +75,18 @@ def check_sym(y_or, clip, codes_dev, scales_dev, deq_dev=None, rows=None):
     return rep
 
 
-def check_kv(y_or, clip, codes_dev, scales_dev, zeros_dev, deq_dev=None):
-    """y_or fp64 [G, D] (groups flattened); codes u8 [G, D/2]; scales/zeros fp16 [G]."""
+def check_kv(y_or, clip, codes_dev, scales_dev, zeros_dev, deq_dev=None, bits=4):
+    """y_or fp64 [G, D] (groups flattened); codes u8 [G, D*bits/8]; scales/zeros fp16 [G]."""
+    qmax = (1 << int(bits)) - 1
     y_or = np.asarray(y_or, dtype=np.float64)
     G, D = y_or.shape
     scales_dev = np.asarray(scales_dev).view(np.float16).reshape(G)
     zeros_dev = np.asarray(zeros_dev).view(np.float16).reshape(G)
-    q_or, s_or, z_or, u_or, zf_or = fo.kv_quantize_asym_int4(y_or, clip)
+    q_or, s_or, z_or, u_or, zf_or = fo.kv_quantize_asym(y_or, clip, bits)
     s_or64, s_dev64 = fo.as_f64(s_or), fo.as_f64(scales_dev)
     z_dev64 = fo.as_f64(zeros_dev)
     assert np.all(np.isfinite(s_dev64)) and np.all(np.isfinite(z_dev64))
-    assert np.all(z_dev64 == np.rint(z_dev64)) and np.all((z_dev64 >= 0) & (z_dev64 <= 15)), "zero point not an integer in [0,15]"
+    assert np.all(z_dev64 == np.rint(z_dev64)) and np.all((z_dev64 >= 0) & (z_dev64 <= qmax)), "zero point not an integer on the grid"
     bad = np.abs(s_dev64 - s_or64) > SCALE_RTOL * s_or64
     assert not bad.any(), f"KV step mismatch at groups {np.nonzero(bad)[0][:8]}"
     sdiff = s_dev64 != s_or64
@@ -94,16 +95,19 @@ def check_kv(y_or, clip, codes_dev, scales_dev, zeros_dev, deq_dev=None):
     mn = a * np.minimum(np.min(y_or, axis=-1), 0.0)
     zf = np.zeros(G)
     np.divide(-mn, s_dev64, out=zf, where=(s_dev64 != 0))
-    z_exp = np.clip(np.rint(zf), 0, 15)
+    z_exp = np.clip(np.rint(zf), 0, qmax)
     zdiff = z_dev64 != z_exp
     if zdiff.any():
         near = np.abs(zf[zdiff] - (np.floor(zf[zdiff]) + 0.5)) <= BAND
         assert near.all() and np.all(np.abs(z_dev64[zdiff] - zf[zdiff]) <= 0.5 + BAND), \
             f"zero point mismatch at groups {np.nonzero(zdiff)[0][:8]}"
-    q_exp, _, _, u, _ = fo.kv_quantize_asym_int4(y_or, clip, scale_fp16=scales_dev, zero=z_dev64)
-    q_dev = fo.unpack_nibbles(codes_dev, signed=False).astype(np.uint8)
+    q_exp, _, _, u, _ = fo.kv_quantize_asym(y_or, clip, bits, scale_fp16=scales_dev, zero=z_dev64)
+    if bits == 4:
+        q_dev = fo.unpack_nibbles(codes_dev, signed=False).astype(np.uint8)
+    else:
+        q_dev = fo.unpack_bits(np.asarray(codes_dev).reshape(G, D * bits // 8), bits, D)
     uz = u + z_dev64[:, None]
-    band = _band_mask(uz, 0, 15)
+    band = _band_mask(uz, 0, qmax)
     neq = q_dev != q_exp
     hard = neq & ~band
     if hard.any():

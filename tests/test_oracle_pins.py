@@ -324,6 +324,63 @@ def test_kv_invariants():
     np.testing.assert_allclose(shared[:, 3], kv.k[:2, 3].astype(np.float64) @ kv.P[0].astype(np.float64), rtol=1e-13)
 
 
+def test_bit_packing_hand_set_bytes():
+    # 3-bit: 1 | 2<<3 | 3<<6 | 4<<9 | 5<<12 | 6<<15 | 7<<18 | 0<<21 = 0x1F58D1, little-endian bytes D1 58 1F
+    assert fo.pack_bits(np.array([1, 2, 3, 4, 5, 6, 7, 0]), 3).tolist() == [0xD1, 0x58, 0x1F]
+    # 2-bit: 1 | 2<<2 | 3<<4 | 0<<6 = 0x39;   3 | 3<<2 | 0 | 2<<6 = 0x8F
+    assert fo.pack_bits(np.array([1, 2, 3, 0, 3, 3, 0, 2]), 2).tolist() == [0x39, 0x8F]
+    # 4-bit is the nibble layout of the rest of the library: even channel in the low nibble
+    q = np.array([[1, 15, 0, 9, 7, 8]])
+    assert fo.pack_bits(q, 4).tolist() == [[0xF1, 0x90, 0x87]]
+    assert np.array_equal(fo.pack_bits(q, 4), fo.pack_nibbles(q.astype(np.int8)))
+    rng = np.random.default_rng(5)
+    for bits in (2, 3, 4):
+        q = rng.integers(0, 1 << bits, size=(3, 5, 128)).astype(np.uint8)
+        p = fo.pack_bits(q, bits)
+        assert p.shape == (3, 5, 16 * bits) and p.dtype == np.uint8
+        assert np.array_equal(fo.unpack_bits(p, bits, 128), q)
+    # a code that crosses a byte boundary (3-bit code 2 occupies bits 6..8)
+    assert fo.pack_bits(np.array([0, 0, 7, 0, 0, 0, 0, 0]), 3).tolist() == [0xC0, 0x01, 0x00]
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_kv_lower_bit_grid(bits):
+    """App. "KV Cache Quantization", tables on key / value bit widths: the same asymmetric group-wise grid with
+    2^b levels.  Pinned by what any such grid must do."""
+    qmax = (1 << bits) - 1
+    kv = synth.kv_cache(T=16)
+    eye = np.broadcast_to(np.eye(kv.D, dtype=np.float16), (kv.H, kv.D, kv.D))
+    res = fo.kv_transform_quant(kv.k, eye, 1.0, bits)
+    q, s, z = res["q"], res["scales"].astype(np.float64), res["zeros"].astype(np.float64)
+    assert res["codes"].shape == (16, kv.H, kv.D * bits // 8)
+    assert q.min() >= 0 and q.max() <= qmax and z.min() >= 0 and z.max() <= qmax
+    assert np.all((q.min(axis=-1) == 0) | (q.max(axis=-1) == qmax))
+    # the step divides the (zero-containing) range into 2^b - 1 intervals
+    rng_ = np.maximum(res["y"].max(-1), 0) - np.minimum(res["y"].min(-1), 0)
+    np.testing.assert_allclose(s, rng_ / qmax, rtol=2.0 ** -11)
+    # every value goes to the nearest level of its group's grid (brute force over the 2^b levels), except that a
+    # tie or the clamped ends may pick a neighbour: the chosen level is never worse than the best by more than that
+    levels = (np.arange(qmax + 1)[None, None, None, :] - z[..., None, None]) * s[..., None, None]
+    best = np.min(np.abs(res["y"][..., None] - levels), axis=-1)
+    yhat = fo.dequantize(res["codes"], res["scales"], res["zeros"], bits)
+    assert np.all(np.abs(yhat - res["y"]) <= best + 1e-9 * s[..., None])
+    # zero is on the grid: an exact 0.0 input comes back as exactly 0.0
+    y0 = kv.k[:2].copy()
+    y0[:, :, 5] = 0
+    r0 = fo.kv_transform_quant(y0, eye, 1.0, bits)
+    assert np.all(fo.dequantize(r0["codes"], r0["scales"], r0["zeros"], bits)[:, :, 5] == 0.0)
+    # a group of exactly 2^b equally spaced values 0, d, 2d, ... is reproduced exactly (d a power of two)
+    ramp = np.zeros((1, 1, 128), dtype=np.float16)
+    ramp[0, 0, :qmax + 1] = 0.25 * np.arange(qmax + 1)
+    rr = fo.kv_transform_quant(ramp, np.eye(128, dtype=np.float16)[None], 1.0, bits)
+    assert float(rr["scales"][0, 0]) == 0.25 and int(rr["zeros"][0, 0]) == 0
+    assert rr["q"][0, 0, :qmax + 1].tolist() == list(range(qmax + 1))
+    # fewer bits never give a finer grid
+    if bits < 4:
+        finer = fo.kv_transform_quant(kv.k, eye, 1.0, bits + 1)
+        assert np.all(finer["scales"].astype(np.float64) <= s * (1 + 2.0 ** -10))
+
+
 # ---- the comparator itself -----------------------------------------------------------
 def test_comparator_accepts_oracle_and_rejects_planted_mistakes():
     c = synth.tiny()
