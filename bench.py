@@ -240,6 +240,14 @@ def main() -> int:
         by = Tk * H * (2 * D + D // 2 + 4)
         extras["kv_cache"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms * 1e3, "groups_per_s": Tk * H / (ms * 1e-3),
                               "gbs": by / (ms * 1e-3) / 1e9, "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        for bits in (3, 2):   # lower-bit caches: same kernel, D * bits / 8 code bytes per group (into the same buffers)
+            def st_kvb(i, bits=bits):
+                k = i % 8
+                fq.flatquant_kv_transform_quant_bits(kvsets[k], Pk, H, 0.95, bits, Tk, H, D, kc[k], ks[k], kz[k], stream=stream)
+            ms = float(np.median([time_region(st_kvb, 40, 8 if r == 0 else 1)[0] for r in range(5)]))
+            by = Tk * H * (2 * D + D * bits // 8 + 4)
+            extras[f"kv_cache_{bits}bit"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms * 1e3, "groups_per_s": Tk * H / (ms * 1e-3),
+                                            "gbs": by / (ms * 1e-3) / 1e9, "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         # query side: per-head transform, fp16 out (same tensors, 2 x 2D bytes per group)
         qo = [torch.empty((Tk, H, D), dtype=torch.float16, device="cuda") for _ in range(4)]
 

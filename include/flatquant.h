@@ -89,6 +89,22 @@ fq_status flatquant_kv_transform_quant(const void* kv, const void* P, int Hp, fl
                                        void* stream);
 
 /*
+ * The same with b-bit codes, b = bits in {2, 3, 4} (App. "KV Cache Quantization", the tables over key and value bit
+ * widths: the group-wise asymmetric grid of Sec. 4.1 with 2^b levels, Omega(b) = {0 .. 2^b - 1} of Sec. 2.1):
+ *     s = fp16( (mx - mn) / (2^b - 1) ),  z = clamp( round_half_even( -mn / s ), 0, 2^b - 1 ),
+ *     q[d] = clamp( round_half_even( y[d] / s ) + z, 0, 2^b - 1 ).
+ *   out_codes  u8 [T, H, D*b/8]: code d of a group at bits [b d, b d + b) of the group's D*b/8 bytes read as one
+ *              little-endian integer (b = 4: the nibble layout above; b = 2: four codes per byte, lowest channel in
+ *              the lowest bits; b = 3: eight codes per three bytes).  16-byte aligned.
+ * Everything else as for flatquant_kv_transform_quant, which is this call with bits = 4.  Keys and values may use
+ * different widths: one call per tensor.
+ */
+fq_status flatquant_kv_transform_quant_bits(const void* kv, const void* P, int Hp, float clip, int bits,
+                                            int64_t T, int H, int D,
+                                            uint8_t* out_codes, void* out_scales, void* out_zeros,
+                                            void* stream);
+
+/*
  * Per-head transform with fp16 output (Sec. 3.2 "Self-Attention": P_h acts head by head and is not decomposed;
  * queries stay in FP16).  out[t, h, :] = fp16( x[t, h, :] P_h ), fp32 accumulation, one rounding.  With the key cache
  * stored as Q(K P_h) the scores are kept by feeding the queries through this call with P = (P_h^-1)^T
@@ -135,6 +151,13 @@ fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, cons
  */
 fq_status flatquant_dequant(const uint8_t* codes, const void* scales, const void* zeros,
                             int64_t rows, int n, float* out, void* stream);
+
+/*
+ * The same for unsigned b-bit codes in the layout of flatquant_kv_transform_quant_bits (bits in {2, 3, 4}):
+ *   out[r, c] = s[r] * (q[r, c] - z[r]);  codes u8 [rows, n*bits/8]; zeros required; n a multiple of 8.
+ */
+fq_status flatquant_dequant_bits(const uint8_t* codes, const void* scales, const void* zeros,
+                                 int64_t rows, int n, int bits, float* out, void* stream);
 
 /*
  * Measurement aid (not part of the method): moves the bytes of flatquant_transform_quant without its arithmetic.

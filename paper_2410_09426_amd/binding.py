@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_PKG, "libflatquant.so")
 FQ_OK, FQ_INVALID_ARG, FQ_UNSUPPORTED_SHAPE, FQ_MISALIGNED, FQ_LAUNCH_FAILED = range(5)
 
 EXPORTS = (
-    "flatquant_transform_quant", "flatquant_kv_transform_quant", "flatquant_dequant", "flatquant_stream_probe",
+    "flatquant_transform_quant", "flatquant_kv_transform_quant", "flatquant_kv_transform_quant_bits",
+    "flatquant_dequant", "flatquant_dequant_bits", "flatquant_stream_probe",
     "flatquant_weight_transform_quant", "fq_inverse_transpose", "flatquant_head_transform", "flatquant_w4a4_gemm",
     "fq_supported", "fq_choose_factors", "fq_default_design_fits", "fq_lds_bytes",
     "fq_status_string", "fq_last_hip_error", "fq_abi_version",
@@ -48,6 +49,10 @@ def lib() -> ctypes.CDLL:
         L.flatquant_kv_transform_quant.restype = i32
         L.flatquant_dequant.argtypes = [vp, vp, vp, i64, i32, vp, vp]
         L.flatquant_dequant.restype = i32
+        L.flatquant_kv_transform_quant_bits.argtypes = [vp, vp, i32, f32, i32, i64, i32, i32, vp, vp, vp, vp]
+        L.flatquant_kv_transform_quant_bits.restype = i32
+        L.flatquant_dequant_bits.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp]
+        L.flatquant_dequant_bits.restype = i32
         L.flatquant_weight_transform_quant.argtypes = L.flatquant_transform_quant.argtypes
         L.flatquant_weight_transform_quant.restype = i32
         L.flatquant_w4a4_gemm.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, i64, vp]
@@ -115,6 +120,23 @@ def flatquant_kv_transform_quant(kv, P, Hp: int, clip: float, T: int, H: int, D:
                                             _ptr(out_codes), _ptr(out_scales), _ptr(out_zeros), _stream(stream))
     if check and st != FQ_OK:
         raise FlatQuantError(st, "flatquant_kv_transform_quant")
+    return st
+
+
+def flatquant_kv_transform_quant_bits(kv, P, Hp: int, clip: float, bits: int, T: int, H: int, D: int, out_codes, out_scales,
+                                      out_zeros, stream=None, check: bool = True) -> int:
+    st = lib().flatquant_kv_transform_quant_bits(_ptr(kv), _ptr(P), int(Hp), float(clip), int(bits), int(T), int(H), int(D),
+                                                 _ptr(out_codes), _ptr(out_scales), _ptr(out_zeros), _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_kv_transform_quant_bits")
+    return st
+
+
+def flatquant_dequant_bits(codes, scales, zeros, rows: int, n: int, bits: int, out, stream=None, check: bool = True) -> int:
+    st = lib().flatquant_dequant_bits(_ptr(codes), _ptr(scales), _ptr(zeros), int(rows), int(n), int(bits), _ptr(out),
+                                      _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_dequant_bits")
     return st
 
 

@@ -101,7 +101,13 @@ fq_status flatquant_weight_transform_quant(const void* w, const void* A1, const 
 
 fq_status flatquant_kv_transform_quant(const void* kv, const void* P, int Hp, float clip, int64_t T, int H, int D,
                                        uint8_t* out_codes, void* out_scales, void* out_zeros, void* stream) {
+    return flatquant_kv_transform_quant_bits(kv, P, Hp, clip, 4, T, H, D, out_codes, out_scales, out_zeros, stream);
+}
+
+fq_status flatquant_kv_transform_quant_bits(const void* kv, const void* P, int Hp, float clip, int bits, int64_t T, int H, int D,
+                                            uint8_t* out_codes, void* out_scales, void* out_zeros, void* stream) {
     if (T < 0 || H < 1 || D < 1 || !(clip > 0.0f)) return FQ_INVALID_ARG;
+    if (bits < 2 || bits > 4) return FQ_INVALID_ARG;
     if (Hp != 1 && Hp != H) return FQ_INVALID_ARG;
     if (D != 128 || H > 65535) return FQ_UNSUPPORTED_SHAPE;
     if (T == 0) return FQ_OK;
@@ -111,11 +117,14 @@ fq_status flatquant_kv_transform_quant(const void* kv, const void* P, int Hp, fl
         (reinterpret_cast<uintptr_t>(out_zeros) & 1))
         return FQ_MISALIGNED;
     const int64_t g = T * H;
-    if (fq::overlap(kv, g * D * 2, out_codes, g * D / 2) || fq::overlap(kv, g * D * 2, out_scales, g * 2) ||
-        fq::overlap(kv, g * D * 2, out_zeros, g * 2) || fq::overlap(out_scales, g * 2, out_zeros, g * 2))
+    const int64_t cb = g * D * bits / 8;
+    if (fq::overlap(kv, g * D * 2, out_codes, cb) || fq::overlap(kv, g * D * 2, out_scales, g * 2) ||
+        fq::overlap(kv, g * D * 2, out_zeros, g * 2) || fq::overlap(out_scales, g * 2, out_zeros, g * 2) ||
+        fq::overlap(out_codes, cb, out_scales, g * 2) || fq::overlap(out_codes, cb, out_zeros, g * 2))
         return FQ_INVALID_ARG;
     fq::KvArgs a;
     a.kv = static_cast<const _Float16*>(kv); a.P = static_cast<const _Float16*>(P); a.Hp = Hp; a.clip = clip;
+    a.bits = bits;
     a.T = T; a.H = H; a.D = D; a.out_codes = out_codes;
     a.out_scales = static_cast<_Float16*>(out_scales); a.out_zeros = static_cast<_Float16*>(out_zeros);
     return fq::finish(fq::kv_launch(a, static_cast<hipStream_t>(stream)));
@@ -160,6 +169,18 @@ fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, cons
     a.w_codes = w_codes; a.w_scales = static_cast<const _Float16*>(w_scales);
     a.out = static_cast<_Float16*>(out); a.T = T; a.out_stride = out_stride; a.m = m; a.n = n;
     return fq::finish(fq::w4a4_launch(a, static_cast<hipStream_t>(stream)));
+}
+
+fq_status flatquant_dequant_bits(const uint8_t* codes, const void* scales, const void* zeros, int64_t rows, int n, int bits,
+                                 float* out, void* stream) {
+    if (rows < 0 || n < 8 || (n & 7) || bits < 2 || bits > 4) return FQ_INVALID_ARG;
+    if (rows == 0) return FQ_OK;
+    if (!codes || !scales || !zeros || !out) return FQ_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(scales) & 1) || (reinterpret_cast<uintptr_t>(zeros) & 1) ||
+        (reinterpret_cast<uintptr_t>(out) & 3))
+        return FQ_MISALIGNED;
+    return fq::finish(fq::dequant_bits_launch(codes, static_cast<const _Float16*>(scales), static_cast<const _Float16*>(zeros),
+                                              rows, n, bits, out, static_cast<hipStream_t>(stream)));
 }
 
 fq_status flatquant_dequant(const uint8_t* codes, const void* scales, const void* zeros, int64_t rows, int n, float* out,
@@ -266,6 +287,6 @@ const char* fq_status_string(fq_status s) {
 
 int fq_last_hip_error(void) { return fq::g_last_hip_error; }
 
-int fq_abi_version(void) { return 1; }
+int fq_abi_version(void) { return 2; }
 
 }  // extern "C"

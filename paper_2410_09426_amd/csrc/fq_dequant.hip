@@ -26,6 +26,38 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict_
     }
 }
 
+// Unsigned b-bit codes (b = 2, 3, 4), code k of a row at bits [b k, b k + b) of the row's bytes read little-endian:
+// one thread per 8 codes = b bytes.  out = s * (q - z).
+__global__ __launch_bounds__(256) void dequant_bits_kernel(const uint8_t* __restrict__ codes, const _Float16* __restrict__ scales,
+                                                            const _Float16* __restrict__ zeros, int64_t rows, int n, int bits,
+                                                            float* __restrict__ out) {
+    const int units = n >> 3;
+    const int64_t total = rows * units;
+    const uint32_t mask = (1u << bits) - 1u;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = g / units;
+        const int u = (int)(g - r * units);
+        const float s = (float)scales[r];
+        const float z = (float)zeros[r];
+        const uint8_t* src = codes + r * ((int64_t)n * bits / 8) + (int64_t)u * bits;
+        uint32_t v = 0;
+        for (int b = 0; b < bits; ++b) v |= (uint32_t)src[b] << (8 * b);
+        float* dst = out + r * (int64_t)n + 8 * u;
+        for (int k = 0; k < 8; ++k) dst[k] = s * ((float)((v >> (bits * k)) & mask) - z);
+    }
+}
+
+hipError_t dequant_bits_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,
+                               int64_t rows, int n, int bits, float* out, hipStream_t stream) {
+    const int64_t total = rows * (n >> 3);
+    int64_t grid = (total + 255) / 256;
+    const int64_t cap = (int64_t)cu_count() * 16;
+    if (grid > cap) grid = cap;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(dequant_bits_kernel, dim3((unsigned)grid), dim3(256), 0, stream, codes, scales, zeros, rows, n, bits, out);
+    return hipGetLastError();
+}
+
 hipError_t dequant_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,
                           int64_t rows, int n, float* out, hipStream_t stream) {
     const int units = ((n >> 1) + 3) >> 2;

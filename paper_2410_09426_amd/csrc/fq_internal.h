@@ -64,9 +64,12 @@ struct KvArgs {
     _Float16* out_scales;
     _Float16* out_zeros;
     bool fp16_out = false;   // transform only: out_codes points at an fp16 [T, H, D] tensor, no steps / zero points
+    int bits = 4;            // code width of the quantizing mode: 2, 3 or 4
 };
 hipError_t kv_launch(const KvArgs& a, hipStream_t stream);
 
+hipError_t dequant_bits_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,
+                               int64_t rows, int n, int bits, float* out, hipStream_t stream);
 hipError_t dequant_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,
                           int64_t rows, int n, float* out, hipStream_t stream);
 

@@ -1,9 +1,10 @@
-// KV-cache variant for gfx950: per-head dense transform + group-wise asymmetric INT4.
+// KV-cache variant for gfx950: per-head dense transform + group-wise asymmetric b-bit codes.
 //
 // For every (token, head) group of D = 128 values: y = kv_g P_h (Sec. 3.2
 // "Self-Attention": P_h / P_v are applied head by head and are not decomposed),
-// then asymmetric INT4 with one step and one zero point per group (Sec. 4.1
-// "Quantization": group size 128 = head_dim).
+// then asymmetric quantization with one step and one zero point per group (Sec. 4.1
+// "Quantization": group size 128 = head_dim, 4 bits; App. "KV Cache Quantization":
+// the same grid with 3 and 2 bits).
 //
 // Mapping: blockIdx.y is the head, so every wave of a workgroup shares one P_h.
 // P_h is fetched once per workgroup with coalesced 16-byte loads and re-laid in
@@ -14,10 +15,12 @@
 // operand comes straight from global memory (lane <-> token, 16 bytes <-> 8
 // consecutive d) and the next 32 tokens are prefetched into registers while the
 // current ones are in the MFMA pipe.  In the result a lane holds, for its token,
-// 64 of the 128 outputs (the other half-wave holds the rest) in runs of 4
-// consecutive d', so min/max need one cross-half exchange and 4 codes pack into
-// 2 bytes in-lane.  Packed rows are staged per wave in LDS and leave with
-// 16-byte stores.
+// 64 of the 128 outputs (the other half-wave holds the rest).  The M index of a
+// 32-row tile is mapped to d' with its 4-row chunks 1 and 2 swapped (a free choice
+// when the fragments are built), which turns the accumulator layout's runs of 4
+// into runs of 8 consecutive d': 8 codes pack into 4, 3 or 2 whole bytes in-lane.
+// min/max need one cross-half exchange.  Packed rows are staged per wave in LDS
+// and leave with 16-byte stores.
 #include "fq_internal.h"
 
 namespace fq {
@@ -32,8 +35,11 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // (measured on gfx950).  So lane s points at row r0 + s/4, columns col0 + 4(s%4).., and lane i ends up with rows
 // r0..r0+3 of column col0 + i.  `lane16` = lane % 16; `col0` is the first column of the lane's 16-lane block.
 typedef short short4v __attribute__((ext_vector_type(4)));
+// Here lane s points at column chunk swap12(s % 4) instead of s % 4 (chunks of 4 columns, 1 and 2 exchanged), so lane i
+// ends up with column col0 + 4 swap12(i / 4) + i % 4.
 __device__ __forceinline__ half8 lds_column8(const _Float16* m, int pitch, int r0, int gap, int col0, int lane16) {
-    const _Float16* a0 = m + (r0 + (lane16 >> 2)) * pitch + col0 + 4 * (lane16 & 3);
+    const int ch = lane16 & 3, chs = ((ch & 1) << 1) | (ch >> 1);
+    const _Float16* a0 = m + (r0 + (lane16 >> 2)) * pitch + col0 + 4 * chs;
     typedef short4v __attribute__((address_space(3))) * lds_ptr;
     const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(a0));
     const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(a0 + gap * pitch));
@@ -53,7 +59,7 @@ constexpr int KV_D = 128;
 constexpr int KV_WAVES = 4;
 constexpr int KV_NT = 64 * KV_WAVES;
 constexpr int KV_TOK = 32;                 // tokens per wave per step
-constexpr int KV_STAGE_PITCH = 80;         // bytes per staged code row (64 + pad)
+constexpr int KV_STAGE_PITCH = 80;         // bytes per staged code row (up to 64 + pad)
 constexpr int KV_MT = KV_D / 32;           // 4 tiles over d'
 constexpr int KV_KB = KV_D / 16;           // 8 K blocks over d
 constexpr int KV_FRAG_BYTES = KV_MT * KV_KB * 64 * 16;        // 32 KB of A fragments
@@ -77,10 +83,12 @@ struct KvDev {
     float clip;
 };
 
-// QUANT: asymmetric INT4 codes + step + zero point per group.  !QUANT: the transformed rows themselves, rounded to
-// fp16 (p.out_codes then points at an fp16 [T, H, D] tensor): the query side of a transformed key cache.
-template <bool QUANT>
+// BITS = 2, 3, 4: asymmetric codes of that width + step + zero point per group.  BITS = 0: the transformed rows
+// themselves, rounded to fp16 (p.out_codes then points at an fp16 [T, H, D] tensor): the query side of a transformed
+// key cache.
+template <int BITS>
 __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void kv_kernel(KvDev p) {
+    constexpr bool QUANT = BITS != 0;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     u32x4* Pf = reinterpret_cast<u32x4*>(smem);                               // fragment table
     _Float16* Pflat = reinterpret_cast<_Float16*>(smem + KV_FRAG_BYTES);      // prologue only
@@ -114,7 +122,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
     u32x4 cur[KV_KB], nxt[KV_KB];
 
     // ---- P_h: coalesced loads -> LDS (padded pitch) -> A fragments: lane (c, h) of fragment (mt, kb) holds
-    // P_h[16kb + 8h + s][32mt + c], s = 0..7.  The LDS copy is made in two passes of 64 rows (3 workgroups per CU), but
+    // P_h[16kb + 8h + s][32mt + c'], s = 0..7, c' = c with its 4-column chunks 1 and 2 (of each 16) exchanged.  The LDS copy is made in two passes of 64 rows (3 workgroups per CU), but
     // all of P_h is requested up front, and the first token rows only once it has arrived.  A CU's vector memory pipe
     // returns data in request order: if the workgroups that start first queued their rows (HBM) at once, the P_h
     // requests (L2) of the workgroups that start a little later on the same CU would wait behind them for microseconds,
@@ -172,16 +180,17 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
             }
         }
         if constexpr (!QUANT) {
-            // fp16 rows: a lane holds runs of 4 consecutive channels of its token -> 8-byte LDS writes, then whole
+            // fp16 rows: a lane holds runs of 8 consecutive channels of its token -> 16-byte LDS writes, then whole
             // 256-byte rows leave with 16-byte stores (lane -> row l/16 + 4k, chunk l%16)
-            typedef _Float16 half4 __attribute__((ext_vector_type(4)));
             uint8_t* srow = stage + c * KV_OUT_PITCH;
 #pragma unroll
             for (int mt = 0; mt < KV_MT; ++mt)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const half4 v = {(_Float16)acc[mt][4 * g], (_Float16)acc[mt][4 * g + 1], (_Float16)acc[mt][4 * g + 2], (_Float16)acc[mt][4 * g + 3]};
-                    *reinterpret_cast<half4*>(srow + 2 * (32 * mt + 8 * g + 4 * h)) = v;
+                for (int u = 0; u < 2; ++u) {
+                    half8 v;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] = (_Float16)acc[mt][8 * u + k];
+                    *reinterpret_cast<half8*>(srow + 2 * (32 * mt + 16 * u + 8 * h)) = v;
                 }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -210,42 +219,62 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
         mn = __builtin_fminf(mn, __shfl_xor(mn, 32));
         mx *= clip;
         mn *= clip;
-        const _Float16 sh = (_Float16)((mx - mn) * 0.0666666701f);   // (mx - mn) / 15, round-to-nearest-even to fp16
+        constexpr int QB = BITS ? BITS : 4;                        // (the fp16-out instance never gets here)
+        constexpr float LV = (float)((1 << QB) - 1);              // 2^b - 1 intervals
+        const _Float16 sh = (_Float16)((mx - mn) * (1.0f / LV));   // round-to-nearest-even to fp16
         const float s = (float)sh;
         const float inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;
-        const float z = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(-mn * inv), 0.0f), 15.0f);
-        // q = clamp(round(y / s) + z, 0, 15) = round(clamp(y, -z s, (15 - z) s) / s + z): clamp, then one fma against
-        // 1.5 * 2^23 leaves the code in the low mantissa bits (zeros above), so codes chain with shift-adds
+        const float z = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(-mn * inv), 0.0f), LV);
+        // q = clamp(round(y / s) + z, 0, LV) = round(clamp(y, -z s, (LV - z) s) / s + z): clamp, then one fma against
+        // 1.5 * 2^23 leaves 0x4B400000 + code in the register, so 8 codes chain with shift-adds and the constant part
+        // (0x4B400000 times the sum of the shifts, modulo 2^32) is taken off once
         const float sl = (inv != 0.0f) ? s : 0.0f;
-        const float lim_lo = -z * sl, lim_hi = (15.0f - z) * sl;
+        const float lim_lo = -z * sl, lim_hi = (LV - z) * sl;
         const float magic = 12582912.0f + z;
+        constexpr uint32_t kMagicBits = 0x4B400000u;
+        constexpr uint32_t kChainConst = kMagicBits * (1u + (1u << QB) + (1u << 2 * QB) + (1u << 3 * QB) + (QB == 4 ? 0x11110000u : (1u << 4 * QB) + (1u << 5 * QB) + (1u << 6 * QB) + (1u << 7 * QB)));
 
         uint8_t* srow = stage + c * KV_STAGE_PITCH;
 #pragma unroll
         for (int mt = 0; mt < KV_MT; ++mt)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                uint32_t bits[4];
+            for (int u = 0; u < 2; ++u) {
+                uint32_t bits[8];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float yc = __builtin_amdgcn_fmed3f(acc[mt][4 * g + k], lim_lo, lim_hi);
+                for (int k = 0; k < 8; ++k) {
+                    const float yc = __builtin_amdgcn_fmed3f(acc[mt][8 * u + k], lim_lo, lim_hi);
                     bits[k] = __builtin_bit_cast(uint32_t, __builtin_fmaf(yc, inv, magic));
                 }
-                const uint32_t pk = lshl_add(lshl_add(bits[3], 4, bits[2]), 8, lshl_add(bits[1], 4, bits[0]));
-                const int dp = 32 * mt + 8 * g + 4 * h;   // first of 4 consecutive output channels
-                *reinterpret_cast<uint16_t*>(srow + (dp >> 1)) = (uint16_t)pk;
+                const uint32_t lo4 = lshl_add(lshl_add(bits[3], QB, bits[2]), 2 * QB, lshl_add(bits[1], QB, bits[0]));
+                const uint32_t hi4 = lshl_add(lshl_add(bits[7], QB, bits[6]), 2 * QB, lshl_add(bits[5], QB, bits[4]));
+                const uint32_t pk = lshl_add(hi4, 4 * QB, lo4) - kChainConst;   // 8 codes, 8 QB bits, nothing above
+                const int dp = 32 * mt + 16 * u + 8 * h;   // first of 8 consecutive output channels
+                if constexpr (QB == 4) {
+                    *reinterpret_cast<uint32_t*>(srow + (dp >> 1)) = pk;
+                } else if constexpr (QB == 2) {
+                    *reinterpret_cast<uint16_t*>(srow + (dp >> 2)) = (uint16_t)pk;
+                } else {
+                    // 3 bytes at byte 3 dp / 8 = 12 mt + 6 u + 3 h: even for h = 0 (2 bytes, then 1), odd for h = 1 (1, then 2)
+                    uint8_t* dst = srow + 12 * mt + 6 * u + 3 * h;
+                    *reinterpret_cast<uint16_t*>(dst + h) = (uint16_t)(pk >> (8 * h));
+                    dst[2 - 2 * h] = (uint8_t)(pk >> (16 - 16 * h));
+                }
             }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // 32 rows x 64 bytes: lane -> (row l/4 + 16k, 16-byte chunk l%4).  Rows past the end hold a copy of the last
-        // token's row (their lanes re-read its input), so they are stored onto it: same bytes, no branch.
+        // 32 rows x 16 QB bytes: 16-byte unit q = l + 64k -> (row q / QB, chunk q % QB).  Rows past the end hold a copy of
+        // the last token's row (their lanes re-read its input), so they are stored onto it: same bytes, no branch.
         const int64_t g0 = first_group(blk);
+        constexpr int NUNIT = 32 * QB;
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int r = (l >> 2) + 16 * k, ch = l & 3;
-            const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * KV_STAGE_PITCH + 16 * ch);
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.out_codes + g0 * (KV_D / 2)) + (size_t)group_ofs(blk, r) * (KV_D / 32) + ch);
+        for (int k = 0; k < (NUNIT + 63) / 64; ++k) {
+            const int q = l + 64 * k;
+            if (NUNIT % 64 == 0 || q < NUNIT) {
+                const int r = q / QB, ch = q % QB;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * KV_STAGE_PITCH + 16 * ch);
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.out_codes + g0 * (KV_D * QB / 8)) + (size_t)group_ofs(blk, r) * QB + ch);
+            }
         }
         if (h == 0) {   // both half-waves hold the same step and zero point: one of them stores
             const size_t go = group_ofs(blk, c);
@@ -264,13 +293,13 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
     }
 }
 
-template <bool QUANT>
+template <int BITS>
 static hipError_t kv_launch_mode(const KvArgs& a, hipStream_t stream) {
-    constexpr int LDS = QUANT ? KV_LDS_BYTES : KV_OUT_LDS_BYTES;
+    constexpr int LDS = BITS ? KV_LDS_BYTES : KV_OUT_LDS_BYTES;
     static OccCache occ_cache;
     int occ = 0;
     {
-        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(kv_kernel<QUANT>), KV_NT, LDS, occ_cache, occ);
+        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(kv_kernel<BITS>), KV_NT, LDS, occ_cache, occ);
         if (e != hipSuccess) return e;
     }
     const int cap = env_int("FLATQUANT_KV_WG_PER_CU", 0);
@@ -284,12 +313,18 @@ static hipError_t kv_launch_mode(const KvArgs& a, hipStream_t stream) {
     KvDev d;
     d.kv = a.kv; d.P = a.P; d.out_codes = a.out_codes; d.out_scales = a.out_scales; d.out_zeros = a.out_zeros;
     d.T = a.T; d.H = a.H; d.Hp = a.Hp; d.clip = a.clip;
-    hipLaunchKernelGGL(kv_kernel<QUANT>, dim3((unsigned)gx, (unsigned)a.H), dim3(KV_NT), LDS, stream, d);
+    hipLaunchKernelGGL(kv_kernel<BITS>, dim3((unsigned)gx, (unsigned)a.H), dim3(KV_NT), LDS, stream, d);
     return hipGetLastError();
 }
 
 hipError_t kv_launch(const KvArgs& a, hipStream_t stream) {
-    return a.fp16_out ? kv_launch_mode<false>(a, stream) : kv_launch_mode<true>(a, stream);
+    if (a.fp16_out) return kv_launch_mode<0>(a, stream);
+    switch (a.bits) {
+        case 2: return kv_launch_mode<2>(a, stream);
+        case 3: return kv_launch_mode<3>(a, stream);
+        case 4: return kv_launch_mode<4>(a, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace fq

@@ -35,8 +35,11 @@ def run_tq(x, P1, P2, clip, clip_mode, n1, n2, x_stride=None, poison=0xCD, guard
     return codes.cpu().numpy().reshape(T, n // 2), scales.cpu().numpy().view(np.float16).reshape(T), codes, scales
 
 
-def run_dequant(codes_dev, scales_dev, zeros_dev, rows, n):
+def run_dequant(codes_dev, scales_dev, zeros_dev, rows, n, bits=None):
     out = torch.full((rows, n), float("nan"), dtype=torch.float32, device="cuda")
-    fq.flatquant_dequant(codes_dev, scales_dev, zeros_dev, rows, n, out, stream=torch.cuda.current_stream())
+    if bits is None:
+        fq.flatquant_dequant(codes_dev, scales_dev, zeros_dev, rows, n, out, stream=torch.cuda.current_stream())
+    else:
+        fq.flatquant_dequant_bits(codes_dev, scales_dev, zeros_dev, rows, n, bits, out, stream=torch.cuda.current_stream())
     torch.cuda.synchronize()
     return out.cpu().numpy()

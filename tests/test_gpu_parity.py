@@ -212,19 +212,23 @@ def test_determinism_and_empty_input():
 
 
 # ---- KV-cache variant --------------------------------------------------------------------
-def run_kv(kv, P, Hp, clip):
+def run_kv(kv, P, Hp, clip, bits=None):
     T, H, D = kv.shape
     G = T * H
+    nb = G * D * (bits or 4) // 8
     kvd, Pd = dev(kv), dev(P)
-    codes = torch.full((G * D // 2 + 128,), 0xCD, dtype=torch.uint8, device="cuda")
+    codes = torch.full((nb + 128,), 0xCD, dtype=torch.uint8, device="cuda")
     sc = torch.full((G + 64,), -1.0, dtype=torch.float16, device="cuda")
     zr = torch.full((G + 64,), -1.0, dtype=torch.float16, device="cuda")
-    fq.flatquant_kv_transform_quant(kvd, Pd, Hp, clip, T, H, D, codes, sc, zr, stream=torch.cuda.current_stream())
+    if bits is None:
+        fq.flatquant_kv_transform_quant(kvd, Pd, Hp, clip, T, H, D, codes, sc, zr, stream=torch.cuda.current_stream())
+    else:
+        fq.flatquant_kv_transform_quant_bits(kvd, Pd, Hp, clip, bits, T, H, D, codes, sc, zr, stream=torch.cuda.current_stream())
     torch.cuda.synchronize()
-    assert bool((codes[G * D // 2:] == 0xCD).all()) and bool((sc[G:] == -1).all()) and bool((zr[G:] == -1).all())
-    deq = run_dequant(codes, sc, zr, G, D)
+    assert bool((codes[nb:] == 0xCD).all()) and bool((sc[G:] == -1).all()) and bool((zr[G:] == -1).all())
+    deq = run_dequant(codes, sc, zr, G, D, bits)
     from gpu_util import host_f16
-    return codes[:G * D // 2].cpu().numpy().reshape(G, D // 2), host_f16(sc[:G]), host_f16(zr[:G]), deq
+    return codes[:nb].cpu().numpy().reshape(G, nb // G), host_f16(sc[:G]), host_f16(zr[:G]), deq
 
 
 @pytest.mark.parametrize("T,H,shared", [(32768, 8, False), (1, 8, False), (77, 3, False), (200, 8, True), (33, 1, True)])
@@ -237,6 +241,36 @@ def test_kv_cache(T, H, shared):
         y = fo.kv_transform(tensor, P).reshape(T * H, kv.D)
         rep = parity.check_kv(y, kv.clip, codes, sc, zr, deq_dev=deq)
         print(f"[parity] kv {name}: {rep}", flush=True)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("T,H,shared", [(4096 + 5, 8, False), (1, 8, False), (77, 3, False), (33, 1, True)])
+def test_kv_cache_lower_bits(bits, T, H, shared):
+    """Key / value caches at 2, 3 and 4 bits through the width-parametrised entry point (4 must equal the INT4 one)."""
+    kv = synth.kv_cache(T=T, H=H)
+    P = kv.P[:1] if shared else kv.P
+    for name, tensor in (("K", kv.k), ("V", kv.v)):
+        print(f"[case] kv {name} bits={bits} T={T} H={H} shared={shared}", flush=True)
+        codes, sc, zr, deq = run_kv(tensor, P, P.shape[0], kv.clip, bits)
+        assert codes.shape == (T * H, kv.D * bits // 8)
+        y = fo.kv_transform(tensor, P).reshape(T * H, kv.D)
+        rep = parity.check_kv(y, kv.clip, codes, sc, zr, deq_dev=deq, bits=bits)
+        print(f"[parity] kv {name} {bits}-bit: {rep}", flush=True)
+        if bits == 4:
+            c4, s4, z4, _ = run_kv(tensor, P, P.shape[0], kv.clip)
+            assert np.array_equal(c4, codes) and np.array_equal(s4.view(np.uint16), sc.view(np.uint16)) and np.array_equal(z4.view(np.uint16), zr.view(np.uint16))
+
+
+def test_dequant_bits_helper():
+    r = np.random.Generator(np.random.PCG64(4))
+    for bits in (2, 3, 4):
+        for rows, n in [(5, 8), (3, 128), (17, 256)]:
+            q = r.integers(0, 1 << bits, size=(rows, n)).astype(np.uint8)
+            codes = fo.pack_bits(q, bits)
+            scales = (r.uniform(0.1, 4, rows)).astype(np.float16)
+            zeros = r.integers(0, 1 << bits, rows).astype(np.float16)
+            out = run_dequant(dev(codes), dev(scales), dev(zeros), rows, n, bits)
+            assert np.array_equal(out.astype(np.float64), fo.dequantize(codes, scales, zeros, bits))
 
 
 def test_dequant_helper_ragged():

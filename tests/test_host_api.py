@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
     L = fq.lib()
     for name in declared:
         assert hasattr(L, name), name
-    assert fq.fq_abi_version() == 1
+    assert fq.fq_abi_version() == 2
 
 
 def test_factor_rule_and_fit_conditions():
@@ -83,6 +83,18 @@ def test_argument_validation_without_a_device():
     assert kv(kv=A + 8) == fq.FQ_MISALIGNED
     assert kv(out_zeros=None) == fq.FQ_INVALID_ARG
     assert kv(out_zeros=A + 0x500000) == fq.FQ_INVALID_ARG      # scales and zeros alias
+    kvb = lambda **k: fq.flatquant_kv_transform_quant_bits(**{**dict(kv=A, P=A + 0x100000, Hp=8, clip=0.95, bits=3, T=4, H=8, D=128,
+                                                                  out_codes=A + 0x400000, out_scales=A + 0x500000, out_zeros=A + 0x600000,
+                                                                  check=False), **k})
+    assert kvb(T=0) == fq.FQ_OK
+    assert kvb(bits=1) == fq.FQ_INVALID_ARG and kvb(bits=5) == fq.FQ_INVALID_ARG and kvb(bits=8) == fq.FQ_INVALID_ARG
+    assert kvb(D=64) == fq.FQ_UNSUPPORTED_SHAPE and kvb(out_codes=A + 8) == fq.FQ_MISALIGNED
+    assert kvb(out_scales=A + 0x400000) == fq.FQ_INVALID_ARG     # steps inside the code buffer
+    dqb = lambda **k: fq.flatquant_dequant_bits(**{**dict(codes=A, scales=A + 0x100000, zeros=A + 0x180000, rows=4, n=64, bits=3,
+                                                       out=A + 0x200000, check=False), **k})
+    assert dqb(rows=0) == fq.FQ_OK
+    assert dqb(n=60) == fq.FQ_INVALID_ARG and dqb(bits=5) == fq.FQ_INVALID_ARG and dqb(zeros=None) == fq.FQ_INVALID_ARG
+    assert dqb(out=A + 0x200002) == fq.FQ_MISALIGNED
 
     assert fq.flatquant_stream_probe(A, 0, 4096, 4096, A + 0x400000, check=False) == fq.FQ_OK
     assert fq.flatquant_stream_probe(A, 4, 4100, 4100, A + 0x400000, check=False) == fq.FQ_UNSUPPORTED_SHAPE
