@@ -36,6 +36,19 @@ What each function follows
   hardware does it (Sec. 3.2, Sec. 3.3): integer dot products of the codes,
   scaled by the activation step of the row and the weight step of the column.
 
+* mx_* / transform_mxfp4       : the MXFP4 data type the paper's "Limitations"
+  name as the next one to combine with the transform.  The paper defines
+  nothing for it; the format is the published OCP Microscaling one: blocks of
+  32 consecutive channels, one shared power-of-two scale per block stored as
+  its biased exponent (E8M0, bias 127), elements in E2M1 (sign, 2 exponent
+  bits, 1 mantissa bit: magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6).  Conversion as
+  that specification states it: scale = 2^(floor(log2(max|v|)) - 2), elements
+  = v / scale rounded to the nearest E2M1 value (ties to the even code),
+  saturating at +-6, sign kept.  The clipping threshold alpha multiplies the
+  block maximum before the exponent is taken (alpha = 1 is the plain
+  conversion).  PARITY UNPINNED by the paper; pinned by the format's value
+  table and hand-worked cases in the CPU tests.
+
 Conventions fixed where the paper is silent (all listed in the design notes):
 row-major reshape (channel c = i * n2 + j); signed grid [-8, 7] with step
 alpha * max|y| / 7; the step is rounded once to fp16 (round-to-nearest-even,
@@ -264,6 +277,76 @@ def kv_transform_quant(kv, P, clip, bits=4):
     y = kv_transform(kv, P)
     q, s, z, u, zf = kv_quantize_asym(y, clip, bits)
     return {"codes": pack_bits(q, bits), "scales": s, "zeros": z, "q": q, "u": u, "y": y, "zf": zf}
+
+
+# --------------------------------------------------------------------------
+# MXFP4 output (named in the paper's "Limitations"; format: OCP Microscaling)
+# --------------------------------------------------------------------------
+MX_BLOCK = 32
+E2M1_VALUES = (0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0)   # magnitude of codes 0..7; bit 3 is the sign
+
+
+def e2m1_round(u) -> np.ndarray:
+    """fp64 -> E2M1 code (uint8, sign-magnitude): nearest of the 8 magnitudes,
+    a tie goes to the even code, anything beyond 6 saturates, the sign bit is
+    the sign of the input (a negative value that rounds to zero is -0)."""
+    u = as_f64(u)
+    a = np.abs(u)
+    grid = np.asarray(E2M1_VALUES)
+    d = np.abs(a[..., None] - grid)                      # distance to each magnitude
+    best = d.min(axis=-1, keepdims=True)
+    cand = d == best                                     # one or (on a tie) two neighbours
+    even = cand & (np.arange(8) % 2 == 0)
+    pick = np.where(cand.sum(axis=-1, keepdims=True) > 1, even, cand)
+    mag = np.argmax(pick, axis=-1).astype(np.uint8)
+    return (mag | (np.signbit(u).astype(np.uint8) << 3)).astype(np.uint8)
+
+
+def e2m1_value(code) -> np.ndarray:
+    code = np.asarray(code, dtype=np.uint8)
+    v = np.asarray(E2M1_VALUES)[code & 7]
+    return np.where(code & 8, -v, v)
+
+
+def mx_scale_exponent(y, clip) -> np.ndarray:
+    """y [..., n], n a multiple of 32 -> biased exponents uint8 [..., n/32]:
+    floor(log2(alpha * max|block|)) - 2 + 127, kept inside [0, 254]; an
+    all-zero block gets exponent 0."""
+    y = as_f64(y)
+    blocks = y.reshape(y.shape[:-1] + (y.shape[-1] // MX_BLOCK, MX_BLOCK))
+    alpha = np.asarray(clip, dtype=np.float64)
+    if alpha.ndim:                                       # one threshold per token
+        alpha = alpha[..., None]
+    m = alpha * np.max(np.abs(blocks), axis=-1)
+    e = np.zeros(m.shape, dtype=np.int64)
+    nz = m > 0
+    _, ex = np.frexp(m[nz])                              # m = f * 2^ex, f in [0.5, 1): floor(log2 m) = ex - 1
+    e[nz] = (ex - 1) - 2 + 127
+    return np.clip(e, 0, 254).astype(np.uint8)
+
+
+def mx_quantize(y, clip, scale_exp=None):
+    """Returns (codes uint8 [..., n] E2M1, exponents uint8 [..., n/32],
+    u fp64 = y / 2^(e - 127))."""
+    y = as_f64(y)
+    e = mx_scale_exponent(y, clip) if scale_exp is None else np.asarray(scale_exp, dtype=np.uint8)
+    x = np.ldexp(1.0, e.astype(np.int64) - 127)          # exact powers of two
+    u = y / np.repeat(x, MX_BLOCK, axis=-1)
+    return e2m1_round(u), e, u
+
+
+def transform_mxfp4(x, P1, P2, clip, P=None):
+    """Transform (Eq. (2), left factor), then MXFP4 per block of 32 channels.
+    codes are packed two per byte, even channel in the low nibble."""
+    y = affine_transform(x, P1, P2, P)
+    q, e, u = mx_quantize(y, clip)
+    return {"codes": pack_nibbles(q.astype(np.int8)), "scales": e, "q": q, "u": u, "y": y}
+
+
+def dequantize_mxfp4(codes_packed, scale_exp) -> np.ndarray:
+    q = unpack_nibbles(codes_packed, signed=False)
+    x = np.ldexp(1.0, np.asarray(scale_exp).astype(np.int64) - 127)
+    return e2m1_value(q) * np.repeat(x, MX_BLOCK, axis=-1)
 
 
 # --------------------------------------------------------------------------

@@ -130,3 +130,47 @@ def check_kv(y_or, clip, codes_dev, scales_dev, zeros_dev, deq_dev=None, bits=4)
         lim = DEQ_TOL * s_or64[:, None]
         assert np.all(err[plain] <= np.broadcast_to(lim, err.shape)[plain]), "KV dequant error above 1e-2 * s"
     return rep
+
+
+MX_BOUNDARIES = ((0.25, 0.5), (0.75, 0.5), (1.25, 0.5), (1.75, 0.5), (2.5, 1.0), (3.5, 1.0), (5.0, 2.0))   # (tie point, grid spacing there)
+
+
+def check_mx(y_or, clip, codes_dev, exps_dev):
+    """MXFP4 output against the oracle.  y_or fp64 [T, n]; codes u8 [T, n/2]; exps u8 [T, n/32].
+    Shared exponents: identical, except where alpha * max|block| lies within 1e-3 (relative) of a power of two.
+    Codes, taken with the exponent the device emitted: identical magnitude outside 1e-3 of a grid spacing around a
+    tie point; the sign bit must match wherever the magnitude is not zero."""
+    y_or = np.asarray(y_or, dtype=np.float64)
+    T, n = y_or.shape
+    exps_dev = np.asarray(exps_dev, dtype=np.uint8).reshape(T, n // fo.MX_BLOCK)
+    e_or = fo.mx_scale_exponent(y_or, clip)
+    assert np.all(exps_dev <= 254), "NaN scale emitted"
+    ediff = exps_dev != e_or
+    if ediff.any():
+        alpha = np.asarray(clip, dtype=np.float64)
+        if alpha.ndim:
+            alpha = alpha[..., None]
+        m = alpha * np.max(np.abs(y_or.reshape(T, n // fo.MX_BLOCK, fo.MX_BLOCK)), axis=-1)
+        hi = np.maximum(exps_dev, e_or).astype(np.int64)
+        edge = np.ldexp(1.0, hi - 127 + 2)                   # the power of two that separates the two exponents
+        ok = (np.abs(exps_dev.astype(np.int64) - e_or.astype(np.int64)) == 1) & (np.abs(m - edge) <= SCALE_RTOL * edge)
+        assert np.all(ok[ediff]), f"shared exponent mismatch at blocks {np.argwhere(ediff & ~ok)[:8].tolist()}"
+    q_exp, _, u = fo.mx_quantize(y_or, clip, scale_exp=exps_dev)
+    q_dev = fo.unpack_nibbles(codes_dev, signed=False).astype(np.uint8)
+    au = np.abs(u)
+    band = np.zeros(u.shape, dtype=bool)
+    for tie, spacing in MX_BOUNDARIES:
+        band |= np.abs(au - tie) <= BAND * spacing
+    mag_neq = (q_dev & 7) != (q_exp & 7)
+    hard = mag_neq & ~band
+    if hard.any():
+        r, c = np.nonzero(hard)
+        msg = [f"token {i} ch {j}: dev {q_dev[i, j]} oracle {q_exp[i, j]} u {u[i, j]:.6f}" for i, j in list(zip(r, c))[:8]]
+        raise AssertionError(f"{hard.sum()} MXFP4 code mismatches outside the band: " + "; ".join(msg))
+    soft = mag_neq & band
+    if soft.any():   # a flip inside the band must still be one of the two neighbours of the tie point
+        assert np.all(np.abs(fo.e2m1_value(q_dev & 7)[soft] - au[soft]) <= np.abs(fo.e2m1_value(q_exp & 7)[soft] - au[soft]) + 2 * BAND * 2.0)
+    sign_neq = ((q_dev ^ q_exp) & 8) != 0
+    assert not np.any(sign_neq & ((q_dev & 7) != 0)), "sign bit differs on a non-zero code"
+    return {"rows": int(T), "exp_differs": int(ediff.sum()), "in_band": int(band.sum()), "band_flips": int(soft.sum()),
+            "zero_sign_differs": int(sign_neq.sum())}

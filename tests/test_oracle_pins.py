@@ -381,6 +381,77 @@ def test_kv_lower_bit_grid(bits):
         assert np.all(finer["scales"].astype(np.float64) <= s * (1 + 2.0 ** -10))
 
 
+# ---- MXFP4 output (format: OCP Microscaling; named by the paper's "Limitations") -------
+def test_e2m1_values_follow_the_format_definition():
+    # sign, 2 exponent bits (bias 1), 1 mantissa bit; exponent field 0 is subnormal: M * 0.5
+    for code in range(16):
+        sgn, e, m = code >> 3, (code >> 1) & 3, code & 1
+        v = (m * 0.5) if e == 0 else (2.0 ** (e - 1)) * (1 + m / 2)
+        assert float(fo.e2m1_value(np.uint8(code))) == (-v if sgn else v)
+    assert max(fo.E2M1_VALUES) == 6.0 and fo.MX_BLOCK == 32
+
+
+def test_e2m1_rounding_hand_cases_and_arithmetic_route():
+    # ties go to the even code; beyond 6 saturates; the sign is kept, also on a zero result
+    cases = {0.0: 0, 0.2: 0, 0.25: 0, 0.26: 1, 0.5: 1, 0.75: 2, 1.0: 2, 1.25: 2, 1.26: 3, 1.75: 4, 2.5: 4, 2.51: 5, 3.0: 5,
+             3.5: 6, 4.0: 6, 5.0: 6, 5.01: 7, 6.0: 7, 7.0: 7, 1e9: 7, -0.1: 8, -0.25: 8, -0.75: 10, -5.0: 14, -100.0: 15}
+    for v, code in cases.items():
+        assert int(fo.e2m1_round(np.float64(v))) == code, v
+    assert int(fo.e2m1_round(np.float64(-0.0))) == 8
+    # the same rounding done arithmetically: spacing 0.5 * 2^max(floor(log2 a), 0), round-half-even in units of it
+    r = np.random.default_rng(11)
+    u = np.concatenate([r.uniform(-8, 8, 20000), r.normal(0, 1.5, 20000), np.arange(-32, 33) / 4.0])
+    a = np.abs(u)
+    k = np.maximum(np.floor(np.log2(np.where(a > 0, a, 1.0))), 0)
+    sp = 0.5 * 2.0 ** k
+    val = np.minimum(np.rint(a / sp) * sp, 6.0)
+    got = fo.e2m1_value(fo.e2m1_round(u))
+    assert np.array_equal(np.abs(got), val) and np.array_equal(np.signbit(got) | (got == 0), np.signbit(u) | (got == 0))
+
+
+def test_mx_shared_exponent_and_block_properties():
+    blk = np.zeros((1, 64))
+    for mx, e in [(6.0, 127), (5.99, 127), (7.9, 127), (8.0, 128), (4.0, 127), (3.99, 126), (1.0, 125), (0.9, 124), (2.0 ** -20, 105)]:
+        blk[0, :32] = 0.0
+        blk[0, 7] = -mx                       # the maximum is taken over magnitudes
+        blk[0, 40] = 2 * mx                   # the second block has its own exponent
+        ex = fo.mx_scale_exponent(blk, 1.0)
+        assert ex.tolist() == [[e, e + 1]], (mx, ex)
+    assert fo.mx_scale_exponent(np.zeros((2, 32)), 1.0).tolist() == [[0], [0]]
+    c = synth.tiny()
+    y = fo.affine_transform(c.x, c.P1, c.P2)
+    y = np.concatenate([y, y], axis=-1)[:, :64] if y.shape[-1] < 64 else y[:, : (y.shape[-1] // 32) * 32]
+    q, e, u = fo.mx_quantize(y, 1.0)
+    ub = np.abs(u).reshape(u.shape[0], -1, 32)
+    top = ub.max(-1)
+    assert np.all((top >= 4.0) & (top < 8.0) | (top == 0))         # the block maximum lands in the top binade
+    assert np.all(((q.reshape(ub.shape) & 7).max(-1) >= 6) | (top == 0))
+    deq = fo.dequantize_mxfp4(fo.pack_nibbles(q.astype(np.int8)), e)
+    x = np.repeat(np.ldexp(1.0, e.astype(np.int64) - 127), 32, axis=-1)
+    au = np.abs(u)
+    spacing = np.where(au < 2, 0.5, np.where(au < 4, 1.0, 2.0))
+    bound = np.where(au <= 6, spacing / 2, au - 6) * x
+    assert np.all(np.abs(deq - y) <= bound * (1 + 1e-12))
+    # idempotent: what comes out is on the grid of its own block
+    q2, e2, _ = fo.mx_quantize(deq, 1.0)
+    assert np.array_equal(e2, e) and np.array_equal(q2 & 7, q & 7)
+    # the clipping threshold multiplies the block maximum: alpha = 1/2 lowers every exponent by one
+    assert np.array_equal(fo.mx_scale_exponent(y, 0.5).astype(int), e.astype(int) - 1)
+    per_tok = np.full(y.shape[0], 0.5)
+    assert np.array_equal(fo.mx_scale_exponent(y, per_tok), fo.mx_scale_exponent(y, 0.5))
+    # the comparator accepts the oracle and rejects planted mistakes (CPU only)
+    codes = fo.pack_nibbles(q.astype(np.int8))
+    rep = parity.check_mx(y, 1.0, codes, e)
+    assert rep["band_flips"] == 0 and rep["exp_differs"] == 0
+    with pytest.raises(AssertionError):
+        parity.check_mx(y, 1.0, codes, e + 1)
+    with pytest.raises(AssertionError):
+        parity.check_mx(y, 1.0, ((codes << 4) | (codes >> 4)).astype(np.uint8), e)
+    trunc = (np.searchsorted(np.asarray(fo.E2M1_VALUES), np.minimum(np.abs(u), 6.0), side="right") - 1).astype(np.uint8) | (q & 8)
+    with pytest.raises(AssertionError):
+        parity.check_mx(y, 1.0, fo.pack_nibbles(trunc.astype(np.int8)), e)
+
+
 # ---- the comparator itself -----------------------------------------------------------
 def test_comparator_accepts_oracle_and_rejects_planted_mistakes():
     c = synth.tiny()
