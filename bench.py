@@ -224,6 +224,19 @@ def main() -> int:
         if not args.no_wide:
             time_shape("prefill_70b_28672", 16384, 112, 256, 5, 1, cold_sets=1)
 
+        # MXFP4 output on the headline shape (2n + n/2 + n/32 bytes per token + clip), cold rotation like the headline
+        mxs = [torch.empty((T, n // 32), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+        mxc = [torch.empty((T, n // 2), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+
+        def st_mx(i):
+            k = i % nsets
+            fq.flatquant_transform_mxfp4(xs[k], P1, P2, clips[k], 1, T, n1, n2, n, mxc[k], mxs[k], stream=stream)
+        ms = float(np.median([time_region(st_mx, 200, 20)[0] for r in range(5)]))
+        by = T * (2 * n + n // 2 + n // 32 + 4)
+        extras["mxfp4_prefill_7b"] = {"T": T, "n1": n1, "n2": n2, "us_per_call": ms * 1e3, "tokens_per_s": T / (ms * 1e-3),
+                                      "gbs": by / (ms * 1e-3) / 1e9, "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del mxs, mxc
+
         # KV-cache variant: 32768 tokens x 8 heads x 128, K and V alternate (two distinct 67 MB inputs + more sets for cold)
         Tk, H, D = 32768, 8, 128
         g = torch.Generator(device="cuda").manual_seed(99)

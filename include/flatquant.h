@@ -69,6 +69,24 @@ fq_status flatquant_transform_quant(const void* x, const void* P1, const void* P
                                     uint8_t* out_codes, void* out_scales, void* stream);
 
 /*
+ * The same transform with MXFP4 output, the data type the paper's "Limitations" name as the next one to combine with
+ * the method (the paper defines nothing for it; the format is the published OCP Microscaling one).  Per token row and
+ * per block of 32 consecutive channels c = 32 b .. 32 b + 31 of Y = P1^T X~ P2 (flattened row-major as above):
+ *     e  = clamp( floor(log2( clip * max|y_block| )) - 2 + 127, 0, 254 )    shared scale 2^(e - 127), stored as e (E8M0);
+ *                                                                            an all-zero block stores e = 0
+ *     q  = E2M1( y / 2^(e - 127) )   nearest of +-{0, 0.5, 1, 1.5, 2, 3, 4, 6}, ties to the even code, saturating,
+ *                                    code = sign << 3 | magnitude index (a negative value that rounds to zero is -0)
+ *   out_codes  u8 [T, n/2], even channel in the low nibble, 16-byte aligned.
+ *   out_scales u8 [T, n/32], 4-byte aligned.
+ * Shapes: n2 = 64, 128 or 256, n1 <= 128, n a multiple of 128; x 16-byte aligned with x_stride a multiple of 8; P1 4-byte
+ * and P2 16-byte aligned, both required.  Other arguments, T == 0 and error behaviour as for flatquant_transform_quant.
+ */
+fq_status flatquant_transform_mxfp4(const void* x, const void* P1, const void* P2,
+                                    const float* clip, int clip_mode,
+                                    int64_t T, int n1, int n2, int64_t x_stride,
+                                    uint8_t* out_codes, uint8_t* out_scales, void* stream);
+
+/*
  * KV-cache path (Sec. 3.2 "Self-Attention": P_h / P_v applied head by head,
  * not decomposed; Sec. 4.1: group-wise asymmetric INT4, group = head_dim).
  * For every (token, head) group g of D values:
@@ -151,6 +169,12 @@ fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, cons
  */
 fq_status flatquant_dequant(const uint8_t* codes, const void* scales, const void* zeros,
                             int64_t rows, int n, float* out, void* stream);
+
+/*
+ * The same for the output of flatquant_transform_mxfp4: out[r, c] = E2M1 value of code (r, c) times 2^(e[r, c/32] - 127).
+ *   codes u8 [rows, n/2] (4-byte aligned), scales u8 [rows, n/32], out fp32 [rows, n]; n a multiple of 32.
+ */
+fq_status flatquant_dequant_mxfp4(const uint8_t* codes, const uint8_t* scales, int64_t rows, int n, float* out, void* stream);
 
 /*
  * The same for unsigned b-bit codes in the layout of flatquant_kv_transform_quant_bits (bits in {2, 3, 4}):

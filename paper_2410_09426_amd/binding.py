@@ -18,7 +18,7 @@ FQ_OK, FQ_INVALID_ARG, FQ_UNSUPPORTED_SHAPE, FQ_MISALIGNED, FQ_LAUNCH_FAILED = r
 
 EXPORTS = (
     "flatquant_transform_quant", "flatquant_kv_transform_quant", "flatquant_kv_transform_quant_bits",
-    "flatquant_dequant", "flatquant_dequant_bits", "flatquant_stream_probe",
+    "flatquant_dequant", "flatquant_dequant_bits", "flatquant_stream_probe", "flatquant_transform_mxfp4", "flatquant_dequant_mxfp4",
     "flatquant_weight_transform_quant", "fq_inverse_transpose", "flatquant_head_transform", "flatquant_w4a4_gemm",
     "fq_supported", "fq_choose_factors", "fq_default_design_fits", "fq_lds_bytes",
     "fq_status_string", "fq_last_hip_error", "fq_abi_version",
@@ -45,6 +45,10 @@ def lib() -> ctypes.CDLL:
         vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float
         L.flatquant_transform_quant.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i64, vp, vp, vp]
         L.flatquant_transform_quant.restype = i32
+        L.flatquant_transform_mxfp4.argtypes = L.flatquant_transform_quant.argtypes
+        L.flatquant_transform_mxfp4.restype = i32
+        L.flatquant_dequant_mxfp4.argtypes = [vp, vp, i64, i32, vp, vp]
+        L.flatquant_dequant_mxfp4.restype = i32
         L.flatquant_kv_transform_quant.argtypes = [vp, vp, i32, f32, i64, i32, i32, vp, vp, vp, vp]
         L.flatquant_kv_transform_quant.restype = i32
         L.flatquant_dequant.argtypes = [vp, vp, vp, i64, i32, vp, vp]
@@ -120,6 +124,22 @@ def flatquant_kv_transform_quant(kv, P, Hp: int, clip: float, T: int, H: int, D:
                                             _ptr(out_codes), _ptr(out_scales), _ptr(out_zeros), _stream(stream))
     if check and st != FQ_OK:
         raise FlatQuantError(st, "flatquant_kv_transform_quant")
+    return st
+
+
+def flatquant_transform_mxfp4(x, P1, P2, clip, clip_mode: int, T: int, n1: int, n2: int, x_stride: int, out_codes, out_scales,
+                              stream=None, check: bool = True) -> int:
+    st = lib().flatquant_transform_mxfp4(_ptr(x), _ptr(P1), _ptr(P2), _ptr(clip), int(clip_mode), int(T), int(n1), int(n2),
+                                         int(x_stride), _ptr(out_codes), _ptr(out_scales), _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_transform_mxfp4")
+    return st
+
+
+def flatquant_dequant_mxfp4(codes, scales, rows: int, n: int, out, stream=None, check: bool = True) -> int:
+    st = lib().flatquant_dequant_mxfp4(_ptr(codes), _ptr(scales), int(rows), int(n), _ptr(out), _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_dequant_mxfp4")
     return st
 
 

@@ -92,6 +92,34 @@ fq_status flatquant_transform_quant(const void* x, const void* P1, const void* P
     return fq::finish(fq::tq_launch(a, static_cast<hipStream_t>(stream)));
 }
 
+fq_status flatquant_transform_mxfp4(const void* x, const void* P1, const void* P2, const float* clip, int clip_mode,
+                                    int64_t T, int n1, int n2, int64_t x_stride, uint8_t* out_codes, uint8_t* out_scales,
+                                    void* stream) {
+    if (T < 0 || n1 < 1 || n2 < 1 || (clip_mode != 0 && clip_mode != 1)) return FQ_INVALID_ARG;
+    const int64_t n = (int64_t)n1 * n2;
+    if (x_stride < n) return FQ_INVALID_ARG;
+    if (n1 > fq::kMaxN1 || !(n2 == 64 || n2 == 128 || n2 == 256) || n % 128 != 0) return FQ_UNSUPPORTED_SHAPE;
+    if (T == 0) return FQ_OK;
+    if (!x || !P1 || !P2 || !clip || !out_codes || !out_scales) return FQ_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(x) & 15) || (x_stride & 7) || (reinterpret_cast<uintptr_t>(P1) & 3) ||
+        (reinterpret_cast<uintptr_t>(P2) & 15) || (reinterpret_cast<uintptr_t>(clip) & 3) ||
+        (reinterpret_cast<uintptr_t>(out_codes) & 15) || (reinterpret_cast<uintptr_t>(out_scales) & 3))
+        return FQ_MISALIGNED;
+    const int64_t xbytes = ((T - 1) * x_stride + n) * 2;
+    if (fq::overlap(x, xbytes, out_codes, T * (n / 2)) || fq::overlap(x, xbytes, out_scales, T * (n / 32)) ||
+        fq::overlap(out_codes, T * (n / 2), out_scales, T * (n / 32)))
+        return FQ_INVALID_ARG;
+    fq::TqArgs a;
+    a.x = static_cast<const _Float16*>(x);
+    a.P1 = static_cast<const _Float16*>(P1);
+    a.P2 = static_cast<const _Float16*>(P2);
+    a.clip = clip; a.clip_mode = clip_mode; a.T = T; a.n1 = n1; a.n2 = n2; a.x_stride = x_stride;
+    a.out_codes = out_codes; a.out_scales = reinterpret_cast<_Float16*>(out_scales);
+    const fq::TqDev d = fq::tq_dev_args(a);
+    if (!fq::tq_mx_applicable(d)) return FQ_UNSUPPORTED_SHAPE;
+    return fq::finish(fq::tq_mx_launch(d, static_cast<hipStream_t>(stream)));
+}
+
 fq_status flatquant_weight_transform_quant(const void* w, const void* A1, const void* A2, const float* clip, int clip_mode,
                                            int64_t m, int n1, int n2, int64_t w_stride, uint8_t* out_codes,
                                            void* out_scales, void* stream) {
@@ -169,6 +197,14 @@ fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, cons
     a.w_codes = w_codes; a.w_scales = static_cast<const _Float16*>(w_scales);
     a.out = static_cast<_Float16*>(out); a.T = T; a.out_stride = out_stride; a.m = m; a.n = n;
     return fq::finish(fq::w4a4_launch(a, static_cast<hipStream_t>(stream)));
+}
+
+fq_status flatquant_dequant_mxfp4(const uint8_t* codes, const uint8_t* scales, int64_t rows, int n, float* out, void* stream) {
+    if (rows < 0 || n < 32 || (n & 31)) return FQ_INVALID_ARG;
+    if (rows == 0) return FQ_OK;
+    if (!codes || !scales || !out) return FQ_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(codes) & 3) || (reinterpret_cast<uintptr_t>(out) & 3)) return FQ_MISALIGNED;
+    return fq::finish(fq::dequant_mxfp4_launch(codes, scales, rows, n, out, static_cast<hipStream_t>(stream)));
 }
 
 fq_status flatquant_dequant_bits(const uint8_t* codes, const void* scales, const void* zeros, int64_t rows, int n, int bits,

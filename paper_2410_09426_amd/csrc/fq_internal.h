@@ -46,6 +46,11 @@ struct TqDev {
 bool tq_fast_applicable(const TqDev& d);
 int64_t tq_fast_lds_bytes(int n1, int n2);
 hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream);
+// MXFP4 output variant of the specialised kernels (d.out_scales points at the u8 [T, n/32] shared exponents).
+bool tq_mx_applicable(const TqDev& d);
+hipError_t tq_mx_launch(const TqDev& d, hipStream_t stream);
+// Fills the kernel-side block from the checked arguments (alignment facts included).
+TqDev tq_dev_args(const TqArgs& a);
 
 // LDS bytes of the fused activation kernel for (n1, n2); 0 if unsupported.
 int64_t tq_lds_bytes(int n1, int n2);
@@ -68,6 +73,7 @@ struct KvArgs {
 };
 hipError_t kv_launch(const KvArgs& a, hipStream_t stream);
 
+hipError_t dequant_mxfp4_launch(const uint8_t* codes, const uint8_t* exps, int64_t rows, int n, float* out, hipStream_t stream);
 hipError_t dequant_bits_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,
                                int64_t rows, int n, int bits, float* out, hipStream_t stream);
 hipError_t dequant_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,

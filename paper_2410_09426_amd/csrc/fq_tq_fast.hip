@@ -119,9 +119,15 @@ __device__ __forceinline__ half8 lds_column8(const _Float16* m, int pitch, int r
 // TPW (KIND 2, one wave per token only): tokens per workgroup.  The waves of a workgroup share the staging of P1 and
 // P2 (the bytes every workgroup pulls through its CU's vector memory path on top of its tokens) and nothing else:
 // after the fragments are built each wave works on its own token, tile and staged codes, with no workgroup barrier.
-template <int A, int B, int SPW, bool FULL1, int KIND, bool ID2 = false, int TPW = 1>
+// MX: MXFP4 output instead of INT4 (the data type the paper's "Limitations" name next; OCP Microscaling format): every
+// 32 consecutive channels (one row of X~, one 32-column slab: exactly the 32 values a lane pair (c, 0), (c, 1) holds
+// after the second contraction) share a power-of-two scale 2^(floor(log2(alpha max|y|)) - 2), stored as its biased
+// exponent; elements are y / scale rounded to E2M1 by v_cvt_scalef32_pk_fp4_f32 (nearest, ties to even, saturating).
+// No per-token absmax, so no exchange between waves.  p.out_scales then points at the u8 [T, n/32] exponents.
+template <int A, int B, int SPW, bool FULL1, int KIND, bool ID2 = false, int TPW = 1, bool MX = false>
 __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_per_eu((KIND == 2 && SPW == 1) ? 4 : 2))) void tq_fast_kernel(TqDev p, const float* __restrict__ clip) {
     static_assert(B % SPW == 0 && 16 % SPW == 0, "slabs per wave must divide the slab count and 16");
+    static_assert(!MX || (KIND != 1 && SPW == 1 && TPW == 1 && !ID2), "MXFP4 output: plain loop or one token per workgroup");
     static_assert(TPW == 1 || (KIND == 2 && B == SPW && A <= 2), "several tokens per workgroup: loop-free kernel, one wave per token");
     constexpr bool PIPE = (KIND == 1), ONE = (KIND == 2);
     using L = FastLds<A, B, PIPE ? 2 : TPW>;
@@ -138,6 +144,7 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
     _Float16* Xs = reinterpret_cast<_Float16*>(smem);
     uint8_t* stage = smem + NBUF * L::XS_BYTES;
     float* red = reinterpret_cast<float*>(smem + NBUF * (L::XS_BYTES + L::STAGE_BYTES));
+    uint8_t* mxs = smem + L::TOTAL;               // MX only: shared exponents of one token, [32 A rows][B slabs]
     u32x4* P1s = reinterpret_cast<u32x4*>(smem + L::R0);
     _Float16* P1flat = reinterpret_cast<_Float16*>(smem);
     _Float16* P2flat = reinterpret_cast<_Float16*>(smem + L::P1FLAT_BYTES);
@@ -479,6 +486,30 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
         // rows past n1 land in the unused tail of the stage buffer (it holds 32 A rows): no branch around the write
         *reinterpret_cast<uint16_t*>(stg + stage_lane + 32 * It * L::SPITCH + (32 * q + 8 * g) / 2) = (uint16_t)pk;
     };
+    // MXFP4: per (row of X~, slab) block of 32 channels; 4 consecutive channels of a lane -> 2 bytes, as for INT4
+    auto mx_quant_to_stage = [&](const f32x16 (&acc2)[SPW][A], float clipv) {
+        uint8_t* stg = stage;
+#pragma unroll
+        for (int q = 0; q < SPW; ++q)
+#pragma unroll
+            for (int It = 0; It < A; ++It) {
+                float m = 0.0f;
+#pragma unroll
+                for (int r = 0; r < 16; r += 2) m = __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(acc2[q][It][r])), __builtin_fabsf(acc2[q][It][r + 1]));
+                m = __builtin_fmaxf(m, __shfl_xor(m, 32)) * clipv;
+                const int be = (int)((__builtin_bit_cast(uint32_t, m) >> 23) & 0xffu);   // biased exponent of alpha * max
+                const int e = be > 2 ? be - 2 : 0;
+                // exponent 0 is reached only by an all-zero block (or one below 2^-125): any scale gives zero codes
+                const float scale = __builtin_bit_cast(float, (uint32_t)(e > 0 ? e : 1) << 23);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    uint32_t pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, acc2[q][It][4 * g], acc2[q][It][4 * g + 1], scale, 0);
+                    pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(pk, acc2[q][It][4 * g + 2], acc2[q][It][4 * g + 3], scale, 1);
+                    *reinterpret_cast<uint16_t*>(stg + stage_lane + 32 * It * L::SPITCH + (32 * q + 8 * g) / 2) = (uint16_t)pk;
+                }
+                if (h == 0) mxs[(32 * It + c) * B + w * SPW + q] = (uint8_t)e;
+            }
+    };
     auto quant_to_stage = [&](const f32x16 (&acc2)[SPW][A], float m, float clipv, int buf) -> _Float16 {
         const Step st = make_step(m, clipv);
 #pragma unroll
@@ -502,7 +533,13 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
             const int nq = n1 * B;
             for (int q = tid; q < nq; q += NT) __builtin_nontemporal_store(stg[(q / B) * (B + 1) + q % B], dst + q);
         }
-        p.out_scales[t] = sh;   // every lane writes the same two bytes: cheaper than a branch around the store
+        if constexpr (MX) {   // n1 * B exponent bytes of the token, a multiple of 4 (checked on the host)
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(mxs);
+            uint32_t* dsc = reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(p.out_scales) + t * ((int64_t)n1 * B));
+            for (int i = tid; i < n1 * B / 4; i += NT) dsc[i] = src[i];
+        } else {
+            p.out_scales[t] = sh;   // every lane writes the same two bytes: cheaper than a branch around the store
+        }
     };
     // Requests are always issued (past the end they re-read the last row): an unconditional request lets the
     // compiler count outstanding loads exactly, so a later wait covers only the older row.
@@ -515,10 +552,15 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
         const float clipv = clip[p.clip_mode ? t : 0];
         f32x16 acc2[SPW][A];
         gemm(ts, acc2, [](int) {});   // [phase:contractions done]
-        absmax_to_lds(acc2, ts);
-        token_sync();                // [phase:absmax exchanged]
-        const float m = absmax_from_lds(ts);
-        const _Float16 sh = quant_to_stage(acc2, m, clipv, ts);   // [phase:codes staged]
+        _Float16 sh = (_Float16)0.0f;
+        if constexpr (MX) {
+            mx_quant_to_stage(acc2, clipv);
+        } else {
+            absmax_to_lds(acc2, ts);
+            token_sync();                // [phase:absmax exchanged]
+            const float m = absmax_from_lds(ts);
+            sh = quant_to_stage(acc2, m, clipv, ts);   // [phase:codes staged]
+        }
         token_sync();
         if (live) copy_out(t, ts, sh);   // [phase:token done]
     } else if constexpr (!PIPE) {
@@ -530,10 +572,15 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
             const float clipv = clip[p.clip_mode ? t : 0];   // wave-uniform address, read-only: a scalar load
             f32x16 acc2[SPW][A];
             gemm(0, acc2, [](int) {});   // [phase:contractions done]
-            absmax_to_lds(acc2, 0);
+            if constexpr (!MX) absmax_to_lds(acc2, 0);
             __syncthreads();   // (A) every wave is also done reading the token tile [phase:absmax exchanged]
-            const float m = absmax_from_lds(0);
-            const _Float16 sh = quant_to_stage(acc2, m, clipv, 0);
+            _Float16 sh = (_Float16)0.0f;
+            if constexpr (MX) {
+                mx_quant_to_stage(acc2, clipv);
+            } else {
+                const float m = absmax_from_lds(0);
+                sh = quant_to_stage(acc2, m, clipv, 0);
+            }
             // [phase:codes staged]
             commit(pre_next);   // past the end this is the re-read last row; nobody uses it
             __syncthreads();    // (B) staged codes and the next tile are visible [phase:next tile in LDS]
@@ -652,6 +699,75 @@ static Variant variant(int A, int B, bool full1, int mode) {
         case 3: return variant_a<3>(B, full1, mode);
         default: return variant_a<4>(B, full1, mode);
     }
+}
+
+// MXFP4 output: n2 = 64, 128 or 256; loop-free kernel while every token gets a resident workgroup (64-wide rows), else
+// the plain persistent loop.  The shared exponents of a token are staged in LDS behind the kernel's usual carve-up.
+template <int A, int B>
+static Variant variant_mx_ab(bool full1, bool one) {
+    if constexpr (A <= 2 && B == 2) {
+        if (one && full1) return Variant{&tq_fast_kernel<A, B, 1, true, 2, false, 1, true>, FastLds<A, B>::TOTAL + 32 * A * B};
+    }
+    return full1 ? Variant{&tq_fast_kernel<A, B, 1, true, 0, false, 1, true>, FastLds<A, B>::TOTAL + 32 * A * B}
+                 : Variant{&tq_fast_kernel<A, B, 1, false, 0, false, 1, true>, FastLds<A, B>::TOTAL + 32 * A * B};
+}
+
+template <int A>
+static Variant variant_mx_a(int B, bool full1, bool one) {
+    switch (B) {
+        case 2: return variant_mx_ab<A, 2>(full1, one);
+        case 4: return variant_mx_ab<A, 4>(full1, one);
+        default: return variant_mx_ab<A, 8>(full1, one);
+    }
+}
+
+static Variant variant_mx(int A, int B, bool full1, bool one) {
+    switch (A) {
+        case 1: return variant_mx_a<1>(B, full1, one);
+        case 2: return variant_mx_a<2>(B, full1, one);
+        case 3: return variant_mx_a<3>(B, full1, one);
+        default: return variant_mx_a<4>(B, full1, one);
+    }
+}
+
+bool tq_mx_applicable(const TqDev& d) {
+    if (!(d.n2 == 64 || d.n2 == 128 || d.n2 == 256) || d.n1 < 1 || d.n1 > kMaxN1) return false;
+    if (((int64_t)d.n1 * d.n2) % 128 != 0 || !d.vec8 || !d.out_vec16 || !d.P1 || !d.P2) return false;
+    if ((reinterpret_cast<uintptr_t>(d.P2) & 15) || (reinterpret_cast<uintptr_t>(d.P1) & 3)) return false;
+    return (reinterpret_cast<uintptr_t>(d.out_scales) & 3) == 0;
+}
+
+hipError_t tq_mx_launch(const TqDev& d, hipStream_t stream) {
+    const int A = (d.n1 + 31) / 32, B = d.n2 / 32;
+    const bool full1 = (d.n1 % 32) == 0;
+    static OccCache occ_cache[4][8][2][2];
+    auto occupancy = [&](bool one, int& occ) -> hipError_t {
+        const Variant v = variant_mx(A, B, full1, one);
+        return kernel_occupancy(reinterpret_cast<const void*>(v.fn), 64 * B, v.lds, occ_cache[A - 1][B - 1][full1][one], occ);
+    };
+    bool one = false;
+    int occ = 0;
+    if (A <= 2 && B == 2 && full1 && d.T <= 0x7fffffff) {
+        hipError_t e = occupancy(true, occ);
+        if (e != hipSuccess) return e;
+        one = d.T <= (int64_t)cu_count() * occ;
+        const int force = env_int("FLATQUANT_MODE", -1);
+        if (force == 0) one = false;
+        if (force == 3) one = true;
+    }
+    if (!one) {
+        hipError_t e = occupancy(false, occ);
+        if (e != hipSuccess) return e;
+    }
+    const Variant v = variant_mx(A, B, full1, one);
+    int64_t grid = d.T;
+    if (!one) {
+        const int64_t resident = (int64_t)cu_count() * occ;
+        const int64_t rounds = (d.T + resident - 1) / resident;
+        grid = (d.T + rounds - 1) / rounds;
+    }
+    hipLaunchKernelGGL(v.fn, dim3((unsigned)grid), dim3(64 * B), v.lds, stream, d, d.clip);
+    return hipGetLastError();
 }
 
 bool tq_fast_applicable(const TqDev& d) {

@@ -305,12 +305,7 @@ int64_t tq_lds_bytes(int n1, int n2) {
     return f > b ? f : b;
 }
 
-hipError_t tq_launch(const TqArgs& a, hipStream_t stream) {
-    const int A = (a.n1 + 31) / 32, B = (a.n2 + 31) / 32;
-    KernelFn fn = kernel_table(A, B);
-    const int lds = (int)generic_lds_bytes(a.n1, a.n2);
-    const int nt = 64 * B;
-
+TqDev tq_dev_args(const TqArgs& a) {
     TqDev d;
     d.x = a.x; d.P1 = a.P1; d.P2 = a.P2; d.clip = a.clip;
     d.out_codes = a.out_codes; d.out_scales = a.out_scales;
@@ -318,6 +313,16 @@ hipError_t tq_launch(const TqArgs& a, hipStream_t stream) {
     d.vec8 = (a.n2 % 8 == 0) && (a.x_stride % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0);
     const int64_t n = (int64_t)a.n1 * a.n2;
     d.out_vec16 = (n % 32 == 0) && ((reinterpret_cast<uintptr_t>(a.out_codes) & 15) == 0);
+    return d;
+}
+
+hipError_t tq_launch(const TqArgs& a, hipStream_t stream) {
+    const int A = (a.n1 + 31) / 32, B = (a.n2 + 31) / 32;
+    KernelFn fn = kernel_table(A, B);
+    const int lds = (int)generic_lds_bytes(a.n1, a.n2);
+    const int nt = 64 * B;
+
+    const TqDev d = tq_dev_args(a);
     // FLATQUANT_FORCE_GENERIC=1 keeps the general kernel testable on shapes the specialised ones would take
     if (tq_fast_applicable(d) && env_int("FLATQUANT_FORCE_GENERIC", 0) == 0) return tq_fast_launch(d, stream);
 

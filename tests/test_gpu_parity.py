@@ -211,6 +211,50 @@ def test_determinism_and_empty_input():
     assert fq.flatquant_transform_quant(x, P1, P2, clip, 1, 0, 64, 64, 4096, None, None) == fq.FQ_OK
 
 
+# ---- MXFP4 output ------------------------------------------------------------------------
+def run_mx(c, rows=None):
+    x, P1, P2, clip = dev(c.x), dev(c.P1), dev(c.P2), dev(c.clip)
+    T, n = c.T, c.n
+    cbuf = torch.full((T * (n // 2) + 256,), 0xCD, dtype=torch.uint8, device="cuda")
+    sbuf = torch.full((T * (n // 32) + 256,), 0xCD, dtype=torch.uint8, device="cuda")
+    fq.flatquant_transform_mxfp4(x, P1, P2, clip, c.clip_mode, T, c.n1, c.n2, n, cbuf, sbuf, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert bool((cbuf[T * (n // 2):] == 0xCD).all()) and bool((sbuf[T * (n // 32):] == 0xCD).all()), "guard band overwritten"
+    codes = cbuf[:T * (n // 2)].cpu().numpy().reshape(T, n // 2)
+    exps = sbuf[:T * (n // 32)].cpu().numpy().reshape(T, n // 32)
+    if T <= 600:   # the de-quantization helper returns exactly value * 2^(e - 127)
+        deq = torch.full((T, n), float("nan"), dtype=torch.float32, device="cuda")
+        fq.flatquant_dequant_mxfp4(cbuf, sbuf, T, n, deq, stream=torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        assert np.array_equal(deq.cpu().numpy().astype(np.float64), fo.dequantize_mxfp4(codes, exps))
+    sel = np.arange(T) if rows is None else np.asarray(rows)
+    y = fo.affine_transform_factored(c.x[sel], c.P1, c.P2)
+    clip_h = c.clip[sel] if c.clip_mode else float(c.clip[0])
+    rep = parity.check_mx(y, clip_h, codes[sel], exps[sel])
+    print(f"[parity] mxfp4 {c.name} T={T} {c.n1}x{c.n2}: {rep}", flush=True)
+    return codes, exps
+
+
+@pytest.mark.parametrize("mode", ["-1", "0", "3"])
+def test_mxfp4_output(monkeypatch, mode):
+    if mode != "-1":
+        monkeypatch.setenv("FLATQUANT_MODE", mode)
+    c = synth.prefill_7b(2048 if mode == "-1" else 515)
+    run_mx(c, rows=subset_rows(c.T, 160, 21, must=(0, 1, c.T - 1)))
+    c = synth.generic(400 + int(mode), 70, 64, 128)
+    run_mx(c)
+    if mode == "-1":
+        for seed, T, n1, n2 in ((411, 33, 86, 128), (412, 9, 112, 256), (413, 1, 32, 64), (414, 300, 2, 64), (415, 40, 50, 256),
+                                (416, 2600, 64, 64)):
+            c = synth.generic(seed, T, n1, n2, clip_mode=seed % 2)
+            run_mx(c, rows=None if T <= 300 else subset_rows(T, 120, 22, must=(0, T - 1)))
+        # zero rows: exponent 0, all codes +0
+        c = synth.generic(417, 6, 64, 64)
+        c.x[2] = 0
+        codes, exps = run_mx(c)
+        assert not codes[2].any() and not exps[2].any()
+
+
 # ---- KV-cache variant --------------------------------------------------------------------
 def run_kv(kv, P, Hp, clip, bits=None):
     T, H, D = kv.shape

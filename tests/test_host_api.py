@@ -73,6 +73,19 @@ def test_argument_validation_without_a_device():
     with pytest.raises(fq.FlatQuantError):
         fq.flatquant_transform_quant(None, A, A, A, 0, 4, 64, 64, 4096, A, A)
 
+    mx = lambda **k: fq.flatquant_transform_mxfp4(**{**dict(x=A, P1=A + 0x100000, P2=A + 0x200000, clip=A + 0x300000, clip_mode=1, T=4, n1=64,
+                                                         n2=64, x_stride=4096, out_codes=A + 0x400000, out_scales=A + 0x500000, check=False), **k})
+    assert mx(T=0) == fq.FQ_OK
+    assert mx(n2=96, x_stride=64 * 96) == fq.FQ_UNSUPPORTED_SHAPE and mx(n1=129, x_stride=129 * 64) == fq.FQ_UNSUPPORTED_SHAPE
+    assert mx(n1=3, n2=64, x_stride=192) == fq.FQ_UNSUPPORTED_SHAPE      # n not a multiple of 128
+    assert mx(P2=None) == fq.FQ_INVALID_ARG and mx(clip_mode=2) == fq.FQ_INVALID_ARG
+    assert mx(x=A + 8) == fq.FQ_MISALIGNED and mx(out_scales=A + 0x500002) == fq.FQ_MISALIGNED and mx(x_stride=4100) == fq.FQ_MISALIGNED
+    assert mx(out_scales=A + 0x400000) == fq.FQ_INVALID_ARG            # exponents inside the code buffer
+
+    dmx = lambda **k: fq.flatquant_dequant_mxfp4(**{**dict(codes=A, scales=A + 0x100000, rows=4, n=64, out=A + 0x200000, check=False), **k})
+    assert dmx(rows=0) == fq.FQ_OK and dmx(n=48) == fq.FQ_INVALID_ARG and dmx(scales=None) == fq.FQ_INVALID_ARG
+    assert dmx(codes=A + 2) == fq.FQ_MISALIGNED
+
     kv = lambda **k: fq.flatquant_kv_transform_quant(**{**dict(kv=A, P=A + 0x100000, Hp=8, clip=0.95, T=4, H=8, D=128,
                                                             out_codes=A + 0x400000, out_scales=A + 0x500000, out_zeros=A + 0x600000,
                                                             check=False), **k})
