@@ -11,8 +11,8 @@
 //
 // Workgroup: 4 waves, C tile 128 tokens x 128 output channels, each wave 64 x 64 (2 x 2 MFMA tiles; the weights are
 // the MFMA's first operand so that a lane ends up with runs of 4 consecutive output channels of one token).  K advances by
-// 256 codes (128 bytes = one cache line per row) per iteration through double-buffered LDS tiles; the next tiles are
-// requested into registers before the MFMAs of the current ones, one barrier per iteration.
+// 256 codes (128 bytes = one cache line per row) per iteration through double-buffered LDS tiles, one barrier per
+// iteration; a tile is requested into registers a whole iteration before it is written to LDS.
 #include "fq_internal.h"
 
 namespace fq {
@@ -76,21 +76,24 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
         bsrc[k] = reinterpret_cast<const u32x4*>(p.wc + (int64_t)orow * kbytes) + ch;
         ldst[k] = row * GPITCH + ch * 16;
     }
-    u32x4 ra[NLD], rb[NLD];
-    auto issue = [&](int it) {
+    // two register sets: a tile is requested two iterations before it is written to LDS
+    struct Regs { u32x4 a[NLD], b[NLD]; };
+    Regs r0, r1;
+    auto issue = [&](int it, Regs& r) {   // past the last tile the last one is re-read (nobody uses it): no branch in the loop body
+        const int itc = it < nk ? it : nk - 1;
 #pragma unroll
         for (int k = 0; k < NLD; ++k) {
-            ra[k] = asrc[k][it * (GKB / 16)];
-            rb[k] = bsrc[k][it * (GKB / 16)];
+            r.a[k] = asrc[k][itc * (GKB / 16)];
+            r.b[k] = bsrc[k][itc * (GKB / 16)];
         }
     };
-    auto commit = [&](int buf) {
+    auto commit = [&](int buf, const Regs& r) {
         unsigned char* A = smem + buf * G_TILE_BYTES;
         unsigned char* B = smem + (2 + buf) * G_TILE_BYTES;
 #pragma unroll
         for (int k = 0; k < NLD; ++k) {
-            *reinterpret_cast<u32x4*>(A + ldst[k]) = ra[k];
-            *reinterpret_cast<u32x4*>(B + ldst[k]) = rb[k];
+            *reinterpret_cast<u32x4*>(A + ldst[k]) = r.a[k];
+            *reinterpret_cast<u32x4*>(B + ldst[k]) = r.b[k];
         }
     };
 
@@ -106,51 +109,67 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
         const int o = o0 + tid;
         reinterpret_cast<float*>(smem + 4 * G_TILE_BYTES)[tid] = (o < p.m) ? (float)p.ws[o] : 0.0f;
     }
-    issue(0);
-    commit(0);
-    __syncthreads();
     const int aoff = (64 * wm + c) * GPITCH + 16 * h;
     const int boff = (64 * wn + c) * GPITCH + 16 * h;
-    for (int it = 0; it < nk; ++it) {
-        const int buf = it & 1;
-        if (it + 1 < nk) issue(it + 1);
-        const unsigned char* A = smem + buf * G_TILE_BYTES + aoff;
-        const unsigned char* B = smem + (2 + buf) * G_TILE_BYTES + boff;
-        // the packed operands of K step pair kp + 1 are read from LDS while pair kp goes through the MFMAs
-        constexpr int NKP = GKB / 32;
-        u32x4 pa[2][2], pb[2][2];
+    constexpr int NKP = GKB / 32;   // K step pairs (64 codes) per tile
+    static_assert(NKP >= 4 && NKP % 2 == 0, "the pipeline below reads two step pairs ahead and alternates two register stages");
+    // packed operands of one K step pair: x = 0, 1: tokens 32 x + c (A); x = 2, 3: output channels 32 (x - 2) + c (B)
+    auto lds_chunk = [&](int buf, int kp, int x) -> u32x4 {
+        const unsigned char* base = smem + ((x >> 1) * 2 + buf) * G_TILE_BYTES + ((x >> 1) ? boff : aoff);
+        return *reinterpret_cast<const u32x4*>(base + 32 * (x & 1) * GPITCH + 32 * kp);
+    };
+    // Software pipeline over K step pairs g = it * NKP + kp, three stages deep: while the MFMAs of pair g run on the
+    // widened operands W[g & 1], pair g + 1 is widened from its packed registers P[(g + 1) & 1] into W[(g + 1) & 1] and
+    // pair g + 2 is read from LDS into P[g & 1].  The work is cut into 8 slices per pair, one MFMA followed by one
+    // slice of widening (6 vector instructions, shorter than the MFMA) and at most one LDS read, in this order in
+    // the instruction stream: a wave issues in order, so only vector work that sits between two MFMAs can run in
+    // the shadow of the first.
+    u32x4 P[2][4];
+    i32x4 W[2][4][2];   // [stage][operand x][K step s]
+    issue(0, r0);
+    commit(0, r0);
+    issue(1, r1);
+    issue(2, r0);
+    __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            pa[0][i] = *reinterpret_cast<const u32x4*>(A + 32 * i * GPITCH);
-            pb[0][i] = *reinterpret_cast<const u32x4*>(B + 32 * i * GPITCH);
-        }
+    for (int x = 0; x < 4; ++x) { P[0][x] = lds_chunk(0, 0, x); P[1][x] = lds_chunk(0, 1, x); }
+    constexpr unsigned M = 0xF0F0F0F0u;
+    auto widen_slice = [&](const u32x4& w, int s) -> i32x4 {
+        return i32x4{(int)((w[2 * s] << 4) & M), (int)(w[2 * s] & M), (int)((w[2 * s + 1] << 4) & M), (int)(w[2 * s + 1] & M)};
+    };
+#pragma unroll
+    for (int x = 0; x < 4; ++x) { W[0][x][0] = widen_slice(P[0][x], 0); W[0][x][1] = widen_slice(P[0][x], 1); }
+    // one iteration: tile `it` through the MFMAs; tile it + 1 (in `rn`, requested two iterations ago) goes to LDS and
+    // its registers take tile it + 3
+    auto iteration = [&](int it, int buf, Regs& rn) {
 #pragma unroll
         for (int kp = 0; kp < NKP; ++kp) {
-            if (kp + 1 < NKP) {
+            const int cur = kp & 1, nxt = cur ^ 1;           // NKP is even: the stage parity of pair g is that of kp
+            const int fkp = (kp + 2) % NKP;                   // pair g + 2: in this tile, or the first pairs of the next one
+            const int fbuf = (kp + 2 < NKP) ? buf : buf ^ 1;
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    pa[(kp + 1) & 1][i] = *reinterpret_cast<const u32x4*>(A + 32 * i * GPITCH + 32 * (kp + 1));
-                    pb[(kp + 1) & 1][i] = *reinterpret_cast<const u32x4*>(B + 32 * i * GPITCH + 32 * (kp + 1));
-                }
-                __builtin_amdgcn_sched_barrier(0);   // keep these reads ahead of the arithmetic on pair kp
+            for (int m = 0; m < 8; ++m) {
+                const int s = m >> 2, i = (m >> 1) & 1, j = m & 1;
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(W[cur][2 + j][s], W[cur][i][s], acc[i][j], 0, 0, 0);
+                W[nxt][m >> 1][m & 1] = widen_slice(P[nxt][m >> 1], m & 1);
+                // P[cur] was widened during the previous pair: its registers take pair g + 2
+                if (m >= 4) P[cur][m - 4] = lds_chunk(fbuf, fkp, m - 4);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            i32x4 a[2][2], b[2][2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                widen(pa[kp & 1][i], a[i][0], a[i][1]);
-                widen(pb[kp & 1][i], b[i][0], b[i][1]);
+            if (kp == NKP - 3) {
+                // the next tile has had two iterations to arrive; its buffer was last read during pair NKP - 3 of
+                // the previous iteration, before that iteration's barrier
+                commit(buf ^ 1, rn);
+                issue(it + 3, rn);
+                __syncthreads();
             }
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[j][s], a[i][s], acc[i][j], 0, 0, 0);
         }
-        if (it + 1 < nk) commit(buf ^ 1);
-        __syncthreads();
+    };
+    for (int it = 0; it < nk; it += 2) {
+        iteration(it, 0, r1);
+        if (it + 1 < nk) iteration(it + 1, 1, r0);
     }
+    __syncthreads();   // every wave is done with the K tiles: the epilogue reuses their space
 
     // epilogue.  The weights are the MFMA's first operand, so in acc[i][j] a lane holds, for token 64 wm + 32 i + c,
     // the output channels 64 wn + 32 j + 8 (r / 4) + 4 h + r % 4: runs of 4 consecutive channels.  They are scaled,
