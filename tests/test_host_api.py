@@ -23,6 +23,37 @@ def test_library_exports_every_declared_symbol():
     assert fq.fq_abi_version() == 2
 
 
+def test_header_is_plain_c_and_links_without_python(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 (and C++), and a C program must link against the
+    shared library and call the host-only entry points."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use.c"
+    src.write_text(
+        '#include "flatquant.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        "    int n1 = 0, n2 = 0;\n"
+        "    if (fq_choose_factors(8192, &n1, &n2) != FQ_OK || n1 != 64 || n2 != 128) return 1;\n"
+        "    if (!fq_supported(64, 64) || fq_supported(129, 64)) return 2;\n"
+        "    if (flatquant_transform_quant(0, 0, 0, 0, 0, 0, 64, 64, 4096, 0, 0, 0) != FQ_OK) return 3;      /* T == 0 */\n"
+        "    if (flatquant_transform_mxfp4(0, 0, 0, 0, 0, 4, 64, 96, 6144, 0, 0, 0) != FQ_UNSUPPORTED_SHAPE) return 4;\n"
+        '    printf("%s %d\\n", fq_status_string(FQ_MISALIGNED), fq_abi_version());\n'
+        "    return 0;\n}\n")
+    inc = os.path.join(ROOT, "include")
+    libdir = os.path.dirname(fq.LIB_PATH)
+    exe = tmp_path / "use"
+    subprocess.run([cc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, str(src), "-o", str(exe),
+                    "-L", libdir, "-lflatquant", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert out[-1] == str(fq.fq_abi_version()) and len(out) >= 2
+    cxx = shutil.which("g++")
+    if cxx:
+        subprocess.run([cxx, "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)], check=True)
+
+
 def test_factor_rule_and_fit_conditions():
     # Sec. 3.1: argmin(n1 + n2), n1 <= n2; (64, 128) for 8192
     assert fq.fq_choose_factors(8192) == (64, 128)
