@@ -12,7 +12,7 @@
 // Workgroup: 4 waves, C tile 128 tokens x 128 output channels, each wave 64 x 64 (2 x 2 MFMA tiles; the weights are
 // the MFMA's first operand so that a lane ends up with runs of 4 consecutive output channels of one token).  K advances by
 // 256 codes (128 bytes = one cache line per row) per iteration through double-buffered LDS tiles, one barrier per
-// iteration; a tile is requested into registers a whole iteration before it is written to LDS.
+// iteration; the tiles go from global memory straight into LDS, a whole iteration before they are read.
 #include "fq_internal.h"
 
 namespace fq {
@@ -26,7 +26,8 @@ constexpr int GT = 128;               // tile edge, tokens and output channels
 #define FQ_GKB 128
 #endif
 constexpr int GKB = FQ_GKB;              // packed bytes of K per row and iteration (256 codes)
-constexpr int GPITCH = GKB + 16;      // LDS row pitch: 16-byte operand reads of 32 consecutive rows fall on distinct banks
+constexpr int GPITCH = GKB;           // LDS row pitch: rows are written by global-to-LDS loads, 8 whole rows per wave and
+                                      // instruction, so there is no padding; the 16-byte chunks of a row are swizzled instead
 constexpr int G_NT = 256;
 constexpr int G_TILE_BYTES = GT * GPITCH;
 constexpr int G_LDS_BYTES = 4 * G_TILE_BYTES + GT * 4;   // A and B, two buffers each, + the weight steps of the tile
@@ -60,41 +61,41 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     const int64_t kbytes = p.n / 2;
     const int nk = p.n / (2 * GKB);
 
-    // tile loads: chunk q = tid + 256 k -> row q / CPR, 16-byte chunk q % CPR; rows past the end re-read the last row
-    constexpr int CPR = GKB / 16, NLD = GT * CPR / G_NT;
-    const u32x4* asrc[NLD];
-    const u32x4* bsrc[NLD];
-    int ldst[NLD];
+    // Tile loads go from global memory straight into LDS (global_load_lds_dwordx4: lane i of a wave writes 16 bytes at
+    // the wave's LDS base + 16 i, from any global address).  One instruction fills 8 rows of 128 bytes; wave w owns rows
+    // 32 w .. 32 w + 31 of both tiles (4 instructions per operand and iteration).  LDS slot j of row r holds the row's
+    // chunk j ^ ((r >> 1) & 7): with that swizzle the 16-byte operand reads of 32 consecutive rows (same chunk) spread
+    // over all banks although the pitch is a multiple of the bank width.  Rows past the end re-read the last row.
+    static_assert(GKB == 128 && GT == 128 && G_NT == 256, "load mapping below");
+    constexpr int NLD = 4;
+    const unsigned char* asrc[NLD];
+    const unsigned char* bsrc[NLD];
 #pragma unroll
     for (int k = 0; k < NLD; ++k) {
-        const int q = tid + G_NT * k, row = q / CPR, ch = q % CPR;
+        const int row = 8 * (4 * w + k) + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
         int64_t tr = t0 + row;
         if (tr >= p.T) tr = p.T - 1;
         int orow = o0 + row;
         if (orow >= p.m) orow = p.m - 1;
-        asrc[k] = reinterpret_cast<const u32x4*>(p.xc + tr * kbytes) + ch;
-        bsrc[k] = reinterpret_cast<const u32x4*>(p.wc + (int64_t)orow * kbytes) + ch;
-        ldst[k] = row * GPITCH + ch * 16;
+        asrc[k] = p.xc + tr * kbytes + 16 * ch;
+        bsrc[k] = p.wc + (int64_t)orow * kbytes + 16 * ch;
     }
-    // two register sets: a tile is requested two iterations before it is written to LDS
-    struct Regs { u32x4 a[NLD], b[NLD]; };
-    Regs r0, r1;
-    auto issue = [&](int it, Regs& r) {   // past the last tile the last one is re-read (nobody uses it): no branch in the loop body
+    typedef const __attribute__((address_space(1))) void* gptr;
+    typedef __attribute__((address_space(3))) void* lptr;
+    auto issue = [&](int it, int buf) {   // past the last tile the last one is re-read (nobody uses it): no branch in the loop body
         const int itc = it < nk ? it : nk - 1;
+        unsigned char* A = smem + buf * G_TILE_BYTES + w * (32 * GPITCH);
+        unsigned char* B = smem + (2 + buf) * G_TILE_BYTES + w * (32 * GPITCH);
 #pragma unroll
         for (int k = 0; k < NLD; ++k) {
-            r.a[k] = asrc[k][itc * (GKB / 16)];
-            r.b[k] = bsrc[k][itc * (GKB / 16)];
+            __builtin_amdgcn_global_load_lds((gptr)(asrc[k] + (int64_t)itc * GKB), (lptr)(A + k * 8 * GPITCH), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr)(bsrc[k] + (int64_t)itc * GKB), (lptr)(B + k * 8 * GPITCH), 16, 0, 0);
         }
     };
-    auto commit = [&](int buf, const Regs& r) {
-        unsigned char* A = smem + buf * G_TILE_BYTES;
-        unsigned char* B = smem + (2 + buf) * G_TILE_BYTES;
-#pragma unroll
-        for (int k = 0; k < NLD; ++k) {
-            *reinterpret_cast<u32x4*>(A + ldst[k]) = r.a[k];
-            *reinterpret_cast<u32x4*>(B + ldst[k]) = r.b[k];
-        }
+    // the tile requested last has arrived in LDS (this wave's part), then every wave's part has
+    auto tile_ready = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
     };
 
     i32x16 acc[2][2];
@@ -109,14 +110,15 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
         const int o = o0 + tid;
         reinterpret_cast<float*>(smem + 4 * G_TILE_BYTES)[tid] = (o < p.m) ? (float)p.ws[o] : 0.0f;
     }
-    const int aoff = (64 * wm + c) * GPITCH + 16 * h;
-    const int boff = (64 * wn + c) * GPITCH + 16 * h;
+    const int aoff = (64 * wm + c) * GPITCH;
+    const int boff = (64 * wn + c) * GPITCH;
+    const int hs = h ^ ((c >> 1) & 7);   // chunk 2 kp + h of row 32 x + c sits in slot (2 kp) ^ hs (the row's swizzle is that of c)
     constexpr int NKP = GKB / 32;   // K step pairs (64 codes) per tile
     static_assert(NKP >= 4 && NKP % 2 == 0, "the pipeline below reads two step pairs ahead and alternates two register stages");
     // packed operands of one K step pair: x = 0, 1: tokens 32 x + c (A); x = 2, 3: output channels 32 (x - 2) + c (B)
     auto lds_chunk = [&](int buf, int kp, int x) -> u32x4 {
         const unsigned char* base = smem + ((x >> 1) * 2 + buf) * G_TILE_BYTES + ((x >> 1) ? boff : aoff);
-        return *reinterpret_cast<const u32x4*>(base + 32 * (x & 1) * GPITCH + 32 * kp);
+        return *reinterpret_cast<const u32x4*>(base + 32 * (x & 1) * GPITCH + 16 * ((2 * kp) ^ hs));
     };
     // Software pipeline over K step pairs g = it * NKP + kp, three stages deep: while the MFMAs of pair g run on the
     // widened operands W[g & 1], pair g + 1 is widened from its packed registers P[(g + 1) & 1] into W[(g + 1) & 1] and
@@ -126,11 +128,9 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     // the shadow of the first.
     u32x4 P[2][4];
     i32x4 W[2][4][2];   // [stage][operand x][K step s]
-    issue(0, r0);
-    commit(0, r0);
-    issue(1, r1);
-    issue(2, r0);
-    __syncthreads();
+    issue(0, 0);
+    tile_ready();
+    issue(1, 1);
 #pragma unroll
     for (int x = 0; x < 4; ++x) { P[0][x] = lds_chunk(0, 0, x); P[1][x] = lds_chunk(0, 1, x); }
     constexpr unsigned M = 0xF0F0F0F0u;
@@ -139,9 +139,9 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     };
 #pragma unroll
     for (int x = 0; x < 4; ++x) { W[0][x][0] = widen_slice(P[0][x], 0); W[0][x][1] = widen_slice(P[0][x], 1); }
-    // one iteration: tile `it` through the MFMAs; tile it + 1 (in `rn`, requested two iterations ago) goes to LDS and
-    // its registers take tile it + 3
-    auto iteration = [&](int it, int buf, Regs& rn) {
+    // one iteration: tile `it` (LDS buffer `buf`) through the MFMAs.  After pair NKP - 3 nobody reads that buffer any
+    // more (the later pairs were read ahead), so behind the barrier that publishes tile it + 1 it takes tile it + 2.
+    auto iteration = [&](int it, int buf) {
 #pragma unroll
         for (int kp = 0; kp < NKP; ++kp) {
             const int cur = kp & 1, nxt = cur ^ 1;           // NKP is even: the stage parity of pair g is that of kp
@@ -157,19 +157,16 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (kp == NKP - 3) {
-                // the next tile has had two iterations to arrive; its buffer was last read during pair NKP - 3 of
-                // the previous iteration, before that iteration's barrier
-                commit(buf ^ 1, rn);
-                issue(it + 3, rn);
-                __syncthreads();
+                tile_ready();
+                issue(it + 2, buf);
             }
         }
     };
     for (int it = 0; it < nk; it += 2) {
-        iteration(it, 0, r1);
-        if (it + 1 < nk) iteration(it + 1, 1, r0);
+        iteration(it, 0);
+        if (it + 1 < nk) iteration(it + 1, 1);
     }
-    __syncthreads();   // every wave is done with the K tiles: the epilogue reuses their space
+    tile_ready();   // no load is still writing, every wave is done with the K tiles: the epilogue reuses their space
 
     // epilogue.  The weights are the MFMA's first operand, so in acc[i][j] a lane holds, for token 64 wm + 32 i + c,
     // the output channels 64 wn + 32 j + 8 (r / 4) + 4 h + r % 4: runs of 4 consecutive channels.  They are scaled,
