@@ -397,6 +397,42 @@ def test_weight_side_parity_and_quantized_layer(T, m, n1, n2):
     assert abs(rel - rel_o) <= 1e-3 * max(rel_o, 1e-6) + 1e-6 * (int(flips_x.sum()) + int(flips_w.sum()) + 1)
 
 
+def test_mxfp4_layer_both_factors():
+    """The same two-factor layer with MXFP4 on both sides: the weight rows go through flatquant_transform_mxfp4 with
+    the inverse-transposed factors; the product of the two de-quantized factors must agree with the oracle's."""
+    T, m, n1, n2 = 96, 160, 64, 64
+    n = n1 * n2
+    c, W, cw, A1, A2 = _layer_case(T, m, n1, n2, 9, 760)
+
+    def mx(xa, Pa, Pb, clip, rows):
+        cbuf = torch.empty((rows, n // 2), dtype=torch.uint8, device="cuda")
+        sbuf = torch.empty((rows, n // 32), dtype=torch.uint8, device="cuda")
+        fq.flatquant_transform_mxfp4(dev(xa), dev(Pa), dev(Pb), dev(clip), 1, rows, n1, n2, n, cbuf, sbuf, stream=torch.cuda.current_stream())
+        deq = torch.empty((rows, n), dtype=torch.float32, device="cuda")
+        fq.flatquant_dequant_mxfp4(cbuf, sbuf, rows, n, deq, stream=torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        return cbuf.cpu().numpy(), sbuf.cpu().numpy(), deq.cpu().numpy().astype(np.float64)
+
+    xc, xe, xq = mx(c.x, c.P1, c.P2, c.clip, T)
+    wc, we, wq = mx(W, A1, A2, cw, m)
+    parity.check_mx(fo.affine_transform_factored(c.x, c.P1, c.P2), c.clip, xc, xe)
+    parity.check_mx(fo.weight_transform_factored(W, A1, A2), cw, wc, we)
+    ox = fo.transform_mxfp4(c.x, c.P1, c.P2, c.clip)
+    qw, ew, _ = fo.mx_quantize(fo.weight_transform_factored(W, A1, A2), cw)
+    xo = fo.dequantize_mxfp4(ox["codes"], ox["scales"])
+    wo = fo.dequantize_mxfp4(fo.pack_nibbles(qw.astype(np.int8)), ew)
+    Yq, Yo = xq @ wq.T, xo @ wo.T
+    Y = c.x.astype(np.float64) @ W.astype(np.float64).T
+    # elements that differ (rounding ties inside the comparator's band) move one factor by at most one grid step
+    dx, dw = np.abs(xq - xo), np.abs(wq - wo)
+    slack = dx.sum(1)[:, None] * np.abs(wo).max(1)[None, :] + dw.sum(1)[None, :] * np.abs(xo).max(1)[:, None] + dx.sum(1)[:, None] * dw.max(1)[None, :]
+    assert np.all(np.abs(Yq - Yo) <= slack * (1 + 1e-9) + 1e-9 * np.abs(Yo) + 1e-12)
+    rel, rel_o = np.linalg.norm(Yq - Y) / np.linalg.norm(Y), np.linalg.norm(Yo - Y) / np.linalg.norm(Y)
+    print(f"[layer] MXFP4 x MXFP4 {n1}x{n2}: relative error of the layer output {rel:.4f} (oracle's codes: {rel_o:.4f}); "
+          f"elements that differ x {int((dx > 0).sum())} w {int((dw > 0).sum())}", flush=True)
+    assert abs(rel - rel_o) <= 1e-3 * rel_o + 1e-6 * (int((dx > 0).sum()) + int((dw > 0).sum()) + 1)
+
+
 # ---- one-sided transforms (a factor left out = identity) ------------------------------------------------------------
 @pytest.mark.parametrize("n1,n2,T,which", [(32, 128, 200, "P1 only"), (32, 128, 3000, "P1 only"), (64, 64, 2048, "P1 only"),
                                            (64, 128, 2500, "P1 only"), (64, 128, 129, "P1 only"), (32, 128, 1, "P1 only"),
