@@ -36,7 +36,7 @@ What each function follows
   hardware does it (Sec. 3.2, Sec. 3.3): integer dot products of the codes,
   scaled by the activation step of the row and the weight step of the column.
 
-* mx_* / transform_mxfp4       : the MXFP4 data type the paper's "Limitations"
+* mx_* / transform_mxfp4 / mxfp4_gemm : the MXFP4 data type the paper's "Limitations"
   name as the next one to combine with the transform.  The paper defines
   nothing for it; the format is the published OCP Microscaling one: blocks of
   32 consecutive channels, one shared power-of-two scale per block stored as
@@ -347,6 +347,18 @@ def dequantize_mxfp4(codes_packed, scale_exp) -> np.ndarray:
     q = unpack_nibbles(codes_packed, signed=False)
     x = np.ldexp(1.0, np.asarray(scale_exp).astype(np.int64) - 127)
     return e2m1_value(q) * np.repeat(x, MX_BLOCK, axis=-1)
+
+
+def mxfp4_gemm(x_codes, x_exps, w_codes, w_exps):
+    """Product of two MXFP4 factors, the low-bit matrix multiplication of
+    Sec. 3.2 with the data type of the "Limitations": out[t, o] = sum_k x^[t, k]
+    w^[o, k] with x^, w^ the de-quantized factors (element times the block's
+    power of two).  Returns (y fp64, y rounded once to fp16, sum_k |x^ w^|,
+    which bounds what any summation order can lose)."""
+    xd = dequantize_mxfp4(x_codes, x_exps)
+    wd = dequantize_mxfp4(w_codes, w_exps)
+    y = xd @ wd.T
+    return y, round_to_fp16(y), np.abs(xd) @ np.abs(wd).T
 
 
 # --------------------------------------------------------------------------

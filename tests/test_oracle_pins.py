@@ -452,6 +452,32 @@ def test_mx_shared_exponent_and_block_properties():
         parity.check_mx(y, 1.0, fo.pack_nibbles(trunc.astype(np.int8)), e)
 
 
+def test_mxfp4_product_hand_set_and_brute_force():
+    # one token, one channel, n = 32: x = [1.0, 6.0, -0.5, 0...] * 2^1, w = [3.0, -1.5, 4.0, 0...] * 2^-2
+    xc = np.zeros((1, 16), dtype=np.uint8); wc = np.zeros((1, 16), dtype=np.uint8)
+    xc[0, 0] = 0x72; xc[0, 1] = 0x09          # codes 2 (1.0), 7 (6.0), 9 (-0.5), 0
+    wc[0, 0] = 0xB5; wc[0, 1] = 0x06          # codes 5 (3.0), 11 (-1.5), 6 (4.0), 0
+    y, y16, ab = fo.mxfp4_gemm(xc, np.array([[128]], dtype=np.uint8), wc, np.array([[125]], dtype=np.uint8))
+    want = (1.0 * 3.0 + 6.0 * -1.5 + -0.5 * 4.0) * 2.0 * 0.25
+    assert y[0, 0] == want == -4.0 and float(y16[0, 0]) == -4.0 and ab[0, 0] == (3.0 + 9.0 + 2.0) * 0.5
+    r = np.random.default_rng(17)
+    T, m, n = 5, 7, 96
+    xc = r.integers(0, 256, size=(T, n // 2), dtype=np.uint8); wc = r.integers(0, 256, size=(m, n // 2), dtype=np.uint8)
+    xe = r.integers(120, 132, size=(T, n // 32), dtype=np.uint8); we = r.integers(118, 130, size=(m, n // 32), dtype=np.uint8)
+    y, _, _ = fo.mxfp4_gemm(xc, xe, wc, we)
+    val = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+    for t in range(T):
+        for o in range(m):
+            acc = 0.0
+            for k in range(n):
+                a = (xc[t, k // 2] >> (4 * (k & 1))) & 15
+                b = (wc[o, k // 2] >> (4 * (k & 1))) & 15
+                av = (-1.0 if a & 8 else 1.0) * val[a & 7] * 2.0 ** (int(xe[t, k // 32]) - 127)
+                bv = (-1.0 if b & 8 else 1.0) * val[b & 7] * 2.0 ** (int(we[o, k // 32]) - 127)
+                acc += av * bv
+            assert abs(acc - y[t, o]) <= 1e-12 * max(1.0, abs(acc))
+
+
 # ---- the comparator itself -----------------------------------------------------------
 def test_comparator_accepts_oracle_and_rejects_planted_mistakes():
     c = synth.tiny()
