@@ -313,6 +313,39 @@ def main() -> int:
                             "layer_us_transform_quant_plus_gemm": ms_l * 1e3, "fp16_matmul_us_torch_hipblaslt": ms_h * 1e3,
                             "layer_speedup_vs_fp16_matmul": ms_h / ms_l}
 
+        def time_mx_layer(name, Tn, mo, a, b, steps, warmup):   # the same layer with MXFP4 on both factors (scaled FP4 MFMA)
+            nn = a * b
+            g = torch.Generator(device="cuda").manual_seed(177 + mo + nn + Tn)
+            x = (torch.randn((Tn, nn), generator=g, device="cuda")).half()
+            p1 = (torch.eye(a, device="cuda") + 0.05 * torch.randn((a, a), generator=g, device="cuda")).half()
+            p2 = (torch.eye(b, device="cuda") + 0.05 * torch.randn((b, b), generator=g, device="cuda")).half()
+            cl = torch.full((Tn,), 0.9, device="cuda")
+            xc = torch.empty((Tn, nn // 2), dtype=torch.uint8, device="cuda")
+            xe = torch.empty((Tn, nn // 32), dtype=torch.uint8, device="cuda")
+            wc = torch.randint(0, 256, (mo, nn // 2), generator=g, dtype=torch.uint8, device="cuda")
+            we = torch.randint(112, 118, (mo, nn // 32), generator=g, dtype=torch.uint8, device="cuda")
+            y = torch.empty((Tn, mo), dtype=torch.float16, device="cuda")
+            wh = torch.randn((mo, nn), generator=g, device="cuda").half()
+
+            def st_gemm(i):
+                fq.flatquant_mxfp4_gemm(xc, xe, wc, we, Tn, mo, nn, y, mo, stream=stream)
+
+            def st_layer(i):
+                fq.flatquant_transform_mxfp4(x, p1, p2, cl, 1, Tn, a, b, nn, xc, xe, stream=stream)
+                fq.flatquant_mxfp4_gemm(xc, xe, wc, we, Tn, mo, nn, y, mo, stream=stream)
+
+            def st_fp16(i):
+                torch.matmul(x, wh.t(), out=y)
+            st_layer(0)
+            med = lambda f: float(np.median([time_region(f, steps, warmup if r == 0 else 1)[0] for r in range(5)]))
+            ms_g, ms_l, ms_h = med(st_gemm), med(st_layer), med(st_fp16)
+            ops = 2.0 * Tn * mo * nn
+            extras[name] = {"T": Tn, "m": mo, "n": nn, "gemm_us": ms_g * 1e3, "gemm_tflops": ops / (ms_g * 1e-3) / 1e12,
+                            "gemm_frac_of_fp4_mfma_peak": ops / (ms_g * 1e-3) / 1e12 / 10100.0,
+                            "layer_us_transform_quant_plus_gemm": ms_l * 1e3, "fp16_matmul_us_torch_hipblaslt": ms_h * 1e3,
+                            "layer_speedup_vs_fp16_matmul": ms_h / ms_l}
+
+        time_mx_layer("mxfp4_layer_prefill_qkvo_7b", 2048, 4096, 64, 64, 50, 5)
         time_layer("w4a4_layer_prefill_qkvo_7b", 2048, 4096, 64, 64, 50, 5)
         time_layer("w4a4_layer_prefill_down_7b", 2048, 4096, 86, 128, 30, 5)
         time_layer("w4a4_layer_decode_qkvo_7b", 64, 4096, 64, 64, 200, 20)

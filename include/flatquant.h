@@ -162,6 +162,20 @@ fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, cons
                               int64_t T, int m, int n, void* out, int64_t out_stride, void* stream);
 
 /*
+ * Matrix product of two MXFP4 factors (the same low-bit multiplication for the MXFP4 data type), on the scaled FP4
+ * matrix instruction of gfx950:   out[t, o] = fp16( sum_k x^[t, k] * w^[o, k] ),
+ * x^ and w^ the de-quantized factors (E2M1 element times 2^(e - 127) of its block of 32 channels); products are exact,
+ * the sum is accumulated in fp32 and rounded once to fp16.
+ *   x_codes u8 [T, n/2], x_scales u8 [T, n/32]   : outputs of flatquant_transform_mxfp4
+ *   w_codes u8 [m, n/2], w_scales u8 [m, n/32]   : the same call on the weight rows with the inverse-transposed factors
+ *   out     fp16 [T, m], row t at out + t*out_stride halves, out_stride >= m.
+ * n must be a multiple of 256; code tensors 16-byte aligned, exponent tensors 8-byte aligned.  T == 0 or m == 0
+ * returns FQ_OK.  Values beyond the fp16 range come out as infinities.
+ */
+fq_status flatquant_mxfp4_gemm(const uint8_t* x_codes, const uint8_t* x_scales, const uint8_t* w_codes, const uint8_t* w_scales,
+                               int64_t T, int m, int n, void* out, int64_t out_stride, void* stream);
+
+/*
  * De-quantization check helper (Sec. 2.1: W^ = s * Pi(W / s)).
  *   zeros == NULL : out[r, c] = s[r] * q[r, c]            (signed nibbles)
  *   zeros != NULL : out[r, c] = s[r] * (q[r, c] - z[r])   (unsigned nibbles)

@@ -18,7 +18,7 @@ FQ_OK, FQ_INVALID_ARG, FQ_UNSUPPORTED_SHAPE, FQ_MISALIGNED, FQ_LAUNCH_FAILED = r
 
 EXPORTS = (
     "flatquant_transform_quant", "flatquant_kv_transform_quant", "flatquant_kv_transform_quant_bits",
-    "flatquant_dequant", "flatquant_dequant_bits", "flatquant_stream_probe", "flatquant_transform_mxfp4", "flatquant_dequant_mxfp4",
+    "flatquant_dequant", "flatquant_dequant_bits", "flatquant_stream_probe", "flatquant_transform_mxfp4", "flatquant_dequant_mxfp4", "flatquant_mxfp4_gemm",
     "flatquant_weight_transform_quant", "fq_inverse_transpose", "flatquant_head_transform", "flatquant_w4a4_gemm",
     "fq_supported", "fq_choose_factors", "fq_default_design_fits", "fq_lds_bytes",
     "fq_status_string", "fq_last_hip_error", "fq_abi_version",
@@ -47,6 +47,8 @@ def lib() -> ctypes.CDLL:
         L.flatquant_transform_quant.restype = i32
         L.flatquant_transform_mxfp4.argtypes = L.flatquant_transform_quant.argtypes
         L.flatquant_transform_mxfp4.restype = i32
+        L.flatquant_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, i64, vp]
+        L.flatquant_mxfp4_gemm.restype = i32
         L.flatquant_dequant_mxfp4.argtypes = [vp, vp, i64, i32, vp, vp]
         L.flatquant_dequant_mxfp4.restype = i32
         L.flatquant_kv_transform_quant.argtypes = [vp, vp, i32, f32, i64, i32, i32, vp, vp, vp, vp]
@@ -133,6 +135,15 @@ def flatquant_transform_mxfp4(x, P1, P2, clip, clip_mode: int, T: int, n1: int, 
                                          int(x_stride), _ptr(out_codes), _ptr(out_scales), _stream(stream))
     if check and st != FQ_OK:
         raise FlatQuantError(st, "flatquant_transform_mxfp4")
+    return st
+
+
+def flatquant_mxfp4_gemm(x_codes, x_scales, w_codes, w_scales, T: int, m: int, n: int, out, out_stride: int,
+                         stream=None, check: bool = True) -> int:
+    st = lib().flatquant_mxfp4_gemm(_ptr(x_codes), _ptr(x_scales), _ptr(w_codes), _ptr(w_scales), int(T), int(m), int(n),
+                                    _ptr(out), int(out_stride), _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_mxfp4_gemm")
     return st
 
 

@@ -8,7 +8,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libflatquant.so")
-SOURCES = ["fq_api.hip", "fq_transform_quant.hip", "fq_tq_fast.hip", "fq_kv.hip", "fq_dequant.hip", "fq_probe.hip", "fq_gemm.hip"]
+SOURCES = ["fq_api.hip", "fq_transform_quant.hip", "fq_tq_fast.hip", "fq_kv.hip", "fq_dequant.hip", "fq_probe.hip", "fq_gemm.hip", "fq_gemm_mx.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          # keep hipcc from forming packed-fp32 VALU ops from scalar float code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

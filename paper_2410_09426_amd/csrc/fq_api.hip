@@ -199,6 +199,27 @@ fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, cons
     return fq::finish(fq::w4a4_launch(a, static_cast<hipStream_t>(stream)));
 }
 
+fq_status flatquant_mxfp4_gemm(const uint8_t* x_codes, const uint8_t* x_scales, const uint8_t* w_codes, const uint8_t* w_scales,
+                               int64_t T, int m, int n, void* out, int64_t out_stride, void* stream) {
+    if (T < 0 || m < 0 || n < 1 || out_stride < m) return FQ_INVALID_ARG;
+    if (n % 256 != 0) return FQ_UNSUPPORTED_SHAPE;
+    if (T == 0 || m == 0) return FQ_OK;
+    if (!x_codes || !x_scales || !w_codes || !w_scales || !out) return FQ_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(x_codes) & 15) || (reinterpret_cast<uintptr_t>(w_codes) & 15) ||
+        (reinterpret_cast<uintptr_t>(x_scales) & 7) || (reinterpret_cast<uintptr_t>(w_scales) & 7) ||
+        (reinterpret_cast<uintptr_t>(out) & 1))
+        return FQ_MISALIGNED;
+    if ((T + 127) / 128 > 0x7fffffffLL || (m + 127) / 128 > 65535) return FQ_UNSUPPORTED_SHAPE;   // grid limits
+    const int64_t obytes = ((T - 1) * out_stride + m) * 2;
+    if (fq::overlap(x_codes, T * (n / 2), out, obytes) || fq::overlap(w_codes, (int64_t)m * (n / 2), out, obytes) ||
+        fq::overlap(x_scales, T * (n / 32), out, obytes) || fq::overlap(w_scales, (int64_t)m * (n / 32), out, obytes))
+        return FQ_INVALID_ARG;
+    fq::MxGemmArgs a;
+    a.x_codes = x_codes; a.x_exps = x_scales; a.w_codes = w_codes; a.w_exps = w_scales;
+    a.out = static_cast<_Float16*>(out); a.T = T; a.out_stride = out_stride; a.m = m; a.n = n;
+    return fq::finish(fq::mxfp4_gemm_launch(a, static_cast<hipStream_t>(stream)));
+}
+
 fq_status flatquant_dequant_mxfp4(const uint8_t* codes, const uint8_t* scales, int64_t rows, int n, float* out, void* stream) {
     if (rows < 0 || n < 32 || (n & 31)) return FQ_INVALID_ARG;
     if (rows == 0) return FQ_OK;

@@ -92,6 +92,18 @@ struct GemmArgs {
 // W4A4 matrix product of the two quantized factors (fq_gemm.hip).
 hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream);
 
+struct MxGemmArgs {
+    const uint8_t* x_codes;
+    const uint8_t* x_exps;
+    const uint8_t* w_codes;
+    const uint8_t* w_exps;
+    _Float16* out;
+    int64_t T;
+    int64_t out_stride;
+    int m, n;
+};
+hipError_t mxfp4_gemm_launch(const MxGemmArgs& a, hipStream_t stream);
+
 // Copy-like probe with the activation kernel's traffic (fq_probe.hip).
 hipError_t stream_probe_launch(const void* x, int64_t T, int n, int64_t x_stride, uint8_t* out, hipStream_t stream);
 

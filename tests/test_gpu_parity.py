@@ -433,6 +433,33 @@ def test_mxfp4_layer_both_factors():
     assert abs(rel - rel_o) <= 1e-3 * rel_o + 1e-6 * (int((dx > 0).sum()) + int((dw > 0).sum()) + 1)
 
 
+@pytest.mark.parametrize("T,m,n", [(128, 128, 256), (200, 300, 512), (2048, 256, 4096), (1, 40, 768), (130, 129, 11008), (64, 4096, 1024)])
+def test_mxfp4_gemm(T, m, n):
+    """Scaled-FP4 matrix product against the oracle's fp64 product of the de-quantized factors.  Products are exact; the
+    fp32 accumulation may lose up to n * 2^-24 of sum |x^ w^|, and the result is rounded once to fp16."""
+    r = np.random.Generator(np.random.PCG64(1000 + T + m + n))
+    xc = r.integers(0, 256, size=(T, n // 2), dtype=np.uint8)
+    wc = r.integers(0, 256, size=(m, n // 2), dtype=np.uint8)
+    xe = r.integers(118, 131, size=(T, n // 32), dtype=np.uint8)
+    we = r.integers(112, 126, size=(m, n // 32), dtype=np.uint8)
+    print(f"[case] mxfp4 gemm T={T} m={m} n={n}", flush=True)
+    stride = m + 8
+    out = torch.full((T, stride), float("nan"), dtype=torch.float16, device="cuda")
+    fq.flatquant_mxfp4_gemm(dev(xc), dev(xe), dev(wc), dev(we), T, m, n, out, stride, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    got_all = out.cpu().view(torch.int16).numpy().view(np.float16)
+    assert np.all(np.isnan(got_all[:, m:])), "padding columns overwritten"
+    got = got_all[:, :m].astype(np.float64)
+    y, y16, ab = fo.mxfp4_gemm(xc, xe, wc, we)
+    assert np.all(np.isfinite(got))
+    tol = 2.0 ** -11 * np.abs(y) * (1 + 2.0 ** -9) + n * 2.0 ** -24 * ab + 2.0 ** -25
+    err = np.abs(got - y)
+    assert np.all(err <= tol), f"max err/tol {float((err / tol).max()):.3f}"
+    same = float(np.mean(got == y16.astype(np.float64)))
+    print(f"[parity] mxfp4 gemm: identical to the once-rounded fp64 result in {same * 100:.2f} % of the outputs", flush=True)
+    assert same > 0.9
+
+
 # ---- one-sided transforms (a factor left out = identity) ------------------------------------------------------------
 @pytest.mark.parametrize("n1,n2,T,which", [(32, 128, 200, "P1 only"), (32, 128, 3000, "P1 only"), (64, 64, 2048, "P1 only"),
                                            (64, 128, 2500, "P1 only"), (64, 128, 129, "P1 only"), (32, 128, 1, "P1 only"),
