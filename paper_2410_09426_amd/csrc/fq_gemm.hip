@@ -9,7 +9,8 @@
 // the same permutation for both and every product carries a factor 256 that the epilogue divides out exactly.
 // v_mfma_i32_32x32x32_i8 accumulates in int32 (|sum| <= 128 * 128 * n < 2^31 for n <= 65536).
 //
-// Workgroup: 4 waves, C tile 128 tokens x 128 output channels, each wave 64 x 64 (2 x 2 MFMA tiles; the weights are
+// Workgroup: 4 waves, C tile 128 tokens x 128 output channels (or 8 waves, 256 x 128, when the launch has enough such
+// tiles for every CU), each wave 64 x 64 (2 x 2 MFMA tiles; the weights are
 // the MFMA's first operand so that a lane ends up with runs of 4 consecutive output channels of one token).  K advances by
 // 256 codes (128 bytes = one cache line per row) per iteration through double-buffered LDS tiles, one barrier per
 // iteration; the tiles go from global memory straight into LDS, a whole iteration before they are read.
@@ -31,6 +32,7 @@ constexpr int GPITCH = GKB;           // LDS row pitch: rows are written by glob
 constexpr int G_NT = 256;
 constexpr int G_TILE_BYTES = GT * GPITCH;
 constexpr int G_LDS_BYTES = 4 * G_TILE_BYTES + GT * 4;   // A and B, two buffers each, + the weight steps of the tile
+constexpr int G_LDS_BYTES_WIDE = 6 * G_TILE_BYTES + GT * 4;   // 256-token tile: A twice the size
 
 struct GemmDev {
     const uint8_t* xc;
@@ -50,13 +52,19 @@ __device__ __forceinline__ void widen(const u32x4 w, i32x4& s0, i32x4& s1) {
     s1 = i32x4{(int)((w[2] << 4) & M), (int)(w[2] & M), (int)((w[3] << 4) & M), (int)(w[3] & M)};
 }
 
-__global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void w4a4_kernel(GemmDev p) {
+// TW = waves along the token axis: 2 -> C tile 128 tokens x 128 channels (4 waves), 4 -> 256 x 128 (8 waves): a quarter
+// less operand traffic from L2 per product term, for launches with enough 256-token tiles to fill the chip.
+template <int TW>
+__global__ __launch_bounds__(128 * TW) __attribute__((amdgpu_waves_per_eu(2))) void w4a4_kernel(GemmDev p) {
+    constexpr int GTM = 64 * TW;                       // tokens per tile
+    constexpr int NW = 2 * TW;                         // waves
+    constexpr int A_TILE = GTM * GPITCH, B_TILE = GT * GPITCH, STAGE = A_TILE + B_TILE;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x;
     const int l = tid & 63, c = l & 31, h = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = w & 1, wn = w >> 1;
-    const int64_t t0 = (int64_t)blockIdx.x * GT;
+    const int wm = w % TW, wn = w / TW;
+    const int64_t t0 = (int64_t)blockIdx.x * GTM;
     const int o0 = blockIdx.y * GT;
     const int64_t kbytes = p.n / 2;
     const int nk = p.n / (2 * GKB);
@@ -66,31 +74,34 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     // 32 w .. 32 w + 31 of both tiles (4 instructions per operand and iteration).  LDS slot j of row r holds the row's
     // chunk j ^ ((r >> 1) & 7): with that swizzle the 16-byte operand reads of 32 consecutive rows (same chunk) spread
     // over all banks although the pitch is a multiple of the bank width.  Rows past the end re-read the last row.
-    static_assert(GKB == 128 && GT == 128 && G_NT == 256, "load mapping below");
-    constexpr int NLD = 4;
-    const unsigned char* asrc[NLD];
-    const unsigned char* bsrc[NLD];
+    static_assert(GKB == 128 && GT == 128, "load mapping below");
+    constexpr int NLA = GTM / 8 / NW, NLB = GT / 8 / NW;   // 8-row instructions per wave: 4 and 4 (4 waves), 4 and 2 (8 waves)
+    const unsigned char* asrc[NLA];
+    const unsigned char* bsrc[NLB];
 #pragma unroll
-    for (int k = 0; k < NLD; ++k) {
-        const int row = 8 * (4 * w + k) + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
+    for (int k = 0; k < NLA; ++k) {
+        const int row = 8 * (NLA * w + k) + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
         int64_t tr = t0 + row;
         if (tr >= p.T) tr = p.T - 1;
+        asrc[k] = p.xc + tr * kbytes + 16 * ch;
+    }
+#pragma unroll
+    for (int k = 0; k < NLB; ++k) {
+        const int row = 8 * (NLB * w + k) + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
         int orow = o0 + row;
         if (orow >= p.m) orow = p.m - 1;
-        asrc[k] = p.xc + tr * kbytes + 16 * ch;
         bsrc[k] = p.wc + (int64_t)orow * kbytes + 16 * ch;
     }
     typedef const __attribute__((address_space(1))) void* gptr;
     typedef __attribute__((address_space(3))) void* lptr;
     auto issue = [&](int it, int buf) {   // past the last tile the last one is re-read (nobody uses it): no branch in the loop body
         const int itc = it < nk ? it : nk - 1;
-        unsigned char* A = smem + buf * G_TILE_BYTES + w * (32 * GPITCH);
-        unsigned char* B = smem + (2 + buf) * G_TILE_BYTES + w * (32 * GPITCH);
+        unsigned char* A = smem + buf * STAGE + w * (8 * NLA * GPITCH);
+        unsigned char* B = smem + buf * STAGE + A_TILE + w * (8 * NLB * GPITCH);
 #pragma unroll
-        for (int k = 0; k < NLD; ++k) {
-            __builtin_amdgcn_global_load_lds((gptr)(asrc[k] + (int64_t)itc * GKB), (lptr)(A + k * 8 * GPITCH), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr)(bsrc[k] + (int64_t)itc * GKB), (lptr)(B + k * 8 * GPITCH), 16, 0, 0);
-        }
+        for (int k = 0; k < NLA; ++k) __builtin_amdgcn_global_load_lds((gptr)(asrc[k] + (int64_t)itc * GKB), (lptr)(A + k * 8 * GPITCH), 16, 0, 0);
+#pragma unroll
+        for (int k = 0; k < NLB; ++k) __builtin_amdgcn_global_load_lds((gptr)(bsrc[k] + (int64_t)itc * GKB), (lptr)(B + k * 8 * GPITCH), 16, 0, 0);
     };
     // the tile requested last has arrived in LDS (this wave's part), then every wave's part has
     auto tile_ready = [&]() {
@@ -108,7 +119,7 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
 
     if (tid < GT) {
         const int o = o0 + tid;
-        reinterpret_cast<float*>(smem + 4 * G_TILE_BYTES)[tid] = (o < p.m) ? (float)p.ws[o] : 0.0f;
+        reinterpret_cast<float*>(smem + 2 * STAGE)[tid] = (o < p.m) ? (float)p.ws[o] : 0.0f;
     }
     const int aoff = (64 * wm + c) * GPITCH;
     const int boff = (64 * wn + c) * GPITCH;
@@ -117,7 +128,7 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     static_assert(NKP >= 4 && NKP % 2 == 0, "the pipeline below reads two step pairs ahead and alternates two register stages");
     // packed operands of one K step pair: x = 0, 1: tokens 32 x + c (A); x = 2, 3: output channels 32 (x - 2) + c (B)
     auto lds_chunk = [&](int buf, int kp, int x) -> u32x4 {
-        const unsigned char* base = smem + ((x >> 1) * 2 + buf) * G_TILE_BYTES + ((x >> 1) ? boff : aoff);
+        const unsigned char* base = smem + buf * STAGE + ((x >> 1) ? A_TILE + boff : aoff);
         return *reinterpret_cast<const u32x4*>(base + 32 * (x & 1) * GPITCH + 16 * ((2 * kp) ^ hs));
     };
     // Software pipeline over K step pairs g = it * NKP + kp, three stages deep: while the MFMAs of pair g run on the
@@ -175,7 +186,7 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     typedef _Float16 half4 __attribute__((ext_vector_type(4)));
     constexpr int OPITCH = 2 * GT + 16;
     unsigned char* otile = smem;
-    float* sws = reinterpret_cast<float*>(smem + 4 * G_TILE_BYTES);          // [128] weight steps of this tile
+    float* sws = reinterpret_cast<float*>(smem + 2 * STAGE);          // [128] weight steps of this tile
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int64_t t = t0 + 64 * wm + 32 * i + c;
@@ -194,8 +205,8 @@ __global__ __launch_bounds__(G_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     __syncthreads();
     const bool wide = ((reinterpret_cast<uintptr_t>(p.out) & 15) == 0) && (p.out_stride % 8 == 0);
 #pragma unroll
-    for (int k = 0; k < GT * 16 / G_NT; ++k) {
-        const int q = tid + G_NT * k, row = q >> 4, ch = q & 15;
+    for (int k = 0; k < GTM * 16 / (64 * NW); ++k) {
+        const int q = tid + 64 * NW * k, row = q >> 4, ch = q & 15;
         const int64_t t = t0 + row;
         const int o = o0 + 8 * ch;
         if (t < p.T && o < p.m) {
@@ -455,13 +466,23 @@ hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
         else hipLaunchKernelGGL(w4a4_decode_kernel<2>, grid, dim3(G_NT), 0, stream, d);
         return hipGetLastError();
     }
-    static OccCache ct;
+    static OccCache ct, ctw;
+    // 256-token tiles when they still give every CU a workgroup (FLATQUANT_GEMM_WIDE = 0 / 1 forces a form)
+    const int64_t wide_wgs = ((a.T + 255) / 256) * ((a.m + GT - 1) / GT);
+    const int wide = env_int("FLATQUANT_GEMM_WIDE", wide_wgs >= cu_count() ? 1 : 0);
+    if (wide) {
+        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_kernel<4>), 512, G_LDS_BYTES_WIDE, ctw, unused);
+        if (e != hipSuccess) return e;
+        const dim3 grid((unsigned)((a.T + 255) / 256), (unsigned)((a.m + GT - 1) / GT));
+        hipLaunchKernelGGL(w4a4_kernel<4>, grid, dim3(512), G_LDS_BYTES_WIDE, stream, d);
+        return hipGetLastError();
+    }
     {
-        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_kernel), G_NT, G_LDS_BYTES, ct, unused);
+        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_kernel<2>), G_NT, G_LDS_BYTES, ct, unused);
         if (e != hipSuccess) return e;
     }
     const dim3 grid((unsigned)((a.T + GT - 1) / GT), (unsigned)((a.m + GT - 1) / GT));
-    hipLaunchKernelGGL(w4a4_kernel, grid, dim3(G_NT), G_LDS_BYTES, stream, d);
+    hipLaunchKernelGGL(w4a4_kernel<2>, grid, dim3(G_NT), G_LDS_BYTES, stream, d);
     return hipGetLastError();
 }
 
