@@ -21,7 +21,7 @@ EXPORTS = (
     "flatquant_dequant", "flatquant_dequant_bits", "flatquant_stream_probe", "flatquant_transform_mxfp4", "flatquant_dequant_mxfp4", "flatquant_mxfp4_gemm",
     "flatquant_weight_transform_quant", "fq_inverse_transpose", "flatquant_head_transform", "flatquant_w4a4_gemm",
     "fq_supported", "fq_choose_factors", "fq_default_design_fits", "fq_lds_bytes",
-    "fq_status_string", "fq_last_hip_error", "fq_abi_version",
+    "fq_status_string", "fq_last_hip_error", "fq_abi_version", "fq_set_tuning",
 )
 
 _lib = None
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.fq_status_string.restype = ctypes.c_char_p
         L.fq_last_hip_error.argtypes = []
         L.fq_last_hip_error.restype = i32
+        L.fq_set_tuning.argtypes = [ctypes.c_char_p, i32, i32]
+        L.fq_set_tuning.restype = i32
         L.fq_abi_version.argtypes = []
         L.fq_abi_version.restype = i32
         _lib = L
@@ -243,6 +245,13 @@ def fq_default_design_fits(n1: int, n2: int, m_bytes: int) -> bool:
 
 def fq_lds_bytes(n1: int, n2: int) -> int:
     return int(lib().fq_lds_bytes(int(n1), int(n2)))
+
+
+def fq_set_tuning(name: str, value: Optional[int]) -> None:
+    """Set a tuning override (value) or remove it (None)."""
+    st = lib().fq_set_tuning(name.encode(), 0 if value is None else int(value), 0 if value is None else 1)
+    if st != FQ_OK:
+        raise FlatQuantError(st, f"fq_set_tuning({name})")
 
 
 def fq_abi_version() -> int:

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include <cstdlib>
+#include <cstring>
 
 namespace fq {
 
@@ -44,10 +45,42 @@ hipError_t kernel_occupancy(const void* fn, int threads, int lds, OccCache& cach
     return hipSuccess;
 }
 
+// Tuning overrides (kernel flavour, workgroups per CU, ...): for measurements and for the tests that must reach every
+// code path.  Each starts from the environment variable of the same name, read once per process, and can be changed
+// with fq_set_tuning; a launch only reads two atomics per override (no getenv on the launch path).
+namespace {
+struct Tunable {
+    const char* name;
+    std::atomic<int> state{0};   // 0: environment not read yet, 1: unset (callers use their default), 2: set
+    std::atomic<int> value{0};
+    explicit Tunable(const char* n) : name(n) {}
+};
+Tunable g_tunables[] = {Tunable("FLATQUANT_MODE"), Tunable("FLATQUANT_WG_PER_CU"), Tunable("FLATQUANT_FORCE_GENERIC"),
+                        Tunable("FLATQUANT_KV_WG_PER_CU"), Tunable("FLATQUANT_GEMM_DECODE"), Tunable("FLATQUANT_GEMM_TILED"),
+                        Tunable("FLATQUANT_GEMM_WIDE")};
+Tunable* find_tunable(const char* name) {
+    for (Tunable& t : g_tunables)
+        if (std::strcmp(t.name, name) == 0) return &t;
+    return nullptr;
+}
+}  // namespace
+
 int env_int(const char* name, int dflt) {
-    const char* v = std::getenv(name);
-    if (!v || !*v) return dflt;
-    return std::atoi(v);
+    Tunable* t = find_tunable(name);
+    if (!t) return dflt;
+    int st = t->state.load(std::memory_order_acquire);
+    if (st == 0) {   // first use in this process (a second thread doing the same stores the same values)
+        const char* v = std::getenv(name);
+        if (v && *v) {
+            t->value.store(std::atoi(v), std::memory_order_relaxed);
+            st = 2;
+        } else {
+            st = 1;
+        }
+        int expected = 0;
+        if (!t->state.compare_exchange_strong(expected, st, std::memory_order_acq_rel)) st = expected;   // fq_set_tuning came first
+    }
+    return st == 2 ? t->value.load(std::memory_order_relaxed) : dflt;
 }
 
 static fq_status finish(hipError_t e) {
@@ -343,6 +376,19 @@ const char* fq_status_string(fq_status s) {
 }
 
 int fq_last_hip_error(void) { return fq::g_last_hip_error; }
+
+fq_status fq_set_tuning(const char* name, int value, int enable) {
+    if (!name) return FQ_INVALID_ARG;
+    fq::Tunable* t = fq::find_tunable(name);
+    if (!t) return FQ_INVALID_ARG;
+    if (enable) {
+        t->value.store(value, std::memory_order_relaxed);
+        t->state.store(2, std::memory_order_release);
+    } else {
+        t->state.store(1, std::memory_order_release);
+    }
+    return FQ_OK;
+}
 
 int fq_abi_version(void) { return 2; }
 

@@ -27,3 +27,17 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def tuning():
+    """Sets tuning overrides of the library for one test (fq_set_tuning) and removes them afterwards."""
+    from paper_2410_09426_amd import binding as fq
+    used = []
+
+    def set_(name, value):
+        fq.fq_set_tuning(name, int(value))
+        used.append(name)
+    yield set_
+    for name in used:
+        fq.fq_set_tuning(name, None)

@@ -58,27 +58,27 @@ def test_prefill_7b_full():
     assert rep["rows"] == 2048
 
 
-def test_prefill_7b_forced_persistent_loop(monkeypatch):
+def test_prefill_7b_forced_persistent_loop(tuning):
     # one workgroup per CU: every workgroup walks 8 tokens through the prefetch / double barrier loop
-    monkeypatch.setenv("FLATQUANT_WG_PER_CU", "1")
-    monkeypatch.setenv("FLATQUANT_MODE", "2")
+    tuning("FLATQUANT_WG_PER_CU", "1")
+    tuning("FLATQUANT_MODE", "2")
     c = synth.prefill_7b(2048 + 37)
     check_case(c, rows=subset_rows(c.T, 300, 5, must=(0, 255, 256, 257, 2047, 2048)), with_dequant=False, label="wg_per_cu=1")
 
 
-def test_general_kernel_on_aligned_shapes(monkeypatch):
+def test_general_kernel_on_aligned_shapes(tuning):
     # the specialised kernels would take these shapes; force the general one so that it stays covered
-    monkeypatch.setenv("FLATQUANT_FORCE_GENERIC", "1")
+    tuning("FLATQUANT_FORCE_GENERIC", "1")
     c = synth.prefill_7b(700)
     check_case(c, rows=subset_rows(c.T, 120, 6), with_dequant=False, label="general kernel")
     check_case(synth.decode_7b(64, wide=True), with_dequant=False, label="general kernel")
 
 
 @pytest.mark.parametrize("mode", ["0", "1", "2", "3", "4"])
-def test_every_kernel_flavour(monkeypatch, mode):
+def test_every_kernel_flavour(tuning, mode):
     # 0: one slab per wave; 1: two slabs per wave; 2: software-pipelined loop; 3: one token per workgroup;
     # 4: one wave per token, several tokens per workgroup (the library picks one by shape and T)
-    monkeypatch.setenv("FLATQUANT_MODE", mode)
+    tuning("FLATQUANT_MODE", mode)
     c = synth.prefill_7b(1024 + 3)
     check_case(c, rows=subset_rows(c.T, 150, 11, must=(0, 1, 1023, 1024)), with_dequant=False, label=f"mode {mode}")
     c = synth.generic(90 + int(mode), 600, 64, 128)
@@ -236,9 +236,9 @@ def run_mx(c, rows=None):
 
 
 @pytest.mark.parametrize("mode", ["-1", "0", "3"])
-def test_mxfp4_output(monkeypatch, mode):
+def test_mxfp4_output(tuning, mode):
     if mode != "-1":
-        monkeypatch.setenv("FLATQUANT_MODE", mode)
+        tuning("FLATQUANT_MODE", mode)
     c = synth.prefill_7b(2048 if mode == "-1" else 515)
     run_mx(c, rows=subset_rows(c.T, 160, 21, must=(0, 1, c.T - 1)))
     c = synth.generic(400 + int(mode), 70, 64, 128)

@@ -54,6 +54,15 @@ def test_header_is_plain_c_and_links_without_python(tmp_path):
         subprocess.run([cxx, "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)], check=True)
 
 
+def test_tuning_overrides():
+    assert fq.lib().fq_set_tuning(b"FLATQUANT_NO_SUCH_KNOB", 1, 1) == fq.FQ_INVALID_ARG
+    assert fq.lib().fq_set_tuning(None, 1, 1) == fq.FQ_INVALID_ARG
+    fq.fq_set_tuning("FLATQUANT_MODE", 3)
+    fq.fq_set_tuning("FLATQUANT_MODE", None)
+    with pytest.raises(fq.FlatQuantError):
+        fq.fq_set_tuning("flatquant_mode", 1)
+
+
 def test_factor_rule_and_fit_conditions():
     # Sec. 3.1: argmin(n1 + n2), n1 <= n2; (64, 128) for 8192
     assert fq.fq_choose_factors(8192) == (64, 128)
