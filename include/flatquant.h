@@ -169,7 +169,7 @@ fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, cons
  *   x_codes u8 [T, n/2], x_scales u8 [T, n/32]   : outputs of flatquant_transform_mxfp4
  *   w_codes u8 [m, n/2], w_scales u8 [m, n/32]   : the same call on the weight rows with the inverse-transposed factors
  *   out     fp16 [T, m], row t at out + t*out_stride halves, out_stride >= m.
- * n must be a multiple of 256; code tensors 16-byte aligned, exponent tensors 8-byte aligned.  T == 0 or m == 0
+ * n must be a multiple of 256, at least 1024; code tensors 16-byte aligned, exponent tensors 8-byte aligned.  T == 0 or m == 0
  * returns FQ_OK.  Values beyond the fp16 range come out as infinities.
  */
 fq_status flatquant_mxfp4_gemm(const uint8_t* x_codes, const uint8_t* x_scales, const uint8_t* w_codes, const uint8_t* w_scales,

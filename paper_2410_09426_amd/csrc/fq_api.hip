@@ -235,7 +235,7 @@ fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, cons
 fq_status flatquant_mxfp4_gemm(const uint8_t* x_codes, const uint8_t* x_scales, const uint8_t* w_codes, const uint8_t* w_scales,
                                int64_t T, int m, int n, void* out, int64_t out_stride, void* stream) {
     if (T < 0 || m < 0 || n < 1 || out_stride < m) return FQ_INVALID_ARG;
-    if (n % 256 != 0) return FQ_UNSUPPORTED_SHAPE;
+    if (n % 256 != 0 || n < 1024) return FQ_UNSUPPORTED_SHAPE;   // exponents move 32 bytes (four K iterations) at a time
     if (T == 0 || m == 0) return FQ_OK;
     if (!x_codes || !x_scales || !w_codes || !w_scales || !out) return FQ_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(x_codes) & 15) || (reinterpret_cast<uintptr_t>(w_codes) & 15) ||

@@ -27,7 +27,8 @@ constexpr int XT = 128;               // tile edge, tokens and output channels
 constexpr int XKB = 128;              // packed bytes of K per row and iteration (256 codes, 8 blocks)
 constexpr int X_NT = 256;
 constexpr int X_TILE_BYTES = XT * XKB;
-constexpr int X_LDS_BYTES = 4 * X_TILE_BYTES;   // A and B, two buffers each; the output tile reuses the space
+constexpr int X_EXP_BYTES = 2 * XT * 32;        // exponents of both operands for four iterations: 32 bytes per row
+constexpr int X_LDS_BYTES = 4 * X_TILE_BYTES + 2 * X_EXP_BYTES;   // A and B, two buffers each (the output tile reuses them), + exponents
 
 struct MxGemmDev {
     const uint8_t* xc;
@@ -84,31 +85,50 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
         __syncthreads();
     };
 
-    // exponents of this lane's four operand rows (x = 0, 1: tokens 64 wm + 32 x + c; x = 2, 3: channels 64 wn + 32 (x - 2) + c):
-    // 8 bytes per row and iteration.  K step kp (64 codes) uses block 2 kp + h; the MFMA picks a byte of a register by an
-    // immediate, the same for every lane, so the half-wave h = 1 shifts its bytes down by one: byte 2 (kp & 1) of dword
-    // kp / 2 then is the block of this lane.
-    const unsigned char* esrc[4];
+    // Exponents: 8 bytes per row and iteration.  They take the same road as the codes, 32 bytes per row (four iterations)
+    // at a time: two global-to-LDS instructions per wave and four iterations, lanes 2j, 2j + 1 of instruction k fetching
+    // row 64 w + 32 k + j of the 256 rows of the two tiles (0..127 tokens, 128..255 channels).  Fetching them into registers instead, 8 bytes
+    // per lane, row and iteration, touches four times as many cache lines per iteration as the code tiles do and took
+    // 45 % of the kernel's time.  A row whose iteration count is not a multiple of four ends in a short group: that
+    // group is fetched so that it ends with the row (nothing past the row is read) and read at the matching offset.
+    const int ngrp = (nk + 3) >> 2;
+    const int last_base = (nk & 3) ? 8 * nk - 32 : 32 * (ngrp - 1);   // first byte of the last group (ends with the row)
+    const unsigned char* xsrc[2];
 #pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        if (x < 2) {
-            int64_t tr = t0 + 64 * wm + 32 * x + c;
+    for (int k = 0; k < 2; ++k) {
+        const int row = 64 * w + 32 * k + (l >> 1);
+        if (row < XT) {
+            int64_t tr = t0 + row;
             if (tr >= p.T) tr = p.T - 1;
-            esrc[x] = p.xe + tr * ebytes;
+            xsrc[k] = p.xe + tr * ebytes + 16 * (l & 1);
         } else {
-            int orow = o0 + 64 * wn + 32 * (x - 2) + c;
+            int orow = o0 + row - XT;
             if (orow >= p.m) orow = p.m - 1;
-            esrc[x] = p.we + (int64_t)orow * ebytes;
+            xsrc[k] = p.we + (int64_t)orow * ebytes + 16 * (l & 1);
         }
     }
-    auto load_exps = [&](int it, u32x2 (&e)[4]) {
-        const int itc = it < nk ? it : nk - 1;
+    unsigned char* ebuf = smem + 4 * X_TILE_BYTES;
+    auto issue_exps = [&](int grp) {   // past the last group the last one is re-read (nobody uses it)
+        const int g = grp < ngrp ? grp : ngrp - 1;
+        const int off = g == ngrp - 1 ? last_base : 32 * g;
 #pragma unroll
-        for (int x = 0; x < 4; ++x) e[x] = *reinterpret_cast<const u32x2*>(esrc[x] + 8 * itc);
+        for (int k = 0; k < 2; ++k)
+            __builtin_amdgcn_global_load_lds((gptr)(xsrc[k] + off), (lptr)(ebuf + (grp & 1) * X_EXP_BYTES + w * 2048 + k * 1024), 16, 0, 0);
     };
-    auto shift_exps = [&](u32x2 (&e)[4]) {
+    // this lane's four operand rows (x = 0, 1: tokens 64 wm + 32 x + c; x = 2, 3: channels 64 wn + 32 (x - 2) + c) for
+    // iteration `it`.  K step kp (64 codes) uses block 2 kp + h; the MFMA picks a byte of a register by an immediate, the
+    // same for every lane, so the half-wave h = 1 shifts its bytes down by one: byte 2 (kp & 1) of dword kp / 2 then is
+    // the block of this lane.
+    const int eoff[4] = {(64 * wm + c) * 32, (64 * wm + 32 + c) * 32, (XT + 64 * wn + c) * 32, (XT + 64 * wn + 32 + c) * 32};
+    auto lds_exps = [&](int it, u32x2 (&e)[4]) {
+        const int g = it >> 2;
+        const int within = 8 * it - (g >= ngrp - 1 ? last_base : 32 * g);   // past the end: some in-range garbage
+        const unsigned char* base = ebuf + (g & 1) * X_EXP_BYTES + (within & 24);
 #pragma unroll
-        for (int x = 0; x < 4; ++x) { e[x][0] >>= 8 * h; e[x][1] >>= 8 * h; }
+        for (int x = 0; x < 4; ++x) {
+            const u32x2 v = *reinterpret_cast<const u32x2*>(base + eoff[x]);
+            e[x] = u32x2{v[0] >> (8 * h), v[1] >> (8 * h)};
+        }
     };
 
     f32x16 acc[2][2];
@@ -143,13 +163,12 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     u32x4 P[2][4];
     u32x2 E[2][4];   // exponents of the current and of the next tile
     issue(0, 0);
-    load_exps(0, E[0]);
+    issue_exps(0);
     tile_ready();
     issue(1, 1);
-    load_exps(1, E[1]);
-    shift_exps(E[0]);
 #pragma unroll
     for (int x = 0; x < 4; ++x) P[0][x] = lds_chunk(0, 0, x);
+    lds_exps(0, E[0]);
     auto iteration = [&](int it, int buf, u32x2 (&ec)[4], u32x2 (&en)[4]) {
 #pragma unroll
         for (int kp = 0; kp < NKP; ++kp) {
@@ -164,12 +183,12 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (kp == NKP - 2) {
-                tile_ready();          // also: the exponents of tile it + 1 (requested an iteration ago) are in `en`
+                tile_ready();          // tile it + 1 and, if it starts a pair of iterations, its exponents are in LDS
                 issue(it + 2, buf);
-                shift_exps(en);
+                if ((it & 3) == 2) issue_exps((it + 2) >> 2);   // the next four iterations' exponents
+                lds_exps(it + 1, en);
             }
         }
-        load_exps(it + 2, ec);         // `ec` is done; it becomes the set of tile it + 2
     };
     for (int it = 0; it < nk; it += 2) {
         iteration(it, 0, E[0], E[1]);

@@ -433,7 +433,7 @@ def test_mxfp4_layer_both_factors():
     assert abs(rel - rel_o) <= 1e-3 * rel_o + 1e-6 * (int((dx > 0).sum()) + int((dw > 0).sum()) + 1)
 
 
-@pytest.mark.parametrize("T,m,n", [(128, 128, 256), (200, 300, 512), (2048, 256, 4096), (1, 40, 768), (130, 129, 11008), (64, 4096, 1024)])
+@pytest.mark.parametrize("T,m,n", [(128, 128, 1024), (200, 300, 1280), (2048, 256, 4096), (1, 40, 1792), (130, 129, 11008), (64, 4096, 1024), (300, 140, 1536), (70, 257, 2304)])
 def test_mxfp4_gemm(T, m, n):
     """Scaled-FP4 matrix product against the oracle's fp64 product of the de-quantized factors.  Products are exact; the
     fp32 accumulation may lose up to n * 2^-24 of sum |x^ w^|, and the result is rounded once to fp16."""

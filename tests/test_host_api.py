@@ -123,9 +123,9 @@ def test_argument_validation_without_a_device():
     assert mx(out_scales=A + 0x400000) == fq.FQ_INVALID_ARG            # exponents inside the code buffer
 
     gx = lambda **k: fq.flatquant_mxfp4_gemm(**{**dict(x_codes=A, x_scales=A + 0x100000, w_codes=A + 0x200000, w_scales=A + 0x300000, T=4, m=8,
-                                                     n=512, out=A + 0x400000, out_stride=8, check=False), **k})
+                                                     n=1024, out=A + 0x400000, out_stride=8, check=False), **k})
     assert gx(T=0) == fq.FQ_OK and gx(m=0, out_stride=0) == fq.FQ_OK
-    assert gx(n=500) == fq.FQ_UNSUPPORTED_SHAPE and gx(out_stride=7) == fq.FQ_INVALID_ARG and gx(w_scales=None) == fq.FQ_INVALID_ARG
+    assert gx(n=500) == fq.FQ_UNSUPPORTED_SHAPE and gx(n=768) == fq.FQ_UNSUPPORTED_SHAPE and gx(out_stride=7) == fq.FQ_INVALID_ARG and gx(w_scales=None) == fq.FQ_INVALID_ARG
     assert gx(x_codes=A + 8) == fq.FQ_MISALIGNED and gx(x_scales=A + 0x100004) == fq.FQ_MISALIGNED
     assert gx(out=A + 0x300000) == fq.FQ_INVALID_ARG          # output overlaps the weight exponents
 
