@@ -349,6 +349,32 @@ def dequantize_mxfp4(codes_packed, scale_exp) -> np.ndarray:
     return e2m1_value(q) * np.repeat(x, MX_BLOCK, axis=-1)
 
 
+def mx_tile_scales(e, fill=0) -> np.ndarray:
+    """Row-major exponents [R, n/32] -> the tile order the MXFP4 product reads, as a flat byte array: rows in tiles of
+    128 (padded with `fill`), blocks in groups of 8; byte of (row r, block k) = (((r // 128) * (n // 256) + k // 8) *
+    128 + r % 128) * 8 + k % 8."""
+    e = np.asarray(e, dtype=np.uint8)
+    R, nb = e.shape
+    assert nb % 8 == 0
+    tiles, groups = (R + 127) // 128, nb // 8
+    out = np.full((tiles, groups, 128, 8), fill, dtype=np.uint8)
+    for r in range(R):
+        for k in range(nb):
+            out[r // 128, k // 8, r % 128, k % 8] = e[r, k]
+    return out.reshape(-1)
+
+
+def mx_untile_scales(tiled, rows, n) -> np.ndarray:
+    """Inverse of mx_tile_scales (the padding rows are dropped)."""
+    nb = n // 32
+    t = np.asarray(tiled, dtype=np.uint8).reshape((rows + 127) // 128, nb // 8, 128, 8)
+    out = np.zeros((rows, nb), dtype=np.uint8)
+    for r in range(rows):
+        for k in range(nb):
+            out[r, k] = t[r // 128, k // 8, r % 128, k % 8]
+    return out
+
+
 def mxfp4_gemm(x_codes, x_exps, w_codes, w_exps):
     """Product of two MXFP4 factors, the low-bit matrix multiplication of
     Sec. 3.2 with the data type of the "Limitations": out[t, o] = sum_k x^[t, k]

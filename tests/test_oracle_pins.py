@@ -452,6 +452,19 @@ def test_mx_shared_exponent_and_block_properties():
         parity.check_mx(y, 1.0, fo.pack_nibbles(trunc.astype(np.int8)), e)
 
 
+def test_mx_tile_order_of_exponents():
+    # byte of (row r, block k) = (((r // 128) * (n // 256) + k // 8) * 128 + r % 128) * 8 + k % 8, written out for a few entries
+    R, n = 130, 512
+    e = (np.arange(R * 16) % 251).astype(np.uint8).reshape(R, 16)
+    t = fo.mx_tile_scales(e, fill=0xEE)
+    assert t.shape == (2 * 2 * 128 * 8,)
+    assert t[0] == e[0, 0] and t[7] == e[0, 7] and t[8] == e[1, 0]                      # rows of a group are 8 bytes apart
+    assert t[128 * 8] == e[0, 8] and t[128 * 8 + 127 * 8 + 3] == e[127, 11]              # second group of the first tile
+    assert t[3081] == e[129, 9] and t[2 * 128 * 8 + 0] == e[128, 0]                      # second tile
+    assert t[2 * 128 * 8 + 2 * 8] == 0xEE                                                # padding row 130
+    assert np.array_equal(fo.mx_untile_scales(t, R, n), e)
+
+
 def test_mxfp4_product_hand_set_and_brute_force():
     # one token, one channel, n = 32: x = [1.0, 6.0, -0.5, 0...] * 2^1, w = [3.0, -1.5, 4.0, 0...] * 2^-2
     xc = np.zeros((1, 16), dtype=np.uint8); wc = np.zeros((1, 16), dtype=np.uint8)
