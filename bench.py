@@ -321,9 +321,9 @@ def main() -> int:
             p2 = (torch.eye(b, device="cuda") + 0.05 * torch.randn((b, b), generator=g, device="cuda")).half()
             cl = torch.full((Tn,), 0.9, device="cuda")
             xc = torch.empty((Tn, nn // 2), dtype=torch.uint8, device="cuda")
-            xe = torch.empty((Tn, nn // 32), dtype=torch.uint8, device="cuda")
+            xe = torch.empty((fq.fq_mxfp4_tiled_scale_bytes(Tn, nn),), dtype=torch.uint8, device="cuda")
             wc = torch.randint(0, 256, (mo, nn // 2), generator=g, dtype=torch.uint8, device="cuda")
-            we = torch.randint(112, 118, (mo, nn // 32), generator=g, dtype=torch.uint8, device="cuda")
+            we = torch.randint(112, 118, (fq.fq_mxfp4_tiled_scale_bytes(mo, nn),), generator=g, dtype=torch.uint8, device="cuda")
             y = torch.empty((Tn, mo), dtype=torch.float16, device="cuda")
             wh = torch.randn((mo, nn), generator=g, device="cuda").half()
 
@@ -331,7 +331,7 @@ def main() -> int:
                 fq.flatquant_mxfp4_gemm(xc, xe, wc, we, Tn, mo, nn, y, mo, stream=stream)
 
             def st_layer(i):
-                fq.flatquant_transform_mxfp4(x, p1, p2, cl, 1, Tn, a, b, nn, xc, xe, stream=stream)
+                fq.flatquant_transform_mxfp4_tiled(x, p1, p2, cl, 1, Tn, a, b, nn, xc, xe, stream=stream)
                 fq.flatquant_mxfp4_gemm(xc, xe, wc, we, Tn, mo, nn, y, mo, stream=stream)
 
             def st_fp16(i):

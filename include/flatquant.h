@@ -87,6 +87,21 @@ fq_status flatquant_transform_mxfp4(const void* x, const void* P1, const void* P
                                     uint8_t* out_codes, uint8_t* out_scales, void* stream);
 
 /*
+ * The same, with the exponents written in the tile order that flatquant_mxfp4_gemm reads: rows (tokens) in tiles of
+ * 128, channels in groups of 256 (8 exponents); for tile r/128 and group j the 128 rows' 8 bytes are contiguous:
+ *     byte of (row r, block k)  =  ( ((r / 128) * (n / 256) + k / 8) * 128 + r % 128 ) * 8 + k % 8.
+ * out_scales must hold fq_mxfp4_tiled_scale_bytes(T, n) bytes (rows padded to a multiple of 128; the padding is not
+ * written) and be 16-byte aligned; n must also be a multiple of 256.  Codes and everything else as above.
+ */
+fq_status flatquant_transform_mxfp4_tiled(const void* x, const void* P1, const void* P2,
+                                          const float* clip, int clip_mode,
+                                          int64_t T, int n1, int n2, int64_t x_stride,
+                                          uint8_t* out_codes, uint8_t* out_scales, void* stream);
+
+/* Bytes of a tile-ordered exponent tensor for `rows` rows of n channels (0 if n is not a multiple of 256). */
+int64_t fq_mxfp4_tiled_scale_bytes(int64_t rows, int64_t n);
+
+/*
  * KV-cache path (Sec. 3.2 "Self-Attention": P_h / P_v applied head by head,
  * not decomposed; Sec. 4.1: group-wise asymmetric INT4, group = head_dim).
  * For every (token, head) group g of D values:
@@ -166,10 +181,11 @@ fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, cons
  * matrix instruction of gfx950:   out[t, o] = fp16( sum_k x^[t, k] * w^[o, k] ),
  * x^ and w^ the de-quantized factors (E2M1 element times 2^(e - 127) of its block of 32 channels); products are exact,
  * the sum is accumulated in fp32 and rounded once to fp16.
- *   x_codes u8 [T, n/2], x_scales u8 [T, n/32]   : outputs of flatquant_transform_mxfp4
- *   w_codes u8 [m, n/2], w_scales u8 [m, n/32]   : the same call on the weight rows with the inverse-transposed factors
+ *   x_codes u8 [T, n/2], x_scales tile-ordered exponents  : outputs of flatquant_transform_mxfp4_tiled
+ *   w_codes u8 [m, n/2], w_scales tile-ordered exponents  : the same call on the weight rows with the inverse-transposed factors
  *   out     fp16 [T, m], row t at out + t*out_stride halves, out_stride >= m.
- * n must be a multiple of 256, at least 1024; code tensors 16-byte aligned, exponent tensors 8-byte aligned.  T == 0 or m == 0
+ * n must be a multiple of 256; code and exponent tensors 16-byte aligned; the exponent tensors hold
+ * fq_mxfp4_tiled_scale_bytes(T or m, n) bytes (the rows of the padding are read and ignored).  T == 0 or m == 0
  * returns FQ_OK.  Values beyond the fp16 range come out as infinities.
  */
 fq_status flatquant_mxfp4_gemm(const uint8_t* x_codes, const uint8_t* x_scales, const uint8_t* w_codes, const uint8_t* w_scales,

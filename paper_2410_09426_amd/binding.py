@@ -18,7 +18,8 @@ FQ_OK, FQ_INVALID_ARG, FQ_UNSUPPORTED_SHAPE, FQ_MISALIGNED, FQ_LAUNCH_FAILED = r
 
 EXPORTS = (
     "flatquant_transform_quant", "flatquant_kv_transform_quant", "flatquant_kv_transform_quant_bits",
-    "flatquant_dequant", "flatquant_dequant_bits", "flatquant_stream_probe", "flatquant_transform_mxfp4", "flatquant_dequant_mxfp4", "flatquant_mxfp4_gemm",
+    "flatquant_dequant", "flatquant_dequant_bits", "flatquant_stream_probe", "flatquant_transform_mxfp4", "flatquant_transform_mxfp4_tiled", "fq_mxfp4_tiled_scale_bytes",
+    "flatquant_dequant_mxfp4", "flatquant_mxfp4_gemm",
     "flatquant_weight_transform_quant", "fq_inverse_transpose", "flatquant_head_transform", "flatquant_w4a4_gemm",
     "fq_supported", "fq_choose_factors", "fq_default_design_fits", "fq_lds_bytes",
     "fq_status_string", "fq_last_hip_error", "fq_abi_version", "fq_set_tuning",
@@ -47,6 +48,10 @@ def lib() -> ctypes.CDLL:
         L.flatquant_transform_quant.restype = i32
         L.flatquant_transform_mxfp4.argtypes = L.flatquant_transform_quant.argtypes
         L.flatquant_transform_mxfp4.restype = i32
+        L.flatquant_transform_mxfp4_tiled.argtypes = L.flatquant_transform_quant.argtypes
+        L.flatquant_transform_mxfp4_tiled.restype = i32
+        L.fq_mxfp4_tiled_scale_bytes.argtypes = [i64, i64]
+        L.fq_mxfp4_tiled_scale_bytes.restype = i64
         L.flatquant_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, i64, vp]
         L.flatquant_mxfp4_gemm.restype = i32
         L.flatquant_dequant_mxfp4.argtypes = [vp, vp, i64, i32, vp, vp]
@@ -138,6 +143,19 @@ def flatquant_transform_mxfp4(x, P1, P2, clip, clip_mode: int, T: int, n1: int, 
     if check and st != FQ_OK:
         raise FlatQuantError(st, "flatquant_transform_mxfp4")
     return st
+
+
+def flatquant_transform_mxfp4_tiled(x, P1, P2, clip, clip_mode: int, T: int, n1: int, n2: int, x_stride: int, out_codes,
+                                    out_scales, stream=None, check: bool = True) -> int:
+    st = lib().flatquant_transform_mxfp4_tiled(_ptr(x), _ptr(P1), _ptr(P2), _ptr(clip), int(clip_mode), int(T), int(n1), int(n2),
+                                               int(x_stride), _ptr(out_codes), _ptr(out_scales), _stream(stream))
+    if check and st != FQ_OK:
+        raise FlatQuantError(st, "flatquant_transform_mxfp4_tiled")
+    return st
+
+
+def fq_mxfp4_tiled_scale_bytes(rows: int, n: int) -> int:
+    return int(lib().fq_mxfp4_tiled_scale_bytes(int(rows), int(n)))
 
 
 def flatquant_mxfp4_gemm(x_codes, x_scales, w_codes, w_scales, T: int, m: int, n: int, out, out_stride: int,

@@ -125,22 +125,43 @@ fq_status flatquant_transform_quant(const void* x, const void* P1, const void* P
     return fq::finish(fq::tq_launch(a, static_cast<hipStream_t>(stream)));
 }
 
+static fq_status transform_mxfp4(const void* x, const void* P1, const void* P2, const float* clip, int clip_mode, int64_t T,
+                                 int n1, int n2, int64_t x_stride, uint8_t* out_codes, uint8_t* out_scales, void* stream, int tiled);
+
 fq_status flatquant_transform_mxfp4(const void* x, const void* P1, const void* P2, const float* clip, int clip_mode,
                                     int64_t T, int n1, int n2, int64_t x_stride, uint8_t* out_codes, uint8_t* out_scales,
                                     void* stream) {
+    return transform_mxfp4(x, P1, P2, clip, clip_mode, T, n1, n2, x_stride, out_codes, out_scales, stream, 0);
+}
+
+fq_status flatquant_transform_mxfp4_tiled(const void* x, const void* P1, const void* P2, const float* clip, int clip_mode,
+                                          int64_t T, int n1, int n2, int64_t x_stride, uint8_t* out_codes, uint8_t* out_scales,
+                                          void* stream) {
+    return transform_mxfp4(x, P1, P2, clip, clip_mode, T, n1, n2, x_stride, out_codes, out_scales, stream, 1);
+}
+
+int64_t fq_mxfp4_tiled_scale_bytes(int64_t rows, int64_t n) {
+    if (rows < 0 || n < 256 || n % 256 != 0) return 0;
+    return ((rows + 127) / 128) * 128 * (n / 32);
+}
+
+static fq_status transform_mxfp4(const void* x, const void* P1, const void* P2, const float* clip, int clip_mode, int64_t T,
+                                 int n1, int n2, int64_t x_stride, uint8_t* out_codes, uint8_t* out_scales, void* stream, int tiled) {
     if (T < 0 || n1 < 1 || n2 < 1 || (clip_mode != 0 && clip_mode != 1)) return FQ_INVALID_ARG;
     const int64_t n = (int64_t)n1 * n2;
     if (x_stride < n) return FQ_INVALID_ARG;
     if (n1 > fq::kMaxN1 || !(n2 == 64 || n2 == 128 || n2 == 256) || n % 128 != 0) return FQ_UNSUPPORTED_SHAPE;
+    if (tiled && n % 256 != 0) return FQ_UNSUPPORTED_SHAPE;
     if (T == 0) return FQ_OK;
     if (!x || !P1 || !P2 || !clip || !out_codes || !out_scales) return FQ_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(x) & 15) || (x_stride & 7) || (reinterpret_cast<uintptr_t>(P1) & 3) ||
         (reinterpret_cast<uintptr_t>(P2) & 15) || (reinterpret_cast<uintptr_t>(clip) & 3) ||
-        (reinterpret_cast<uintptr_t>(out_codes) & 15) || (reinterpret_cast<uintptr_t>(out_scales) & 3))
+        (reinterpret_cast<uintptr_t>(out_codes) & 15) || (reinterpret_cast<uintptr_t>(out_scales) & (tiled ? 15 : 3)))
         return FQ_MISALIGNED;
     const int64_t xbytes = ((T - 1) * x_stride + n) * 2;
-    if (fq::overlap(x, xbytes, out_codes, T * (n / 2)) || fq::overlap(x, xbytes, out_scales, T * (n / 32)) ||
-        fq::overlap(out_codes, T * (n / 2), out_scales, T * (n / 32)))
+    const int64_t sbytes = tiled ? fq_mxfp4_tiled_scale_bytes(T, n) : T * (n / 32);
+    if (fq::overlap(x, xbytes, out_codes, T * (n / 2)) || fq::overlap(x, xbytes, out_scales, sbytes) ||
+        fq::overlap(out_codes, T * (n / 2), out_scales, sbytes))
         return FQ_INVALID_ARG;
     fq::TqArgs a;
     a.x = static_cast<const _Float16*>(x);
@@ -148,6 +169,7 @@ fq_status flatquant_transform_mxfp4(const void* x, const void* P1, const void* P
     a.P2 = static_cast<const _Float16*>(P2);
     a.clip = clip; a.clip_mode = clip_mode; a.T = T; a.n1 = n1; a.n2 = n2; a.x_stride = x_stride;
     a.out_codes = out_codes; a.out_scales = reinterpret_cast<_Float16*>(out_scales);
+    a.mx_tiled = tiled;
     const fq::TqDev d = fq::tq_dev_args(a);
     if (!fq::tq_mx_applicable(d)) return FQ_UNSUPPORTED_SHAPE;
     return fq::finish(fq::tq_mx_launch(d, static_cast<hipStream_t>(stream)));
@@ -235,17 +257,18 @@ fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, cons
 fq_status flatquant_mxfp4_gemm(const uint8_t* x_codes, const uint8_t* x_scales, const uint8_t* w_codes, const uint8_t* w_scales,
                                int64_t T, int m, int n, void* out, int64_t out_stride, void* stream) {
     if (T < 0 || m < 0 || n < 1 || out_stride < m) return FQ_INVALID_ARG;
-    if (n % 256 != 0 || n < 1024) return FQ_UNSUPPORTED_SHAPE;   // exponents move 32 bytes (four K iterations) at a time
+    if (n % 256 != 0) return FQ_UNSUPPORTED_SHAPE;
     if (T == 0 || m == 0) return FQ_OK;
     if (!x_codes || !x_scales || !w_codes || !w_scales || !out) return FQ_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(x_codes) & 15) || (reinterpret_cast<uintptr_t>(w_codes) & 15) ||
-        (reinterpret_cast<uintptr_t>(x_scales) & 7) || (reinterpret_cast<uintptr_t>(w_scales) & 7) ||
+        (reinterpret_cast<uintptr_t>(x_scales) & 15) || (reinterpret_cast<uintptr_t>(w_scales) & 15) ||
         (reinterpret_cast<uintptr_t>(out) & 1))
         return FQ_MISALIGNED;
     if ((T + 127) / 128 > 0x7fffffffLL || (m + 127) / 128 > 65535) return FQ_UNSUPPORTED_SHAPE;   // grid limits
     const int64_t obytes = ((T - 1) * out_stride + m) * 2;
     if (fq::overlap(x_codes, T * (n / 2), out, obytes) || fq::overlap(w_codes, (int64_t)m * (n / 2), out, obytes) ||
-        fq::overlap(x_scales, T * (n / 32), out, obytes) || fq::overlap(w_scales, (int64_t)m * (n / 32), out, obytes))
+        fq::overlap(x_scales, fq_mxfp4_tiled_scale_bytes(T, n), out, obytes) ||
+        fq::overlap(w_scales, fq_mxfp4_tiled_scale_bytes(m, n), out, obytes))
         return FQ_INVALID_ARG;
     fq::MxGemmArgs a;
     a.x_codes = x_codes; a.x_exps = x_scales; a.w_codes = w_codes; a.w_exps = w_scales;

@@ -1,7 +1,7 @@
 // Product of two MXFP4 factors on gfx950's scaled FP4 MFMA: out[t, o] = fp16( sum_k x^[t, k] w^[o, k] ), the low-bit
 // matrix multiplication of Sec. 3.2 for the data type the paper's "Limitations" name next.  x^ and w^ are the
-// de-quantized outputs of flatquant_transform_mxfp4 (activations [T, n/2] codes + [T, n/32] exponents, weights
-// [m, n/2] + [m, n/32]): E2M1 elements times one power of two per block of 32 consecutive channels.
+// de-quantized outputs of flatquant_transform_mxfp4_tiled (activations [T, n/2] codes + n/32 exponents per token in
+// tile order, weights likewise): E2M1 elements times one power of two per block of 32 consecutive channels.
 //
 // v_mfma_scale_f32_32x32x64_f8f6f4 with both formats FP4 takes, per lane, 32 consecutive K elements (16 bytes of
 // packed nibbles: lane (c, h) <-> row c, K half h) and one E8M0 exponent for exactly those 32 elements, so the stored
@@ -11,9 +11,9 @@
 // Workgroup and data movement as in the INT4 product (fq_gemm.hip): 4 waves, C tile 128 tokens x 128 output channels,
 // 64 x 64 per wave with the weights as the MFMA's first operand; K advances by 256 codes per iteration through
 // double-buffered LDS tiles filled by global-to-LDS loads (unpadded rows, 16-byte chunks swizzled), one barrier per
-// iteration.  The exponents (8 bytes per row and iteration) go from global memory to registers, one iteration ahead.
-// (A ring of four 128-code stages with three in flight, exponents through LDS as well, measured slower: 64-byte row
-// pieces and 4-byte exponent fetches multiply the number of L2 requests by four.)
+// iteration.  The exponents (8 bytes per row and iteration, stored in tile order) travel the same way.
+// (A ring of four 128-code stages with three in flight measured slower: 64-byte row pieces multiply the number of
+// L2 requests.)
 #include "fq_internal.h"
 
 namespace fq {
@@ -27,7 +27,7 @@ constexpr int XT = 128;               // tile edge, tokens and output channels
 constexpr int XKB = 128;              // packed bytes of K per row and iteration (256 codes, 8 blocks)
 constexpr int X_NT = 256;
 constexpr int X_TILE_BYTES = XT * XKB;
-constexpr int X_EXP_BYTES = 2 * XT * 32;        // exponents of both operands for four iterations: 32 bytes per row
+constexpr int X_EXP_BYTES = 2 * XT * 8;         // exponents of both tiles for one iteration: 8 bytes per row
 constexpr int X_LDS_BYTES = 4 * X_TILE_BYTES + 2 * X_EXP_BYTES;   // A and B, two buffers each (the output tile reuses them), + exponents
 
 struct MxGemmDev {
@@ -50,7 +50,6 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     const int64_t t0 = (int64_t)blockIdx.x * XT;
     const int o0 = blockIdx.y * XT;
     const int64_t kbytes = p.n / 2;
-    const int64_t ebytes = p.n / 32;
     const int nk = p.n / (2 * XKB);
 
     // code tiles: one instruction fills 8 rows of 128 bytes; wave w owns rows 32 w .. 32 w + 31 of both tiles.  LDS slot
@@ -85,48 +84,28 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
         __syncthreads();
     };
 
-    // Exponents: 8 bytes per row and iteration.  They take the same road as the codes, 32 bytes per row (four iterations)
-    // at a time: two global-to-LDS instructions per wave and four iterations, lanes 2j, 2j + 1 of instruction k fetching
-    // row 64 w + 32 k + j of the 256 rows of the two tiles (0..127 tokens, 128..255 channels).  Fetching them into registers instead, 8 bytes
-    // per lane, row and iteration, touches four times as many cache lines per iteration as the code tiles do and took
-    // 45 % of the kernel's time.  A row whose iteration count is not a multiple of four ends in a short group: that
-    // group is fetched so that it ends with the row (nothing past the row is read) and read at the matching offset.
-    const int ngrp = (nk + 3) >> 2;
-    const int last_base = (nk & 3) ? 8 * nk - 32 : 32 * (ngrp - 1);   // first byte of the last group (ends with the row)
-    const unsigned char* xsrc[2];
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        const int row = 64 * w + 32 * k + (l >> 1);
-        if (row < XT) {
-            int64_t tr = t0 + row;
-            if (tr >= p.T) tr = p.T - 1;
-            xsrc[k] = p.xe + tr * ebytes + 16 * (l & 1);
-        } else {
-            int orow = o0 + row - XT;
-            if (orow >= p.m) orow = p.m - 1;
-            xsrc[k] = p.we + (int64_t)orow * ebytes + 16 * (l & 1);
-        }
-    }
+    // Exponents: 8 bytes per row and iteration, stored in tile order (rows in tiles of 128; per tile and iteration the
+    // 128 rows' 8 bytes are contiguous), so one iteration's exponents of a tile are 1 KB in one piece: one global-to-LDS
+    // instruction per operand, issued with the code tiles (wave 0: tokens, wave 1: channels).  Measured on the way: with
+    // row-major exponents fetched into registers (8 bytes per lane, row and iteration: four times as many cache lines
+    // touched per iteration as the code tiles) the exponents took 45 % of the kernel's time; fetched through LDS 32
+    // bytes per row at a time, still 25 %.
+    const int64_t tile_e = (int64_t)nk * 1024;   // bytes of exponents per tile of 128 rows
+    const unsigned char* xsrc = (w == 0 ? p.xe + (int64_t)blockIdx.x * tile_e : p.we + (int64_t)blockIdx.y * tile_e) + 16 * l;
     unsigned char* ebuf = smem + 4 * X_TILE_BYTES;
-    auto issue_exps = [&](int grp) {   // past the last group the last one is re-read (nobody uses it)
-        const int g = grp < ngrp ? grp : ngrp - 1;
-        const int off = g == ngrp - 1 ? last_base : 32 * g;
-#pragma unroll
-        for (int k = 0; k < 2; ++k)
-            __builtin_amdgcn_global_load_lds((gptr)(xsrc[k] + off), (lptr)(ebuf + (grp & 1) * X_EXP_BYTES + w * 2048 + k * 1024), 16, 0, 0);
+    auto issue_exps = [&](int it, int buf) {   // past the last iteration the last one is re-read (nobody uses it)
+        const int itc = it < nk ? it : nk - 1;
+        if (w < 2) __builtin_amdgcn_global_load_lds((gptr)(xsrc + (int64_t)itc * 1024), (lptr)(ebuf + buf * X_EXP_BYTES + w * 1024), 16, 0, 0);
     };
-    // this lane's four operand rows (x = 0, 1: tokens 64 wm + 32 x + c; x = 2, 3: channels 64 wn + 32 (x - 2) + c) for
-    // iteration `it`.  K step kp (64 codes) uses block 2 kp + h; the MFMA picks a byte of a register by an immediate, the
-    // same for every lane, so the half-wave h = 1 shifts its bytes down by one: byte 2 (kp & 1) of dword kp / 2 then is
-    // the block of this lane.
-    const int eoff[4] = {(64 * wm + c) * 32, (64 * wm + 32 + c) * 32, (XT + 64 * wn + c) * 32, (XT + 64 * wn + 32 + c) * 32};
-    auto lds_exps = [&](int it, u32x2 (&e)[4]) {
-        const int g = it >> 2;
-        const int within = 8 * it - (g >= ngrp - 1 ? last_base : 32 * g);   // past the end: some in-range garbage
-        const unsigned char* base = ebuf + (g & 1) * X_EXP_BYTES + (within & 24);
+    // this lane's four operand rows (x = 0, 1: tokens 64 wm + 32 x + c; x = 2, 3: channels 64 wn + 32 (x - 2) + c).  K
+    // step kp (64 codes) uses block 2 kp + h; the MFMA picks a byte of a register by an immediate, the same for every
+    // lane, so the half-wave h = 1 shifts its bytes down by one: byte 2 (kp & 1) of dword kp / 2 then is the block of
+    // this lane.
+    const int eoff[4] = {(64 * wm + c) * 8, (64 * wm + 32 + c) * 8, (XT + 64 * wn + c) * 8, (XT + 64 * wn + 32 + c) * 8};
+    auto lds_exps = [&](int buf, u32x2 (&e)[4]) {
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
-            const u32x2 v = *reinterpret_cast<const u32x2*>(base + eoff[x]);
+            const u32x2 v = *reinterpret_cast<const u32x2*>(ebuf + buf * X_EXP_BYTES + eoff[x]);
             e[x] = u32x2{v[0] >> (8 * h), v[1] >> (8 * h)};
         }
     };
@@ -163,9 +142,10 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     u32x4 P[2][4];
     u32x2 E[2][4];   // exponents of the current and of the next tile
     issue(0, 0);
-    issue_exps(0);
+    issue_exps(0, 0);
     tile_ready();
     issue(1, 1);
+    issue_exps(1, 1);
 #pragma unroll
     for (int x = 0; x < 4; ++x) P[0][x] = lds_chunk(0, 0, x);
     lds_exps(0, E[0]);
@@ -183,10 +163,10 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (kp == NKP - 2) {
-                tile_ready();          // tile it + 1 and, if it starts a pair of iterations, its exponents are in LDS
+                tile_ready();          // tile it + 1 and its exponents are in LDS; buffer `buf` is free
+                lds_exps(buf ^ 1, en);
                 issue(it + 2, buf);
-                if ((it & 3) == 2) issue_exps((it + 2) >> 2);   // the next four iterations' exponents
-                lds_exps(it + 1, en);
+                issue_exps(it + 2, buf);
             }
         }
     };

@@ -24,6 +24,7 @@ struct TqArgs {
     int64_t x_stride;
     uint8_t* out_codes;
     _Float16* out_scales;
+    int mx_tiled = 0;
 };
 
 // Kernel-side argument block of the activation kernels.
@@ -40,6 +41,7 @@ struct TqDev {
     int clip_mode;
     int vec8;       // rows can be moved in 16-byte chunks that never straddle a row of X~
     int out_vec16;  // code rows are whole 16-byte units at 16-byte aligned addresses
+    int mx_tiled = 0;   // MXFP4 output only: exponents in the tile order the MXFP4 product reads (see flatquant.h)
 };
 
 // Specialised kernels for n2 a multiple of 32 and 16-byte aligned buffers (fq_tq_fast.hip).

@@ -534,9 +534,18 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
             for (int q = tid; q < nq; q += NT) __builtin_nontemporal_store(stg[(q / B) * (B + 1) + q % B], dst + q);
         }
         if constexpr (MX) {   // n1 * B exponent bytes of the token, a multiple of 4 (checked on the host)
-            const uint32_t* src = reinterpret_cast<const uint32_t*>(mxs);
-            uint32_t* dsc = reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(p.out_scales) + t * ((int64_t)n1 * B));
-            for (int i = tid; i < n1 * B / 4; i += NT) dsc[i] = src[i];
+            if (p.mx_tiled) {
+                // tile order of the MXFP4 product: rows in tiles of 128; per tile and K iteration (256 channels = 8
+                // exponents) the 128 rows' 8 bytes are contiguous: byte (((t / 128) KI + j) 128 + t % 128) 8 + b
+                const uint2* src = reinterpret_cast<const uint2*>(mxs);
+                const int ki = n1 * B / 8;   // a whole number of iterations (checked on the host)
+                uint2* dsc = reinterpret_cast<uint2*>(p.out_scales) + (t >> 7) * ((int64_t)ki * 128) + (t & 127);
+                for (int j = tid; j < ki; j += NT) dsc[(int64_t)j * 128] = src[j];
+            } else {
+                const uint32_t* src = reinterpret_cast<const uint32_t*>(mxs);
+                uint32_t* dsc = reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(p.out_scales) + t * ((int64_t)n1 * B));
+                for (int i = tid; i < n1 * B / 4; i += NT) dsc[i] = src[i];
+            }
         } else {
             p.out_scales[t] = sh;   // every lane writes the same two bytes: cheaper than a branch around the store
         }

@@ -125,8 +125,15 @@ def test_argument_validation_without_a_device():
     gx = lambda **k: fq.flatquant_mxfp4_gemm(**{**dict(x_codes=A, x_scales=A + 0x100000, w_codes=A + 0x200000, w_scales=A + 0x300000, T=4, m=8,
                                                      n=1024, out=A + 0x400000, out_stride=8, check=False), **k})
     assert gx(T=0) == fq.FQ_OK and gx(m=0, out_stride=0) == fq.FQ_OK
-    assert gx(n=500) == fq.FQ_UNSUPPORTED_SHAPE and gx(n=768) == fq.FQ_UNSUPPORTED_SHAPE and gx(out_stride=7) == fq.FQ_INVALID_ARG and gx(w_scales=None) == fq.FQ_INVALID_ARG
-    assert gx(x_codes=A + 8) == fq.FQ_MISALIGNED and gx(x_scales=A + 0x100004) == fq.FQ_MISALIGNED
+    assert gx(n=500) == fq.FQ_UNSUPPORTED_SHAPE and gx(out_stride=7) == fq.FQ_INVALID_ARG and gx(w_scales=None) == fq.FQ_INVALID_ARG
+    assert gx(x_codes=A + 8) == fq.FQ_MISALIGNED and gx(x_scales=A + 0x100008) == fq.FQ_MISALIGNED
+    assert fq.fq_mxfp4_tiled_scale_bytes(1, 256) == 128 * 8 and fq.fq_mxfp4_tiled_scale_bytes(129, 512) == 256 * 16
+    assert fq.fq_mxfp4_tiled_scale_bytes(5, 300) == 0
+    mxt = lambda **k: fq.flatquant_transform_mxfp4_tiled(**{**dict(x=A, P1=A + 0x100000, P2=A + 0x200000, clip=A + 0x300000, clip_mode=1, T=4,
+                                                                n1=64, n2=64, x_stride=4096, out_codes=A + 0x400000, out_scales=A + 0x500000,
+                                                                check=False), **k})
+    assert mxt(T=0) == fq.FQ_OK and mxt(out_scales=A + 0x500004) == fq.FQ_MISALIGNED
+    assert mxt(n1=2, n2=64, x_stride=128) == fq.FQ_UNSUPPORTED_SHAPE      # 128 channels: not a whole group of 8 exponents
     assert gx(out=A + 0x300000) == fq.FQ_INVALID_ARG          # output overlaps the weight exponents
 
     dmx = lambda **k: fq.flatquant_dequant_mxfp4(**{**dict(codes=A, scales=A + 0x100000, rows=4, n=64, out=A + 0x200000, check=False), **k})
