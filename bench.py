@@ -346,6 +346,7 @@ def main() -> int:
                             "layer_speedup_vs_fp16_matmul": ms_h / ms_l}
 
         time_mx_layer("mxfp4_layer_prefill_qkvo_7b", 2048, 4096, 64, 64, 50, 5)
+        time_mx_layer("mxfp4_layer_prefill_down_7b", 2048, 4096, 86, 128, 30, 5)
         time_layer("w4a4_layer_prefill_qkvo_7b", 2048, 4096, 64, 64, 50, 5)
         time_layer("w4a4_layer_prefill_down_7b", 2048, 4096, 86, 128, 30, 5)
         time_layer("w4a4_layer_decode_qkvo_7b", 64, 4096, 64, 64, 200, 20)
