@@ -546,10 +546,7 @@ def test_head_transform_fp16_out(T, H, shared):
 
 
 # ---- W4A4 matrix product ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("T,m,n,pad", [(300, 260, 512, 0), (128, 128, 256, 0), (1, 1, 256, 0), (2048, 384, 4096, 0), (77, 200, 11008, 24),
-                                       (64, 4096, 4096, 0), (33, 100, 512, 0), (17, 4099, 11008, 5), (32, 64, 256, 0), (65, 96, 768, 0),
-                                       (9, 40, 2304, 0), (64, 33, 11008, 0), (8, 64, 4096, 0)])
-def test_w4a4_gemm(T, m, n, pad):
+def _w4a4_case(T, m, n, pad):
     """Integer accumulation is exact, so the only freedom is the final rounding: two fp32 multiplications and one fp16
     rounding against the oracle's single rounding of the fp64 value (2^-11 relative + two fp32 roundings)."""
     r = np.random.Generator(np.random.PCG64(900 + T + m + n))
@@ -577,3 +574,20 @@ def test_w4a4_gemm(T, m, n, pad):
     same = float((body[:, :m] == y16).mean())
     print(f"[parity] w4a4 T={T} m={m} n={n}: max err/tol {float((err / tol).max()):.3f}, identical to the oracle's fp16 in {same * 100:.3f} %", flush=True)
     assert same > 0.99
+
+
+@pytest.mark.parametrize("T,m,n,pad", [(300, 260, 512, 0), (128, 128, 256, 0), (1, 1, 256, 0), (2048, 384, 4096, 0), (77, 200, 11008, 24),
+                                       (64, 4096, 4096, 0), (33, 100, 512, 0), (17, 4099, 11008, 5), (32, 64, 256, 0), (65, 96, 768, 0),
+                                       (9, 40, 2304, 0), (64, 33, 11008, 0), (8, 64, 4096, 0)])
+def test_w4a4_gemm(T, m, n, pad):
+    _w4a4_case(T, m, n, pad)
+
+
+@pytest.mark.parametrize("knob,value,T,m,n", [("FLATQUANT_GEMM_WIDE", 1, 300, 260, 768), ("FLATQUANT_GEMM_WIDE", 1, 513, 129, 256),
+                                              ("FLATQUANT_GEMM_WIDE", 0, 2048, 4224, 512), ("FLATQUANT_GEMM_DECODE", 0, 40, 100, 1024),
+                                              ("FLATQUANT_GEMM_DECODE", 1, 5, 70, 512), ("FLATQUANT_GEMM_TILED", 1, 33, 96, 768)])
+def test_w4a4_gemm_every_form(tuning, knob, value, T, m, n):
+    """The forms the library would not pick by itself for these sizes: 256-token tiles on a small launch, 128-token
+    tiles on a large one, both few-token forms on either side of their switch-over, the tiled product for few tokens."""
+    tuning(knob, value)
+    _w4a4_case(T, m, n, 0)
