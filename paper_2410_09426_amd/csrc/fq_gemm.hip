@@ -444,12 +444,171 @@ __global__ __launch_bounds__(G_NT) void w4a4_decode_lds_kernel(GemmDev p) {
     }
 }
 
+// ---- few tokens, third form: every operand byte goes from global memory straight into LDS, a whole cache line per
+// row at a time, many lines ahead.  The two forms above feed the MFMA from registers, 32 bytes of 32 rows per load: four
+// instructions (and tag look-ups) per cache line, and only as much in flight as the registers hold.  Here a wave owns
+// every fourth 128-byte line of K (256 codes) of the workgroup's 32 weight rows and of the token rows, with a ring of
+// `depth` line slots of its own in LDS: one global-to-LDS instruction moves 8 whole rows, the wave waits only for its
+// own oldest slot (no barrier in the loop), multiplies it and requests the line `depth` steps ahead into the same slot.
+// The slots use the swizzle of the tiled kernel (slot chunk j of row r holds the row's chunk j ^ ((r >> 1) & 7)).
+template <int NTD>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8 for T <= 8, 16, 32, 64
+__global__ __launch_bounds__(1024) void w4a4_skinny_kernel(GemmDev p, int depth) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int NTT = NTD > 4 ? NTD / 4 : 1;           // MFMA token tiles of 32
+    constexpr int XROWS = 8 * NTD;
+    constexpr int SLOT = (32 + XROWS) * 128;             // weight rows, then token rows, one line each
+    constexpr int NI = 4 + NTD;                          // load instructions per step
+    const int tid = threadIdx.x;
+    const int l = tid & 63, c = l & 31, h = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int o0 = blockIdx.x * 32;
+    const int64_t kbytes = p.n / 2;
+    const int nl = p.n / 256;                            // lines per row
+    const int nwv = blockDim.x >> 6;                     // waves: 4, 8 or 16
+    const int ns = (nl - w + nwv - 1) / nwv;             // this wave's steps: lines w, w + nwv, ...
+    unsigned char* ring = smem + w * depth * SLOT;
+
+    const unsigned char* wsrc[4];
+    const unsigned char* xsrc[NTD];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int row = 8 * k + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
+        int orow = o0 + row;
+        if (orow >= p.m) orow = p.m - 1;
+        wsrc[k] = p.wc + (int64_t)orow * kbytes + 128 * w + 16 * ch;
+    }
+#pragma unroll
+    for (int k = 0; k < NTD; ++k) {
+        const int row = 8 * k + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
+        int64_t t = row;
+        if (t >= p.T) t = p.T - 1;
+        xsrc[k] = p.xc + t * kbytes + 128 * w + 16 * ch;
+    }
+    typedef const __attribute__((address_space(1))) void* gptr;
+    typedef __attribute__((address_space(3))) void* lptr;
+    auto issue = [&](int s, int slot) {
+        unsigned char* base = ring + slot * SLOT;
+        const int64_t off = (int64_t)s * (128 * nwv);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) __builtin_amdgcn_global_load_lds((gptr)(wsrc[k] + off), (lptr)(base + k * 1024), 16, 0, 0);
+#pragma unroll
+        for (int k = 0; k < NTD; ++k) __builtin_amdgcn_global_load_lds((gptr)(xsrc[k] + off), (lptr)(base + 4096 + k * 1024), 16, 0, 0);
+    };
+    i32x16 acc[NTT];
+#pragma unroll
+    for (int i = 0; i < NTT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    const int woff = c * 128;
+    const int whs = h ^ ((c >> 1) & 7);
+    int xoff[NTT], xhs[NTT];
+#pragma unroll
+    for (int i = 0; i < NTT; ++i) {
+        const int row = (32 * i + c) & (XROWS - 1);       // fewer than 32 token rows: the lanes past them repeat rows
+        xoff[i] = 4096 + row * 128;
+        xhs[i] = h ^ ((row >> 1) & 7);
+    }
+    const int npre = ns < depth ? ns : depth;
+    for (int s = 0; s < npre; ++s) issue(s, s);
+    int slot = 0;
+    for (int s = 0; s < ns; ++s) {
+        const int left = ns - 1 - s;
+        wait_ring_step<NI>(left < depth - 1 ? left : depth - 1);
+        const unsigned char* base = ring + slot * SLOT;
+        u32x4 wv[4], xv[4][NTT];
+#pragma unroll
+        for (int kp = 0; kp < 4; ++kp) {
+            wv[kp] = *reinterpret_cast<const u32x4*>(base + woff + 16 * ((2 * kp) ^ whs));
+#pragma unroll
+            for (int i = 0; i < NTT; ++i) xv[kp][i] = *reinterpret_cast<const u32x4*>(base + xoff[i] + 16 * ((2 * kp) ^ xhs[i]));
+        }
+#pragma unroll
+        for (int kp = 0; kp < 4; ++kp) {
+            i32x4 ws0, ws1;
+            widen(wv[kp], ws0, ws1);
+#pragma unroll
+            for (int i = 0; i < NTT; ++i) {
+                i32x4 xs0, xs1;
+                widen(xv[kp][i], xs0, xs1);
+                acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws0, xs0, acc[i], 0, 0, 0);
+                acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws1, xs1, acc[i], 0, 0, 0);
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the slot has been read: it may take the next line
+        if (s + depth < ns) issue(s + depth, slot);
+        slot = (slot + 1 == depth) ? 0 : slot + 1;
+    }
+    wait_vm_pending<0>();
+    __syncthreads();                                     // every wave is done with its ring: the partial sums go there
+    i32x4* part = reinterpret_cast<i32x4*>(smem);
+#pragma unroll
+    for (int i = 0; i < NTT; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            part[((w * NTT + i) * 4 + g) * 64 + l] = i32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
+    __syncthreads();
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    const bool wide = ((reinterpret_cast<uintptr_t>(p.out) & 7) == 0) && (p.out_stride % 4 == 0);
+    for (int e = tid; e < NTT * 4 * 64; e += (int)blockDim.x) {
+        const int el = e & 63, g = (e >> 6) & 3, i = e >> 8;
+        i32x4 sum = part[e];
+        for (int ww = 1; ww < nwv; ++ww) sum += part[ww * NTT * 4 * 64 + e];
+        const int64_t t = 32 * i + (el & 31);
+        const int o = o0 + 8 * g + 4 * (el >> 5);
+        if (t < p.T && o < p.m) {
+            const float sx = (float)p.xs[t];
+            _Float16 v[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) v[x] = (_Float16)((float)(sum[x] >> 8) * sx * (float)p.ws[o + x < p.m ? o + x : p.m - 1]);
+            _Float16* dst = p.out + t * p.out_stride + o;
+            if (wide && o + 4 <= p.m) {
+                *reinterpret_cast<half4*>(dst) = half4{v[0], v[1], v[2], v[3]};
+            } else {
+                for (int x = 0; x < 4; ++x)
+                    if (o + x < p.m) dst[x] = v[x];
+            }
+        }
+    }
+}
+
+template <int NTD>
+static hipError_t skinny_launch(const GemmDev& d, hipStream_t stream) {
+    static OccCache oc;
+    int unused = 0;
+    hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_skinny_kernel<NTD>), 1024, kRingLdsMax, oc, unused);
+    if (e != hipSuccess) return e;
+    constexpr int SLOT = (32 + 8 * NTD) * 128, NI = 4 + NTD;
+    const unsigned wgs = (unsigned)((d.m + 31) / 32);
+    const int nl = d.n / 256;
+    // One workgroup per CU (or fewer): 8 waves, so that every SIMD has two to overlap, and two slots each.  More than
+    // one per CU: small workgroups (4 waves, one slot) that are all resident at once; what the second slot or the
+    // other four waves would hide, the neighbouring workgroup hides.  (Measured on 4096 / 11008-wide layers.)
+    const bool crowded = (int)wgs > cu_count();
+    int nwv = env_int("FLATQUANT_GEMM_WAVES", crowded ? 4 : 8);
+    int depth = env_int("FLATQUANT_GEMM_DEPTH", crowded ? 1 : 2);
+    if ((nwv != 4 && nwv != 8 && nwv != 16) || depth < 1 || depth > kRingMaxDepth) return hipErrorInvalidValue;
+    while (nwv > 4 && nwv * SLOT > kRingLdsMax) nwv >>= 1;
+    const int steps = (nl + nwv - 1) / nwv;                               // of the wave with the most lines
+    if (depth > steps) depth = steps;
+    while (depth > 1 && (nwv * depth * SLOT > kRingLdsMax || (depth - 1) * NI > 63)) --depth;
+    const int bytes = nwv * depth * SLOT;                                 // the partial sums (4 KB per wave and token tile) reuse the rings
+    hipLaunchKernelGGL(w4a4_skinny_kernel<NTD>, dim3(wgs), dim3(64 * nwv), bytes, stream, d, depth);
+    return hipGetLastError();
+}
+
 hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
     int unused = 0;
     GemmDev d;
     d.xc = a.x_codes; d.xs = a.x_scales; d.wc = a.w_codes; d.ws = a.w_scales; d.out = a.out;
     d.T = a.T; d.out_stride = a.out_stride; d.m = a.m; d.n = a.n;
     if (a.T <= 64 && env_int("FLATQUANT_GEMM_TILED", 0) == 0) {   // decode: one pass over the weights, K split inside a workgroup
+        // FLATQUANT_GEMM_DECODE = 0 / 1 forces one of the register-fed forms, 2 (the default) the LDS ring
+        if (env_int("FLATQUANT_GEMM_DECODE", 2) == 2) {
+            if (a.T <= 8) return skinny_launch<1>(d, stream);
+            if (a.T <= 16) return skinny_launch<2>(d, stream);
+            if (a.T <= 32) return skinny_launch<4>(d, stream);
+            return skinny_launch<8>(d, stream);
+        }
         const dim3 grid((unsigned)((a.m + 31) / 32));
         // more than a few tokens: activation codes through LDS (FLATQUANT_GEMM_DECODE = 0 / 1 forces one form)
         const int form = env_int("FLATQUANT_GEMM_DECODE", a.T > 8 ? 1 : 0);

@@ -212,10 +212,181 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     }
 }
 
+// ---- few tokens (T <= 64): the weights are read once and the kernel is bound by how fast a CU takes them in.  A
+// workgroup owns 32 output channels for all tokens; its waves split K by 128-byte lines (256 codes: wave w takes
+// lines w, w + waves, ...) and each keeps a ring of line slots of its own in LDS: four global-to-LDS instructions
+// bring 32 weight rows of a line (8 whole rows each), one per 8 token rows the tokens, one the 256 bytes of weight
+// exponents (the tile order keeps them contiguous) and one per 32 tokens theirs.  A wave waits only for its own
+// oldest slot (no barrier in the loop).  The partial sums of the waves are added in fp32 through LDS at the end.
+template <int NTD>   // token rows in groups of 8: 1, 2, 4, 8 for T <= 8, 16, 32, 64
+__global__ __launch_bounds__(1024) void mxfp4_skinny_kernel(MxGemmDev p, int depth) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int NTT = NTD > 4 ? NTD / 4 : 1;           // MFMA token tiles of 32
+    constexpr int XROWS = 8 * NTD;
+    constexpr int XOFF = 4096, WEOFF = XOFF + 1024 * NTD, XEOFF = WEOFF + 256;
+    constexpr int SLOT = XEOFF + 256 * NTT;
+    constexpr int NI = 4 + NTD + 1 + NTT;                // load instructions per step
+    const int tid = threadIdx.x;
+    const int l = tid & 63, c = l & 31, h = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwv = blockDim.x >> 6;
+    const int o0 = blockIdx.x * 32;
+    const int64_t kbytes = p.n / 2;
+    const int nl = p.n / 256;                            // lines per row
+    const int ns = (nl - w + nwv - 1) / nwv;             // this wave's steps
+    unsigned char* ring = smem + w * depth * SLOT;
+
+    const unsigned char* wsrc[4];
+    const unsigned char* xsrc[NTD];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int row = 8 * k + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
+        int orow = o0 + row;
+        if (orow >= p.m) orow = p.m - 1;
+        wsrc[k] = p.wc + (int64_t)orow * kbytes + 128 * w + 16 * ch;
+    }
+#pragma unroll
+    for (int k = 0; k < NTD; ++k) {
+        const int row = 8 * k + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
+        int64_t t = row;
+        if (t >= p.T) t = p.T - 1;
+        xsrc[k] = p.xc + t * kbytes + 128 * w + 16 * ch;
+    }
+    // exponents of line j: 1 KB per tile of 128 rows, 8 bytes per row.  The workgroup's 32 channels are 256 bytes of
+    // their tile; the tokens are rows 0 .. of tile 0 (the tensor is padded to whole tiles, so rows past T exist).
+    const unsigned char* wesrc = p.we + (int64_t)(o0 >> 7) * nl * 1024 + 8 * (o0 & 127) + 1024 * w + 4 * l;
+    const unsigned char* xesrc = p.xe + 1024 * w + 4 * l;
+    typedef const __attribute__((address_space(1))) void* gptr;
+    typedef __attribute__((address_space(3))) void* lptr;
+    auto issue = [&](int s, int slot) {
+        unsigned char* base = ring + slot * SLOT;
+        const int64_t off = (int64_t)s * (128 * nwv);
+        const int64_t eoff = (int64_t)s * (1024 * nwv);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) __builtin_amdgcn_global_load_lds((gptr)(wsrc[k] + off), (lptr)(base + k * 1024), 16, 0, 0);
+#pragma unroll
+        for (int k = 0; k < NTD; ++k) __builtin_amdgcn_global_load_lds((gptr)(xsrc[k] + off), (lptr)(base + XOFF + k * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr)(wesrc + eoff), (lptr)(base + WEOFF), 4, 0, 0);
+#pragma unroll
+        for (int i = 0; i < NTT; ++i) __builtin_amdgcn_global_load_lds((gptr)(xesrc + eoff + 256 * i), (lptr)(base + XEOFF + 256 * i), 4, 0, 0);
+    };
+
+    f32x16 acc[NTT];
+#pragma unroll
+    for (int i = 0; i < NTT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    const int woff = c * 128;
+    const int whs = h ^ ((c >> 1) & 7);
+    int xoff[NTT], xhs[NTT];
+#pragma unroll
+    for (int i = 0; i < NTT; ++i) {
+        const int row = (32 * i + c) & (XROWS - 1);       // fewer than 32 token rows: the lanes past them repeat rows
+        xoff[i] = XOFF + row * 128;
+        xhs[i] = h ^ ((row >> 1) & 7);
+    }
+    const int npre = ns < depth ? ns : depth;
+    for (int s = 0; s < npre; ++s) issue(s, s);
+    int slot = 0;
+    for (int s = 0; s < ns; ++s) {
+        const int left = ns - 1 - s;
+        wait_ring_step<NI>(left < depth - 1 ? left : depth - 1);
+        const unsigned char* base = ring + slot * SLOT;
+        // block 2 kp + h of this lane's row: after the shift by 8 h, byte 2 (kp & 1) of dword kp / 2
+        u32x2 ew = *reinterpret_cast<const u32x2*>(base + WEOFF + 8 * c);
+        ew = u32x2{ew[0] >> (8 * h), ew[1] >> (8 * h)};
+        u32x2 ex[NTT];
+#pragma unroll
+        for (int i = 0; i < NTT; ++i) {
+            const u32x2 v = *reinterpret_cast<const u32x2*>(base + XEOFF + 256 * i + 8 * c);
+            ex[i] = u32x2{v[0] >> (8 * h), v[1] >> (8 * h)};
+        }
+        u32x4 wv[4], xv[4][NTT];
+#pragma unroll
+        for (int kp = 0; kp < 4; ++kp) {
+            wv[kp] = *reinterpret_cast<const u32x4*>(base + woff + 16 * ((2 * kp) ^ whs));
+#pragma unroll
+            for (int i = 0; i < NTT; ++i) xv[kp][i] = *reinterpret_cast<const u32x4*>(base + xoff[i] + 16 * ((2 * kp) ^ xhs[i]));
+        }
+#pragma unroll
+        for (int kp = 0; kp < 4; ++kp) {
+            const i32x8 a = {(int)wv[kp][0], (int)wv[kp][1], (int)wv[kp][2], (int)wv[kp][3], 0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < NTT; ++i) {
+                const i32x8 b = {(int)xv[kp][i][0], (int)xv[kp][i][1], (int)xv[kp][i][2], (int)xv[kp][i][3], 0, 0, 0, 0};
+                if (kp & 1) acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i], 4, 4, 2, (int)ew[kp >> 1], 2, (int)ex[i][kp >> 1]);
+                else acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i], 4, 4, 0, (int)ew[kp >> 1], 0, (int)ex[i][kp >> 1]);
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the slot has been read: it may take the next line
+        if (s + depth < ns) issue(s + depth, slot);
+        slot = (slot + 1 == depth) ? 0 : slot + 1;
+    }
+    wait_vm_pending<0>();
+    __syncthreads();                                     // every wave is done with its ring: the partial sums go there
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    f32x4* part = reinterpret_cast<f32x4*>(smem);        // [wave][tile][quad g][lane] x 4 floats
+#pragma unroll
+    for (int i = 0; i < NTT; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            part[((w * NTT + i) * 4 + g) * 64 + l] = f32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
+    __syncthreads();
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    const bool wide = ((reinterpret_cast<uintptr_t>(p.out) & 7) == 0) && (p.out_stride % 4 == 0);
+    for (int e = tid; e < NTT * 4 * 64; e += (int)blockDim.x) {
+        const int el = e & 63, g = (e >> 6) & 3, i = e >> 8;
+        f32x4 sum = part[e];
+        for (int ww = 1; ww < nwv; ++ww) sum += part[ww * NTT * 4 * 64 + e];
+        const int64_t t = 32 * i + (el & 31);
+        const int o = o0 + 8 * g + 4 * (el >> 5);
+        if (t < p.T && o < p.m) {
+            const _Float16 v[4] = {(_Float16)sum[0], (_Float16)sum[1], (_Float16)sum[2], (_Float16)sum[3]};
+            _Float16* dst = p.out + t * p.out_stride + o;
+            if (wide && o + 4 <= p.m) {
+                *reinterpret_cast<half4*>(dst) = half4{v[0], v[1], v[2], v[3]};
+            } else {
+                for (int x = 0; x < 4; ++x)
+                    if (o + x < p.m) dst[x] = v[x];
+            }
+        }
+    }
+}
+
+template <int NTD>
+static hipError_t mx_skinny_launch(const MxGemmDev& d, hipStream_t stream) {
+    static OccCache oc;
+    int unused = 0;
+    hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(mxfp4_skinny_kernel<NTD>), 1024, kRingLdsMax, oc, unused);
+    if (e != hipSuccess) return e;
+    constexpr int NTT = NTD > 4 ? NTD / 4 : 1;
+    constexpr int SLOT = 4096 + 1024 * NTD + 256 + 256 * NTT, NI = 4 + NTD + 1 + NTT;
+    const unsigned wgs = (unsigned)((d.m + 31) / 32);
+    const int nl = d.n / 256;
+    // as for the INT4 product: 8 waves and two slots when there is at most one workgroup per CU, else 4 waves and one
+    const bool crowded = (int)wgs > cu_count();
+    int nwv = env_int("FLATQUANT_GEMM_WAVES", crowded ? 4 : 8);
+    int depth = env_int("FLATQUANT_GEMM_DEPTH", crowded ? 1 : 2);
+    if ((nwv != 4 && nwv != 8 && nwv != 16) || depth < 1 || depth > kRingMaxDepth) return hipErrorInvalidValue;
+    while (nwv > 4 && nwv * SLOT > kRingLdsMax) nwv >>= 1;
+    const int steps = (nl + nwv - 1) / nwv;
+    if (depth > steps) depth = steps;
+    while (depth > 1 && (nwv * depth * SLOT > kRingLdsMax || (depth - 1) * NI > 63)) --depth;
+    const int bytes = nwv * depth * SLOT;                // the partial sums (4 KB per wave and token tile) reuse the rings
+    hipLaunchKernelGGL(mxfp4_skinny_kernel<NTD>, dim3(wgs), dim3(64 * nwv), bytes, stream, d, depth);
+    return hipGetLastError();
+}
+
 hipError_t mxfp4_gemm_launch(const MxGemmArgs& a, hipStream_t stream) {
     MxGemmDev d;
     d.xc = a.x_codes; d.xe = a.x_exps; d.wc = a.w_codes; d.we = a.w_exps; d.out = a.out;
     d.T = a.T; d.out_stride = a.out_stride; d.m = a.m; d.n = a.n;
+    if (a.T <= 64 && env_int("FLATQUANT_GEMM_TILED", 0) == 0) {
+        if (a.T <= 8) return mx_skinny_launch<1>(d, stream);
+        if (a.T <= 16) return mx_skinny_launch<2>(d, stream);
+        if (a.T <= 32) return mx_skinny_launch<4>(d, stream);
+        return mx_skinny_launch<8>(d, stream);
+    }
     static OccCache cache;
     int unused = 0;
     hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(mxfp4_gemm_kernel), X_NT, X_LDS_BYTES, cache, unused);

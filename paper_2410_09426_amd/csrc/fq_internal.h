@@ -106,6 +106,33 @@ struct MxGemmArgs {
 };
 hipError_t mxfp4_gemm_launch(const MxGemmArgs& a, hipStream_t stream);
 
+// Few-token products (fq_gemm.hip, fq_gemm_mx.hip): per wave a ring of LDS slots filled by global-to-LDS loads.
+constexpr int kRingMaxDepth = 8;
+constexpr int kRingLdsMax = 160 * 1024;
+#if defined(__HIP_DEVICE_COMPILE__) || defined(__HIPCC__)
+// until at most N of this wave's vector-memory loads are outstanding (they complete in order)
+template <int N>
+__device__ __forceinline__ void wait_vm_pending() {
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// until the ring step with `pend` later steps of NI load instructions each in flight has landed
+template <int NI>
+__device__ __forceinline__ void wait_ring_step(int pend) {
+    switch (pend) {
+        case 0: wait_vm_pending<0>(); break;
+        case 1: if constexpr (NI <= 63) wait_vm_pending<NI>(); else wait_vm_pending<0>(); break;
+        case 2: if constexpr (2 * NI <= 63) wait_vm_pending<2 * NI>(); else wait_vm_pending<0>(); break;
+        case 3: if constexpr (3 * NI <= 63) wait_vm_pending<3 * NI>(); else wait_vm_pending<0>(); break;
+        case 4: if constexpr (4 * NI <= 63) wait_vm_pending<4 * NI>(); else wait_vm_pending<0>(); break;
+        case 5: if constexpr (5 * NI <= 63) wait_vm_pending<5 * NI>(); else wait_vm_pending<0>(); break;
+        case 6: if constexpr (6 * NI <= 63) wait_vm_pending<6 * NI>(); else wait_vm_pending<0>(); break;
+        case 7: if constexpr (7 * NI <= 63) wait_vm_pending<7 * NI>(); else wait_vm_pending<0>(); break;
+        default: wait_vm_pending<0>(); break;
+    }
+}
+#endif
+
 // Copy-like probe with the activation kernel's traffic (fq_probe.hip).
 hipError_t stream_probe_launch(const void* x, int64_t T, int n, int64_t x_stride, uint8_t* out, hipStream_t stream);
 

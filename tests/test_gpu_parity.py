@@ -468,8 +468,32 @@ def test_mxfp4_layer_both_factors():
     assert abs(rel - rel_o) <= 1e-3 * rel_o + 1e-6 * (int((dx > 0).sum()) + int((dw > 0).sum()) + 1)
 
 
-@pytest.mark.parametrize("T,m,n", [(128, 128, 256), (200, 300, 1280), (2048, 256, 4096), (1, 40, 768), (130, 129, 11008), (64, 4096, 1024), (300, 140, 512)])
+@pytest.mark.parametrize("T,m,n", [(128, 128, 256), (200, 300, 1280), (2048, 256, 4096), (1, 40, 768), (130, 129, 11008), (64, 4096, 1024), (300, 140, 512),
+                                   (8, 200, 256), (16, 300, 2304), (17, 129, 11008), (33, 4099, 512), (50, 96, 4096), (64, 11008, 4096), (3, 8200, 1024)])
 def test_mxfp4_gemm(T, m, n):
+    _mxfp4_gemm_case(T, m, n)
+
+
+@pytest.mark.parametrize("waves,depth,T,m,n", [(16, 1, 5, 100, 4096), (16, 2, 64, 70, 2304), (4, 3, 20, 330, 11008), (8, 8, 40, 64, 4096),
+                                               (4, 1, 1, 33, 256), (8, 2, 9, 8200, 512)])
+@pytest.mark.parametrize("kind", ["int4", "mxfp4"])
+def test_few_token_products_every_launch_shape(tuning, kind, waves, depth, T, m, n):
+    """The few-token kernels split K over 4, 8 or 16 waves with rings of 1 to 8 line slots; the library picks one shape
+    per launch, the others are forced here (a depth the ring cannot hold is cut back by the launcher)."""
+    tuning("FLATQUANT_GEMM_WAVES", waves)
+    tuning("FLATQUANT_GEMM_DEPTH", depth)
+    if kind == "int4":
+        _w4a4_case(T, m, n, 0)
+    else:
+        _mxfp4_gemm_case(T, m, n)
+
+
+def test_few_token_mxfp4_product_tiled_form(tuning):
+    tuning("FLATQUANT_GEMM_TILED", 1)
+    _mxfp4_gemm_case(40, 200, 1024)
+
+
+def _mxfp4_gemm_case(T, m, n):
     """Scaled-FP4 matrix product against the oracle's fp64 product of the de-quantized factors.  Products are exact; the
     fp32 accumulation may lose up to n * 2^-24 of sum |x^ w^|, and the result is rounded once to fp16."""
     r = np.random.Generator(np.random.PCG64(1000 + T + m + n))
@@ -585,9 +609,10 @@ def test_w4a4_gemm(T, m, n, pad):
 
 @pytest.mark.parametrize("knob,value,T,m,n", [("FLATQUANT_GEMM_WIDE", 1, 300, 260, 768), ("FLATQUANT_GEMM_WIDE", 1, 513, 129, 256),
                                               ("FLATQUANT_GEMM_WIDE", 0, 2048, 4224, 512), ("FLATQUANT_GEMM_DECODE", 0, 40, 100, 1024),
-                                              ("FLATQUANT_GEMM_DECODE", 1, 5, 70, 512), ("FLATQUANT_GEMM_TILED", 1, 33, 96, 768)])
+                                              ("FLATQUANT_GEMM_DECODE", 1, 5, 70, 512), ("FLATQUANT_GEMM_DECODE", 0, 7, 45, 768),
+                                              ("FLATQUANT_GEMM_DECODE", 1, 64, 130, 2304), ("FLATQUANT_GEMM_TILED", 1, 33, 96, 768)])
 def test_w4a4_gemm_every_form(tuning, knob, value, T, m, n):
     """The forms the library would not pick by itself for these sizes: 256-token tiles on a small launch, 128-token
-    tiles on a large one, both few-token forms on either side of their switch-over, the tiled product for few tokens."""
+    tiles on a large one, both register-fed few-token forms, the tiled product for few tokens."""
     tuning(knob, value)
     _w4a4_case(T, m, n, 0)
