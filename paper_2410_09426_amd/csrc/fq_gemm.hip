@@ -451,27 +451,33 @@ __global__ __launch_bounds__(G_NT) void w4a4_decode_lds_kernel(GemmDev p) {
 // `depth` line slots of its own in LDS: one global-to-LDS instruction moves 8 whole rows, the wave waits only for its
 // own oldest slot (no barrier in the loop), multiplies it and requests the line `depth` steps ahead into the same slot.
 // The slots use the swizzle of the tiled kernel (slot chunk j of row r holds the row's chunk j ^ ((r >> 1) & 7)).
-template <int NTD>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8 for T <= 8, 16, 32, 64
+// ROWS = 16: the workgroup owns 16 output channels only (twice as many workgroups, for layers with too few channels
+// to give every CU one of 32); the MFMA's upper 16 rows repeat the lower ones and are dropped.
+template <int NTD, int ROWS>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8 for T <= 8, 16, 32, 64
 __global__ __launch_bounds__(1024) void w4a4_skinny_kernel(GemmDev p, int depth) {
+    static_assert(ROWS == 16 || ROWS == 32, "weight rows per workgroup");
+    constexpr int NWI = ROWS / 8;                        // load instructions per line of the weight rows
+    constexpr int NG = ROWS / 8;                         // groups of 8 output channels
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int NTT = NTD > 4 ? NTD / 4 : 1;           // MFMA token tiles of 32
     constexpr int XROWS = 8 * NTD;
-    constexpr int SLOT = (32 + XROWS) * 128;             // weight rows, then token rows, one line each
-    constexpr int NI = 4 + NTD;                          // load instructions per step
+    constexpr int XOFF = ROWS * 128;
+    constexpr int SLOT = (ROWS + XROWS) * 128;           // weight rows, then token rows, one line each
+    constexpr int NI = NWI + NTD;                        // load instructions per step
     const int tid = threadIdx.x;
     const int l = tid & 63, c = l & 31, h = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int o0 = blockIdx.x * 32;
+    const int o0 = blockIdx.x * ROWS;
     const int64_t kbytes = p.n / 2;
     const int nl = p.n / 256;                            // lines per row
     const int nwv = blockDim.x >> 6;                     // waves: 4, 8 or 16
     const int ns = (nl - w + nwv - 1) / nwv;             // this wave's steps: lines w, w + nwv, ...
     unsigned char* ring = smem + w * depth * SLOT;
 
-    const unsigned char* wsrc[4];
+    const unsigned char* wsrc[NWI];
     const unsigned char* xsrc[NTD];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < NWI; ++k) {
         const int row = 8 * k + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
         int orow = o0 + row;
         if (orow >= p.m) orow = p.m - 1;
@@ -490,23 +496,41 @@ __global__ __launch_bounds__(1024) void w4a4_skinny_kernel(GemmDev p, int depth)
         unsigned char* base = ring + slot * SLOT;
         const int64_t off = (int64_t)s * (128 * nwv);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) __builtin_amdgcn_global_load_lds((gptr)(wsrc[k] + off), (lptr)(base + k * 1024), 16, 0, 0);
+        for (int k = 0; k < NWI; ++k) __builtin_amdgcn_global_load_lds((gptr)(wsrc[k] + off), (lptr)(base + k * 1024), 16, 0, 0);
 #pragma unroll
-        for (int k = 0; k < NTD; ++k) __builtin_amdgcn_global_load_lds((gptr)(xsrc[k] + off), (lptr)(base + 4096 + k * 1024), 16, 0, 0);
+        for (int k = 0; k < NTD; ++k) __builtin_amdgcn_global_load_lds((gptr)(xsrc[k] + off), (lptr)(base + XOFF + k * 1024), 16, 0, 0);
     };
     i32x16 acc[NTT];
 #pragma unroll
     for (int i = 0; i < NTT; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0;
-    const int woff = c * 128;
-    const int whs = h ^ ((c >> 1) & 7);
+    const int woff = (c & (ROWS - 1)) * 128;
+    const int whs = h ^ (((c & (ROWS - 1)) >> 1) & 7);
     int xoff[NTT], xhs[NTT];
 #pragma unroll
     for (int i = 0; i < NTT; ++i) {
         const int row = (32 * i + c) & (XROWS - 1);       // fewer than 32 token rows: the lanes past them repeat rows
-        xoff[i] = 4096 + row * 128;
+        xoff[i] = XOFF + row * 128;
         xhs[i] = h ^ ((row >> 1) & 7);
+    }
+    // The epilogue's element e = tid + k blockDim is 4 output channels of one token: their steps are requested now, so
+    // that the kernel's tail does not wait for them (at least 256 threads and at most 512 elements: k < 2).
+    constexpr int NE = NTT * NG * 64;
+    unsigned esx[2] = {}, esw[2][4] = {};                // raw fp16 bits, converted in the epilogue: nothing waits for them here
+    const uint16_t* xs_bits = reinterpret_cast<const uint16_t*>(p.xs);
+    const uint16_t* ws_bits = reinterpret_cast<const uint16_t*>(p.ws);
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int e = tid + k * (int)blockDim.x;
+        const int el = e & 63, g = (e >> 6) % NG, i = (e >> 6) / NG;
+        const int64_t t = 32 * i + (el & 31);
+        const int o = o0 + 8 * g + 4 * (el >> 5);
+        if (e < NE) {
+            esx[k] = xs_bits[t < p.T ? t : p.T - 1];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) esw[k][x] = ws_bits[o + x < p.m ? o + x : p.m - 1];
+        }
     }
     const int npre = ns < depth ? ns : depth;
     for (int s = 0; s < npre; ++s) issue(s, s);
@@ -544,22 +568,27 @@ __global__ __launch_bounds__(1024) void w4a4_skinny_kernel(GemmDev p, int depth)
 #pragma unroll
     for (int i = 0; i < NTT; ++i)
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-            part[((w * NTT + i) * 4 + g) * 64 + l] = i32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
+        for (int g = 0; g < NG; ++g)
+            part[((w * NTT + i) * NG + g) * 64 + l] = i32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
     __syncthreads();
     typedef _Float16 half4 __attribute__((ext_vector_type(4)));
     const bool wide = ((reinterpret_cast<uintptr_t>(p.out) & 7) == 0) && (p.out_stride % 4 == 0);
-    for (int e = tid; e < NTT * 4 * 64; e += (int)blockDim.x) {
-        const int el = e & 63, g = (e >> 6) & 3, i = e >> 8;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int e = tid + k * (int)blockDim.x;
+        if (e >= NE) break;
+        const int el = e & 63, g = (e >> 6) % NG, i = (e >> 6) / NG;
         i32x4 sum = part[e];
-        for (int ww = 1; ww < nwv; ++ww) sum += part[ww * NTT * 4 * 64 + e];
+        for (int ww = 1; ww < nwv; ++ww) sum += part[ww * NE + e];
         const int64_t t = 32 * i + (el & 31);
         const int o = o0 + 8 * g + 4 * (el >> 5);
         if (t < p.T && o < p.m) {
-            const float sx = (float)p.xs[t];
+            // (the empty statement pins the conversions here: hoisted to the loads, they would stall the kernel's start)
+            asm volatile("" : "+v"(esx[k]), "+v"(esw[k][0]), "+v"(esw[k][1]), "+v"(esw[k][2]), "+v"(esw[k][3]));
+            const float sx = (float)__builtin_bit_cast(_Float16, (uint16_t)esx[k]);
             _Float16 v[4];
 #pragma unroll
-            for (int x = 0; x < 4; ++x) v[x] = (_Float16)((float)(sum[x] >> 8) * sx * (float)p.ws[o + x < p.m ? o + x : p.m - 1]);
+            for (int x = 0; x < 4; ++x) v[x] = (_Float16)((float)(sum[x] >> 8) * sx * (float)__builtin_bit_cast(_Float16, (uint16_t)esw[k][x]));
             _Float16* dst = p.out + t * p.out_stride + o;
             if (wide && o + 4 <= p.m) {
                 *reinterpret_cast<half4*>(dst) = half4{v[0], v[1], v[2], v[3]};
@@ -571,14 +600,14 @@ __global__ __launch_bounds__(1024) void w4a4_skinny_kernel(GemmDev p, int depth)
     }
 }
 
-template <int NTD>
-static hipError_t skinny_launch(const GemmDev& d, hipStream_t stream) {
+template <int NTD, int ROWS>
+static hipError_t skinny_launch_rows(const GemmDev& d, hipStream_t stream) {
     static OccCache oc;
     int unused = 0;
-    hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_skinny_kernel<NTD>), 1024, kRingLdsMax, oc, unused);
+    hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_skinny_kernel<NTD, ROWS>), 1024, kRingLdsMax, oc, unused);
     if (e != hipSuccess) return e;
-    constexpr int SLOT = (32 + 8 * NTD) * 128, NI = 4 + NTD;
-    const unsigned wgs = (unsigned)((d.m + 31) / 32);
+    constexpr int SLOT = (ROWS + 8 * NTD) * 128, NI = ROWS / 8 + NTD;
+    const unsigned wgs = (unsigned)((d.m + ROWS - 1) / ROWS);
     const int nl = d.n / 256;
     // One workgroup per CU (or fewer): 8 waves, so that every SIMD has two to overlap, and two slots each.  More than
     // one per CU: small workgroups (4 waves, one slot) that are all resident at once; what the second slot or the
@@ -591,9 +620,18 @@ static hipError_t skinny_launch(const GemmDev& d, hipStream_t stream) {
     const int steps = (nl + nwv - 1) / nwv;                               // of the wave with the most lines
     if (depth > steps) depth = steps;
     while (depth > 1 && (nwv * depth * SLOT > kRingLdsMax || (depth - 1) * NI > 63)) --depth;
-    const int bytes = nwv * depth * SLOT;                                 // the partial sums (4 KB per wave and token tile) reuse the rings
-    hipLaunchKernelGGL(w4a4_skinny_kernel<NTD>, dim3(wgs), dim3(64 * nwv), bytes, stream, d, depth);
+    const int bytes = nwv * depth * SLOT;                                 // the partial sums (at most 4 KB per wave and token tile) reuse the rings
+    hipLaunchKernelGGL((w4a4_skinny_kernel<NTD, ROWS>), dim3(wgs), dim3(64 * nwv), bytes, stream, d, depth);
     return hipGetLastError();
+}
+// 16 channels per workgroup while that still leaves at most one workgroup per CU (FLATQUANT_GEMM_ROWS forces 16 or 32):
+// the kernel is bound by what one CU takes in, so the channels go to as many CUs as there are.
+template <int NTD>
+static hipError_t skinny_launch(const GemmDev& d, hipStream_t stream) {
+    const int rows = env_int("FLATQUANT_GEMM_ROWS", (d.m + 15) / 16 <= cu_count() ? 16 : 32);
+    if (rows == 16) return skinny_launch_rows<NTD, 16>(d, stream);
+    if (rows == 32) return skinny_launch_rows<NTD, 32>(d, stream);
+    return hipErrorInvalidValue;
 }
 
 hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {

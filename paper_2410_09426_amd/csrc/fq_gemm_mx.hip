@@ -218,28 +218,33 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
 // bring 32 weight rows of a line (8 whole rows each), one per 8 token rows the tokens, one the 256 bytes of weight
 // exponents (the tile order keeps them contiguous) and one per 32 tokens theirs.  A wave waits only for its own
 // oldest slot (no barrier in the loop).  The partial sums of the waves are added in fp32 through LDS at the end.
-template <int NTD>   // token rows in groups of 8: 1, 2, 4, 8 for T <= 8, 16, 32, 64
+// ROWS = 16: the workgroup owns 16 output channels only (twice as many workgroups, for layers with too few channels
+// to give every CU one of 32); the MFMA's upper 16 rows repeat the lower ones and are dropped.
+template <int NTD, int ROWS>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8 for T <= 8, 16, 32, 64
 __global__ __launch_bounds__(1024) void mxfp4_skinny_kernel(MxGemmDev p, int depth) {
+    static_assert(ROWS == 16 || ROWS == 32, "weight rows per workgroup");
+    constexpr int NWI = ROWS / 8;                        // load instructions per line of the weight rows
+    constexpr int NG = ROWS / 8;                         // groups of 8 output channels
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int NTT = NTD > 4 ? NTD / 4 : 1;           // MFMA token tiles of 32
     constexpr int XROWS = 8 * NTD;
-    constexpr int XOFF = 4096, WEOFF = XOFF + 1024 * NTD, XEOFF = WEOFF + 256;
+    constexpr int XOFF = ROWS * 128, WEOFF = XOFF + 1024 * NTD, XEOFF = WEOFF + 256;
     constexpr int SLOT = XEOFF + 256 * NTT;
-    constexpr int NI = 4 + NTD + 1 + NTT;                // load instructions per step
+    constexpr int NI = NWI + NTD + 1 + NTT;              // load instructions per step
     const int tid = threadIdx.x;
     const int l = tid & 63, c = l & 31, h = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nwv = blockDim.x >> 6;
-    const int o0 = blockIdx.x * 32;
+    const int o0 = blockIdx.x * ROWS;
     const int64_t kbytes = p.n / 2;
     const int nl = p.n / 256;                            // lines per row
     const int ns = (nl - w + nwv - 1) / nwv;             // this wave's steps
     unsigned char* ring = smem + w * depth * SLOT;
 
-    const unsigned char* wsrc[4];
+    const unsigned char* wsrc[NWI];
     const unsigned char* xsrc[NTD];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < NWI; ++k) {
         const int row = 8 * k + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
         int orow = o0 + row;
         if (orow >= p.m) orow = p.m - 1;
@@ -254,7 +259,7 @@ __global__ __launch_bounds__(1024) void mxfp4_skinny_kernel(MxGemmDev p, int dep
     }
     // exponents of line j: 1 KB per tile of 128 rows, 8 bytes per row.  The workgroup's 32 channels are 256 bytes of
     // their tile; the tokens are rows 0 .. of tile 0 (the tensor is padded to whole tiles, so rows past T exist).
-    const unsigned char* wesrc = p.we + (int64_t)(o0 >> 7) * nl * 1024 + 8 * (o0 & 127) + 1024 * w + 4 * l;
+    const unsigned char* wesrc = p.we + (int64_t)(o0 >> 7) * nl * 1024 + 8 * (o0 & 127) + 1024 * w + 4 * (l & (2 * ROWS - 1));
     const unsigned char* xesrc = p.xe + 1024 * w + 4 * l;
     typedef const __attribute__((address_space(1))) void* gptr;
     typedef __attribute__((address_space(3))) void* lptr;
@@ -263,7 +268,7 @@ __global__ __launch_bounds__(1024) void mxfp4_skinny_kernel(MxGemmDev p, int dep
         const int64_t off = (int64_t)s * (128 * nwv);
         const int64_t eoff = (int64_t)s * (1024 * nwv);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) __builtin_amdgcn_global_load_lds((gptr)(wsrc[k] + off), (lptr)(base + k * 1024), 16, 0, 0);
+        for (int k = 0; k < NWI; ++k) __builtin_amdgcn_global_load_lds((gptr)(wsrc[k] + off), (lptr)(base + k * 1024), 16, 0, 0);
 #pragma unroll
         for (int k = 0; k < NTD; ++k) __builtin_amdgcn_global_load_lds((gptr)(xsrc[k] + off), (lptr)(base + XOFF + k * 1024), 16, 0, 0);
         __builtin_amdgcn_global_load_lds((gptr)(wesrc + eoff), (lptr)(base + WEOFF), 4, 0, 0);
@@ -276,8 +281,8 @@ __global__ __launch_bounds__(1024) void mxfp4_skinny_kernel(MxGemmDev p, int dep
     for (int i = 0; i < NTT; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
-    const int woff = c * 128;
-    const int whs = h ^ ((c >> 1) & 7);
+    const int woff = (c & (ROWS - 1)) * 128;
+    const int whs = h ^ (((c & (ROWS - 1)) >> 1) & 7);
     int xoff[NTT], xhs[NTT];
 #pragma unroll
     for (int i = 0; i < NTT; ++i) {
@@ -293,7 +298,7 @@ __global__ __launch_bounds__(1024) void mxfp4_skinny_kernel(MxGemmDev p, int dep
         wait_ring_step<NI>(left < depth - 1 ? left : depth - 1);
         const unsigned char* base = ring + slot * SLOT;
         // block 2 kp + h of this lane's row: after the shift by 8 h, byte 2 (kp & 1) of dword kp / 2
-        u32x2 ew = *reinterpret_cast<const u32x2*>(base + WEOFF + 8 * c);
+        u32x2 ew = *reinterpret_cast<const u32x2*>(base + WEOFF + 8 * (c & (ROWS - 1)));
         ew = u32x2{ew[0] >> (8 * h), ew[1] >> (8 * h)};
         u32x2 ex[NTT];
 #pragma unroll
@@ -329,15 +334,15 @@ __global__ __launch_bounds__(1024) void mxfp4_skinny_kernel(MxGemmDev p, int dep
 #pragma unroll
     for (int i = 0; i < NTT; ++i)
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-            part[((w * NTT + i) * 4 + g) * 64 + l] = f32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
+        for (int g = 0; g < NG; ++g)
+            part[((w * NTT + i) * NG + g) * 64 + l] = f32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
     __syncthreads();
     typedef _Float16 half4 __attribute__((ext_vector_type(4)));
     const bool wide = ((reinterpret_cast<uintptr_t>(p.out) & 7) == 0) && (p.out_stride % 4 == 0);
-    for (int e = tid; e < NTT * 4 * 64; e += (int)blockDim.x) {
-        const int el = e & 63, g = (e >> 6) & 3, i = e >> 8;
+    for (int e = tid; e < NTT * NG * 64; e += (int)blockDim.x) {
+        const int el = e & 63, g = (e >> 6) % NG, i = (e >> 6) / NG;
         f32x4 sum = part[e];
-        for (int ww = 1; ww < nwv; ++ww) sum += part[ww * NTT * 4 * 64 + e];
+        for (int ww = 1; ww < nwv; ++ww) sum += part[ww * NTT * NG * 64 + e];
         const int64_t t = 32 * i + (el & 31);
         const int o = o0 + 8 * g + 4 * (el >> 5);
         if (t < p.T && o < p.m) {
@@ -353,15 +358,15 @@ __global__ __launch_bounds__(1024) void mxfp4_skinny_kernel(MxGemmDev p, int dep
     }
 }
 
-template <int NTD>
-static hipError_t mx_skinny_launch(const MxGemmDev& d, hipStream_t stream) {
+template <int NTD, int ROWS>
+static hipError_t mx_skinny_launch_rows(const MxGemmDev& d, hipStream_t stream) {
     static OccCache oc;
     int unused = 0;
-    hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(mxfp4_skinny_kernel<NTD>), 1024, kRingLdsMax, oc, unused);
+    hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(mxfp4_skinny_kernel<NTD, ROWS>), 1024, kRingLdsMax, oc, unused);
     if (e != hipSuccess) return e;
     constexpr int NTT = NTD > 4 ? NTD / 4 : 1;
-    constexpr int SLOT = 4096 + 1024 * NTD + 256 + 256 * NTT, NI = 4 + NTD + 1 + NTT;
-    const unsigned wgs = (unsigned)((d.m + 31) / 32);
+    constexpr int SLOT = ROWS * 128 + 1024 * NTD + 256 + 256 * NTT, NI = ROWS / 8 + NTD + 1 + NTT;
+    const unsigned wgs = (unsigned)((d.m + ROWS - 1) / ROWS);
     const int nl = d.n / 256;
     // as for the INT4 product: 8 waves and two slots when there is at most one workgroup per CU, else 4 waves and one
     const bool crowded = (int)wgs > cu_count();
@@ -372,9 +377,17 @@ static hipError_t mx_skinny_launch(const MxGemmDev& d, hipStream_t stream) {
     const int steps = (nl + nwv - 1) / nwv;
     if (depth > steps) depth = steps;
     while (depth > 1 && (nwv * depth * SLOT > kRingLdsMax || (depth - 1) * NI > 63)) --depth;
-    const int bytes = nwv * depth * SLOT;                // the partial sums (4 KB per wave and token tile) reuse the rings
-    hipLaunchKernelGGL(mxfp4_skinny_kernel<NTD>, dim3(wgs), dim3(64 * nwv), bytes, stream, d, depth);
+    const int bytes = nwv * depth * SLOT;                // the partial sums (at most 4 KB per wave and token tile) reuse the rings
+    hipLaunchKernelGGL((mxfp4_skinny_kernel<NTD, ROWS>), dim3(wgs), dim3(64 * nwv), bytes, stream, d, depth);
     return hipGetLastError();
+}
+// 16 channels per workgroup while that still leaves at most one workgroup per CU (FLATQUANT_GEMM_ROWS forces 16 or 32)
+template <int NTD>
+static hipError_t mx_skinny_launch(const MxGemmDev& d, hipStream_t stream) {
+    const int rows = env_int("FLATQUANT_GEMM_ROWS", (d.m + 15) / 16 <= cu_count() ? 16 : 32);
+    if (rows == 16) return mx_skinny_launch_rows<NTD, 16>(d, stream);
+    if (rows == 32) return mx_skinny_launch_rows<NTD, 32>(d, stream);
+    return hipErrorInvalidValue;
 }
 
 hipError_t mxfp4_gemm_launch(const MxGemmArgs& a, hipStream_t stream) {

@@ -474,14 +474,16 @@ def test_mxfp4_gemm(T, m, n):
     _mxfp4_gemm_case(T, m, n)
 
 
-@pytest.mark.parametrize("waves,depth,T,m,n", [(16, 1, 5, 100, 4096), (16, 2, 64, 70, 2304), (4, 3, 20, 330, 11008), (8, 8, 40, 64, 4096),
-                                               (4, 1, 1, 33, 256), (8, 2, 9, 8200, 512)])
+@pytest.mark.parametrize("waves,depth,rows,T,m,n", [(16, 1, 32, 5, 100, 4096), (16, 2, 16, 64, 70, 2304), (4, 3, 32, 20, 330, 11008), (8, 8, 16, 40, 64, 4096),
+                                                    (4, 1, 16, 1, 33, 256), (8, 2, 32, 9, 8200, 512), (8, 2, 16, 12, 8200, 512), (4, 2, 32, 64, 4096, 1024)])
 @pytest.mark.parametrize("kind", ["int4", "mxfp4"])
-def test_few_token_products_every_launch_shape(tuning, kind, waves, depth, T, m, n):
-    """The few-token kernels split K over 4, 8 or 16 waves with rings of 1 to 8 line slots; the library picks one shape
-    per launch, the others are forced here (a depth the ring cannot hold is cut back by the launcher)."""
+def test_few_token_products_every_launch_shape(tuning, kind, waves, depth, rows, T, m, n):
+    """The few-token kernels give a workgroup 16 or 32 output channels and split K over 4, 8 or 16 waves with rings of
+    1 to 8 line slots; the library picks one shape per launch, the others are forced here (a depth the ring cannot hold
+    is cut back by the launcher)."""
     tuning("FLATQUANT_GEMM_WAVES", waves)
     tuning("FLATQUANT_GEMM_DEPTH", depth)
+    tuning("FLATQUANT_GEMM_ROWS", rows)
     if kind == "int4":
         _w4a4_case(T, m, n, 0)
     else:
