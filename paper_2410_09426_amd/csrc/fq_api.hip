@@ -56,7 +56,7 @@ struct Tunable {
     explicit Tunable(const char* n) : name(n) {}
 };
 Tunable g_tunables[] = {Tunable("FLATQUANT_MODE"), Tunable("FLATQUANT_WG_PER_CU"), Tunable("FLATQUANT_FORCE_GENERIC"),
-                        Tunable("FLATQUANT_KV_WG_PER_CU"), Tunable("FLATQUANT_GEMM_DECODE"), Tunable("FLATQUANT_GEMM_TILED"),
+                        Tunable("FLATQUANT_KV_WG_PER_CU"), Tunable("FLATQUANT_GEMM_TILED"),
                         Tunable("FLATQUANT_GEMM_WIDE"), Tunable("FLATQUANT_GEMM_DEPTH"), Tunable("FLATQUANT_GEMM_WAVES"), Tunable("FLATQUANT_GEMM_ROWS")};
 Tunable* find_tunable(const char* name) {
     for (Tunable& t : g_tunables)

@@ -223,238 +223,19 @@ __global__ __launch_bounds__(128 * TW) __attribute__((amdgpu_waves_per_eu(2))) v
     }
 }
 
-// ---- few tokens (decode): the weights are read once and the kernel is bound by that stream.  A workgroup owns 32
-// output channels for all (<= 64) tokens; its 4 waves split K in interleaved units of 64 codes, each wave feeding
-// the MFMA straight from global memory (lane <-> weight row / token row, 16 bytes = two K steps), and the four partial
-// accumulators are added through LDS.
-template <int NTT>   // token tiles of 32
-__global__ __launch_bounds__(G_NT) void w4a4_decode_kernel(GemmDev p) {
-    __shared__ __attribute__((aligned(16))) i32x4 part[4 * NTT * 4 * 64];
-    const int tid = threadIdx.x;
-    const int l = tid & 63, c = l & 31, h = l >> 5;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int o0 = blockIdx.x * 32;
-    const int64_t kbytes = p.n / 2;
-    const int units = p.n / 64 / 4;            // units of 64 codes (32 bytes per row) per wave
-    int orow = o0 + c;
-    if (orow >= p.m) orow = p.m - 1;
-    const u32x4* wsrc = reinterpret_cast<const u32x4*>(p.wc + (int64_t)orow * kbytes) + 2 * w + h;
-    const u32x4* xsrc[NTT];
-#pragma unroll
-    for (int i = 0; i < NTT; ++i) {
-        int64_t t = 32 * i + c;
-        if (t >= p.T) t = p.T - 1;
-        xsrc[i] = reinterpret_cast<const u32x4*>(p.xc + t * kbytes) + 2 * w + h;
-    }
-    i32x16 acc[NTT];
-#pragma unroll
-    for (int i = 0; i < NTT; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
-    constexpr int BATCH = 8;                   // units in flight per wave (the tail of a batch re-reads the last unit)
-    for (int u0 = 0; u0 < units; u0 += BATCH) {
-        u32x4 wv[BATCH], xv[BATCH][NTT];
-#pragma unroll
-        for (int b = 0; b < BATCH; ++b) {
-            const int u = (u0 + b < units) ? u0 + b : units - 1;
-            wv[b] = __builtin_nontemporal_load(wsrc + 8 * u);     // unit u of this wave: chunks 8u + 2w + h
-#pragma unroll
-            for (int i = 0; i < NTT; ++i) xv[b][i] = xsrc[i][8 * u];
-        }
-#pragma unroll
-        for (int b = 0; b < BATCH; ++b) {
-            if (u0 + b < units) {
-                i32x4 ws0, ws1;
-                widen(wv[b], ws0, ws1);
-#pragma unroll
-                for (int i = 0; i < NTT; ++i) {
-                    i32x4 xs0, xs1;
-                    widen(xv[b][i], xs0, xs1);
-                    acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws0, xs0, acc[i], 0, 0, 0);
-                    acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws1, xs1, acc[i], 0, 0, 0);
-                }
-            }
-        }
-    }
-    // partial sums -> LDS as [wave][tile][quad g][lane] x 4 ints, then 4-way add, scale, round, 8-byte stores
-#pragma unroll
-    for (int i = 0; i < NTT; ++i)
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-            part[((w * NTT + i) * 4 + g) * 64 + l] = i32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
-    __syncthreads();
-    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-    const bool wide = ((reinterpret_cast<uintptr_t>(p.out) & 7) == 0) && (p.out_stride % 4 == 0);
-    for (int e = tid; e < NTT * 4 * 64; e += G_NT) {
-        const int el = e & 63, g = (e >> 6) & 3, i = e >> 8;
-        i32x4 sum = part[e];
-#pragma unroll
-        for (int ww = 1; ww < 4; ++ww) sum += part[ww * NTT * 4 * 64 + e];
-        const int64_t t = 32 * i + (el & 31);
-        const int o = o0 + 8 * g + 4 * (el >> 5);
-        if (t < p.T && o < p.m) {
-            const float sx = (float)p.xs[t];
-            _Float16 v[4];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) v[x] = (_Float16)((float)(sum[x] >> 8) * sx * (float)p.ws[o + x < p.m ? o + x : p.m - 1]);
-            _Float16* dst = p.out + t * p.out_stride + o;
-            if (wide && o + 4 <= p.m) {
-                *reinterpret_cast<half4*>(dst) = half4{v[0], v[1], v[2], v[3]};
-            } else {
-                for (int x = 0; x < 4; ++x)
-                    if (o + x < p.m) dst[x] = v[x];
-            }
-        }
-    }
-}
-
-// ---- few tokens, second form: the activation codes go through LDS.  In the kernel above every wave gathers 16 bytes
-// per token row per load (a quarter of a cache line from 32 rows at once), which costs more than the weight stream
-// itself once there are more than a few tokens.  Here the workgroup copies the token rows, 1 KB of K at a time, with
-// whole-row loads into an LDS tile; the waves split each 1 KB slice four ways, read their activation operands from the
-// tile and their weight rows from global memory.  The next slice is requested before the current one is multiplied.
-constexpr int DSB = 1024;            // packed bytes of K per token row and pass (2048 codes)
-constexpr int DPITCH = DSB + 16;     // 16-byte operand reads of 32 consecutive rows fall on distinct banks
-template <int NTT>
-__global__ __launch_bounds__(G_NT) void w4a4_decode_lds_kernel(GemmDev p) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int R = 32 * NTT;
-    constexpr int NLD = R * (DSB / 16) / G_NT;
-    const int tid = threadIdx.x;
-    const int l = tid & 63, c = l & 31, h = l >> 5;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int o0 = blockIdx.x * 32;
-    const int kbytes = p.n / 2;
-    const int npass = (kbytes + DSB - 1) / DSB;
-    int orow = o0 + c;
-    if (orow >= p.m) orow = p.m - 1;
-    const unsigned char* wrow = p.wc + (int64_t)orow * kbytes + 16 * h;
-
-    i32x16 acc[NTT];
-#pragma unroll
-    for (int i = 0; i < NTT; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
-
-    u32x4 tl[NLD];
-    // slice `ps`: `bytes` per row (a multiple of 128), `bytes / 16` chunks per row; chunk q of the tile = row q / cpr
-    auto slice_bytes = [&](int ps) { const int left = kbytes - ps * DSB; return left < DSB ? left : DSB; };
-    auto issue_tile = [&](int ps) {
-        const int cpr = slice_bytes(ps) >> 4;
-#pragma unroll
-        for (int k = 0; k < NLD; ++k) {
-            const int q = tid + G_NT * k;
-            int row = q / cpr;
-            const int ch = q - row * cpr;
-            if (row > R - 1) row = R - 1;            // chunks past the tile (short last slice) re-read its last row
-            int64_t t = row;
-            if (t >= p.T) t = p.T - 1;
-            tl[k] = *reinterpret_cast<const u32x4*>(p.xc + t * kbytes + ps * DSB + ch * 16);
-        }
-    };
-    auto commit_tile = [&](int ps) {
-        const int cpr = slice_bytes(ps) >> 4;
-#pragma unroll
-        for (int k = 0; k < NLD; ++k) {
-            const int q = tid + G_NT * k;
-            const int row = q / cpr, ch = q - row * cpr;
-            if (row < R) *reinterpret_cast<u32x4*>(smem + row * DPITCH + ch * 16) = tl[k];
-        }
-    };
-    auto issue_w = [&](int ps, u32x4 (&wv)[8]) {
-        const int per_wave = slice_bytes(ps) >> 2;   // a multiple of 32: units of 64 codes
-        const int nu = per_wave >> 5;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int uu = u < nu ? u : nu - 1;
-            wv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow + ps * DSB + w * per_wave + 32 * uu));
-        }
-    };
-    auto compute = [&](int ps, const u32x4 (&wv)[8]) {
-        const int per_wave = slice_bytes(ps) >> 2;
-        const int nu = per_wave >> 5;
-        const unsigned char* xr = smem + c * DPITCH + w * per_wave + 16 * h;
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (u < nu) {
-                i32x4 ws0, ws1;
-                widen(wv[u], ws0, ws1);
-#pragma unroll
-                for (int i = 0; i < NTT; ++i) {
-                    i32x4 xs0, xs1;
-                    widen(*reinterpret_cast<const u32x4*>(xr + 32 * i * DPITCH + 32 * u), xs0, xs1);
-                    acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws0, xs0, acc[i], 0, 0, 0);
-                    acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws1, xs1, acc[i], 0, 0, 0);
-                }
-            }
-    };
-    // Weight rows (the HBM stream) are requested two slices ahead, the token tile (L2-resident) one slice ahead.
-    u32x4 wv0[8], wv1[8];
-    issue_tile(0);
-    issue_w(0, wv0);
-    if (npass > 1) issue_w(1, wv1);
-    commit_tile(0);
-    __syncthreads();
-    for (int ps = 0; ps < npass; ps += 2) {
-        if (ps + 1 < npass) issue_tile(ps + 1);
-        compute(ps, wv0);
-        if (ps + 2 < npass) issue_w(ps + 2, wv0);
-        __syncthreads();                       // every wave is done with the tile
-        if (ps + 1 >= npass) break;
-        commit_tile(ps + 1);
-        __syncthreads();
-        if (ps + 2 < npass) issue_tile(ps + 2);
-        compute(ps + 1, wv1);
-        if (ps + 3 < npass) issue_w(ps + 3, wv1);
-        __syncthreads();
-        if (ps + 2 >= npass) break;
-        commit_tile(ps + 2);
-        __syncthreads();
-    }
-    // partial sums -> LDS (the tile is dead) as [wave][tile][quad g][lane] x 4 ints, then 4-way add, scale, round, 8-byte stores
-    i32x4* part = reinterpret_cast<i32x4*>(smem);
-#pragma unroll
-    for (int i = 0; i < NTT; ++i)
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-            part[((w * NTT + i) * 4 + g) * 64 + l] = i32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
-    __syncthreads();
-    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-    const bool wide = ((reinterpret_cast<uintptr_t>(p.out) & 7) == 0) && (p.out_stride % 4 == 0);
-    for (int e = tid; e < NTT * 4 * 64; e += G_NT) {
-        const int el = e & 63, g = (e >> 6) & 3, i = e >> 8;
-        i32x4 sum = part[e];
-#pragma unroll
-        for (int ww = 1; ww < 4; ++ww) sum += part[ww * NTT * 4 * 64 + e];
-        const int64_t t = 32 * i + (el & 31);
-        const int o = o0 + 8 * g + 4 * (el >> 5);
-        if (t < p.T && o < p.m) {
-            const float sx = (float)p.xs[t];
-            _Float16 v[4];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) v[x] = (_Float16)((float)(sum[x] >> 8) * sx * (float)p.ws[o + x < p.m ? o + x : p.m - 1]);
-            _Float16* dst = p.out + t * p.out_stride + o;
-            if (wide && o + 4 <= p.m) {
-                *reinterpret_cast<half4*>(dst) = half4{v[0], v[1], v[2], v[3]};
-            } else {
-                for (int x = 0; x < 4; ++x)
-                    if (o + x < p.m) dst[x] = v[x];
-            }
-        }
-    }
-}
-
-// ---- few tokens, third form: every operand byte goes from global memory straight into LDS, a whole cache line per
-// row at a time, many lines ahead.  The two forms above feed the MFMA from registers, 32 bytes of 32 rows per load: four
-// instructions (and tag look-ups) per cache line, and only as much in flight as the registers hold.  Here a wave owns
-// every fourth 128-byte line of K (256 codes) of the workgroup's 32 weight rows and of the token rows, with a ring of
-// `depth` line slots of its own in LDS: one global-to-LDS instruction moves 8 whole rows, the wave waits only for its
-// own oldest slot (no barrier in the loop), multiplies it and requests the line `depth` steps ahead into the same slot.
-// The slots use the swizzle of the tiled kernel (slot chunk j of row r holds the row's chunk j ^ ((r >> 1) & 7)).
+// ---- few tokens (T <= 128, decode): the weights are read once, and what bounds the kernel is how fast the CUs take
+// them in.  A workgroup owns 32 (or 16) output channels for all tokens.  Every operand byte goes from global memory
+// straight into LDS, a whole cache line per row at a time: a wave owns every nwv-th 128-byte line of K (256 codes) of
+// the workgroup's weight rows and of the token rows, with a ring of `depth` line slots of its own in LDS.  One
+// global-to-LDS instruction moves 8 whole rows; the wave waits only for its own oldest slot (no barrier in the loop),
+// multiplies it and requests the line `depth` steps ahead into the same slot.  The slots use the swizzle of the tiled
+// kernel (slot chunk j of row r holds the row's chunk j ^ ((r >> 1) & 7)).  The partial sums of the waves are added
+// through LDS at the end.  (Feeding the MFMA from registers instead, 32 bytes of 32 rows per load, costs four
+// instructions and tag look-ups per cache line and holds far less in flight: 1.5 to 3 times slower.)
 // ROWS = 16: the workgroup owns 16 output channels only (twice as many workgroups, for layers with too few channels
 // to give every CU one of 32); the MFMA's upper 16 rows repeat the lower ones and are dropped.
-template <int NTD, int ROWS>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8 for T <= 8, 16, 32, 64
-__global__ __launch_bounds__(1024) void w4a4_skinny_kernel(GemmDev p, int depth) {
+template <int NTD, int ROWS>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8, 16 for T <= 8, 16, 32, 64, 128
+__global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void w4a4_skinny_kernel(GemmDev p, int depth) {
     static_assert(ROWS == 16 || ROWS == 32, "weight rows per workgroup");
     constexpr int NWI = ROWS / 8;                        // load instructions per line of the weight rows
     constexpr int NG = ROWS / 8;                         // groups of 8 output channels
@@ -515,13 +296,14 @@ __global__ __launch_bounds__(1024) void w4a4_skinny_kernel(GemmDev p, int depth)
         xhs[i] = h ^ ((row >> 1) & 7);
     }
     // The epilogue's element e = tid + k blockDim is 4 output channels of one token: their steps are requested now, so
-    // that the kernel's tail does not wait for them (at least 256 threads and at most 512 elements: k < 2).
+    // that the kernel's tail does not wait for them (at least 256 threads: k < NK).
     constexpr int NE = NTT * NG * 64;
-    unsigned esx[2] = {}, esw[2][4] = {};                // raw fp16 bits, converted in the epilogue: nothing waits for them here
+    constexpr int NK = (NE + 255) / 256;
+    unsigned esx[NK] = {}, esw[NK][4] = {};              // raw fp16 bits, converted in the epilogue: nothing waits for them here
     const uint16_t* xs_bits = reinterpret_cast<const uint16_t*>(p.xs);
     const uint16_t* ws_bits = reinterpret_cast<const uint16_t*>(p.ws);
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
+    for (int k = 0; k < NK; ++k) {
         const int e = tid + k * (int)blockDim.x;
         const int el = e & 63, g = (e >> 6) % NG, i = (e >> 6) / NG;
         const int64_t t = 32 * i + (el & 31);
@@ -574,7 +356,7 @@ __global__ __launch_bounds__(1024) void w4a4_skinny_kernel(GemmDev p, int depth)
     typedef _Float16 half4 __attribute__((ext_vector_type(4)));
     const bool wide = ((reinterpret_cast<uintptr_t>(p.out) & 7) == 0) && (p.out_stride % 4 == 0);
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
+    for (int k = 0; k < NK; ++k) {
         const int e = tid + k * (int)blockDim.x;
         if (e >= NE) break;
         const int el = e & 63, g = (e >> 6) % NG, i = (e >> 6) / NG;
@@ -604,7 +386,7 @@ template <int NTD, int ROWS>
 static hipError_t skinny_launch_rows(const GemmDev& d, hipStream_t stream) {
     static OccCache oc;
     int unused = 0;
-    hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_skinny_kernel<NTD, ROWS>), 1024, kRingLdsMax, oc, unused);
+    hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_skinny_kernel<NTD, ROWS>), NTD >= 8 ? 512 : 1024, kRingLdsMax, oc, unused);
     if (e != hipSuccess) return e;
     constexpr int SLOT = (ROWS + 8 * NTD) * 128, NI = ROWS / 8 + NTD;
     const unsigned wgs = (unsigned)((d.m + ROWS - 1) / ROWS);
@@ -616,6 +398,7 @@ static hipError_t skinny_launch_rows(const GemmDev& d, hipStream_t stream) {
     int nwv = env_int("FLATQUANT_GEMM_WAVES", crowded ? 4 : 8);
     int depth = env_int("FLATQUANT_GEMM_DEPTH", crowded ? 1 : 2);
     if ((nwv != 4 && nwv != 8 && nwv != 16) || depth < 1 || depth > kRingMaxDepth) return hipErrorInvalidValue;
+    if (NTD >= 8 && nwv > 8) nwv = 8;                                      // two or four token tiles of accumulators: compiled for at most 8 waves
     while (nwv > 4 && nwv * SLOT > kRingLdsMax) nwv >>= 1;
     const int steps = (nl + nwv - 1) / nwv;                               // of the wave with the most lines
     if (depth > steps) depth = steps;
@@ -628,7 +411,8 @@ static hipError_t skinny_launch_rows(const GemmDev& d, hipStream_t stream) {
 // the kernel is bound by what one CU takes in, so the channels go to as many CUs as there are.
 template <int NTD>
 static hipError_t skinny_launch(const GemmDev& d, hipStream_t stream) {
-    const int rows = env_int("FLATQUANT_GEMM_ROWS", (d.m + 15) / 16 <= cu_count() ? 16 : 32);
+    // (not for more than 64 tokens: every workgroup reads all token rows, which then outweigh its weight rows)
+    const int rows = env_int("FLATQUANT_GEMM_ROWS", (NTD <= 8 && (d.m + 15) / 16 <= cu_count()) ? 16 : 32);
     if (rows == 16) return skinny_launch_rows<NTD, 16>(d, stream);
     if (rows == 32) return skinny_launch_rows<NTD, 32>(d, stream);
     return hipErrorInvalidValue;
@@ -639,29 +423,12 @@ hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
     GemmDev d;
     d.xc = a.x_codes; d.xs = a.x_scales; d.wc = a.w_codes; d.ws = a.w_scales; d.out = a.out;
     d.T = a.T; d.out_stride = a.out_stride; d.m = a.m; d.n = a.n;
-    if (a.T <= 64 && env_int("FLATQUANT_GEMM_TILED", 0) == 0) {   // decode: one pass over the weights, K split inside a workgroup
-        // FLATQUANT_GEMM_DECODE = 0 / 1 forces one of the register-fed forms, 2 (the default) the LDS ring
-        if (env_int("FLATQUANT_GEMM_DECODE", 2) == 2) {
-            if (a.T <= 8) return skinny_launch<1>(d, stream);
-            if (a.T <= 16) return skinny_launch<2>(d, stream);
-            if (a.T <= 32) return skinny_launch<4>(d, stream);
-            return skinny_launch<8>(d, stream);
-        }
-        const dim3 grid((unsigned)((a.m + 31) / 32));
-        // more than a few tokens: activation codes through LDS (FLATQUANT_GEMM_DECODE = 0 / 1 forces one form)
-        const int form = env_int("FLATQUANT_GEMM_DECODE", a.T > 8 ? 1 : 0);
-        if (form == 1) {
-            static OccCache c1, c2;
-            hipError_t e = (a.T <= 32) ? kernel_occupancy(reinterpret_cast<const void*>(w4a4_decode_lds_kernel<1>), G_NT, 32 * DPITCH, c1, unused)
-                                       : kernel_occupancy(reinterpret_cast<const void*>(w4a4_decode_lds_kernel<2>), G_NT, 64 * DPITCH, c2, unused);
-            if (e != hipSuccess) return e;
-            if (a.T <= 32) hipLaunchKernelGGL(w4a4_decode_lds_kernel<1>, grid, dim3(G_NT), 32 * DPITCH, stream, d);
-            else hipLaunchKernelGGL(w4a4_decode_lds_kernel<2>, grid, dim3(G_NT), 64 * DPITCH, stream, d);
-            return hipGetLastError();
-        }
-        if (a.T <= 32) hipLaunchKernelGGL(w4a4_decode_kernel<1>, grid, dim3(G_NT), 0, stream, d);
-        else hipLaunchKernelGGL(w4a4_decode_kernel<2>, grid, dim3(G_NT), 0, stream, d);
-        return hipGetLastError();
+    if (a.T <= 128 && env_int("FLATQUANT_GEMM_TILED", 0) == 0) {   // decode: one pass over the weights, K split inside a workgroup
+        if (a.T <= 8) return skinny_launch<1>(d, stream);
+        if (a.T <= 16) return skinny_launch<2>(d, stream);
+        if (a.T <= 32) return skinny_launch<4>(d, stream);
+        if (a.T <= 64) return skinny_launch<8>(d, stream);
+        return skinny_launch<16>(d, stream);
     }
     static OccCache ct, ctw;
     // 256-token tiles when they still give every CU a workgroup (FLATQUANT_GEMM_WIDE = 0 / 1 forces a form)

@@ -220,8 +220,8 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
 // oldest slot (no barrier in the loop).  The partial sums of the waves are added in fp32 through LDS at the end.
 // ROWS = 16: the workgroup owns 16 output channels only (twice as many workgroups, for layers with too few channels
 // to give every CU one of 32); the MFMA's upper 16 rows repeat the lower ones and are dropped.
-template <int NTD, int ROWS>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8 for T <= 8, 16, 32, 64
-__global__ __launch_bounds__(1024) void mxfp4_skinny_kernel(MxGemmDev p, int depth) {
+template <int NTD, int ROWS>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8, 16 for T <= 8, 16, 32, 64, 128
+__global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void mxfp4_skinny_kernel(MxGemmDev p, int depth) {
     static_assert(ROWS == 16 || ROWS == 32, "weight rows per workgroup");
     constexpr int NWI = ROWS / 8;                        // load instructions per line of the weight rows
     constexpr int NG = ROWS / 8;                         // groups of 8 output channels
@@ -362,7 +362,7 @@ template <int NTD, int ROWS>
 static hipError_t mx_skinny_launch_rows(const MxGemmDev& d, hipStream_t stream) {
     static OccCache oc;
     int unused = 0;
-    hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(mxfp4_skinny_kernel<NTD, ROWS>), 1024, kRingLdsMax, oc, unused);
+    hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(mxfp4_skinny_kernel<NTD, ROWS>), NTD >= 8 ? 512 : 1024, kRingLdsMax, oc, unused);
     if (e != hipSuccess) return e;
     constexpr int NTT = NTD > 4 ? NTD / 4 : 1;
     constexpr int SLOT = ROWS * 128 + 1024 * NTD + 256 + 256 * NTT, NI = ROWS / 8 + NTD + 1 + NTT;
@@ -373,6 +373,7 @@ static hipError_t mx_skinny_launch_rows(const MxGemmDev& d, hipStream_t stream) 
     int nwv = env_int("FLATQUANT_GEMM_WAVES", crowded ? 4 : 8);
     int depth = env_int("FLATQUANT_GEMM_DEPTH", crowded ? 1 : 2);
     if ((nwv != 4 && nwv != 8 && nwv != 16) || depth < 1 || depth > kRingMaxDepth) return hipErrorInvalidValue;
+    if (NTD >= 8 && nwv > 8) nwv = 8;                     // two or four token tiles of accumulators: compiled for at most 8 waves
     while (nwv > 4 && nwv * SLOT > kRingLdsMax) nwv >>= 1;
     const int steps = (nl + nwv - 1) / nwv;
     if (depth > steps) depth = steps;
@@ -384,7 +385,8 @@ static hipError_t mx_skinny_launch_rows(const MxGemmDev& d, hipStream_t stream) 
 // 16 channels per workgroup while that still leaves at most one workgroup per CU (FLATQUANT_GEMM_ROWS forces 16 or 32)
 template <int NTD>
 static hipError_t mx_skinny_launch(const MxGemmDev& d, hipStream_t stream) {
-    const int rows = env_int("FLATQUANT_GEMM_ROWS", (d.m + 15) / 16 <= cu_count() ? 16 : 32);
+    // (not for more than 64 tokens: every workgroup reads all token rows, which then outweigh its weight rows)
+    const int rows = env_int("FLATQUANT_GEMM_ROWS", (NTD <= 8 && (d.m + 15) / 16 <= cu_count()) ? 16 : 32);
     if (rows == 16) return mx_skinny_launch_rows<NTD, 16>(d, stream);
     if (rows == 32) return mx_skinny_launch_rows<NTD, 32>(d, stream);
     return hipErrorInvalidValue;
@@ -394,11 +396,14 @@ hipError_t mxfp4_gemm_launch(const MxGemmArgs& a, hipStream_t stream) {
     MxGemmDev d;
     d.xc = a.x_codes; d.xe = a.x_exps; d.wc = a.w_codes; d.we = a.w_exps; d.out = a.out;
     d.T = a.T; d.out_stride = a.out_stride; d.m = a.m; d.n = a.n;
-    if (a.T <= 64 && env_int("FLATQUANT_GEMM_TILED", 0) == 0) {
+    if (a.T <= 128 && env_int("FLATQUANT_GEMM_TILED", 0) == 0) {
         if (a.T <= 8) return mx_skinny_launch<1>(d, stream);
         if (a.T <= 16) return mx_skinny_launch<2>(d, stream);
         if (a.T <= 32) return mx_skinny_launch<4>(d, stream);
-        return mx_skinny_launch<8>(d, stream);
+        if (a.T <= 64) return mx_skinny_launch<8>(d, stream);
+        // 65 .. 128 tokens: every workgroup of the ring kernel reads all token rows, four times its weight rows; with
+        // enough 128-channel tiles the tiled kernel is faster (measured: 32 tiles 12.4 against 9.2 us, 86 tiles 13.0 against 17.5 us)
+        if ((a.m + XT - 1) / XT < 64) return mx_skinny_launch<16>(d, stream);
     }
     static OccCache cache;
     int unused = 0;

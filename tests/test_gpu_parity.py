@@ -469,13 +469,14 @@ def test_mxfp4_layer_both_factors():
 
 
 @pytest.mark.parametrize("T,m,n", [(128, 128, 256), (200, 300, 1280), (2048, 256, 4096), (1, 40, 768), (130, 129, 11008), (64, 4096, 1024), (300, 140, 512),
-                                   (8, 200, 256), (16, 300, 2304), (17, 129, 11008), (33, 4099, 512), (50, 96, 4096), (64, 11008, 4096), (3, 8200, 1024)])
+                                   (8, 200, 256), (16, 300, 2304), (17, 129, 11008), (33, 4099, 512), (50, 96, 4096), (64, 11008, 4096), (3, 8200, 1024),
+                                   (65, 100, 2304), (128, 4100, 1024), (100, 40, 11008), (129, 70, 512), (70, 8300, 256)])
 def test_mxfp4_gemm(T, m, n):
     _mxfp4_gemm_case(T, m, n)
 
 
 @pytest.mark.parametrize("waves,depth,rows,T,m,n", [(16, 1, 32, 5, 100, 4096), (16, 2, 16, 64, 70, 2304), (4, 3, 32, 20, 330, 11008), (8, 8, 16, 40, 64, 4096),
-                                                    (4, 1, 16, 1, 33, 256), (8, 2, 32, 9, 8200, 512), (8, 2, 16, 12, 8200, 512), (4, 2, 32, 64, 4096, 1024)])
+                                                    (4, 1, 16, 1, 33, 256), (8, 2, 32, 9, 8200, 512), (8, 2, 16, 12, 8200, 512), (4, 2, 32, 64, 4096, 1024), (16, 3, 32, 120, 200, 2304), (4, 2, 16, 90, 100, 1024)])
 @pytest.mark.parametrize("kind", ["int4", "mxfp4"])
 def test_few_token_products_every_launch_shape(tuning, kind, waves, depth, rows, T, m, n):
     """The few-token kernels give a workgroup 16 or 32 output channels and split K over 4, 8 or 16 waves with rings of
@@ -604,17 +605,17 @@ def _w4a4_case(T, m, n, pad):
 
 @pytest.mark.parametrize("T,m,n,pad", [(300, 260, 512, 0), (128, 128, 256, 0), (1, 1, 256, 0), (2048, 384, 4096, 0), (77, 200, 11008, 24),
                                        (64, 4096, 4096, 0), (33, 100, 512, 0), (17, 4099, 11008, 5), (32, 64, 256, 0), (65, 96, 768, 0),
-                                       (9, 40, 2304, 0), (64, 33, 11008, 0), (8, 64, 4096, 0)])
+                                       (9, 40, 2304, 0), (64, 33, 11008, 0), (8, 64, 4096, 0), (65, 100, 2304, 0), (128, 4100, 1024, 3),
+                                       (100, 40, 11008, 0), (129, 70, 512, 0)])
 def test_w4a4_gemm(T, m, n, pad):
     _w4a4_case(T, m, n, pad)
 
 
 @pytest.mark.parametrize("knob,value,T,m,n", [("FLATQUANT_GEMM_WIDE", 1, 300, 260, 768), ("FLATQUANT_GEMM_WIDE", 1, 513, 129, 256),
-                                              ("FLATQUANT_GEMM_WIDE", 0, 2048, 4224, 512), ("FLATQUANT_GEMM_DECODE", 0, 40, 100, 1024),
-                                              ("FLATQUANT_GEMM_DECODE", 1, 5, 70, 512), ("FLATQUANT_GEMM_DECODE", 0, 7, 45, 768),
-                                              ("FLATQUANT_GEMM_DECODE", 1, 64, 130, 2304), ("FLATQUANT_GEMM_TILED", 1, 33, 96, 768)])
+                                              ("FLATQUANT_GEMM_WIDE", 0, 2048, 4224, 512), ("FLATQUANT_GEMM_TILED", 1, 33, 96, 768),
+                                              ("FLATQUANT_GEMM_TILED", 1, 100, 200, 1024)])
 def test_w4a4_gemm_every_form(tuning, knob, value, T, m, n):
     """The forms the library would not pick by itself for these sizes: 256-token tiles on a small launch, 128-token
-    tiles on a large one, both register-fed few-token forms, the tiled product for few tokens."""
+    tiles on a large one, the tiled product for few tokens."""
     tuning(knob, value)
     _w4a4_case(T, m, n, 0)
