@@ -275,6 +275,9 @@ def main() -> int:
         # the activations, then the product with pre-quantized weights) beside the FP16 matrix product it replaces
         INT8_PEAK_TOPS = 5000.0
 
+        def weight_copies(Tn, nbytes):   # prefill: one copy (the product is compute-bound); decode: 320 MB worth, past L2 + Infinity Cache
+            return 1 if Tn > 128 else max(2, -(-320_000_000 // nbytes))
+
         def time_layer(name, Tn, mo, a, b, steps, warmup):
             nn = a * b
             g = torch.Generator(device="cuda").manual_seed(77 + mo + nn + Tn)
@@ -284,20 +287,24 @@ def main() -> int:
             cl = torch.full((Tn,), 0.9, device="cuda")
             xc = torch.empty((Tn, nn // 2), dtype=torch.uint8, device="cuda")
             xs_ = torch.empty((Tn,), dtype=torch.float16, device="cuda")
-            wc = torch.randint(0, 256, (mo, nn // 2), generator=g, dtype=torch.uint8, device="cuda")
+            # few tokens: the weights are the traffic, so they rotate through more copies than the caches hold (a decode
+            # step reads every layer's weights from HBM); the FP16 weights beside them likewise
+            nwc, nwh = weight_copies(Tn, mo * nn // 2), weight_copies(Tn, mo * nn * 2)
+            wcs = [torch.randint(0, 256, (mo, nn // 2), generator=g, dtype=torch.uint8, device="cuda") for _ in range(nwc)]
+            wc = wcs[0]
             ws = (torch.rand((mo,), generator=g, device="cuda") * 1e-3 + 1e-4).half()
             y = torch.empty((Tn, mo), dtype=torch.float16, device="cuda")
-            wh = torch.randn((mo, nn), generator=g, device="cuda").half()
+            whs = [torch.randn((mo, nn), generator=g, device="cuda").half() for _ in range(nwh)]
 
             def st_gemm(i):
-                fq.flatquant_w4a4_gemm(xc, xs_, wc, ws, Tn, mo, nn, y, mo, stream=stream)
+                fq.flatquant_w4a4_gemm(xc, xs_, wcs[i % nwc], ws, Tn, mo, nn, y, mo, stream=stream)
 
             def st_layer(i):
                 fq.flatquant_transform_quant(x, p1, p2, cl, 1, Tn, a, b, nn, xc, xs_, stream=stream)
-                fq.flatquant_w4a4_gemm(xc, xs_, wc, ws, Tn, mo, nn, y, mo, stream=stream)
+                fq.flatquant_w4a4_gemm(xc, xs_, wcs[i % nwc], ws, Tn, mo, nn, y, mo, stream=stream)
 
             def st_fp16(i):
-                torch.matmul(x, wh.t(), out=y)
+                torch.matmul(x, whs[i % nwh].t(), out=y)
             st_layer(0)
             med = lambda f: float(np.median([time_region(f, steps, warmup if r == 0 else 1)[0] for r in range(5)]))
             ms_g, ms_l, ms_h = med(st_gemm), med(st_layer), med(st_fp16)
@@ -308,7 +315,7 @@ def main() -> int:
                     fq.flatquant_transform_quant(x, p1, p2, cl, 1, Tn, a, b, nn, xc, xs_, stream=gs)
                     fq.flatquant_w4a4_gemm(xc, xs_, wc, ws, Tn, mo, nn, y, mo, stream=gs)
                 layer_graph = graph_replay_us(name, one_layer)
-            extras[name] = {"T": Tn, "m": mo, "n": nn, "layer_us_graph_replay": layer_graph, "gemm_us": ms_g * 1e3, "gemm_tops": ops / (ms_g * 1e-3) / 1e12,
+            extras[name] = {"T": Tn, "m": mo, "n": nn, "weight_copies_rotated": nwc, "layer_us_graph_replay_weights_cached": layer_graph, "gemm_us": ms_g * 1e3, "gemm_tops": ops / (ms_g * 1e-3) / 1e12,
                             "gemm_frac_of_int8_mfma_peak": ops / (ms_g * 1e-3) / 1e12 / INT8_PEAK_TOPS,
                             "layer_us_transform_quant_plus_gemm": ms_l * 1e3, "fp16_matmul_us_torch_hipblaslt": ms_h * 1e3,
                             "layer_speedup_vs_fp16_matmul": ms_h / ms_l}
@@ -322,25 +329,26 @@ def main() -> int:
             cl = torch.full((Tn,), 0.9, device="cuda")
             xc = torch.empty((Tn, nn // 2), dtype=torch.uint8, device="cuda")
             xe = torch.empty((fq.fq_mxfp4_tiled_scale_bytes(Tn, nn),), dtype=torch.uint8, device="cuda")
-            wc = torch.randint(0, 256, (mo, nn // 2), generator=g, dtype=torch.uint8, device="cuda")
+            nwc, nwh = weight_copies(Tn, mo * nn // 2), weight_copies(Tn, mo * nn * 2)
+            wcs = [torch.randint(0, 256, (mo, nn // 2), generator=g, dtype=torch.uint8, device="cuda") for _ in range(nwc)]
             we = torch.randint(112, 118, (fq.fq_mxfp4_tiled_scale_bytes(mo, nn),), generator=g, dtype=torch.uint8, device="cuda")
             y = torch.empty((Tn, mo), dtype=torch.float16, device="cuda")
-            wh = torch.randn((mo, nn), generator=g, device="cuda").half()
+            whs = [torch.randn((mo, nn), generator=g, device="cuda").half() for _ in range(nwh)]
 
             def st_gemm(i):
-                fq.flatquant_mxfp4_gemm(xc, xe, wc, we, Tn, mo, nn, y, mo, stream=stream)
+                fq.flatquant_mxfp4_gemm(xc, xe, wcs[i % nwc], we, Tn, mo, nn, y, mo, stream=stream)
 
             def st_layer(i):
                 fq.flatquant_transform_mxfp4_tiled(x, p1, p2, cl, 1, Tn, a, b, nn, xc, xe, stream=stream)
-                fq.flatquant_mxfp4_gemm(xc, xe, wc, we, Tn, mo, nn, y, mo, stream=stream)
+                fq.flatquant_mxfp4_gemm(xc, xe, wcs[i % nwc], we, Tn, mo, nn, y, mo, stream=stream)
 
             def st_fp16(i):
-                torch.matmul(x, wh.t(), out=y)
+                torch.matmul(x, whs[i % nwh].t(), out=y)
             st_layer(0)
             med = lambda f: float(np.median([time_region(f, steps, warmup if r == 0 else 1)[0] for r in range(5)]))
             ms_g, ms_l, ms_h = med(st_gemm), med(st_layer), med(st_fp16)
             ops = 2.0 * Tn * mo * nn
-            extras[name] = {"T": Tn, "m": mo, "n": nn, "gemm_us": ms_g * 1e3, "gemm_tflops": ops / (ms_g * 1e-3) / 1e12,
+            extras[name] = {"T": Tn, "m": mo, "n": nn, "weight_copies_rotated": nwc, "gemm_us": ms_g * 1e3, "gemm_tflops": ops / (ms_g * 1e-3) / 1e12,
                             "gemm_frac_of_fp4_mfma_peak": ops / (ms_g * 1e-3) / 1e12 / 10100.0,
                             "layer_us_transform_quant_plus_gemm": ms_l * 1e3, "fp16_matmul_us_torch_hipblaslt": ms_h * 1e3,
                             "layer_speedup_vs_fp16_matmul": ms_h / ms_l}
@@ -350,6 +358,11 @@ def main() -> int:
         time_layer("w4a4_layer_prefill_qkvo_7b", 2048, 4096, 64, 64, 50, 5)
         time_layer("w4a4_layer_prefill_down_7b", 2048, 4096, 86, 128, 30, 5)
         time_layer("w4a4_layer_decode_qkvo_7b", 64, 4096, 64, 64, 200, 20)
+        time_layer("w4a4_layer_decode_down_7b", 64, 4096, 86, 128, 200, 20)
+        time_layer("w4a4_layer_decode_batch1_qkvo_7b", 1, 4096, 64, 64, 200, 20)
+        time_mx_layer("mxfp4_layer_decode_qkvo_7b", 64, 4096, 64, 64, 200, 20)
+        time_mx_layer("mxfp4_layer_decode_down_7b", 64, 4096, 86, 128, 200, 20)
+        time_mx_layer("mxfp4_layer_decode_batch1_qkvo_7b", 1, 4096, 64, 64, 200, 20)
         out["extras"] = extras
 
     # ------------------------------------------------------------------ CPU oracle: baseline timing + parity of the timed buffers
