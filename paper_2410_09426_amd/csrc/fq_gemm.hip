@@ -14,6 +14,7 @@
 // the MFMA's first operand so that a lane ends up with runs of 4 consecutive output channels of one token).  K advances by
 // 256 codes (128 bytes = one cache line per row) per iteration through double-buffered LDS tiles, one barrier per
 // iteration; the tiles go from global memory straight into LDS, a whole iteration before they are read.
+// Launches of up to 128 tokens (decode) take the few-token kernel further down instead.
 #include "fq_internal.h"
 
 namespace fq {

@@ -212,8 +212,8 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     }
 }
 
-// ---- few tokens (T <= 64): the weights are read once and the kernel is bound by how fast a CU takes them in.  A
-// workgroup owns 32 output channels for all tokens; its waves split K by 128-byte lines (256 codes: wave w takes
+// ---- few tokens (T <= 128): the weights are read once and the kernel is bound by how fast a CU takes them in.  A
+// workgroup owns 32 (or 16) output channels for all tokens; its waves split K by 128-byte lines (256 codes: wave w takes
 // lines w, w + waves, ...) and each keeps a ring of line slots of its own in LDS: four global-to-LDS instructions
 // bring 32 weight rows of a line (8 whole rows each), one per 8 token rows the tokens, one the 256 bytes of weight
 // exponents (the tile order keeps them contiguous) and one per 32 tokens theirs.  A wave waits only for its own
