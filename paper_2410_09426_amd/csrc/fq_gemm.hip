@@ -14,7 +14,8 @@
 // the MFMA's first operand so that a lane ends up with runs of 4 consecutive output channels of one token).  K advances by
 // 256 codes (128 bytes = one cache line per row) per iteration through double-buffered LDS tiles, one barrier per
 // iteration; the tiles go from global memory straight into LDS, a whole iteration before they are read.
-// Launches of up to 128 tokens (decode) take the few-token kernel further down instead.
+// Launches whose 128 x 128 tiles would reach at most half of the CUs (decode, short prefill chunks) take the few-token
+// kernel further down instead.
 #include "fq_internal.h"
 
 namespace fq {
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(128 * TW) __attribute__((amdgpu_waves_per_eu(2))) v
     }
 }
 
-// ---- few tokens (T <= 128, decode): the weights are read once, and what bounds the kernel is how fast the CUs take
+// ---- few tokens (decode, short prefill chunks): the weights are read once (per tile of 64 tokens), and what bounds the kernel is how fast the CUs take
 // them in.  A workgroup owns 32 (or 16) output channels for all tokens.  Every operand byte goes from global memory
 // straight into LDS, a whole cache line per row at a time: a wave owns every nwv-th 128-byte line of K (256 codes) of
 // the workgroup's weight rows and of the token rows, with a ring of `depth` line slots of its own in LDS.  One
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(128 * TW) __attribute__((amdgpu_waves_per_eu(2))) v
 // instructions and tag look-ups per cache line and holds far less in flight: 1.5 to 3 times slower.)
 // ROWS = 16: the workgroup owns 16 output channels only (twice as many workgroups, for layers with too few channels
 // to give every CU one of 32); the MFMA's upper 16 rows repeat the lower ones and are dropped.
-template <int NTD, int ROWS>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8, 16 for T <= 8, 16, 32, 64, 128
+template <int NTD, int ROWS>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8 for T <= 8, 16, 32, 64
 __global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void w4a4_skinny_kernel(GemmDev p, int depth) {
     static_assert(ROWS == 16 || ROWS == 32, "weight rows per workgroup");
     constexpr int NWI = ROWS / 8;                        // load instructions per line of the weight rows
@@ -250,6 +251,7 @@ __global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void w4a4_skinny_kernel(Gemm
     const int l = tid & 63, c = l & 31, h = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int o0 = blockIdx.x * ROWS;
+    const int64_t t0 = (int64_t)blockIdx.y * XROWS;      // more than one token tile: launches past 64 tokens (tiles of 64)
     const int64_t kbytes = p.n / 2;
     const int nl = p.n / 256;                            // lines per row
     const int nwv = blockDim.x >> 6;                     // waves: 4, 8 or 16
@@ -268,7 +270,7 @@ __global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void w4a4_skinny_kernel(Gemm
 #pragma unroll
     for (int k = 0; k < NTD; ++k) {
         const int row = 8 * k + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
-        int64_t t = row;
+        int64_t t = t0 + row;
         if (t >= p.T) t = p.T - 1;
         xsrc[k] = p.xc + t * kbytes + 128 * w + 16 * ch;
     }
@@ -307,7 +309,7 @@ __global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void w4a4_skinny_kernel(Gemm
     for (int k = 0; k < NK; ++k) {
         const int e = tid + k * (int)blockDim.x;
         const int el = e & 63, g = (e >> 6) % NG, i = (e >> 6) / NG;
-        const int64_t t = 32 * i + (el & 31);
+        const int64_t t = t0 + 32 * i + (el & 31);
         const int o = o0 + 8 * g + 4 * (el >> 5);
         if (e < NE) {
             esx[k] = xs_bits[t < p.T ? t : p.T - 1];
@@ -363,7 +365,7 @@ __global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void w4a4_skinny_kernel(Gemm
         const int el = e & 63, g = (e >> 6) % NG, i = (e >> 6) / NG;
         i32x4 sum = part[e];
         for (int ww = 1; ww < nwv; ++ww) sum += part[ww * NE + e];
-        const int64_t t = 32 * i + (el & 31);
+        const int64_t t = t0 + 32 * i + (el & 31);
         const int o = o0 + 8 * g + 4 * (el >> 5);
         if (t < p.T && o < p.m) {
             // (the empty statement pins the conversions here: hoisted to the loads, they would stall the kernel's start)
@@ -384,38 +386,39 @@ __global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void w4a4_skinny_kernel(Gemm
 }
 
 template <int NTD, int ROWS>
-static hipError_t skinny_launch_rows(const GemmDev& d, hipStream_t stream) {
+static hipError_t skinny_launch_rows(const GemmDev& d, hipStream_t stream, int token_tiles) {
+    if (token_tiles < 1 || (token_tiles > 1 && NTD < 4)) return hipErrorInvalidValue;   // tiles of 32 tokens or more keep their exponents inside one 128-row tile
     static OccCache oc;
     int unused = 0;
     hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_skinny_kernel<NTD, ROWS>), NTD >= 8 ? 512 : 1024, kRingLdsMax, oc, unused);
     if (e != hipSuccess) return e;
     constexpr int SLOT = (ROWS + 8 * NTD) * 128, NI = ROWS / 8 + NTD;
-    const unsigned wgs = (unsigned)((d.m + ROWS - 1) / ROWS);
+    const unsigned wgx = (unsigned)((d.m + ROWS - 1) / ROWS);
+    const int64_t wgs = (int64_t)wgx * token_tiles;
     const int nl = d.n / 256;
     // One workgroup per CU (or fewer): 8 waves, so that every SIMD has two to overlap, and two slots each.  More than
     // one per CU: small workgroups (4 waves, one slot) that are all resident at once; what the second slot or the
     // other four waves would hide, the neighbouring workgroup hides.  (Measured on 4096 / 11008-wide layers.)
-    const bool crowded = (int)wgs > cu_count();
+    const bool crowded = wgs > cu_count();
     int nwv = env_int("FLATQUANT_GEMM_WAVES", crowded ? 4 : 8);
     int depth = env_int("FLATQUANT_GEMM_DEPTH", crowded ? 1 : 2);
     if ((nwv != 4 && nwv != 8 && nwv != 16) || depth < 1 || depth > kRingMaxDepth) return hipErrorInvalidValue;
-    if (NTD >= 8 && nwv > 8) nwv = 8;                                      // two or four token tiles of accumulators: compiled for at most 8 waves
+    if (NTD >= 8 && nwv > 8) nwv = 8;                                      // two token tiles of accumulators: compiled for at most 8 waves
     while (nwv > 4 && nwv * SLOT > kRingLdsMax) nwv >>= 1;
     const int steps = (nl + nwv - 1) / nwv;                               // of the wave with the most lines
     if (depth > steps) depth = steps;
     while (depth > 1 && (nwv * depth * SLOT > kRingLdsMax || (depth - 1) * NI > 63)) --depth;
     const int bytes = nwv * depth * SLOT;                                 // the partial sums (at most 4 KB per wave and token tile) reuse the rings
-    hipLaunchKernelGGL((w4a4_skinny_kernel<NTD, ROWS>), dim3(wgs), dim3(64 * nwv), bytes, stream, d, depth);
+    hipLaunchKernelGGL((w4a4_skinny_kernel<NTD, ROWS>), dim3(wgx, (unsigned)token_tiles), dim3(64 * nwv), bytes, stream, d, depth);
     return hipGetLastError();
 }
 // 16 channels per workgroup while that still leaves at most one workgroup per CU (FLATQUANT_GEMM_ROWS forces 16 or 32):
 // the kernel is bound by what one CU takes in, so the channels go to as many CUs as there are.
 template <int NTD>
-static hipError_t skinny_launch(const GemmDev& d, hipStream_t stream) {
-    // (not for more than 64 tokens: every workgroup reads all token rows, which then outweigh its weight rows)
-    const int rows = env_int("FLATQUANT_GEMM_ROWS", (NTD <= 8 && (d.m + 15) / 16 <= cu_count()) ? 16 : 32);
-    if (rows == 16) return skinny_launch_rows<NTD, 16>(d, stream);
-    if (rows == 32) return skinny_launch_rows<NTD, 32>(d, stream);
+static hipError_t skinny_launch(const GemmDev& d, hipStream_t stream, int token_tiles = 1) {
+    const int rows = env_int("FLATQUANT_GEMM_ROWS", (int64_t)((d.m + 15) / 16) * token_tiles <= cu_count() ? 16 : 32);
+    if (rows == 16) return skinny_launch_rows<NTD, 16>(d, stream, token_tiles);
+    if (rows == 32) return skinny_launch_rows<NTD, 32>(d, stream, token_tiles);
     return hipErrorInvalidValue;
 }
 
@@ -424,12 +427,19 @@ hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
     GemmDev d;
     d.xc = a.x_codes; d.xs = a.x_scales; d.wc = a.w_codes; d.ws = a.w_scales; d.out = a.out;
     d.T = a.T; d.out_stride = a.out_stride; d.m = a.m; d.n = a.n;
-    if (a.T <= 128 && env_int("FLATQUANT_GEMM_TILED", 0) == 0) {   // decode: one pass over the weights, K split inside a workgroup
+    if (env_int("FLATQUANT_GEMM_TILED", 0) == 0) {
+        // decode and short prefill chunks: one pass over the weights, K split inside a workgroup (the ring kernel)
         if (a.T <= 8) return skinny_launch<1>(d, stream);
         if (a.T <= 16) return skinny_launch<2>(d, stream);
         if (a.T <= 32) return skinny_launch<4>(d, stream);
         if (a.T <= 64) return skinny_launch<8>(d, stream);
-        return skinny_launch<16>(d, stream);
+        // More tokens: the ring kernel on tiles of 64 tokens, as long as the 128 x 128 tiles of the kernel below would
+        // reach at most half of the CUs (measured cross-over on 1024 .. 11008 channels; FLATQUANT_GEMM_RING_MAX_T
+        // replaces the rule by a token count).
+        const int64_t tiled_wgs = ((a.T + GT - 1) / GT) * ((a.m + GT - 1) / GT);
+        const int ring_max = env_int("FLATQUANT_GEMM_RING_MAX_T", -1);
+        if (ring_max >= 0 ? a.T <= ring_max : (2 * tiled_wgs <= cu_count() && a.T <= 4096))
+            return skinny_launch<8>(d, stream, (int)((a.T + 63) / 64));
     }
     static OccCache ct, ctw;
     // 256-token tiles when they still give every CU a workgroup (FLATQUANT_GEMM_WIDE = 0 / 1 forces a form)

@@ -212,7 +212,7 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
     }
 }
 
-// ---- few tokens (T <= 128): the weights are read once and the kernel is bound by how fast a CU takes them in.  A
+// ---- few tokens (decode, short prefill chunks; tiles of up to 64 tokens): the weights are read once per tile and the kernel is bound by how fast a CU takes them in.  A
 // workgroup owns 32 (or 16) output channels for all tokens; its waves split K by 128-byte lines (256 codes: wave w takes
 // lines w, w + waves, ...) and each keeps a ring of line slots of its own in LDS: four global-to-LDS instructions
 // bring 32 weight rows of a line (8 whole rows each), one per 8 token rows the tokens, one the 256 bytes of weight
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(X_NT) __attribute__((amdgpu_waves_per_eu(2))) void 
 // oldest slot (no barrier in the loop).  The partial sums of the waves are added in fp32 through LDS at the end.
 // ROWS = 16: the workgroup owns 16 output channels only (twice as many workgroups, for layers with too few channels
 // to give every CU one of 32); the MFMA's upper 16 rows repeat the lower ones and are dropped.
-template <int NTD, int ROWS>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8, 16 for T <= 8, 16, 32, 64, 128
+template <int NTD, int ROWS>   // token rows in groups of 8 (one load instruction each): 1, 2, 4, 8 for T <= 8, 16, 32, 64
 __global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void mxfp4_skinny_kernel(MxGemmDev p, int depth) {
     static_assert(ROWS == 16 || ROWS == 32, "weight rows per workgroup");
     constexpr int NWI = ROWS / 8;                        // load instructions per line of the weight rows
@@ -236,6 +236,7 @@ __global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void mxfp4_skinny_kernel(MxG
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nwv = blockDim.x >> 6;
     const int o0 = blockIdx.x * ROWS;
+    const int64_t t0 = (int64_t)blockIdx.y * XROWS;      // more than one token tile: launches past 64 tokens (tiles of 64)
     const int64_t kbytes = p.n / 2;
     const int nl = p.n / 256;                            // lines per row
     const int ns = (nl - w + nwv - 1) / nwv;             // this wave's steps
@@ -253,14 +254,15 @@ __global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void mxfp4_skinny_kernel(MxG
 #pragma unroll
     for (int k = 0; k < NTD; ++k) {
         const int row = 8 * k + (l >> 3), ch = (l & 7) ^ ((row >> 1) & 7);
-        int64_t t = row;
+        int64_t t = t0 + row;
         if (t >= p.T) t = p.T - 1;
         xsrc[k] = p.xc + t * kbytes + 128 * w + 16 * ch;
     }
     // exponents of line j: 1 KB per tile of 128 rows, 8 bytes per row.  The workgroup's 32 channels are 256 bytes of
-    // their tile; the tokens are rows 0 .. of tile 0 (the tensor is padded to whole tiles, so rows past T exist).
+    // their tile; the tokens are 32, 64 or 128 consecutive rows of one tile (the tensor is padded to whole tiles, so rows
+    // past T exist).
     const unsigned char* wesrc = p.we + (int64_t)(o0 >> 7) * nl * 1024 + 8 * (o0 & 127) + 1024 * w + 4 * (l & (2 * ROWS - 1));
-    const unsigned char* xesrc = p.xe + 1024 * w + 4 * l;
+    const unsigned char* xesrc = p.xe + (t0 >> 7) * nl * 1024 + 8 * (t0 & 127) + 1024 * w + 4 * l;
     typedef const __attribute__((address_space(1))) void* gptr;
     typedef __attribute__((address_space(3))) void* lptr;
     auto issue = [&](int s, int slot) {
@@ -343,7 +345,7 @@ __global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void mxfp4_skinny_kernel(MxG
         const int el = e & 63, g = (e >> 6) % NG, i = (e >> 6) / NG;
         f32x4 sum = part[e];
         for (int ww = 1; ww < nwv; ++ww) sum += part[ww * NTT * NG * 64 + e];
-        const int64_t t = 32 * i + (el & 31);
+        const int64_t t = t0 + 32 * i + (el & 31);
         const int o = o0 + 8 * g + 4 * (el >> 5);
         if (t < p.T && o < p.m) {
             const _Float16 v[4] = {(_Float16)sum[0], (_Float16)sum[1], (_Float16)sum[2], (_Float16)sum[3]};
@@ -359,36 +361,37 @@ __global__ __launch_bounds__(NTD >= 8 ? 512 : 1024) void mxfp4_skinny_kernel(MxG
 }
 
 template <int NTD, int ROWS>
-static hipError_t mx_skinny_launch_rows(const MxGemmDev& d, hipStream_t stream) {
+static hipError_t mx_skinny_launch_rows(const MxGemmDev& d, hipStream_t stream, int token_tiles) {
+    if (token_tiles < 1 || (token_tiles > 1 && NTD < 4)) return hipErrorInvalidValue;   // tiles of 32 tokens or more keep their exponents inside one 128-row tile
     static OccCache oc;
     int unused = 0;
     hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(mxfp4_skinny_kernel<NTD, ROWS>), NTD >= 8 ? 512 : 1024, kRingLdsMax, oc, unused);
     if (e != hipSuccess) return e;
     constexpr int NTT = NTD > 4 ? NTD / 4 : 1;
     constexpr int SLOT = ROWS * 128 + 1024 * NTD + 256 + 256 * NTT, NI = ROWS / 8 + NTD + 1 + NTT;
-    const unsigned wgs = (unsigned)((d.m + ROWS - 1) / ROWS);
+    const unsigned wgx = (unsigned)((d.m + ROWS - 1) / ROWS);
+    const int64_t wgs = (int64_t)wgx * token_tiles;
     const int nl = d.n / 256;
     // as for the INT4 product: 8 waves and two slots when there is at most one workgroup per CU, else 4 waves and one
-    const bool crowded = (int)wgs > cu_count();
+    const bool crowded = wgs > cu_count();
     int nwv = env_int("FLATQUANT_GEMM_WAVES", crowded ? 4 : 8);
     int depth = env_int("FLATQUANT_GEMM_DEPTH", crowded ? 1 : 2);
     if ((nwv != 4 && nwv != 8 && nwv != 16) || depth < 1 || depth > kRingMaxDepth) return hipErrorInvalidValue;
-    if (NTD >= 8 && nwv > 8) nwv = 8;                     // two or four token tiles of accumulators: compiled for at most 8 waves
+    if (NTD >= 8 && nwv > 8) nwv = 8;                     // two token tiles of accumulators: compiled for at most 8 waves
     while (nwv > 4 && nwv * SLOT > kRingLdsMax) nwv >>= 1;
     const int steps = (nl + nwv - 1) / nwv;
     if (depth > steps) depth = steps;
     while (depth > 1 && (nwv * depth * SLOT > kRingLdsMax || (depth - 1) * NI > 63)) --depth;
     const int bytes = nwv * depth * SLOT;                // the partial sums (at most 4 KB per wave and token tile) reuse the rings
-    hipLaunchKernelGGL((mxfp4_skinny_kernel<NTD, ROWS>), dim3(wgs), dim3(64 * nwv), bytes, stream, d, depth);
+    hipLaunchKernelGGL((mxfp4_skinny_kernel<NTD, ROWS>), dim3(wgx, (unsigned)token_tiles), dim3(64 * nwv), bytes, stream, d, depth);
     return hipGetLastError();
 }
 // 16 channels per workgroup while that still leaves at most one workgroup per CU (FLATQUANT_GEMM_ROWS forces 16 or 32)
 template <int NTD>
-static hipError_t mx_skinny_launch(const MxGemmDev& d, hipStream_t stream) {
-    // (not for more than 64 tokens: every workgroup reads all token rows, which then outweigh its weight rows)
-    const int rows = env_int("FLATQUANT_GEMM_ROWS", (NTD <= 8 && (d.m + 15) / 16 <= cu_count()) ? 16 : 32);
-    if (rows == 16) return mx_skinny_launch_rows<NTD, 16>(d, stream);
-    if (rows == 32) return mx_skinny_launch_rows<NTD, 32>(d, stream);
+static hipError_t mx_skinny_launch(const MxGemmDev& d, hipStream_t stream, int token_tiles = 1) {
+    const int rows = env_int("FLATQUANT_GEMM_ROWS", (int64_t)((d.m + 15) / 16) * token_tiles <= cu_count() ? 16 : 32);
+    if (rows == 16) return mx_skinny_launch_rows<NTD, 16>(d, stream, token_tiles);
+    if (rows == 32) return mx_skinny_launch_rows<NTD, 32>(d, stream, token_tiles);
     return hipErrorInvalidValue;
 }
 
@@ -396,14 +399,19 @@ hipError_t mxfp4_gemm_launch(const MxGemmArgs& a, hipStream_t stream) {
     MxGemmDev d;
     d.xc = a.x_codes; d.xe = a.x_exps; d.wc = a.w_codes; d.we = a.w_exps; d.out = a.out;
     d.T = a.T; d.out_stride = a.out_stride; d.m = a.m; d.n = a.n;
-    if (a.T <= 128 && env_int("FLATQUANT_GEMM_TILED", 0) == 0) {
+    if (env_int("FLATQUANT_GEMM_TILED", 0) == 0) {
+        // decode and short prefill chunks: one pass over the weights, K split inside a workgroup (the ring kernel)
         if (a.T <= 8) return mx_skinny_launch<1>(d, stream);
         if (a.T <= 16) return mx_skinny_launch<2>(d, stream);
         if (a.T <= 32) return mx_skinny_launch<4>(d, stream);
         if (a.T <= 64) return mx_skinny_launch<8>(d, stream);
-        // 65 .. 128 tokens: every workgroup of the ring kernel reads all token rows, four times its weight rows; with
-        // enough 128-channel tiles the tiled kernel is faster (measured: 32 tiles 12.4 against 9.2 us, 86 tiles 13.0 against 17.5 us)
-        if ((a.m + XT - 1) / XT < 64) return mx_skinny_launch<16>(d, stream);
+        // More tokens: the ring kernel on tiles of 64 tokens, as long as the 128 x 128 tiles of the kernel below would
+        // reach at most half of the CUs (measured cross-over on 1024 .. 11008 channels; FLATQUANT_GEMM_RING_MAX_T
+        // replaces the rule by a token count).
+        const int64_t tiled_wgs = ((a.T + XT - 1) / XT) * ((a.m + XT - 1) / XT);
+        const int ring_max = env_int("FLATQUANT_GEMM_RING_MAX_T", -1);
+        if (ring_max >= 0 ? a.T <= ring_max : (2 * tiled_wgs <= cu_count() && a.T <= 4096))
+            return mx_skinny_launch<8>(d, stream, (int)((a.T + 63) / 64));
     }
     static OccCache cache;
     int unused = 0;

@@ -491,6 +491,17 @@ def test_few_token_products_every_launch_shape(tuning, kind, waves, depth, rows,
         _mxfp4_gemm_case(T, m, n)
 
 
+@pytest.mark.parametrize("kind", ["int4", "mxfp4"])
+@pytest.mark.parametrize("T,m,n", [(129, 100, 512), (200, 4100, 1024), (333, 70, 2304), (512, 64, 11008)])
+def test_ring_products_on_several_token_tiles(tuning, kind, T, m, n):
+    """Past 128 tokens the ring kernels run on tiles of 64 tokens (second grid dimension); forced here for any T."""
+    tuning("FLATQUANT_GEMM_RING_MAX_T", 1 << 20)
+    if kind == "int4":
+        _w4a4_case(T, m, n, 0)
+    else:
+        _mxfp4_gemm_case(T, m, n)
+
+
 def test_few_token_mxfp4_product_tiled_form(tuning):
     tuning("FLATQUANT_GEMM_TILED", 1)
     _mxfp4_gemm_case(40, 200, 1024)
