@@ -203,6 +203,7 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
     // for it: the place to queue further requests that nothing in the prologue depends on.
     auto stage_p1 = [&](auto&& after_first_loads) {
         const int n1sq = n1 * n1;
+        bool queued = false;               // after_first_loads() has run
         auto copy_batched = [&](auto* dst, const auto* src, int count) {
             constexpr int BATCH = 8;
             for (int base = 0; base < count; base += BATCH * NTA) {
@@ -215,6 +216,7 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
                 if (base == 0) {
                     __builtin_amdgcn_sched_barrier(0);
                     after_first_loads();
+                    queued = true;
                     __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
@@ -235,6 +237,7 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
             copy_batched(reinterpret_cast<uint32_t*>(P1flat), reinterpret_cast<const uint32_t*>(p.P1), n1sq >> 1);
             if ((n1sq & 1) && tida == 0) P1flat[n1sq - 1] = tail;
         }
+        if (!queued) after_first_loads();   // a P1 of fewer elements than one load unit (n1 = 1, 2): no batch ran
     };
     half8 p2f[ID2 ? 1 : SPW][ID2 ? 1 : KB2];
     half8 p1f[P1LDS ? 1 : A][P1LDS ? 1 : KB1];

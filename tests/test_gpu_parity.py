@@ -116,7 +116,8 @@ def test_prefill_70b_28672_sampled():
 
 
 @pytest.mark.parametrize("n1,n2,T", [(64, 172, 33), (128, 224, 19), (1, 2, 5), (2, 2, 7), (3, 6, 70), (33, 34, 11),
-                                      (16, 256, 9), (128, 32, 13), (96, 64, 300), (32, 96, 1), (50, 20, 64)])
+                                      (16, 256, 9), (128, 32, 13), (96, 64, 300), (32, 96, 1), (50, 20, 64),
+                                      (1, 128, 3000), (2, 64, 2500), (3, 128, 40), (87, 128, 600), (45, 64, 77)])
 def test_shape_sweep(n1, n2, T):
     check_case(synth.generic(n1 * 1000 + n2, T, n1, n2, sigma=0.05 if n1 * n2 > 64 else 0.3))
 
