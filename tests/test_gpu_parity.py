@@ -256,6 +256,39 @@ def test_mxfp4_output(tuning, mode):
         assert not codes[2].any() and not exps[2].any()
 
 
+def _grid_cases():
+    """Left factors around every row-tile edge x right factors of every slab count x token counts below, at and above
+    what is resident at once (a seeded selection of the full grid: every value of each axis appears several times)."""
+    n1s = [1, 2, 3, 4, 31, 32, 33, 48, 63, 64, 65, 95, 96, 97, 127, 128]
+    n2s = [32, 64, 96, 128, 160, 192, 224, 256, 2, 34, 130]
+    Ts = [1, 2, 63, 300, 2049, 2600, 5000]
+    r = np.random.Generator(np.random.PCG64(20241009))
+    cases = set()
+    for n1 in n1s:
+        for n2 in r.choice(n2s, size=4, replace=False):
+            cases.add((int(n1), int(n2), int(r.choice(Ts))))
+    for n2 in n2s:
+        for n1 in r.choice(n1s, size=3, replace=False):
+            cases.add((int(n1), int(n2), int(r.choice(Ts))))
+    # wide rows: fewer tokens (host-side generation time), still more than the workgroups resident for those shapes
+    cases = {(n1, n2, min(T, max(600, 20_000_000 // (n1 * n2)))) for n1, n2, T in cases}
+    return sorted(c for c in cases if (c[0] * c[1]) % 2 == 0)
+
+
+@pytest.mark.parametrize("n1,n2,T", _grid_cases())
+def test_shape_grid(n1, n2, T):
+    """Codes and steps against the oracle's factored form of Eq. (2) (pinned to the dense Kronecker form on the CPU) on a
+    subset of rows: the first and last tokens of the launch and of the first workgroups' second round."""
+    c = synth.generic(7 * n1 + 13 * n2 + T, T, n1, n2, sigma=0.05 if n1 * n2 > 64 else 0.3)
+    print(f"[case] grid {n1}x{n2} T={T}", flush=True)
+    codes, scales, _, _ = run_tq(dev(c.x), dev(c.P1), dev(c.P2), dev(c.clip), c.clip_mode, n1, n2)
+    rows = subset_rows(T, 96, n1 + n2, must=(0, 1, 2047, 2048, 2049, T - 2))
+    y = fo.affine_transform_factored(c.x[rows], c.P1, c.P2)
+    rep = parity.check_sym(y, c.clip[rows], codes[rows], scales[rows], rows=rows)
+    print(f"[parity] {rep}", flush=True)
+    assert rep["band_flips"] <= max(4, rep["in_band"])
+
+
 # ---- KV-cache variant --------------------------------------------------------------------
 def run_kv(kv, P, Hp, clip, bits=None):
     T, H, D = kv.shape
@@ -286,6 +319,20 @@ def test_kv_cache(T, H, shared):
         y = fo.kv_transform(tensor, P).reshape(T * H, kv.D)
         rep = parity.check_kv(y, kv.clip, codes, sc, zr, deq_dev=deq)
         print(f"[parity] kv {name}: {rep}", flush=True)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("T,H", [(31, 2), (32, 5), (33, 16), (64, 40), (127, 1), (129, 2), (1000, 5), (3, 33), (4097, 3)])
+def test_kv_cache_token_and_head_counts(bits, T, H):
+    """Token counts around the 32-token step of a wave and head counts that are not powers of two."""
+    kv = synth.kv_cache(T=T, H=H)
+    shared = (T + H) % 2 == 0
+    P = kv.P[:1] if shared else kv.P
+    print(f"[case] kv bits={bits} T={T} H={H} shared={shared}", flush=True)
+    codes, sc, zr, deq = run_kv(kv.k, P, P.shape[0], kv.clip, bits)
+    y = fo.kv_transform(kv.k, P).reshape(T * H, kv.D)
+    rep = parity.check_kv(y, kv.clip, codes, sc, zr, deq_dev=deq, bits=bits)
+    print(f"[parity] {rep}", flush=True)
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
@@ -497,6 +544,32 @@ def test_few_token_products_every_launch_shape(tuning, kind, waves, depth, rows,
 def test_ring_products_on_several_token_tiles(tuning, kind, T, m, n):
     """Past 128 tokens the ring kernels run on tiles of 64 tokens (second grid dimension); forced here for any T."""
     tuning("FLATQUANT_GEMM_RING_MAX_T", 1 << 20)
+    if kind == "int4":
+        _w4a4_case(T, m, n, 0)
+    else:
+        _mxfp4_gemm_case(T, m, n)
+
+
+def _product_grid():
+    Ts = [1, 7, 8, 9, 16, 17, 32, 33, 64, 65, 127, 128, 129, 191, 193, 256, 257, 500, 1100]
+    ms = [1, 15, 16, 17, 31, 32, 33, 127, 128, 129, 255, 257, 1000, 4100]
+    ns = [256, 512, 768, 1280, 4096, 11008]
+    r = np.random.Generator(np.random.PCG64(9426))
+    cases = set()
+    for T in Ts:
+        for _ in range(3):
+            cases.add((T, int(r.choice(ms)), int(r.choice(ns))))
+    for m in ms:
+        for _ in range(2):
+            cases.add((int(r.choice(Ts)), m, int(r.choice(ns))))
+    return sorted(c for c in cases if c[0] * c[1] * c[2] <= 1_500_000_000)
+
+
+@pytest.mark.parametrize("T,m,n", _product_grid())
+@pytest.mark.parametrize("kind", ["int4", "mxfp4"])
+def test_product_grid(kind, T, m, n):
+    """Token and channel counts around every tile edge of the ring kernels (8, 16, 32, 64 tokens; 16, 32 channels) and
+    of the tiled kernels (128, 256), in the launch shape the library picks by itself."""
     if kind == "int4":
         _w4a4_case(T, m, n, 0)
     else:
