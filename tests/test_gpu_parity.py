@@ -236,6 +236,24 @@ def run_mx(c, rows=None):
     return codes, exps
 
 
+def _mx_grid():
+    r = np.random.Generator(np.random.PCG64(3141))
+    cases = set()
+    for n1 in [1, 2, 3, 31, 32, 33, 63, 64, 65, 96, 100, 127, 128]:
+        for n2 in (64, 128, 256):
+            if (n1 * n2) % 128 == 0 and r.random() < 0.75:
+                T = int(r.choice([1, 2, 63, 300, 2049, 2600]))
+                cases.add((n1, n2, min(T, max(600, 20_000_000 // (n1 * n2)))))
+    return sorted(cases)
+
+
+@pytest.mark.parametrize("n1,n2,T", _mx_grid())
+def test_mxfp4_output_shape_grid(n1, n2, T):
+    c = synth.generic(17 * n1 + n2 + T, T, n1, n2, clip_mode=(n1 + T) % 2)
+    print(f"[case] mxfp4 grid {n1}x{n2} T={T}", flush=True)
+    run_mx(c, rows=None if T <= 300 else subset_rows(T, 100, n1, must=(0, 1, 2047, 2048, T - 2)))
+
+
 @pytest.mark.parametrize("mode", ["-1", "0", "3"])
 def test_mxfp4_output(tuning, mode):
     if mode != "-1":
@@ -626,6 +644,33 @@ def test_one_sided_transforms(n1, n2, T, which):
     y = fo.affine_transform(c.x[rows], P1, P2)
     rep = parity.check_sym(y, c.clip[rows], codes[rows], scales[rows], rows=rows)
     print(f"[parity] one-sided {which}: {rep}", flush=True)
+    assert rep["band_flips"] <= max(4, rep["in_band"])
+
+
+def _one_sided_grid():
+    r = np.random.Generator(np.random.PCG64(2718))
+    cases = set()
+    for n1 in [1, 2, 31, 32, 33, 64, 65, 96, 128]:
+        for n2 in [32, 64, 128, 160, 256, 34, 2]:
+            if (n1 * n2) % 2 == 0 and r.random() < 0.55:
+                T = int(r.choice([1, 2, 63, 300, 2049, 2600]))
+                which = str(r.choice(["P1 only", "P2 only", "none"]))
+                cases.add((n1, n2, min(T, max(600, 20_000_000 // (n1 * n2))), which))
+    return sorted(cases)
+
+
+@pytest.mark.parametrize("n1,n2,T,which", _one_sided_grid())
+def test_one_sided_shape_grid(n1, n2, T, which):
+    c = synth.generic(900 + 3 * n1 + n2 + T, T, n1, n2, sigma=0.05 if n1 * n2 > 64 else 0.3)
+    use1, use2 = which == "P1 only", which == "P2 only"
+    P1 = c.P1 if use1 else np.eye(n1, dtype=np.float16)
+    P2 = c.P2 if use2 else np.eye(n2, dtype=np.float16)
+    print(f"[case] one-sided grid {which} {n1}x{n2} T={T}", flush=True)
+    codes, scales, _, _ = run_tq(dev(c.x), dev(c.P1) if use1 else None, dev(c.P2) if use2 else None, dev(c.clip), c.clip_mode, n1, n2)
+    rows = subset_rows(T, 100, 32, must=(0, 1, 2047, 2048, T - 2))
+    y = fo.affine_transform_factored(c.x[rows], P1, P2)
+    rep = parity.check_sym(y, c.clip[rows], codes[rows], scales[rows], rows=rows)
+    print(f"[parity] {rep}", flush=True)
     assert rep["band_flips"] <= max(4, rep["in_band"])
 
 
