@@ -463,6 +463,32 @@ def test_weight_side_parity_and_quantized_layer(T, m, n1, n2):
     assert abs(rel - rel_o) <= 1e-3 * max(rel_o, 1e-6) + 1e-6 * (int(flips_x.sum()) + int(flips_w.sum()) + 1)
 
 
+@pytest.mark.parametrize("n1,n2,T", [(64, 64, 1), (64, 64, 127), (64, 64, 128), (64, 64, 129), (86, 128, 300), (32, 256, 257), (4, 64, 640),
+                                      (64, 64, 2600), (64, 128, 2100), (128, 256, 130)])
+def test_mxfp4_tiled_exponents_equal_row_major(n1, n2, T):
+    """Tile order of the exponents (what the MXFP4 product reads) against the row-major output of the same launch shape:
+    same codes, same exponents after undoing the order, padding rows of the last tile untouched."""
+    n = n1 * n2
+    c = synth.generic(1300 + n1 + n2 + T, T, n1, n2)
+    xd, P1, P2, cd = dev(c.x), dev(c.P1), dev(c.P2), dev(c.clip)
+    c0 = torch.empty((T, n // 2), dtype=torch.uint8, device="cuda")
+    e0 = torch.empty((T, n // 32), dtype=torch.uint8, device="cuda")
+    c1 = torch.empty((T, n // 2), dtype=torch.uint8, device="cuda")
+    e1 = torch.full((fq.fq_mxfp4_tiled_scale_bytes(T, n) + 64,), 0xFF, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream()
+    print(f"[case] tiled exponents {n1}x{n2} T={T}", flush=True)
+    fq.flatquant_transform_mxfp4(xd, P1, P2, cd, c.clip_mode, T, n1, n2, n, c0, e0, stream=st)
+    fq.flatquant_transform_mxfp4_tiled(xd, P1, P2, cd, c.clip_mode, T, n1, n2, n, c1, e1, stream=st)
+    torch.cuda.synchronize()
+    assert torch.equal(c0, c1)
+    e1h = e1.cpu().numpy()
+    assert np.all(e1h[-64:] == 0xFF), "bytes past the tensor written"
+    e1h = e1h[:-64]
+    assert np.array_equal(fo.mx_untile_scales(e1h, T, n), e0.cpu().numpy())
+    if T % 128:
+        assert np.all(e1h.reshape(-1, n // 256, 128, 8)[-1, :, T % 128:, :] == 0xFF), "padding rows written"
+
+
 def test_mxfp4_tiled_exponents_and_product_end_to_end():
     """The tile-ordered output equals the row-major one, and feeding it to the product reproduces the oracle's product of
     the same codes."""
