@@ -200,6 +200,30 @@ def test_strided_and_unaligned_buffers():
     assert np.array_equal(b_codes, ref_codes) and np.array_equal(b_scales.view(np.uint16), ref_scales.view(np.uint16))
 
 
+@pytest.mark.parametrize("n1,n2,T", [(64, 64, 70), (86, 128, 19), (32, 96, 300), (3, 6, 50), (64, 128, 2100), (33, 34, 40)])
+@pytest.mark.parametrize("pad,xoff,poff,guard", [(2, 0, 0, 64), (8, 0, 0, 64), (10, 2, 0, 63), (0, 4, 1, 64), (24, 6, 1, 61), (0, 0, 1, 64)])
+def test_alignment_and_stride_grid(n1, n2, T, pad, xoff, poff, guard):
+    """Row strides that are not multiples of 8 elements, inputs that start 4, 8 or 12 bytes into a 16-byte unit, factors
+    that start 2 bytes in, codes on odd addresses: whichever kernel the library falls back to, against the oracle."""
+    n = n1 * n2
+    c = synth.generic(60 + n1 + n2 + pad + xoff, T, n1, n2, sigma=0.05 if n > 64 else 0.3)
+    stride = n + pad
+    flat = torch.zeros((xoff + T * stride + 8,), dtype=torch.float16, device="cuda")
+    xv = flat[xoff:xoff + T * stride].view(T, stride)
+    xv[:, :n] = dev(c.x)
+    xv[:, n:] = 777.0                                    # the gap between rows must not leak into any row
+    def shifted(a):
+        t = torch.zeros((a.size + 8,), dtype=torch.float16, device="cuda")
+        t[poff:poff + a.size] = dev(a).reshape(-1)
+        return t[poff:poff + a.size].view(*a.shape)
+    print(f"[case] alignment grid {n1}x{n2} T={T} stride n+{pad} x+{xoff} P+{poff} guard {guard}", flush=True)
+    codes, scales, _, _ = run_tq(xv, shifted(c.P1), shifted(c.P2), dev(c.clip), c.clip_mode, n1, n2, x_stride=stride, guard=guard)
+    rows = subset_rows(T, 100, 33, must=(0, 1, T - 2))
+    y = fo.affine_transform_factored(c.x[rows], c.P1, c.P2)
+    rep = parity.check_sym(y, c.clip[rows], codes[rows], scales[rows], rows=rows)
+    assert rep["band_flips"] <= max(4, rep["in_band"])
+
+
 def test_determinism_and_empty_input():
     c = synth.prefill_7b(512)
     x, P1, P2, clip = dev(c.x), dev(c.P1), dev(c.P2), dev(c.clip)
