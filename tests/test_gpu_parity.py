@@ -724,7 +724,8 @@ def test_one_sided_shape_grid(n1, n2, T, which):
     assert rep["band_flips"] <= max(4, rep["in_band"])
 
 
-@pytest.mark.parametrize("T,H,shared", [(4096, 8, False), (1, 8, False), (77, 3, False), (200, 8, True)])
+@pytest.mark.parametrize("T,H,shared", [(4096, 8, False), (1, 8, False), (77, 3, False), (200, 8, True), (31, 2, True), (32, 5, False), (33, 16, True),
+                                        (127, 1, False), (129, 2, True), (1000, 5, False), (3, 33, False), (4097, 3, True), (64, 40, False)])
 def test_head_transform_fp16_out(T, H, shared):
     """Query side of a transformed key cache: fp16(x P_h) against the oracle's single rounding of the fp64 product.
     Tolerance from the arithmetic: fp32 accumulation of 128 exact fp16 products (<= 128 * 2^-24 of the sum of their
