@@ -644,6 +644,17 @@ def test_product_grid(kind, T, m, n):
         _mxfp4_gemm_case(T, m, n)
 
 
+@pytest.mark.parametrize("kind", ["int4", "mxfp4"])
+@pytest.mark.parametrize("T,m", [(5, 33), (64, 100), (150, 40), (700, 130)])
+def test_products_at_the_longest_rows(kind, T, m):
+    """n = 65536: the longest row the INT4 product accepts (its int32 sums reach 2^30), 256 lines per row for the ring
+    kernels and 256 iterations for the tiled ones."""
+    if kind == "int4":
+        _w4a4_case(T, m, 65536, 0)
+    else:
+        _mxfp4_gemm_case(T, m, 65536)
+
+
 def test_few_token_mxfp4_product_tiled_form(tuning):
     tuning("FLATQUANT_GEMM_TILED", 1)
     _mxfp4_gemm_case(40, 200, 1024)
@@ -763,7 +774,8 @@ def _w4a4_case(T, m, n, pad):
     cx[0, :] = 0x88      # every code -8: the largest magnitude sums
     cw[0, :] = 0x88
     sx = r.uniform(0.01, 4.0, size=T).astype(np.float16)
-    sw = r.uniform(0.001, 0.2 * 256 / n, size=m).astype(np.float16)     # keeps 64 n s_x s_w inside the fp16 range
+    sw_hi = 0.2 * 256 / n                                                # keeps 64 n s_x s_w inside the fp16 range
+    sw = r.uniform(min(0.001, sw_hi / 4), sw_hi, size=m).astype(np.float16)
     print(f"[case] w4a4 T={T} m={m} n={n}", flush=True)
     out = torch.full((64 + T * (m + pad) + 64,), float("nan"), dtype=torch.float16, device="cuda")
     fq.flatquant_w4a4_gemm(dev(cx), dev(sx), dev(cw), dev(sw), T, m, n, out[64:], m + pad, stream=torch.cuda.current_stream())
