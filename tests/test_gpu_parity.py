@@ -655,6 +655,23 @@ def test_products_at_the_longest_rows(kind, T, m):
         _mxfp4_gemm_case(T, m, 65536)
 
 
+@pytest.mark.parametrize("knob,value", [("FLATQUANT_GEMM_WAVES", 5), ("FLATQUANT_GEMM_DEPTH", 0), ("FLATQUANT_GEMM_DEPTH", 9), ("FLATQUANT_GEMM_ROWS", 24)])
+def test_ring_kernel_overrides_out_of_range_are_launch_errors(tuning, knob, value):
+    """A tuning override the ring kernels cannot honour is reported (no launch, outputs untouched), not silently replaced."""
+    tuning(knob, value)
+    T, m, n = 8, 64, 512
+    z = lambda *shape: torch.zeros(shape, dtype=torch.uint8, device="cuda")
+    out = torch.full((T, m), float("nan"), dtype=torch.float16, device="cuda")
+    sx = torch.ones((T,), dtype=torch.float16, device="cuda")
+    sw = torch.ones((m,), dtype=torch.float16, device="cuda")
+    assert fq.flatquant_w4a4_gemm(z(T, n // 2), sx, z(m, n // 2), sw, T, m, n, out, m, stream=torch.cuda.current_stream(), check=False) == fq.FQ_LAUNCH_FAILED
+    assert fq.flatquant_mxfp4_gemm(z(T, n // 2), z(fq.fq_mxfp4_tiled_scale_bytes(T, n)), z(m, n // 2), z(fq.fq_mxfp4_tiled_scale_bytes(m, n)), T, m, n, out, m,
+                                   stream=torch.cuda.current_stream(), check=False) == fq.FQ_LAUNCH_FAILED
+    assert fq.last_hip_error() != 0
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(out).all())
+
+
 def test_few_token_mxfp4_product_tiled_form(tuning):
     tuning("FLATQUANT_GEMM_TILED", 1)
     _mxfp4_gemm_case(40, 200, 1024)
