@@ -186,7 +186,10 @@ fq_status flatquant_w4a4_gemm(const uint8_t* x_codes, const void* x_scales, cons
  *   out     fp16 [T, m], row t at out + t*out_stride halves, out_stride >= m.
  * n must be a multiple of 256; code and exponent tensors 16-byte aligned; the exponent tensors hold
  * fq_mxfp4_tiled_scale_bytes(T or m, n) bytes (the rows of the padding are read and ignored).  T == 0 or m == 0
- * returns FQ_OK.  Values beyond the fp16 range come out as infinities.
+ * returns FQ_OK.  Values beyond the fp16 range come out as infinities.  The order of the fp32 additions belongs to the
+ * kernel the library picks for (T, m, n) on the device at hand (K split over the waves of a workgroup for few tokens,
+ * K in sequence for many): the same call gives the same bits every time, two different T need not agree in the last
+ * bit of a row they share.  (The INT4 product sums integers and has no such dependence.)
  */
 fq_status flatquant_mxfp4_gemm(const uint8_t* x_codes, const uint8_t* x_scales, const uint8_t* w_codes, const uint8_t* w_scales,
                                int64_t T, int m, int n, void* out, int64_t out_stride, void* stream);
