@@ -672,6 +672,46 @@ def test_ring_kernel_overrides_out_of_range_are_launch_errors(tuning, knob, valu
     assert bool(torch.isnan(out).all())
 
 
+def test_int4_product_rows_do_not_depend_on_the_launch(tuning):
+    """Integer sums and one fixed order of the two fp32 multiplications: a token's output row has the same bits whether it
+    is computed alone, among 40 tokens (ring kernel), among 700 (tiled kernel) or by any forced form."""
+    r = np.random.Generator(np.random.PCG64(77))
+    T, m, n = 700, 200, 2304
+    cx = dev(r.integers(0, 256, size=(T, n // 2), dtype=np.uint8))
+    cw = dev(r.integers(0, 256, size=(m, n // 2), dtype=np.uint8))
+    sx = dev(r.uniform(0.01, 2.0, size=T).astype(np.float16))
+    sw = dev(r.uniform(0.001, 0.02, size=m).astype(np.float16))
+    def run(Tn):
+        out = torch.empty((Tn, m), dtype=torch.float16, device="cuda")
+        fq.flatquant_w4a4_gemm(cx, sx, cw, sw, Tn, m, n, out, m, stream=torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        return out.cpu().view(torch.int16).numpy()
+    full = run(T)
+    for Tn in (1, 8, 40, 64, 130, 300):
+        assert np.array_equal(run(Tn), full[:Tn]), f"rows differ between T={Tn} and T={T}"
+    tuning("FLATQUANT_GEMM_TILED", 1)
+    assert np.array_equal(run(40), full[:40])
+    tuning("FLATQUANT_GEMM_RING_MAX_T", 1 << 20)
+    tuning("FLATQUANT_GEMM_TILED", 0)
+    assert np.array_equal(run(T), full)
+
+
+def test_mxfp4_product_is_reproducible():
+    r = np.random.Generator(np.random.PCG64(78))
+    for T, m, n in ((40, 200, 2304), (700, 200, 2304)):
+        xc = dev(r.integers(0, 256, size=(T, n // 2), dtype=np.uint8))
+        wc = dev(r.integers(0, 256, size=(m, n // 2), dtype=np.uint8))
+        xe = dev(fo.mx_tile_scales(r.integers(118, 131, size=(T, n // 32), dtype=np.uint8), fill=0xFF))
+        we = dev(fo.mx_tile_scales(r.integers(112, 126, size=(m, n // 32), dtype=np.uint8), fill=0xFF))
+        outs = []
+        for _ in range(3):
+            out = torch.empty((T, m), dtype=torch.float16, device="cuda")
+            fq.flatquant_mxfp4_gemm(xc, xe, wc, we, T, m, n, out, m, stream=torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            outs.append(out.cpu().view(torch.int16).numpy())
+        assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
 def test_few_token_mxfp4_product_tiled_form(tuning):
     tuning("FLATQUANT_GEMM_TILED", 1)
     _mxfp4_gemm_case(40, 200, 1024)
