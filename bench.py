@@ -253,6 +253,14 @@ def main() -> int:
         by = Tk * H * (2 * D + D // 2 + 4)
         extras["kv_cache"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms * 1e3, "groups_per_s": Tk * H / (ms * 1e-3),
                               "gbs": by / (ms * 1e-3) / 1e9, "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        Pshared = Pk[:1].contiguous()                     # the paper's setting: one P_h per layer, shared by the heads
+
+        def st_kvs(i):
+            k = i % 8
+            fq.flatquant_kv_transform_quant(kvsets[k], Pshared, 1, 0.95, Tk, H, D, kc[k], ks[k], kz[k], stream=stream)
+        ms_s = float(np.median([time_region(st_kvs, 40, 8 if r == 0 else 1)[0] for r in range(5)]))
+        extras["kv_cache_shared_matrix"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms_s * 1e3, "groups_per_s": Tk * H / (ms_s * 1e-3),
+                                            "gbs": by / (ms_s * 1e-3) / 1e9, "hbm_frac": by / (ms_s * 1e-3) / 1e9 / HBM_PEAK_GBS}
         for bits in (3, 2):   # lower-bit caches: same kernel, D * bits / 8 code bytes per group (into the same buffers)
             def st_kvb(i, bits=bits):
                 k = i % 8

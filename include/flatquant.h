@@ -262,7 +262,8 @@ int fq_abi_version(void);
  * workgroups), FLATQUANT_FORCE_GENERIC (1: general kernel on shapes the specialised ones would take),
  * FLATQUANT_GEMM_TILED (1: tiled product for any T), FLATQUANT_GEMM_WIDE (0 / 1: 128- or 256-token tiles),
  * FLATQUANT_GEMM_ROWS (16 / 32 output channels per workgroup), FLATQUANT_GEMM_WAVES (4 / 8 / 16) and
- * FLATQUANT_GEMM_DEPTH (1..8 line slots per wave) of the few-token products.  enable != 0 sets the override to `value`, enable == 0
+ * FLATQUANT_GEMM_DEPTH (1..8 line slots per wave) of the few-token products, FLATQUANT_GEMM_RING_MAX_T (token count up to
+ * which the few-token kernel is used), FLATQUANT_KV_FOLD_HEADS (0: a shared P_h is applied head by head like separate ones).  enable != 0 sets the override to `value`, enable == 0
  * removes it.  Each override starts from the environment variable of the same name, read once per process.
  * Process-wide; affects launches issued after the call returns.  Unknown names return FQ_INVALID_ARG.
  */

@@ -317,7 +317,15 @@ static hipError_t kv_launch_mode(const KvArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t kv_launch(const KvArgs& a, hipStream_t stream) {
+hipError_t kv_launch(const KvArgs& a0, hipStream_t stream) {
+    // One matrix for all heads (the paper's setting: one P_h per layer): the (token, head) groups are then T * H rows
+    // of one head, which a wave takes 32 consecutive ones at a time (8 KB in one piece) instead of 32 rows that lie
+    // H * 256 bytes apart.  Same results bit for bit; 32768 x 8 x 128: 23.2 -> 19.9 us.
+    KvArgs a = a0;
+    if (a.Hp == 1 && a.H > 1 && env_int("FLATQUANT_KV_FOLD_HEADS", 1)) {
+        a.T = a.T * a.H;
+        a.H = 1;
+    }
     if (a.fp16_out) return kv_launch_mode<0>(a, stream);
     switch (a.bits) {
         case 2: return kv_launch_mode<2>(a, stream);

@@ -377,6 +377,27 @@ def test_kv_cache_token_and_head_counts(bits, T, H):
     print(f"[parity] {rep}", flush=True)
 
 
+@pytest.mark.parametrize("bits,T,H", [(4, 1000, 8), (3, 33, 5), (2, 4097, 3), (4, 31, 40), (None, 700, 8)])
+def test_shared_head_matrix_folded_or_not(tuning, bits, T, H):
+    """One P_h for all heads: the library treats the groups as T * H rows of a single head; head by head (forced) must
+    give the same bits.  bits = None: the fp16-out transform."""
+    kv = synth.kv_cache(T=T, H=H)
+    P = kv.P[:1]
+    res = []
+    for fold in (1, 0):
+        tuning("FLATQUANT_KV_FOLD_HEADS", fold)
+        if bits is None:
+            out = torch.full((T * H * kv.D,), float("nan"), dtype=torch.float16, device="cuda")
+            fq.flatquant_head_transform(dev(kv.k), dev(P), 1, T, H, kv.D, out, stream=torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            res.append((out.cpu().view(torch.int16).numpy(),))
+        else:
+            codes, sc, zr, _ = run_kv(kv.k, P, 1, kv.clip, bits)
+            res.append((codes, sc.view(np.uint16), zr.view(np.uint16)))
+    for a, b in zip(*res):
+        assert np.array_equal(a, b)
+
+
 @pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("T,H,shared", [(4096 + 5, 8, False), (1, 8, False), (77, 3, False), (33, 1, True)])
 def test_kv_cache_lower_bits(bits, T, H, shared):
