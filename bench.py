@@ -269,6 +269,16 @@ def main() -> int:
             by = Tk * H * (2 * D + D * bits // 8 + 4)
             extras[f"kv_cache_{bits}bit"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms * 1e3, "groups_per_s": Tk * H / (ms * 1e-3),
                                             "gbs": by / (ms * 1e-3) / 1e9, "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        # a decode step's share of the cache: 64 new tokens x 32 heads (one launch each for K and V in a layer)
+        Td, Hd = 64, 32
+        kvd = torch.randn((Td, Hd, D), generator=g, device="cuda").half()
+        Pd = (torch.eye(D, device="cuda").expand(Hd, D, D) + 0.05 * torch.randn((Hd, D, D), generator=g, device="cuda")).half().contiguous()
+
+        def st_kvd(i, s_=None):
+            fq.flatquant_kv_transform_quant(kvd, Pd, Hd, 0.95, Td, Hd, D, kc[0], ks[0], kz[0], stream=s_ or stream)
+        ms = float(np.median([time_region(st_kvd, 200, 20 if r == 0 else 1)[0] for r in range(5)]))
+        extras["kv_cache_decode"] = {"T": Td, "H": Hd, "D": D, "us_per_call": ms * 1e3,
+                                     "us_per_call_graph_replay": graph_replay_us("kv_cache_decode", lambda gs: st_kvd(0, gs))}
         # query side: per-head transform, fp16 out (same tensors, 2 x 2D bytes per group)
         qo = [torch.empty((Tk, H, D), dtype=torch.float16, device="cuda") for _ in range(4)]
 
