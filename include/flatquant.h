@@ -112,7 +112,8 @@ int64_t fq_mxfp4_tiled_scale_bytes(int64_t rows, int64_t n);
  *
  *   kv         fp16 [T, H, D] contiguous, 16-byte aligned.  D must be 128.
  *   P          fp16 [Hp, D, D] row-major; Hp == 1 (one matrix shared by all
- *              heads) or Hp == H (one per head).
+ *              heads: the groups are then read as T*H consecutive rows, which is
+ *              the faster of the two) or Hp == H (one per head).
  *   out_codes  u8 [T, H, D/2], unsigned nibbles, even channel in the low nibble; 16-byte aligned.
  *   out_scales fp16 [T, H];  out_zeros fp16 [T, H] holding the integer z.
  */
