@@ -63,7 +63,8 @@ constexpr int KV_STAGE_PITCH = 80;         // bytes per staged code row (up to 6
 constexpr int KV_MT = KV_D / 32;           // 4 tiles over d'
 constexpr int KV_KB = KV_D / 16;           // 8 K blocks over d
 constexpr int KV_FRAG_BYTES = KV_MT * KV_KB * 64 * 16;        // 32 KB of A fragments
-constexpr int KV_FLAT_ROWS = KV_D / 2;                        // P_h is re-laid in two passes of 64 rows
+constexpr int KV_FLAT_ROWS = KV_D;                            // rows of P_h staged per pass (all of them: one workgroup per CU has the LDS)
+constexpr int KV_PASSES = KV_D / KV_FLAT_ROWS;
 constexpr int KV_FLAT_BYTES = KV_FLAT_ROWS * (KV_D + 8) * 2;  // row-major, padded pitch, while fragments are built
 constexpr int KV_STAGE_BYTES = KV_WAVES * 32 * KV_STAGE_PITCH;
 constexpr int KV_LDS_BYTES = KV_FRAG_BYTES + (KV_FLAT_BYTES > KV_STAGE_BYTES ? KV_FLAT_BYTES : KV_STAGE_BYTES);
@@ -122,37 +123,37 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
     u32x4 cur[KV_KB], nxt[KV_KB];
 
     // ---- P_h: coalesced loads -> LDS (padded pitch) -> A fragments: lane (c, h) of fragment (mt, kb) holds
-    // P_h[16kb + 8h + s][32mt + c'], s = 0..7, c' = c with its 4-column chunks 1 and 2 (of each 16) exchanged.  The LDS copy is made in two passes of 64 rows (3 workgroups per CU), but
+    // P_h[16kb + 8h + s][32mt + c'], s = 0..7, c' = c with its 4-column chunks 1 and 2 (of each 16) exchanged.  The LDS copy is made in KV_PASSES passes, but
     // all of P_h is requested up front, and the first token rows only once it has arrived.  A CU's vector memory pipe
     // returns data in request order: if the workgroups that start first queued their rows (HBM) at once, the P_h
     // requests (L2) of the workgroups that start a little later on the same CU would wait behind them for microseconds,
     // and those workgroups would end the kernel late (measured: 11 us to build the fragments instead of 3).
-    constexpr int CH = KV_FLAT_ROWS * KV_D / 8;   // 1024 chunks of 16 bytes per pass, 4 per thread
-    u32x4 v[2][CH / KV_NT];
+    constexpr int CH = KV_FLAT_ROWS * KV_D / 8;   // chunks of 16 bytes per pass
+    u32x4 v[KV_PASSES][CH / KV_NT];
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass)
+    for (int pass = 0; pass < KV_PASSES; ++pass)
 #pragma unroll
         for (int k = 0; k < CH / KV_NT; ++k) v[pass][k] = reinterpret_cast<const u32x4*>(Ph)[pass * CH + tid + k * KV_NT];
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int pass = 0; pass < KV_PASSES; ++pass) {
         if (pass > 0) __syncthreads();   // previous pass fully consumed
 #pragma unroll
         for (int k = 0; k < CH / KV_NT; ++k) {
             const int q = tid + k * KV_NT, r = q >> 4, cc = q & 15;
             *reinterpret_cast<u32x4*>(Pflat + r * (KV_D + 8) + cc * 8) = v[pass][k];
         }
-        if (pass == 1) {   // all of P_h has arrived: only now request the first token rows (see above)
+        if (pass == KV_PASSES - 1) {   // all of P_h has arrived: only now request the first token rows (see above)
             __builtin_amdgcn_sched_barrier(0);
             issue(blk, cur);
             __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
-        for (int e = tid; e < KV_MT * (KV_KB / 2) * 64; e += KV_NT) {
-            const int ln = e & 63, kbl = (e >> 6) % (KV_KB / 2), mt = (e >> 6) / (KV_KB / 2);
+        for (int e = tid; e < KV_MT * (KV_KB / KV_PASSES) * 64; e += KV_NT) {
+            const int ln = e & 63, kbl = (e >> 6) % (KV_KB / KV_PASSES), mt = (e >> 6) / (KV_KB / KV_PASSES);
             const int cc = ln & 31, hh = ln >> 5;
             // e % 64 is the lane, so whole 16-lane blocks cooperate in the transposing reads
             const half8 f = lds_column8(Pflat, KV_D + 8, 16 * kbl + 8 * hh, 4, 32 * mt + (cc & 16), ln & 15);
-            *reinterpret_cast<half8*>(&Pf[(mt * KV_KB + pass * (KV_KB / 2) + kbl) * 64 + ln]) = f;
+            *reinterpret_cast<half8*>(&Pf[(mt * KV_KB + pass * (KV_KB / KV_PASSES) + kbl) * 64 + ln]) = f;
         }
     }
     __syncthreads();   // fragments ready; the flat copy's space becomes the stage buffers
@@ -302,9 +303,10 @@ static hipError_t kv_launch_mode(const KvArgs& a, hipStream_t stream) {
         hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(kv_kernel<BITS>), KV_NT, LDS, occ_cache, occ);
         if (e != hipSuccess) return e;
     }
-    // One workgroup per CU although two fit: the same tokens in half as many, twice as long-lived workgroups (half as
-    // many P_h fragment tables to build, eight steps per wave instead of four at 32768 x 8) measured 5 - 15 % faster
-    // from T = 8192 up and the same below.  FLATQUANT_KV_WG_PER_CU overrides (0: as many as fit).
+    // One workgroup per CU (its LDS holds the fragment table and, while that is built, all of P_h).  With P_h staged in
+    // two halves two workgroups fit, and measured 5 - 15 % slower from T = 8192 up (twice as many fragment tables to
+    // build, four steps per wave instead of eight at 32768 x 8) and the same below.  FLATQUANT_KV_WG_PER_CU caps the
+    // number further (0: as many as fit).
     const int cap = env_int("FLATQUANT_KV_WG_PER_CU", 1);
     if (cap > 0 && cap < occ) occ = cap;
     const int64_t nblk = (a.T + KV_TOK - 1) / KV_TOK;
