@@ -274,7 +274,9 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
             if (NUNIT % 64 == 0 || q < NUNIT) {
                 const int r = q / QB, ch = q % QB;
                 const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * KV_STAGE_PITCH + 16 * ch);
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.out_codes + g0 * (KV_D * QB / 8)) + (size_t)group_ofs(blk, r) * QB + ch);
+                u32x4* dst = reinterpret_cast<u32x4*>(p.out_codes + g0 * (KV_D * QB / 8)) + (size_t)group_ofs(blk, r) * QB + ch;
+                if constexpr (QB == 3) *dst = v;   // 48-byte rows end inside a 32-byte sector: leave them to L2 to merge with their neighbours
+                else __builtin_nontemporal_store(v, dst);
             }
         }
         if (h == 0) {   // both half-waves hold the same step and zero point: one of them stores
