@@ -19,8 +19,11 @@ What each function follows
   b = 2 and 3 in the appendix tables on key / value bit widths), group =
   head_dim, on the unsigned grid {0 .. 2^b - 1} of Sec. 2.1.  The paper
   prints no formula for the asymmetric grid; the textbook min/max affine grid
-  that contains zero is used.  PARITY UNPINNED by the paper for this function;
-  it is pinned by invariants in the CPU tests.
+  that contains zero is used, with the clipping threshold of Sec. 3.1
+  multiplying both ends of the range.  The paper prints no value to compare
+  with (PARITY UNPINNED by the paper); this reading is pinned in the CPU tests
+  by hand-worked groups with and without clipping, an exact-rational scaling
+  law, brute force over the levels and invariants.
 * pack_bits / unpack_bits      : storage of b-bit codes (not fixed by the
   paper): code k of a group sits at bits [b k, b k + b) of the group's bytes
   read as one little-endian integer; for b = 4 this is pack_nibbles.

@@ -299,6 +299,133 @@ def test_kv_hand_worked():
     assert float(res["scales"][0, 0]) == float(g["kv_asym.scale"]) and int(res["zeros"][0, 0]) == int(g["kv_asym.zero"])
 
 
+@pytest.mark.parametrize("case", ["kv_clip_half", "kv_clip_half_3bit", "kv_clip_095", "kv_clip_075"])
+def test_kv_hand_worked_with_clipping(case):
+    """Sec. 3.1 "Learnable Clipping Thresholds" on the group-wise asymmetric grid of Sec. 4.1: the threshold scales both
+    ends of the range.  Values derived on paper (tests/golden/hand_worked.txt), none of them by the oracle."""
+    g = read_golden("hand_worked.txt")
+    yv = [float(v) for v in g[case + ".y"].split()]
+    clip, bits = float(g[case + ".clip"]), int(g[case + ".bits"])
+    D = 8                                                    # pad the group with zeros: b-bit rows need D * b % 8 == 0
+    y = np.zeros((1, 1, D), dtype=np.float16)
+    y[0, 0, :len(yv)] = yv
+    res = fo.kv_transform_quant(y, np.eye(D, dtype=np.float16)[None], clip, bits)
+    want = [int(v) for v in g[case + ".codes"].split()]
+    assert res["q"][0, 0, :len(yv)].tolist() == want
+    assert float(res["scales"][0, 0]) == float(g[case + ".scale"])
+    assert int(res["zeros"][0, 0]) == int(g[case + ".zero"])
+    # zero inputs sit on the zero point, and the packed row holds the same codes
+    assert np.all(res["q"][0, 0, len(yv):] == int(g[case + ".zero"]))
+    assert fo.unpack_bits(res["codes"], bits, D)[0, 0, :len(yv)].tolist() == want
+
+
+def test_kv_clip_scales_both_ends_exactly():
+    """With a power-of-two threshold and power-of-two-friendly data the clipped grid is the unclipped grid of the
+    scaled range: step(alpha) = alpha * step(1), same zero point; codes = clamp(rne(y / (alpha s)) + z)."""
+    y = np.array([[[-3.0, 0.0, 4.5, 12.0, 1.0, -1.5, 6.0, 11.0]]], dtype=np.float16)
+    eye = np.eye(8, dtype=np.float16)[None]
+    full = fo.kv_transform_quant(y, eye, 1.0)
+    for alpha in (0.5, 0.25):
+        res = fo.kv_transform_quant(y, eye, alpha)
+        assert float(res["scales"][0, 0]) == alpha * float(full["scales"][0, 0])
+        assert int(res["zeros"][0, 0]) == int(full["zeros"][0, 0]) == 3
+        want = [min(15, max(0, exact_round_half_even(frac(v) / frac(alpha)) + 3)) for v in y[0, 0].tolist()]
+        assert res["q"][0, 0].tolist() == want
+
+
+def test_kv_transform_index_by_index():
+    """y[t, h, e] = sum_d kv[t, h, d] P[h, d, e], written out over every index in exact rationals, with a different
+    matrix per head (so a head permutation or a transposed P_h cannot pass), and with distinct permutation matrices."""
+    r = rng(77)
+    T, H, D = 2, 3, 4
+    kv = rand_fp16(r, (T, H, D))
+    P = rand_fp16(r, (H, D, D))
+    got = fo.kv_transform(kv, P)
+    for t in range(T):
+        for h in range(H):
+            for e in range(D):
+                acc = Fraction(0)
+                for d in range(D):
+                    acc += frac(kv[t, h, d]) * frac(P[h, d, e])
+                assert abs(Fraction(float(got[t, h, e])) - acc) <= abs(acc) * Fraction(1, 2 ** 48) + Fraction(1, 2 ** 60)
+    shared = fo.kv_transform(kv, P[1:2])
+    for t in range(T):
+        for h in range(H):
+            for e in range(D):
+                acc = sum(frac(kv[t, h, d]) * frac(P[1, d, e]) for d in range(D))
+                assert abs(Fraction(float(shared[t, h, e])) - acc) <= abs(acc) * Fraction(1, 2 ** 48) + Fraction(1, 2 ** 60)
+    # permutation matrices, a different one per head: P_h[d, perm_h[d]] = 1 sends input dim d to output dim perm_h[d]
+    perms = [[1, 2, 3, 0], [3, 2, 1, 0], [2, 0, 3, 1]]
+    Pp = np.zeros((H, D, D), dtype=np.float16)
+    for h, pm in enumerate(perms):
+        for d, e in enumerate(pm):
+            Pp[h, d, e] = 1
+    yp = fo.kv_transform(kv, Pp)
+    for h, pm in enumerate(perms):
+        for d, e in enumerate(pm):
+            assert np.array_equal(yp[:, h, e], kv[:, h, d].astype(np.float64))
+
+
+def test_kv_comparator_accepts_oracle_and_rejects_planted_mistakes():
+    kv = synth.kv_cache(T=12)
+    G = kv.T * kv.H
+    clip = 0.95
+    res = fo.kv_transform_quant(kv.k, kv.P, clip)
+    y = res["y"].reshape(G, kv.D)
+    codes, s, z = res["codes"].reshape(G, -1), res["scales"].reshape(G), res["zeros"].reshape(G).astype(np.float16)
+    rep = parity.check_kv(y, clip, codes, s, z, deq_dev=fo.dequantize(codes, s, z))
+    assert rep["band_flips"] == 0 and rep["step_differs"] == 0 and rep["zero_differs"] == 0
+    yk = y.reshape(kv.T, kv.H, kv.D)
+
+    def grid_with(mx_scale, mn_scale):
+        """A planted variant of the grid (CPU only): the two range ends scaled separately."""
+        mx = mx_scale * np.maximum(y.max(-1), 0.0)
+        mn = mn_scale * np.minimum(y.min(-1), 0.0)
+        sw = ((mx - mn) / 15).astype(np.float16)
+        zw = np.clip(np.rint(-mn / sw.astype(np.float64)), 0, 15)
+        qw = np.clip(np.rint(y / sw.astype(np.float64)[:, None]) + zw[:, None], 0, 15).astype(np.uint8)
+        return fo.pack_bits(qw, 4), sw, zw.astype(np.float16)
+
+    ok = grid_with(clip, clip)                                # the same construction with the right reading passes
+    parity.check_kv(y, clip, *ok)
+    with pytest.raises(AssertionError):                       # threshold on the upper end only
+        parity.check_kv(y, clip, *grid_with(clip, 1.0))
+    with pytest.raises(AssertionError):                       # threshold on the lower end only
+        parity.check_kv(y, clip, *grid_with(1.0, clip))
+    with pytest.raises(AssertionError):                       # no threshold at all
+        parity.check_kv(y, clip, *grid_with(1.0, 1.0))
+    with pytest.raises(AssertionError):                       # zero point off by one, codes consistent with it
+        z1 = np.where(z.astype(np.float64) < 15, z.astype(np.float64) + 1, 14).astype(np.float16)
+        q1, _, _, _, _ = fo.kv_quantize_asym(y, clip, 4, scale_fp16=s, zero=z1.astype(np.float64))
+        parity.check_kv(y, clip, fo.pack_bits(q1, 4), s, z1)
+    with pytest.raises(AssertionError):                       # zero point off by one, codes stale
+        parity.check_kv(y, clip, codes, s, z1)
+    with pytest.raises(AssertionError):                       # swapped nibbles
+        parity.check_kv(y, clip, ((codes << 4) | (codes >> 4)).astype(np.uint8), s, z)
+    with pytest.raises(AssertionError):                       # step one ulp off, codes stale (not re-derived with it)
+        s_up = (s.view(np.uint16) + 1).view(np.float16)
+        q_up, _, _, _, _ = fo.kv_quantize_asym(y, clip, 4, scale_fp16=s_up, zero=z.astype(np.float64))
+        assert np.any(q_up != res["q"].reshape(G, kv.D))      # the case does separate the two
+        parity.check_kv(y, clip, codes, s_up, z)
+    with pytest.raises(AssertionError):                       # two heads' results exchanged
+        perm = np.arange(kv.H); perm[[0, 1]] = [1, 0]
+        cs = res["codes"][:, perm].reshape(G, -1); ss = res["scales"][:, perm].reshape(G); zs = res["zeros"][:, perm].reshape(G)
+        parity.check_kv(y, clip, cs, ss, zs.astype(np.float16))
+    with pytest.raises(AssertionError):                       # the transposed head matrix
+        wrong = fo.kv_transform_quant(kv.k, np.ascontiguousarray(kv.P.transpose(0, 2, 1)), clip)
+        parity.check_kv(y, clip, wrong["codes"].reshape(G, -1), wrong["scales"].reshape(G), wrong["zeros"].reshape(G).astype(np.float16))
+    with pytest.raises(AssertionError):                       # truncation instead of rounding
+        qt = np.clip(np.trunc(res["u"].reshape(G, kv.D)) + z.astype(np.float64)[:, None], 0, 15).astype(np.uint8)
+        parity.check_kv(y, clip, fo.pack_bits(qt, 4), s, z)
+    # an adjacent fp16 step with codes re-derived from it is legitimate
+    q_ok, _, _, _, _ = fo.kv_quantize_asym(y, clip, 4, scale_fp16=s_up, zero=z.astype(np.float64))
+    zf_up = -clip * np.minimum(y.min(-1), 0.0) / s_up.astype(np.float64)
+    same_z = np.clip(np.rint(zf_up), 0, 15) == z.astype(np.float64)
+    rep = parity.check_kv(y[same_z], clip, fo.pack_bits(q_ok, 4)[same_z], s_up[same_z], z[same_z])
+    assert rep["step_differs"] == int(same_z.sum())
+    del yk
+
+
 def test_kv_invariants():
     kv = synth.kv_cache(T=24)
     eye = np.broadcast_to(np.eye(kv.D, dtype=np.float16), (kv.H, kv.D, kv.D))
