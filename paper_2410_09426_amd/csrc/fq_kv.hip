@@ -22,38 +22,9 @@
 // min/max need one cross-half exchange.  Packed rows are staged per wave in LDS
 // and leave with 16-byte stores.
 #include "fq_internal.h"
+#include "fq_device.h"
 
 namespace fq {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-// Eight fp16 values of one column of a row-major fp16 matrix in LDS, rows r0..r0+3 and r0+gap..r0+gap+3, for every
-// lane: two transposing LDS reads (ds_read_b64_tr_b16).  Within each block of 16 lanes, lane s supplies the address
-// of a 64-bit chunk and lane i receives element i%4 of the chunks supplied by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4
-// (measured on gfx950).  So lane s points at row r0 + s/4, columns col0 + 4(s%4).., and lane i ends up with rows
-// r0..r0+3 of column col0 + i.  `lane16` = lane % 16; `col0` is the first column of the lane's 16-lane block.
-typedef short short4v __attribute__((ext_vector_type(4)));
-// Here lane s points at column chunk swap12(s % 4) instead of s % 4 (chunks of 4 columns, 1 and 2 exchanged), so lane i
-// ends up with column col0 + 4 swap12(i / 4) + i % 4.
-__device__ __forceinline__ half8 lds_column8(const _Float16* m, int pitch, int r0, int gap, int col0, int lane16) {
-    const int ch = lane16 & 3, chs = ((ch & 1) << 1) | (ch >> 1);
-    const _Float16* a0 = m + (r0 + (lane16 >> 2)) * pitch + col0 + 4 * chs;
-    typedef short4v __attribute__((address_space(3))) * lds_ptr;
-    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(a0));
-    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(a0 + gap * pitch));
-    typedef short short8v __attribute__((ext_vector_type(8)));
-    const short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-    return __builtin_bit_cast(half8, v);
-}
-
-// (a << sh) + b in one instruction (the compiler otherwise re-associates the nibble chain into more operations)
-__device__ __forceinline__ uint32_t lshl_add(uint32_t a, int sh, uint32_t b) {
-    uint32_t r;
-    asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "n"(sh), "v"(b));
-    return r;
-}
 
 constexpr int KV_D = 128;
 constexpr int KV_WAVES = 4;
@@ -152,7 +123,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
             const int ln = e & 63, kbl = (e >> 6) % (KV_KB / KV_PASSES), mt = (e >> 6) / (KV_KB / KV_PASSES);
             const int cc = ln & 31, hh = ln >> 5;
             // e % 64 is the lane, so whole 16-lane blocks cooperate in the transposing reads
-            const half8 f = lds_column8(Pflat, KV_D + 8, 16 * kbl + 8 * hh, 4, 32 * mt + (cc & 16), ln & 15);
+            const half8 f = lds_column8<true>(Pflat, KV_D + 8, 16 * kbl + 8 * hh, 4, 32 * mt + (cc & 16), ln & 15);
             *reinterpret_cast<half8*>(&Pf[(mt * KV_KB + pass * (KV_KB / KV_PASSES) + kbl) * 64 + ln]) = f;
         }
     }

@@ -1,0 +1,278 @@
+// Fused transform + INT4 kernel for 64-wide rows (n2 = 64, n1 = 32 or 64): one wavefront per token, nothing shared
+// between tokens after the prologue.
+//
+// Same method as the other activation kernels (Eq. (2) left factor, fused as in Sec. 3.3: Z = X~ P2, Y^T = Z^T P1 with Z
+// split into fp16 hi + lo, per-token absmax, clip, round, pack), different data movement:
+//   * A wave owns a whole token (both 32-column slabs): its rows are fetched with coalesced 16-byte loads (8 whole
+//     128-byte rows per instruction), written to a tile of LDS that belongs to this wave alone, and read back as
+//     MFMA A operands with 16-byte reads.  No workgroup barrier per token: LDS executes a wave's instructions in
+//     order, and the wave waits for its own loads only.  (Fetching the operands straight from global memory in MFMA
+//     layout, 32 bytes out of 32 different rows per instruction, was tried first: the vector memory path then needs
+//     four times as many cycles per instruction and the rows arrive 2 us later.)
+//   * The absmax is a wave reduction, and the codes of a row of X~ (64 channels = 32 bytes) sit in one lane pair
+//     (c, 0), (c, 1): one cross-half exchange (v_permlane32_swap) gives each lane 16 contiguous bytes, stored from
+//     registers: a wave's store covers 1 KB of consecutive bytes.
+//   * Rounding: y / s lands in the top nibble of a 16-bit field through v_cvt_pknorm_i16_f32 (clamp to [-1, 1], times
+//     32767, round to nearest): with r = (4096 (u + 0.5) - 0.5) / 32767 the field's top nibble is
+//     clamp(rne(u), -8, 7) in two's complement, so clamping, rounding and half of the packing are one fma plus half an
+//     instruction per value.  The thresholds between codes move by less than 2e-6 code units (fp32 rounding of the
+//     two constants and of the fma), exact ties excepted.
+//   * P1 and P2 are requested before the token rows (a CU's vector memory path returns data in request order), staged
+//     in LDS once per workgroup and turned into MFMA fragments while the token rows are still on their way from HBM.
+#include "fq_internal.h"
+#include "fq_device.h"
+
+namespace fq {
+
+typedef short short2v __attribute__((ext_vector_type(2)));
+
+// TPW waves (= tokens in flight) per workgroup.  LOOP: persistent workgroups, a wave takes tokens t, t + G, ...
+// (G = all waves of the grid) with the next token's rows requested before the current one is worked on.
+template <int A, int TPW, bool LOOP, int STAGGER = 0>
+__global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) void tq_wave_kernel(const _Float16* __restrict__ aP2, const _Float16* __restrict__ aP1, const _Float16* __restrict__ ax, int64_t ax_stride, int64_t aT,
+                    const float* __restrict__ clip, uint8_t* __restrict__ aout_codes, _Float16* __restrict__ aout_scales, int aclip_mode) {
+    // (plain arguments in the order they are needed, so that the first ones can be delivered in registers at wave start)
+    struct { const _Float16* x; const _Float16* P1; const _Float16* P2; uint8_t* out_codes; _Float16* out_scales; int64_t x_stride, T; int clip_mode; } p =
+        {ax, aP1, aP2, aout_codes, aout_scales, ax_stride, aT, aclip_mode};
+    constexpr int N1 = 32 * A, N2 = 64, KB1 = 2 * A, KB2 = 4, NT = 64 * TPW;
+    constexpr int CH2 = N2 * N2 / 8, CH1 = N1 * N1 / 8, CH = CH1 + CH2;   // 16-byte chunks of P2, P1
+    constexpr int NLD = (CH + NT - 1) / NT;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    _Float16* P2flat = reinterpret_cast<_Float16*>(smem);
+    _Float16* P1flat = P2flat + N2 * N2;
+    constexpr int TILE_BYTES = N1 * N2 * 2;          // one token, rows unpadded (the loads write whole 1 KB runs)
+
+    const int tid = threadIdx.x;
+    const int l = tid & 63, c = l & 31, h = l >> 5;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    unsigned char* tile = smem + CH * 16 + wv * TILE_BYTES;
+    const int64_t G = (int64_t)gridDim.x * TPW;
+    int64_t t = (int64_t)blockIdx.x * TPW + wv;
+    if (t >= p.T) t = p.T - 1;                       // spare waves of the last workgroup redo token T - 1: same bytes stored twice
+
+    // ---- requests: the transforms first, then this wave's first token
+    u32x4 pv[NLD];
+#pragma unroll
+    for (int k = 0; k < NLD; ++k) {
+        int idx = tid + k * NT;
+        if (idx >= CH) idx = CH - 1;
+        const u32x4* src = idx < CH2 ? reinterpret_cast<const u32x4*>(p.P2) + idx : reinterpret_cast<const u32x4*>(p.P1) + (idx - CH2);
+        pv[k] = *src;
+    }
+    // Token rows: load k brings rows 8 k .. 8 k + 7 (lane i: 16 bytes; every byte of the token is read once, whole
+    // 128-byte lines per 8 lanes), and is written to LDS at tile + 1024 k + 16 i.  Slot j of row r holds the row's chunk
+    // j ^ ((r >> 1) & 7): with that swizzle the 16-byte operand reads of 32 consecutive rows (same chunk) spread over all
+    // banks although the pitch is a multiple of the bank width.
+    constexpr int NROW = N1 / 8;
+    const int ld_ofs = (l >> 3) * (N2 * 2) + 16 * ((l & 7) ^ ((l >> 4) & 3));   // rows 8 k + l / 8: (r >> 1) & 7 = 4 (k & 1) + (l >> 4)
+    auto issue = [&](int64_t tok, u32x4 (&pre)[NROW]) {
+        const unsigned char* row = reinterpret_cast<const unsigned char*>(p.x + tok * p.x_stride);
+#pragma unroll
+        for (int k = 0; k < NROW; ++k)
+            pre[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + k * (8 * N2 * 2) + (ld_ofs ^ (64 * (k & 1)))));
+    };
+    auto commit = [&](const u32x4 (&pre)[NROW]) {
+#pragma unroll
+        for (int k = 0; k < NROW; ++k) *reinterpret_cast<u32x4*>(tile + k * 1024 + 16 * l) = pre[k];
+    };
+    // lane (c, h), row tile It, K block kb: X~[32 It + c][16 kb + 8 h .. + 7] = chunk 2 kb + h of row 32 It + c
+    const int rd_ofs = c * (N2 * 2);
+    const int rd_swz = (c >> 1) & 7;
+    auto fetch = [&](u32x4 (&a)[A][KB2]) {
+#pragma unroll
+        for (int It = 0; It < A; ++It)
+#pragma unroll
+            for (int kb = 0; kb < KB2; ++kb)
+                a[It][kb] = *reinterpret_cast<const u32x4*>(tile + It * (32 * N2 * 2) + rd_ofs + 16 * ((2 * kb + h) ^ rd_swz));
+    };
+    u32x4 pre[NROW];
+    // A CU's vector memory path takes requests and returns data in order, whatever wave they come from: the barrier
+    // puts every wave's share of P1 / P2 (L2) in front of every wave's token rows (HBM).  Without it the last wave's
+    // share queues behind the other waves' rows and the fragments are ready no sooner than the rows.
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (STAGGER > 0) {
+        // A CU's vector memory path takes requests and returns data in order.  Left alone, the waves of a workgroup
+        // interleave their requests and every token is complete only when nearly all of them are; spaced by about the
+        // time the path needs for one token's requests, the tokens arrive one after the other and the first waves
+        // start on theirs while the rest is still on its way.
+        for (int i = 0; i < wv; ++i) __builtin_amdgcn_s_sleep(STAGGER);
+    }
+    issue(t, pre);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- transforms -> LDS -> fragments (while the token rows are in flight)
+#pragma unroll
+    for (int k = 0; k < NLD; ++k) {
+        const int idx = tid + k * NT;
+        if (CH % NT == 0 || idx < CH) reinterpret_cast<u32x4*>(smem)[idx] = pv[k];   // (the compiler's wait covers the older P loads only)
+    }
+    __syncthreads();
+    // B operand of the first contraction: lane (c, h) holds P2[16 kb + 8 h + s][32 q + c], s = 0..7
+    half8 p2f[2][KB2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int kb = 0; kb < KB2; ++kb) p2f[q][kb] = lds_column8(P2flat, N2, 16 * kb + 8 * h, 4, 32 * q + (c & 16), l & 15);
+    // B operand of the second contraction, gathered with the K permutation of the accumulator layout that feeds it:
+    // K block kk, slot s, half-wave h  <->  i = 32 (kk / 2) + 8 (2 (kk % 2) + s / 4) + 4 h + s % 4
+    half8 p1f[A][KB1];
+#pragma unroll
+    for (int It = 0; It < A; ++It)
+#pragma unroll
+        for (int kk = 0; kk < KB1; ++kk)
+            p1f[It][kk] = lds_column8(P1flat, N1, 32 * (kk >> 1) + 16 * (kk & 1) + 4 * h, 8, 32 * It + (c & 16), l & 15);
+
+    // ---- one token: rows in `xr` -> codes and step in global memory
+    auto token = [&](int64_t tok, const u32x4 (&xr)[A][KB2]) {
+        const float clipv = clip[p.clip_mode ? tok : 0];   // wave-uniform address: a scalar load
+        f32x16 acc2[2][A];
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int It = 0; It < A; ++It)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc2[q][It][r] = 0.0f;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            f32x16 acc1[A];
+#pragma unroll
+            for (int It = 0; It < A; ++It)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc1[It][r] = 0.0f;
+            // Z[:, slab q] = X~ P2[:, slab q]
+#pragma unroll
+            for (int kb = 0; kb < KB2; ++kb)
+#pragma unroll
+                for (int It = 0; It < A; ++It)
+                    acc1[It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, xr[It][kb]), p2f[q][kb], acc1[It], 0, 0, 0);
+            // Y^T[slab q, :] += Z^T[slab q, K block] P1[K block, :], hi and lo parts of Z
+#pragma unroll
+            for (int It = 0; It < A; ++It)
+#pragma unroll
+                for (int kq = 0; kq < 2; ++kq) {
+                    const int kk = 2 * It + kq;
+                    half8 zh, zl;
+                    split_hi_lo(acc1[It], 8 * kq, zh, zl);
+#pragma unroll
+                    for (int I2 = 0; I2 < A; ++I2) acc2[q][I2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh, p1f[I2][kk], acc2[q][I2], 0, 0, 0);
+#pragma unroll
+                    for (int I2 = 0; I2 < A; ++I2) acc2[q][I2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zl, p1f[I2][kk], acc2[q][I2], 0, 0, 0);
+                }
+        }
+        // ---- per-token absmax: in-lane, then over the wave
+        float m = 0.0f;
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int It = 0; It < A; ++It)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(acc2[q][It][r]));
+        m = wave_max(m);
+        // ---- step = alpha * max / 7, rounded to fp16; the rounded step divides
+        const _Float16 sh = (_Float16)(clipv * m * 0.142857149f);
+        const float s = (float)sh;
+        const float inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;   // 1 ulp: < 1e-6 code units
+        const float kmul = inv * (4096.0f / 32767.0f);
+        constexpr float kadd = 2047.5f / 32767.0f;
+        // ---- round, clamp, pack.  Lane (c, h) holds, of row ip = 32 It + c of X~, the channels 32 q + 8 g + 4 h + k
+        // in acc2[q][It][4 g + k].  Eight of them (g = 2 m, 2 m + 1) become one dword of nibbles.
+        uint8_t* out_row = p.out_codes + tok * (int64_t)(N1 * N2 / 2) + c * (N2 / 2) + 16 * h;
+#pragma unroll
+        for (int It = 0; It < A; ++It) {
+            uint32_t W[2][2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int mm = 0; mm < 2; ++mm) {
+                    uint32_t D[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float r0 = __builtin_fmaf(acc2[q][It][8 * mm + k], kmul, kadd);
+                        const float r1 = __builtin_fmaf(acc2[q][It][8 * mm + 4 + k], kmul, kadd);
+                        D[k] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pknorm_i16(r0, r1));
+                    }
+                    // bytes 1 and 3 of D[k] carry nibbles k and k + 4 on top: even nibbles -> E, odd ones -> F
+                    const uint32_t E = __builtin_amdgcn_perm(D[2], D[0], 0x07030501u);
+                    const uint32_t F = __builtin_amdgcn_perm(D[3], D[1], 0x07030501u);
+                    W[q][mm] = (F & 0xF0F0F0F0u) | ((E >> 4) & 0x0F0F0F0Fu);
+                }
+            // lane pair exchange: afterwards lane (c, h) holds slab q = h of both lanes: P = half-wave 0's, Q = half-wave 1's
+            u32x4 o;
+#pragma unroll
+            for (int mm = 0; mm < 2; ++mm) {
+                const auto sw = __builtin_amdgcn_permlane32_swap(W[0][mm], W[1][mm], false, false);
+                const uint32_t P = sw[0], Q = sw[1];
+                o[2 * mm] = __builtin_amdgcn_perm(Q, P, 0x05040100u);       // group g = 2 mm: 2 bytes of P, 2 bytes of Q
+                o[2 * mm + 1] = __builtin_amdgcn_perm(Q, P, 0x07060302u);   // group g = 2 mm + 1
+            }
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(out_row + It * (32 * N2 / 2)));
+        }
+        p.out_scales[tok] = sh;   // every lane writes the same two bytes: cheaper than a branch around the store
+    };
+
+    __builtin_amdgcn_sched_barrier(0);   // the fragment reads are issued before anything waits for the token rows
+    // The tile belongs to this wave alone and LDS executes a wave's instructions in order: no barrier between writing
+    // the rows and reading them back as operands, nor before the next token's rows overwrite them.
+    u32x4 xr[A][KB2];
+    if constexpr (!LOOP) {
+        commit(pre);
+        fetch(xr);
+        token(t, xr);
+    } else {
+        // Past the end a wave re-reads the last token's rows: an unconditional request keeps the compiler's count of
+        // outstanding loads exact, so the wait before a token covers its rows only.
+        while (true) {
+            commit(pre);
+            fetch(xr);
+            const int64_t tn = t + G;
+            issue(tn < p.T ? tn : p.T - 1, pre);
+            __builtin_amdgcn_sched_barrier(0);
+            token(t, xr);
+            t = tn;
+            if (t >= p.T) break;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+bool tq_wave_applicable(const TqDev& d) {
+    if (d.n2 != 64 || (d.n1 != 32 && d.n1 != 64) || !d.P1 || !d.P2 || !d.vec8 || !d.out_vec16) return false;
+    if ((reinterpret_cast<uintptr_t>(d.P1) | reinterpret_cast<uintptr_t>(d.P2)) & 15) return false;
+    return d.T >= 1 && d.T <= 0x7fffffff;
+}
+
+using WaveFn = void (*)(const _Float16*, const _Float16*, const _Float16*, int64_t, int64_t, const float*, uint8_t*, _Float16*, int);
+template <int TPW>
+static WaveFn wave_fn(int A, bool loop) {
+    if (A == 1) return loop ? &tq_wave_kernel<1, TPW, true> : &tq_wave_kernel<1, TPW, false>;
+    return loop ? &tq_wave_kernel<2, TPW, true> : &tq_wave_kernel<2, TPW, false>;
+}
+
+// tpw: 2, 4 or 8 waves per workgroup; loop: persistent workgroups (grid = as many as are resident), else one token per wave
+hipError_t tq_wave_launch(const TqDev& d, hipStream_t stream, int tpw, bool loop) {
+    const int A = d.n1 / 32;
+    WaveFn fn = tpw == 2 ? wave_fn<2>(A, loop) : tpw == 4 ? wave_fn<4>(A, loop) : wave_fn<8>(A, loop);
+    if (tpw != 2 && tpw != 4) tpw = 8;
+    const int lds = (64 * 64 + d.n1 * d.n1) * 2 + tpw * d.n1 * 64 * 2;   // P2, P1, one tile per wave
+    static OccCache occ_cache[2][3][2];   // per variant and device; the first call also raises the kernel's LDS limit
+    int occ = 0;
+    {
+        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(fn), 64 * tpw, lds, occ_cache[A - 1][tpw == 2 ? 0 : tpw == 4 ? 1 : 2][loop], occ);
+        if (e != hipSuccess) return e;
+    }
+    int64_t grid = (d.T + tpw - 1) / tpw;
+    if (loop) {
+        // every wave gets the same number of tokens (+-1)
+        const int64_t resident = (int64_t)cu_count() * occ;
+        const int64_t rounds = (grid + resident - 1) / resident;
+        grid = (grid + rounds - 1) / rounds;
+    }
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(64 * tpw), lds, stream, d.P2, d.P1, d.x, d.x_stride, d.T, d.clip, d.out_codes, d.out_scales, d.clip_mode);
+    return hipGetLastError();
+}
+
+}  // namespace fq

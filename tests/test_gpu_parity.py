@@ -89,6 +89,26 @@ def test_every_kernel_flavour(tuning, mode):
         check_case(synth.generic(195 + int(mode) + T, T, n1, 64), with_dequant=False, label=f"mode {mode}")
 
 
+@pytest.mark.parametrize("mode", ["5", "6"])
+@pytest.mark.parametrize("tpw", ["2", "4", "8"])
+def test_wave_per_token_kernel(tuning, mode, tpw):
+    # 5: one token per wave, no loop; 6: persistent loop.  tpw = waves (tokens in flight) per workgroup
+    tuning("FLATQUANT_MODE", mode)
+    tuning("FLATQUANT_WAVE_TPW", tpw)
+    c = synth.prefill_7b(2048 + 37)
+    check_case(c, rows=subset_rows(c.T, 260, 21, must=(0, 1, 7, 8, 2047, 2048, 2084)), with_dequant=False, label=f"wave kernel {mode}/{tpw}")
+    c = synth.generic(300 + int(mode), 4099, 32, 64)
+    check_case(c, rows=subset_rows(c.T, 200, 22, must=(0, 4095, 4096, 4098)), with_dequant=False, label=f"wave kernel {mode}/{tpw}")
+    for T in (1, 3, 9, 17):   # fewer tokens than a workgroup has waves, and a ragged last workgroup
+        check_case(synth.generic(310 + T, T, 64, 64), with_dequant=False, label=f"wave kernel {mode}/{tpw} T={T}")
+    # a zero row, a small row, large magnitudes
+    c = synth.generic(333, 40, 64, 64)
+    c.x[3] = 0
+    c.x[5] = (c.x[5].astype(np.float32) * 2.0 ** -4).astype(np.float16)
+    c.x[7] = (np.sign(c.x[7].astype(np.float32)) * 900).astype(np.float16)
+    check_case(c, with_dequant=False, label=f"wave kernel {mode}/{tpw} edge rows")
+
+
 def test_mid_length_stream_uses_multi_token_workgroups():
     # more tokens than resident single-token workgroups, fewer than the wave-per-token loop wants; T % 4 = 3
     c = synth.prefill_7b(4096 + 3)
