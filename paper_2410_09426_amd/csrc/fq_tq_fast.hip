@@ -780,6 +780,7 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     {   // modes 5 / 6: the wave-per-token kernel without LDS traffic per token, one shot / persistent loop
         const int m = env_int("FLATQUANT_MODE", -1);
         if ((m == 5 || m == 6) && tq_wave_applicable(d)) return tq_wave_launch(d, stream, env_int("FLATQUANT_WAVE_TPW", 8), m == 6);
+        if (m == 7 && tq_quad_applicable(d)) return tq_quad_launch(d, stream, env_int("FLATQUANT_QUAD_NTOK", 4));
     }
     int mode = (A <= 2) ? 2 : 0;
     if (A == 2 && B >= 7) mode = 0;   // two row tiles x 224 or 256 columns: the plain loop is 4 - 25 % faster (64 x 256, T = 16384: 226 against 290 us)

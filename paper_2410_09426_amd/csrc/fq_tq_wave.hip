@@ -128,48 +128,70 @@ __global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) v
     // ---- one token: rows in `xr` -> codes and step in global memory
     auto token = [&](int64_t tok, const u32x4 (&xr)[A][KB2]) {
         const float clipv = clip[p.clip_mode ? tok : 0];   // wave-uniform address: a scalar load
-        f32x16 acc2[2][A];
+        // The schedule is written out: the wave has nobody to hide its own latencies behind but itself (and one other
+        // wave of its SIMD), so the vector-ALU work of one slab runs in the shadow of the other slab's MFMAs.
+        //   S1  Z0 = X~ P2[:, slab 0]                         (MFMA)
+        //   S2  Z1 = X~ P2[:, slab 1]                         (MFMA)   |  split Z0 into hi + lo     (VALU)
+        //   S3  Y^T[slab 0] = Z0^T P1, hi and lo             (MFMA)   |  split Z1                   (VALU)
+        //   S4  Y^T[slab 1] = Z1^T P1                         (MFMA)   |  absmax over slab 0         (VALU)
+        //   S5  absmax over slab 1, step, round, pack, store  (VALU)
+        // A unit is one K block (16 rows of X~) of the second contraction: kk = 2 It + kq.
+        constexpr int NU = 2 * A;
+        f32x16 acc1[2][A], acc2[2][A];
 #pragma unroll
         for (int q = 0; q < 2; ++q)
 #pragma unroll
             for (int It = 0; It < A; ++It)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc2[q][It][r] = 0.0f;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            f32x16 acc1[A];
-#pragma unroll
-            for (int It = 0; It < A; ++It)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc1[It][r] = 0.0f;
-            // Z[:, slab q] = X~ P2[:, slab q]
-#pragma unroll
-            for (int kb = 0; kb < KB2; ++kb)
-#pragma unroll
-                for (int It = 0; It < A; ++It)
-                    acc1[It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, xr[It][kb]), p2f[q][kb], acc1[It], 0, 0, 0);
-            // Y^T[slab q, :] += Z^T[slab q, K block] P1[K block, :], hi and lo parts of Z
+                for (int r = 0; r < 16; ++r) { acc1[q][It][r] = 0.0f; acc2[q][It][r] = 0.0f; }
+        half8 zh[2][NU], zl[2][NU];
+        auto first = [&](int q, int kb) {
 #pragma unroll
             for (int It = 0; It < A; ++It)
+                acc1[q][It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, xr[It][kb]), p2f[q][kb], acc1[q][It], 0, 0, 0);
+        };
+        auto second = [&](int q, int u) {
 #pragma unroll
-                for (int kq = 0; kq < 2; ++kq) {
-                    const int kk = 2 * It + kq;
-                    half8 zh, zl;
-                    split_hi_lo(acc1[It], 8 * kq, zh, zl);
+            for (int I2 = 0; I2 < A; ++I2) acc2[q][I2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh[q][u], p1f[I2][u], acc2[q][I2], 0, 0, 0);
 #pragma unroll
-                    for (int I2 = 0; I2 < A; ++I2) acc2[q][I2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh, p1f[I2][kk], acc2[q][I2], 0, 0, 0);
-#pragma unroll
-                    for (int I2 = 0; I2 < A; ++I2) acc2[q][I2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zl, p1f[I2][kk], acc2[q][I2], 0, 0, 0);
-                }
-        }
-        // ---- per-token absmax: in-lane, then over the wave
+            for (int I2 = 0; I2 < A; ++I2) acc2[q][I2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zl[q][u], p1f[I2][u], acc2[q][I2], 0, 0, 0);
+        };
         float m = 0.0f;
+        auto absmax_part = [&](int q, int u) {   // a quarter (A = 2) or half (A = 1) of slab q's accumulators
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
+            for (int j = 0; j < 16 * A / NU; j += 2) {
+                const int e = u * (16 * A / NU) + j;
+                m = __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(acc2[q][e / 16][e % 16])), __builtin_fabsf(acc2[q][e / 16][e % 16 + 1]));
+            }
+        };
+        // S1
 #pragma unroll
-            for (int It = 0; It < A; ++It)
+        for (int kb = 0; kb < KB2; ++kb) first(0, kb);
+        __builtin_amdgcn_sched_barrier(0);
+        // S2: KB2 = 4 MFMA groups against NU split units
 #pragma unroll
-                for (int r = 0; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(acc2[q][It][r]));
+        for (int g = 0; g < 4; ++g) {
+            first(1, g);
+            if (NU == 4 || g % 2 == 0) split_hi_lo(acc1[0][(NU == 4 ? g : g / 2) / 2], 8 * ((NU == 4 ? g : g / 2) % 2), zh[0][NU == 4 ? g : g / 2], zl[0][NU == 4 ? g : g / 2]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // S3
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            second(0, u);
+            split_hi_lo(acc1[1][u / 2], 8 * (u % 2), zh[1][u], zl[1][u]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // S4
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            second(1, u);
+            absmax_part(0, u);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // S5
+#pragma unroll
+        for (int u = 0; u < NU; ++u) absmax_part(1, u);
         m = wave_max(m);
         // ---- step = alpha * max / 7, rounded to fp16; the rounded step divides
         const _Float16 sh = (_Float16)(clipv * m * 0.142857149f);
