@@ -8,7 +8,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libflatquant.so")
-SOURCES = ["fq_api.hip", "fq_transform_quant.hip", "fq_tq_fast.hip", "fq_tq_wave.hip", "fq_tq_quad.hip", "fq_kv.hip", "fq_dequant.hip", "fq_probe.hip", "fq_gemm.hip", "fq_gemm_mx.hip"]
+SOURCES = ["fq_api.hip", "fq_transform_quant.hip", "fq_tq_fast.hip", "fq_tq_wave.hip", "fq_kv.hip", "fq_dequant.hip", "fq_probe.hip", "fq_gemm.hip", "fq_gemm_mx.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          # keep hipcc from forming packed-fp32 VALU ops from scalar float code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -25,8 +25,7 @@ def hipcc() -> str:
 # the compiler quiets every operand first (one extra instruction per element).  Inputs are finite by contract.
 # The wave-per-token kernel takes plain arguments in the order it needs them; the first 14 dwords are delivered in
 # registers at wave start (kernel-argument preloading), which takes a scalar-memory round trip off the front of every wave.
-FILE_FLAGS = {"fq_kv.hip": ["-fno-honor-nans"], "fq_tq_wave.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=16"],
-              "fq_tq_quad.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=16"]}
+FILE_FLAGS = {"fq_kv.hip": ["-fno-honor-nans"], "fq_tq_wave.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=16"]}
 
 
 def build(verbose: bool = True, extra_flags=()) -> str:

@@ -51,9 +51,6 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream);
 // One wavefront per token, token rows straight from global memory into MFMA operands (fq_tq_wave.hip; n2 = 64).
 bool tq_wave_applicable(const TqDev& d);
 hipError_t tq_wave_launch(const TqDev& d, hipStream_t stream, int tpw, bool loop);
-// Four wavefronts per token, tokens of a workgroup one after the other (fq_tq_quad.hip; 64 x 64).
-bool tq_quad_applicable(const TqDev& d);
-hipError_t tq_quad_launch(const TqDev& d, hipStream_t stream, int ntok);
 // MXFP4 output variant of the specialised kernels (d.out_scales points at the u8 [T, n/32] shared exponents).
 bool tq_mx_applicable(const TqDev& d);
 hipError_t tq_mx_launch(const TqDev& d, hipStream_t stream);

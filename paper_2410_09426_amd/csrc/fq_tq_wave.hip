@@ -28,7 +28,7 @@ typedef short short2v __attribute__((ext_vector_type(2)));
 
 // TPW waves (= tokens in flight) per workgroup.  LOOP: persistent workgroups, a wave takes tokens t, t + G, ...
 // (G = all waves of the grid) with the next token's rows requested before the current one is worked on.
-template <int A, int TPW, bool LOOP, int STAGGER = 0>
+template <int A, int TPW, bool LOOP>
 __global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) void tq_wave_kernel(const _Float16* __restrict__ aP2, const _Float16* __restrict__ aP1, const _Float16* __restrict__ ax, int64_t ax_stride, int64_t aT,
                     const float* __restrict__ clip, uint8_t* __restrict__ aout_codes, _Float16* __restrict__ aout_scales, int aclip_mode) {
     // (plain arguments in the order they are needed, so that the first ones can be delivered in registers at wave start)
@@ -93,13 +93,6 @@ __global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) v
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (STAGGER > 0) {
-        // A CU's vector memory path takes requests and returns data in order.  Left alone, the waves of a workgroup
-        // interleave their requests and every token is complete only when nearly all of them are; spaced by about the
-        // time the path needs for one token's requests, the tokens arrive one after the other and the first waves
-        // start on theirs while the rest is still on its way.
-        for (int i = 0; i < wv; ++i) __builtin_amdgcn_s_sleep(STAGGER);
-    }
     issue(t, pre);
     __builtin_amdgcn_sched_barrier(0);
 

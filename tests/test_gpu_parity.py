@@ -109,31 +109,23 @@ def test_wave_per_token_kernel(tuning, mode, tpw):
     check_case(c, with_dequant=False, label=f"wave kernel {mode}/{tpw} edge rows")
 
 
-@pytest.mark.parametrize("ntok", ["1", "2", "4", "8"])
-def test_four_waves_per_token_kernel(tuning, ntok):
-    # mode 7: a token split over four waves; ntok = tokens a workgroup takes one after the other
-    tuning("FLATQUANT_MODE", "7")
-    tuning("FLATQUANT_QUAD_NTOK", ntok)
-    c = synth.prefill_7b(2048 + 37)
-    check_case(c, rows=subset_rows(c.T, 260, 31, must=(0, 1, 3, 4, 7, 8, 2047, 2048, 2084)), with_dequant=False, label=f"quad kernel ntok {ntok}")
-    for T in (1, 3, 5, 9, 17):   # fewer tokens than a workgroup takes, ragged last workgroup
-        check_case(synth.generic(410 + T, T, 64, 64), with_dequant=False, label=f"quad kernel ntok {ntok} T={T}")
-    c = synth.generic(433, 40, 64, 64, clip_mode=0)   # a zero row, a small row, large magnitudes, scalar clipping threshold
-    c.x[3] = 0
-    c.x[5] = (c.x[5].astype(np.float32) * 2.0 ** -4).astype(np.float16)
-    c.x[7] = (np.sign(c.x[7].astype(np.float32)) * 900).astype(np.float16)
-    check_case(c, with_dequant=False, label=f"quad kernel ntok {ntok} edge rows")
-
-
-def test_mid_length_stream_uses_multi_token_workgroups():
-    # more tokens than resident single-token workgroups, fewer than the wave-per-token loop wants; T % 4 = 3
+@pytest.mark.parametrize("mode", [None, "4"])
+def test_mid_length_stream(tuning, mode):
+    # more tokens than are resident at once; T % 4 = 3.  Default: the wave-per-token kernel, workgroups handed out by the
+    # hardware; mode 4: four single-wave tokens per workgroup of the slab kernels
+    if mode is not None:
+        tuning("FLATQUANT_MODE", mode)
     c = synth.prefill_7b(4096 + 3)
-    check_case(c, rows=subset_rows(c.T, 200, 14, must=(0, 3, 4, 4095, 4096, 4097, 4098)), with_dequant=False, label="2048 < T < 32768")
+    check_case(c, rows=subset_rows(c.T, 200, 14, must=(0, 3, 4, 4095, 4096, 4097, 4098)), with_dequant=False, label=f"2048 < T < 32768, mode {mode}")
 
 
-def test_long_stream_uses_wave_per_token_path():
-    c = synth.prefill_7b(32768 + 5)
-    check_case(c, rows=subset_rows(c.T, 200, 13, must=(0, 32767, 32768)), with_dequant=False, label="T >= 32768")
+@pytest.mark.parametrize("mode,T", [(None, 49152 + 5), ("1", 32768 + 5)])
+def test_long_stream(tuning, mode, T):
+    # default: persistent wave-per-token workgroups from T = 49152 on; mode 1: two slabs per wave in a persistent loop
+    if mode is not None:
+        tuning("FLATQUANT_MODE", mode)
+    c = synth.prefill_7b(T)
+    check_case(c, rows=subset_rows(c.T, 200, 13, must=(0, 1, 2047, 2048, 32767, 32768, T - 2)), with_dequant=False, label=f"long stream, mode {mode}")
 
 
 def test_decode_shapes():
