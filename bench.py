@@ -6,7 +6,9 @@ clip, round, pack, store) over one batch: one flatquant_transform_quant launch o
 LLaMA-2-7B prefill shape (T=2048 tokens, n=4096 = 64 x 64).  Inputs are resident in
 HBM before the timed region; launches rotate over enough distinct input/output sets
 that no launch finds its data in the 256 MB last-level cache ("cold", the headline),
-and the same is repeated on a single set ("warm").  Prints ONE JSON line.
+and the same is repeated on a single set ("warm").  One rotation counter runs through warm-up and every timed region, so
+no timed launch touches a set that any of the last ~1.2 GB of traffic touched.  The headline is the median of REPS
+regions of --steps launches each (HIP events on the launch stream).  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -22,6 +24,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA, published
+REPS = 5                       # timed regions per figure; the median is reported
 
 
 def alg_bytes_per_token(n: int, per_token_clip: bool = True) -> int:
@@ -74,6 +77,41 @@ def main() -> int:
         wall_ms = (time.perf_counter() - t0) * 1e3
         return e0.elapsed_time(e1) / steps, wall_ms / steps
 
+    class Rotation:
+        """A step function over `nsets` buffer sets whose set index keeps counting through warm-up and all timed regions."""
+        def __init__(self, launch, nsets):
+            self.launch, self.nsets, self.count = launch, nsets, 0
+
+        def __call__(self, _i=0):
+            self.launch(self.count % self.nsets)
+            self.count += 1
+
+    def median_regions(fn, steps, warmup, reps=None):
+        """Median over several regions of `steps` launches (REPS of them, 21 when a region is shorter than 200 launches: a
+        short region carries its first launch on an idle stream and its last kernel's drain, several us in all, and
+        scatters more).  The warm-up runs once, before the first region."""
+        if reps is None:
+            reps = REPS if steps >= 200 else 21
+        ms, wall = [], []
+        for r in range(reps):
+            m, w = time_region(fn, steps, warmup if r == 0 else 0)
+            ms.append(m)
+            wall.append(w)
+        return float(np.median(ms)), float(np.median(wall)), [float(v) for v in ms]
+
+    def single_launch_us(fn, n=41):
+        """One launch between two events, stream idle before it: launch latency + kernel, median of n."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        v = []
+        for _ in range(n):
+            torch.cuda.synchronize()
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            v.append(e0.elapsed_time(e1) * 1e3)
+        return float(np.median(v))
+
     # ------------------------------------------------------------------ headline: prefill 7B
     c = synth.prefill_7b()
     T, n, n1, n2 = c.T, c.n, c.n1, c.n2
@@ -86,31 +124,37 @@ def main() -> int:
     scales = [torch.empty((T,), dtype=torch.float16, device="cuda") for _ in range(nsets)]
     clips = [clip] + [clip.clone() for _ in range(nsets - 1)]
 
-    def step_cold(i):
-        k = i % nsets
-        fq.flatquant_transform_quant(xs[k], P1, P2, clips[k], 1, T, n1, n2, n, codes[k], scales[k], stream=stream)
+    step_cold = Rotation(lambda k: fq.flatquant_transform_quant(xs[k], P1, P2, clips[k], 1, T, n1, n2, n, codes[k], scales[k], stream=stream), nsets)
+    step_warm = Rotation(lambda k: fq.flatquant_transform_quant(xs[0], P1, P2, clips[0], 1, T, n1, n2, n, codes[0], scales[0], stream=stream), 1)
+    # the same buffers and the same rotation without the arithmetic: what a copy-like launch of this size reaches on this
+    # box.  Three launch shapes of the probe are timed; the fastest is the ceiling.
+    step_probe = Rotation(lambda k: fq.flatquant_stream_probe(xs[k], T, n, n, codes[k], stream=stream), nsets)
+    probe_us = {}
+    for shape, label in ((0, "persistent_two_wave_workgroups"), (1, "wave_per_row_nontemporal"), (2, "wave_per_row_plain_loads")):
+        fq.fq_set_tuning("FLATQUANT_PROBE_SHAPE", shape)
+        probe_us[label] = median_regions(step_probe, args.steps, args.warmup)[0] * 1e3
+    fq.fq_set_tuning("FLATQUANT_PROBE_SHAPE", None)
+    ms_probe = min(probe_us.values()) * 1e-3
 
-    def step_warm(i):
-        fq.flatquant_transform_quant(xs[0], P1, P2, clips[0], 1, T, n1, n2, n, codes[0], scales[0], stream=stream)
-
-    def step_probe(i):   # same buffers, same rotation, no arithmetic: the ceiling for a launch of this size
-        k = i % nsets
-        fq.flatquant_stream_probe(xs[k], T, n, n, codes[k], stream=stream)
-
-    ms_probe, _ = time_region(step_probe, args.steps, args.warmup)
-    ms_cold, wall_cold = time_region(step_cold, args.steps, args.warmup)
-    ms_warm, _ = time_region(step_warm, args.steps, args.warmup)
-    for k in range(1, min(nsets, max(args.steps, args.warmup))):    # every rotation set that was used produced the same bytes
+    ms_cold, wall_cold, cold_regions = median_regions(step_cold, args.steps, args.warmup)
+    us_single_cold = single_launch_us(step_cold)
+    ms_cold_long = median_regions(step_cold, 1000, 0, reps=3)[0]   # steady state, whatever --steps is
+    ms_warm, _, _ = median_regions(step_warm, args.steps, args.warmup)
+    used = min(nsets, step_cold.count)
+    for k in range(1, used):    # every rotation set that was used produced the same bytes
         assert torch.equal(codes[k], codes[0]) and torch.equal(scales[k].view(torch.int16), scales[0].view(torch.int16))
 
     tokens_per_s = T / (ms_cold * 1e-3)
     achieved = bytes_per_launch / (ms_cold * 1e-3) / 1e9
     flops_min = 2 * n * (n1 + n2) * T
-    traffic = None
+    # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counters: not measured in this run (a counter run is a run of
+    # its own under rocprofv3), read from the committed summary of the same command
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "tq_prefill_7b_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
+        traffic_source = "profiles/tq_prefill_7b_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the copy probe; not measured in this run)"
 
     out = {
         "metric": "fused transform+INT4-quant tokens/s (n=4096, T=2048)",
@@ -119,6 +163,7 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "repetitions": len(cold_regions),
         "ms_per_step": ms_cold,
         "higher_is_better": True,
         "scaling": "weak",
@@ -128,12 +173,14 @@ def main() -> int:
         "config": {"workload": "LLaMA-2-7B prefill shape: T=2048, n=4096 (n1=n2=64), per-token clip, fp16 in, INT4 codes + fp16 step out",
                    "cache": f"cold: rotation over {nsets} input/output sets ({nsets * bytes_per_launch / 1e9:.2f} GB)"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                     "frac_of_copy_probe": ms_probe / ms_cold},
         "detail": {
             "algorithmic_bytes_per_launch": bytes_per_launch,
-            "us_per_call_cold": ms_cold * 1e3, "us_per_call_warm": ms_warm * 1e3,
+            "us_per_call_cold": ms_cold * 1e3, "us_per_call_cold_regions": [v * 1e3 for v in cold_regions], "us_per_call_warm": ms_warm * 1e3,
+            "us_single_launch_cold_idle_stream": us_single_cold, "us_per_call_cold_1000_step_regions": ms_cold_long * 1e3,
             "host_wall_us_per_call_cold": wall_cold * 1e3,
-            "stream_probe_us_per_call_cold": ms_probe * 1e3,
+            "stream_probe_us_per_call_cold": ms_probe * 1e3, "stream_probe_us_by_shape": probe_us,
             "stream_probe_gbs": T * (2 * n + n // 2) / (ms_probe * 1e-3) / 1e9,
             "tokens_per_s_warm": T / (ms_warm * 1e-3),
             "gbs_warm": bytes_per_launch / (ms_warm * 1e-3) / 1e9,
@@ -199,10 +246,9 @@ def main() -> int:
             oc = [torch.empty((Tn, nn // 2), dtype=torch.uint8, device="cuda") for _ in range(cold_sets)]
             os_ = [torch.empty((Tn,), dtype=torch.float16, device="cuda") for _ in range(cold_sets)]
 
-            def st(i):
-                k = i % cold_sets
-                fq.flatquant_transform_quant(xsets[k], p1 if use_p1 else None, p2 if use_p2 else None, cl, 1, Tn, a, b, nn, oc[k], os_[k], stream=stream)
-            ms = float(np.median([time_region(st, steps, warmup if r == 0 else 1)[0] for r in range(5)]))   # median of 5 repetitions
+            st = Rotation(lambda k: fq.flatquant_transform_quant(xsets[k], p1 if use_p1 else None, p2 if use_p2 else None, cl, 1, Tn, a, b, nn,
+                                                                 oc[k], os_[k], stream=stream), cold_sets)
+            ms = median_regions(st, steps, warmup)[0]
             by = Tn * alg_bytes_per_token(nn)
             pad32 = 32 * ((a + 31) // 32)
             graph_us = None
@@ -219,6 +265,8 @@ def main() -> int:
         time_shape("decode_4096", 64, 64, 64, 500, 50)
         time_shape("decode_11008", 64, 86, 128, 500, 50)
         time_shape("prefill_70b_8192", 16384, 64, 128, 20, 4, cold_sets=4)
+        # the batch-64 row of the paper's kernel table (Table "kernel speedup"): 64 x 2048 tokens of 4096 channels, 1.3 GB per launch
+        time_shape("prefill_7b_batch64", 131072, 64, 64, 6, 2, cold_sets=1)
         # online part of P_o for LLaMA-2-7B: 32 heads x 128, left factor only (the per-head factor is fused offline)
         time_shape("p_o_left_only_32x128", 2048, 32, 128, 200, 20, cold_sets=60, use_p2=False)
         if not args.no_wide:
@@ -228,10 +276,8 @@ def main() -> int:
         mxs = [torch.empty((T, n // 32), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
         mxc = [torch.empty((T, n // 2), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
 
-        def st_mx(i):
-            k = i % nsets
-            fq.flatquant_transform_mxfp4(xs[k], P1, P2, clips[k], 1, T, n1, n2, n, mxc[k], mxs[k], stream=stream)
-        ms = float(np.median([time_region(st_mx, 200, 20)[0] for r in range(5)]))
+        st_mx = Rotation(lambda k: fq.flatquant_transform_mxfp4(xs[k], P1, P2, clips[k], 1, T, n1, n2, n, mxc[k], mxs[k], stream=stream), nsets)
+        ms = median_regions(st_mx, 200, 20)[0]
         by = T * (2 * n + n // 2 + n // 32 + 4)
         extras["mxfp4_prefill_7b"] = {"T": T, "n1": n1, "n2": n2, "us_per_call": ms * 1e3, "tokens_per_s": T / (ms * 1e-3),
                                       "gbs": by / (ms * 1e-3) / 1e9, "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
@@ -246,26 +292,20 @@ def main() -> int:
         ks = [torch.empty((Tk * H,), dtype=torch.float16, device="cuda") for _ in range(8)]
         kz = [torch.empty((Tk * H,), dtype=torch.float16, device="cuda") for _ in range(8)]
 
-        def st_kv(i):
-            k = i % 8
-            fq.flatquant_kv_transform_quant(kvsets[k], Pk, H, 0.95, Tk, H, D, kc[k], ks[k], kz[k], stream=stream)
-        ms = float(np.median([time_region(st_kv, 40, 8 if r == 0 else 1)[0] for r in range(5)]))
+        st_kv = Rotation(lambda k: fq.flatquant_kv_transform_quant(kvsets[k], Pk, H, 0.95, Tk, H, D, kc[k], ks[k], kz[k], stream=stream), 8)
+        ms = median_regions(st_kv, 40, 8)[0]
         by = Tk * H * (2 * D + D // 2 + 4)
         extras["kv_cache"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms * 1e3, "groups_per_s": Tk * H / (ms * 1e-3),
                               "gbs": by / (ms * 1e-3) / 1e9, "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         Pshared = Pk[:1].contiguous()                     # the paper's setting: one P_h per layer, shared by the heads
 
-        def st_kvs(i):
-            k = i % 8
-            fq.flatquant_kv_transform_quant(kvsets[k], Pshared, 1, 0.95, Tk, H, D, kc[k], ks[k], kz[k], stream=stream)
-        ms_s = float(np.median([time_region(st_kvs, 40, 8 if r == 0 else 1)[0] for r in range(5)]))
+        st_kvs = Rotation(lambda k: fq.flatquant_kv_transform_quant(kvsets[k], Pshared, 1, 0.95, Tk, H, D, kc[k], ks[k], kz[k], stream=stream), 8)
+        ms_s = median_regions(st_kvs, 40, 8)[0]
         extras["kv_cache_shared_matrix"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms_s * 1e3, "groups_per_s": Tk * H / (ms_s * 1e-3),
                                             "gbs": by / (ms_s * 1e-3) / 1e9, "hbm_frac": by / (ms_s * 1e-3) / 1e9 / HBM_PEAK_GBS}
         for bits in (3, 2):   # lower-bit caches: same kernel, D * bits / 8 code bytes per group (into the same buffers)
-            def st_kvb(i, bits=bits):
-                k = i % 8
-                fq.flatquant_kv_transform_quant_bits(kvsets[k], Pk, H, 0.95, bits, Tk, H, D, kc[k], ks[k], kz[k], stream=stream)
-            ms = float(np.median([time_region(st_kvb, 40, 8 if r == 0 else 1)[0] for r in range(5)]))
+            st_kvb = Rotation(lambda k, bits=bits: fq.flatquant_kv_transform_quant_bits(kvsets[k], Pk, H, 0.95, bits, Tk, H, D, kc[k], ks[k], kz[k], stream=stream), 8)
+            ms = median_regions(st_kvb, 40, 8)[0]
             by = Tk * H * (2 * D + D * bits // 8 + 4)
             extras[f"kv_cache_{bits}bit"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms * 1e3, "groups_per_s": Tk * H / (ms * 1e-3),
                                             "gbs": by / (ms * 1e-3) / 1e9, "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
@@ -276,21 +316,20 @@ def main() -> int:
 
         def st_kvd(i, s_=None):
             fq.flatquant_kv_transform_quant(kvd, Pd, Hd, 0.95, Td, Hd, D, kc[0], ks[0], kz[0], stream=s_ or stream)
-        ms = float(np.median([time_region(st_kvd, 200, 20 if r == 0 else 1)[0] for r in range(5)]))
+        ms = median_regions(st_kvd, 200, 20)[0]
         extras["kv_cache_decode"] = {"T": Td, "H": Hd, "D": D, "us_per_call": ms * 1e3,
                                      "us_per_call_graph_replay": graph_replay_us("kv_cache_decode", lambda gs: st_kvd(0, gs))}
         # query side: per-head transform, fp16 out (same tensors, 2 x 2D bytes per group)
         qo = [torch.empty((Tk, H, D), dtype=torch.float16, device="cuda") for _ in range(4)]
 
-        def st_q(i):
-            fq.flatquant_head_transform(kvsets[i % 8], Pk, H, Tk, H, D, qo[i % 4], stream=stream)
-        ms = float(np.median([time_region(st_q, 40, 8 if r == 0 else 1)[0] for r in range(5)]))
+        st_q = Rotation(lambda k: fq.flatquant_head_transform(kvsets[k], Pk, H, Tk, H, D, qo[k % 4], stream=stream), 8)
+        ms = median_regions(st_q, 40, 8)[0]
         by = Tk * H * 4 * D
         extras["head_transform_fp16"] = {"T": Tk, "H": H, "D": D, "us_per_call": ms * 1e3, "gbs": by / (ms * 1e-3) / 1e9,
                                          "hbm_frac": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         del kvsets, kc, ks, kz, qo
         # ---- the consumer: W4A4 matrix product on int8 MFMA, and the whole quantized linear layer (transform + quantization of
-        # the activations, then the product with pre-quantized weights) beside the FP16 matrix product it replaces
+        # the activations, then the product with pre-quantized weights), as fractions of the MFMA peak of its data type
         INT8_PEAK_TOPS = 5000.0
 
         def weight_copies(Tn, nbytes):   # prefill: one copy (the product is compute-bound); decode: 320 MB worth, past L2 + Infinity Cache
@@ -307,25 +346,19 @@ def main() -> int:
             xs_ = torch.empty((Tn,), dtype=torch.float16, device="cuda")
             # few tokens: the weights are the traffic, so they rotate through more copies than the caches hold (a decode
             # step reads every layer's weights from HBM); the FP16 weights beside them likewise
-            nwc, nwh = weight_copies(Tn, mo * nn // 2), weight_copies(Tn, mo * nn * 2)
+            nwc = weight_copies(Tn, mo * nn // 2)
             wcs = [torch.randint(0, 256, (mo, nn // 2), generator=g, dtype=torch.uint8, device="cuda") for _ in range(nwc)]
             wc = wcs[0]
             ws = (torch.rand((mo,), generator=g, device="cuda") * 1e-3 + 1e-4).half()
             y = torch.empty((Tn, mo), dtype=torch.float16, device="cuda")
-            whs = [torch.randn((mo, nn), generator=g, device="cuda").half() for _ in range(nwh)]
+            st_gemm = Rotation(lambda k: fq.flatquant_w4a4_gemm(xc, xs_, wcs[k], ws, Tn, mo, nn, y, mo, stream=stream), nwc)
 
-            def st_gemm(i):
-                fq.flatquant_w4a4_gemm(xc, xs_, wcs[i % nwc], ws, Tn, mo, nn, y, mo, stream=stream)
-
-            def st_layer(i):
+            def layer(k):
                 fq.flatquant_transform_quant(x, p1, p2, cl, 1, Tn, a, b, nn, xc, xs_, stream=stream)
-                fq.flatquant_w4a4_gemm(xc, xs_, wcs[i % nwc], ws, Tn, mo, nn, y, mo, stream=stream)
-
-            def st_fp16(i):
-                torch.matmul(x, whs[i % nwh].t(), out=y)
-            st_layer(0)
-            med = lambda f: float(np.median([time_region(f, steps, warmup if r == 0 else 1)[0] for r in range(5)]))
-            ms_g, ms_l, ms_h = med(st_gemm), med(st_layer), med(st_fp16)
+                fq.flatquant_w4a4_gemm(xc, xs_, wcs[k], ws, Tn, mo, nn, y, mo, stream=stream)
+            st_layer = Rotation(layer, nwc)
+            st_layer()
+            ms_g, ms_l = median_regions(st_gemm, steps, warmup)[0], median_regions(st_layer, steps, warmup)[0]
             ops = 2.0 * Tn * mo * nn
             layer_graph = None
             if Tn <= 256:
@@ -335,8 +368,7 @@ def main() -> int:
                 layer_graph = graph_replay_us(name, one_layer)
             extras[name] = {"T": Tn, "m": mo, "n": nn, "weight_copies_rotated": nwc, "layer_us_graph_replay_weights_cached": layer_graph, "gemm_us": ms_g * 1e3, "gemm_tops": ops / (ms_g * 1e-3) / 1e12,
                             "gemm_frac_of_int8_mfma_peak": ops / (ms_g * 1e-3) / 1e12 / INT8_PEAK_TOPS,
-                            "layer_us_transform_quant_plus_gemm": ms_l * 1e3, "fp16_matmul_us_torch_hipblaslt": ms_h * 1e3,
-                            "layer_speedup_vs_fp16_matmul": ms_h / ms_l}
+                            "layer_us_transform_quant_plus_gemm": ms_l * 1e3}
 
         def time_mx_layer(name, Tn, mo, a, b, steps, warmup):   # the same layer with MXFP4 on both factors (scaled FP4 MFMA)
             nn = a * b
@@ -347,29 +379,22 @@ def main() -> int:
             cl = torch.full((Tn,), 0.9, device="cuda")
             xc = torch.empty((Tn, nn // 2), dtype=torch.uint8, device="cuda")
             xe = torch.empty((fq.fq_mxfp4_tiled_scale_bytes(Tn, nn),), dtype=torch.uint8, device="cuda")
-            nwc, nwh = weight_copies(Tn, mo * nn // 2), weight_copies(Tn, mo * nn * 2)
+            nwc = weight_copies(Tn, mo * nn // 2)
             wcs = [torch.randint(0, 256, (mo, nn // 2), generator=g, dtype=torch.uint8, device="cuda") for _ in range(nwc)]
             we = torch.randint(112, 118, (fq.fq_mxfp4_tiled_scale_bytes(mo, nn),), generator=g, dtype=torch.uint8, device="cuda")
             y = torch.empty((Tn, mo), dtype=torch.float16, device="cuda")
-            whs = [torch.randn((mo, nn), generator=g, device="cuda").half() for _ in range(nwh)]
+            st_gemm = Rotation(lambda k: fq.flatquant_mxfp4_gemm(xc, xe, wcs[k], we, Tn, mo, nn, y, mo, stream=stream), nwc)
 
-            def st_gemm(i):
-                fq.flatquant_mxfp4_gemm(xc, xe, wcs[i % nwc], we, Tn, mo, nn, y, mo, stream=stream)
-
-            def st_layer(i):
+            def layer(k):
                 fq.flatquant_transform_mxfp4_tiled(x, p1, p2, cl, 1, Tn, a, b, nn, xc, xe, stream=stream)
-                fq.flatquant_mxfp4_gemm(xc, xe, wcs[i % nwc], we, Tn, mo, nn, y, mo, stream=stream)
-
-            def st_fp16(i):
-                torch.matmul(x, whs[i % nwh].t(), out=y)
-            st_layer(0)
-            med = lambda f: float(np.median([time_region(f, steps, warmup if r == 0 else 1)[0] for r in range(5)]))
-            ms_g, ms_l, ms_h = med(st_gemm), med(st_layer), med(st_fp16)
+                fq.flatquant_mxfp4_gemm(xc, xe, wcs[k], we, Tn, mo, nn, y, mo, stream=stream)
+            st_layer = Rotation(layer, nwc)
+            st_layer()
+            ms_g, ms_l = median_regions(st_gemm, steps, warmup)[0], median_regions(st_layer, steps, warmup)[0]
             ops = 2.0 * Tn * mo * nn
             extras[name] = {"T": Tn, "m": mo, "n": nn, "weight_copies_rotated": nwc, "gemm_us": ms_g * 1e3, "gemm_tflops": ops / (ms_g * 1e-3) / 1e12,
                             "gemm_frac_of_fp4_mfma_peak": ops / (ms_g * 1e-3) / 1e12 / 10100.0,
-                            "layer_us_transform_quant_plus_gemm": ms_l * 1e3, "fp16_matmul_us_torch_hipblaslt": ms_h * 1e3,
-                            "layer_speedup_vs_fp16_matmul": ms_h / ms_l}
+                            "layer_us_transform_quant_plus_gemm": ms_l * 1e3}
 
         time_mx_layer("mxfp4_layer_prefill_qkvo_7b", 2048, 4096, 64, 64, 50, 5)
         time_mx_layer("mxfp4_layer_prefill_down_7b", 2048, 4096, 86, 128, 30, 5)
@@ -387,11 +412,12 @@ def main() -> int:
     if not args.no_cpu:
         from oracle import flatquant_oracle as fo
         from oracle import parity
+        cores = len(os.sched_getaffinity(0))     # the cores this process may run on
         try:
             from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+            blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
-            cores = len(os.sched_getaffinity(0))
+            blas_threads = None
         t0 = time.perf_counter()
         P = fo.kron_dense(c.P1, c.P2)
         t_kron = time.perf_counter() - t0
@@ -403,7 +429,7 @@ def main() -> int:
             reps += 1
         out["cpu_baseline"] = {"value": T * reps / t_run, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
                                "sample": f"all {T} tokens of the headline workload, {reps} passes of the fp64 dense-Kronecker oracle "
-                                         f"(numpy); building the {n}x{n} matrix once took {t_kron:.2f} s and is not in the rate"}
+                                         f"(numpy + its BLAS, thread pool of {blas_threads}); building the {n}x{n} matrix once took {t_kron:.2f} s and is not in the rate"}
         # a second CPU line: the same oracle through the factored form of Eq. (2) (two small contractions per token)
         reps_f, t_f = 0, 0.0
         while reps_f < 2 or (t_f < 5.0 and reps_f < 400):

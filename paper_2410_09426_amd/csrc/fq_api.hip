@@ -57,7 +57,7 @@ struct Tunable {
 };
 Tunable g_tunables[] = {Tunable("FLATQUANT_MODE"), Tunable("FLATQUANT_WG_PER_CU"), Tunable("FLATQUANT_FORCE_GENERIC"),
                         Tunable("FLATQUANT_KV_WG_PER_CU"), Tunable("FLATQUANT_GEMM_TILED"),
-                        Tunable("FLATQUANT_GEMM_WIDE"), Tunable("FLATQUANT_GEMM_DEPTH"), Tunable("FLATQUANT_GEMM_WAVES"), Tunable("FLATQUANT_GEMM_ROWS"), Tunable("FLATQUANT_GEMM_RING_MAX_T"), Tunable("FLATQUANT_KV_FOLD_HEADS"), Tunable("FLATQUANT_WAVE_TPW")};
+                        Tunable("FLATQUANT_GEMM_WIDE"), Tunable("FLATQUANT_GEMM_DEPTH"), Tunable("FLATQUANT_GEMM_WAVES"), Tunable("FLATQUANT_GEMM_ROWS"), Tunable("FLATQUANT_GEMM_RING_MAX_T"), Tunable("FLATQUANT_KV_FOLD_HEADS"), Tunable("FLATQUANT_WAVE_TPW"), Tunable("FLATQUANT_PROBE_SHAPE")};
 Tunable* find_tunable(const char* name) {
     for (Tunable& t : g_tunables)
         if (std::strcmp(t.name, name) == 0) return &t;
