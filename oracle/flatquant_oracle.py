@@ -294,8 +294,8 @@ def e2m1_round(u) -> np.ndarray:
     a tie goes to the even code, anything beyond 6 saturates, the sign bit is
     the sign of the input (a negative value that rounds to zero is -0)."""
     u = as_f64(u)
-    a = np.abs(u)
-    grid = np.asarray(E2M1_VALUES)
+    a = np.minimum(np.abs(u), max(E2M1_VALUES))          # saturating: beyond the largest magnitude is the largest magnitude
+    grid = np.asarray(E2M1_VALUES)                       # (left unclamped, a value above 2^53 is equally far from all 8 in fp64)
     d = np.abs(a[..., None] - grid)                      # distance to each magnitude
     best = d.min(axis=-1, keepdims=True)
     cand = d == best                                     # one or (on a tie) two neighbours

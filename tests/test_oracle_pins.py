@@ -525,6 +525,9 @@ def test_e2m1_rounding_hand_cases_and_arithmetic_route():
     for v, code in cases.items():
         assert int(fo.e2m1_round(np.float64(v))) == code, v
     assert int(fo.e2m1_round(np.float64(-0.0))) == 8
+    # saturation holds however large the value is (beyond 2^53 an fp64 distance no longer tells the magnitudes apart)
+    for v, code in ((1e17, 7), (-1e17, 15), (1e30, 7), (-1e300, 15), (float(2 ** 60), 7)):
+        assert int(fo.e2m1_round(np.float64(v))) == code, v
     # the same rounding done arithmetically: spacing 0.5 * 2^max(floor(log2 a), 0), round-half-even in units of it
     r = np.random.default_rng(11)
     u = np.concatenate([r.uniform(-8, 8, 20000), r.normal(0, 1.5, 20000), np.arange(-32, 33) / 4.0])
