@@ -75,6 +75,15 @@ def check_sym(y_or, clip, codes_dev, scales_dev, deq_dev=None, rows=None):
     return rep
 
 
+def band_flip_allowance(in_band: int) -> int:
+    """How many of the `in_band` elements (pre-round value within BAND of a tie) may come out as the other neighbour.
+    The kernels' arithmetic error is about 1e-5 code units (fp32 accumulation, hi + lo split of the intermediate,
+    reciprocal of the step), a hundredth of the band, so about one in a hundred in-band elements lies close enough to
+    its tie to flip.  A tenth of them (and never fewer than 2) is the ceiling: more means the error is ten times what the
+    arithmetic explains."""
+    return max(2, int(in_band) // 10)
+
+
 def check_kv(y_or, clip, codes_dev, scales_dev, zeros_dev, deq_dev=None, bits=4):
     """y_or fp64 [G, D] (groups flattened); codes u8 [G, D*bits/8]; scales/zeros fp16 [G]."""
     qmax = (1 << int(bits)) - 1

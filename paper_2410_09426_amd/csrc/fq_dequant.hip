@@ -73,8 +73,7 @@ hipError_t dequant_mxfp4_launch(const uint8_t* codes, const uint8_t* exps, int64
     const int64_t cap = (int64_t)cu_count() * 16;
     if (grid > cap) grid = cap;
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL(dequant_mxfp4_kernel, dim3((unsigned)grid), dim3(256), 0, stream, codes, exps, rows, n, out);
-    return hipGetLastError();
+    return launch(dequant_mxfp4_kernel, dim3((unsigned)grid), dim3(256), 0, stream, codes, exps, rows, n, out);
 }
 
 hipError_t dequant_bits_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,
@@ -84,8 +83,7 @@ hipError_t dequant_bits_launch(const uint8_t* codes, const _Float16* scales, con
     const int64_t cap = (int64_t)cu_count() * 16;
     if (grid > cap) grid = cap;
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL(dequant_bits_kernel, dim3((unsigned)grid), dim3(256), 0, stream, codes, scales, zeros, rows, n, bits, out);
-    return hipGetLastError();
+    return launch(dequant_bits_kernel, dim3((unsigned)grid), dim3(256), 0, stream, codes, scales, zeros, rows, n, bits, out);
 }
 
 hipError_t dequant_launch(const uint8_t* codes, const _Float16* scales, const _Float16* zeros,
@@ -96,8 +94,7 @@ hipError_t dequant_launch(const uint8_t* codes, const _Float16* scales, const _F
     const int64_t cap = (int64_t)cu_count() * 16;
     if (grid > cap) grid = cap;
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL(dequant_kernel, dim3((unsigned)grid), dim3(256), 0, stream, codes, scales, zeros, rows, n, out);
-    return hipGetLastError();
+    return launch(dequant_kernel, dim3((unsigned)grid), dim3(256), 0, stream, codes, scales, zeros, rows, n, out);
 }
 
 }  // namespace fq

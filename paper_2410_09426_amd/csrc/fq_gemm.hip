@@ -25,10 +25,7 @@ typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int GT = 128;               // tile edge, tokens and output channels
-#ifndef FQ_GKB
-#define FQ_GKB 128
-#endif
-constexpr int GKB = FQ_GKB;              // packed bytes of K per row and iteration (256 codes)
+constexpr int GKB = 128;              // packed bytes of K per row and iteration (256 codes)
 constexpr int GPITCH = GKB;           // LDS row pitch: rows are written by global-to-LDS loads, 8 whole rows per wave and
                                       // instruction, so there is no padding; the 16-byte chunks of a row are swizzled instead
 constexpr int G_NT = 256;
@@ -409,8 +406,7 @@ static hipError_t skinny_launch_rows(const GemmDev& d, hipStream_t stream, int t
     if (depth > steps) depth = steps;
     while (depth > 1 && (nwv * depth * SLOT > kRingLdsMax || (depth - 1) * NI > 63)) --depth;
     const int bytes = nwv * depth * SLOT;                                 // the partial sums (at most 4 KB per wave and token tile) reuse the rings
-    hipLaunchKernelGGL((w4a4_skinny_kernel<NTD, ROWS>), dim3(wgx, (unsigned)token_tiles), dim3(64 * nwv), bytes, stream, d, depth);
-    return hipGetLastError();
+    return launch((w4a4_skinny_kernel<NTD, ROWS>), dim3(wgx, (unsigned)token_tiles), dim3(64 * nwv), bytes, stream, d, depth);
 }
 // 16 channels per workgroup while that still leaves at most one workgroup per CU (FLATQUANT_GEMM_ROWS forces 16 or 32):
 // the kernel is bound by what one CU takes in, so the channels go to as many CUs as there are.
@@ -449,16 +445,14 @@ hipError_t w4a4_launch(const GemmArgs& a, hipStream_t stream) {
         hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_kernel<4>), 512, G_LDS_BYTES_WIDE, ctw, unused);
         if (e != hipSuccess) return e;
         const dim3 grid((unsigned)((a.T + 255) / 256), (unsigned)((a.m + GT - 1) / GT));
-        hipLaunchKernelGGL(w4a4_kernel<4>, grid, dim3(512), G_LDS_BYTES_WIDE, stream, d);
-        return hipGetLastError();
+        return launch(w4a4_kernel<4>, grid, dim3(512), G_LDS_BYTES_WIDE, stream, d);
     }
     {
         hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(w4a4_kernel<2>), G_NT, G_LDS_BYTES, ct, unused);
         if (e != hipSuccess) return e;
     }
     const dim3 grid((unsigned)((a.T + GT - 1) / GT), (unsigned)((a.m + GT - 1) / GT));
-    hipLaunchKernelGGL(w4a4_kernel<2>, grid, dim3(G_NT), G_LDS_BYTES, stream, d);
-    return hipGetLastError();
+    return launch(w4a4_kernel<2>, grid, dim3(G_NT), G_LDS_BYTES, stream, d);
 }
 
 }  // namespace fq

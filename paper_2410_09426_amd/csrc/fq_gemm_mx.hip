@@ -383,8 +383,7 @@ static hipError_t mx_skinny_launch_rows(const MxGemmDev& d, hipStream_t stream, 
     if (depth > steps) depth = steps;
     while (depth > 1 && (nwv * depth * SLOT > kRingLdsMax || (depth - 1) * NI > 63)) --depth;
     const int bytes = nwv * depth * SLOT;                // the partial sums (at most 4 KB per wave and token tile) reuse the rings
-    hipLaunchKernelGGL((mxfp4_skinny_kernel<NTD, ROWS>), dim3(wgx, (unsigned)token_tiles), dim3(64 * nwv), bytes, stream, d, depth);
-    return hipGetLastError();
+    return launch((mxfp4_skinny_kernel<NTD, ROWS>), dim3(wgx, (unsigned)token_tiles), dim3(64 * nwv), bytes, stream, d, depth);
 }
 // 16 channels per workgroup while that still leaves at most one workgroup per CU (FLATQUANT_GEMM_ROWS forces 16 or 32)
 template <int NTD>
@@ -418,8 +417,7 @@ hipError_t mxfp4_gemm_launch(const MxGemmArgs& a, hipStream_t stream) {
     hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(mxfp4_gemm_kernel), X_NT, X_LDS_BYTES, cache, unused);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((a.T + XT - 1) / XT), (unsigned)((a.m + XT - 1) / XT));
-    hipLaunchKernelGGL(mxfp4_gemm_kernel, grid, dim3(X_NT), X_LDS_BYTES, stream, d);
-    return hipGetLastError();
+    return launch(mxfp4_gemm_kernel, grid, dim3(X_NT), X_LDS_BYTES, stream, d);
 }
 
 }  // namespace fq

@@ -113,6 +113,15 @@ hipError_t mxfp4_gemm_launch(const MxGemmArgs& a, hipStream_t stream);
 constexpr int kRingMaxDepth = 8;
 constexpr int kRingLdsMax = 160 * 1024;
 #if defined(__HIP_DEVICE_COMPILE__) || defined(__HIPCC__)
+// Every kernel launch of the library goes through here.  The runtime keeps the last error of any earlier call on the
+// thread (the caller's own, unrelated ones included) until somebody reads it: it is read and dropped first, so that
+// what is returned belongs to this launch.
+template <typename... KArgs, typename... Args>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, int lds, hipStream_t stream, Args&&... args) {
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(kernel, grid, block, lds, stream, static_cast<KArgs>(args)...);
+    return hipGetLastError();
+}
 // until at most N of this wave's vector-memory loads are outstanding (they complete in order)
 template <int N>
 __device__ __forceinline__ void wait_vm_pending() {

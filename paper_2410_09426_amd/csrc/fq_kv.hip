@@ -197,14 +197,17 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
         const float s = (float)sh;
         const float inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;
         const float z = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(-mn * inv), 0.0f), LV);
-        // q = clamp(round(y / s) + z, 0, LV) = round(clamp(y, -z s, (LV - z) s) / s + z): clamp, then one fma against
-        // 1.5 * 2^23 leaves 0x4B400000 + code in the register, so 8 codes chain with shift-adds and the constant part
-        // (0x4B400000 times the sum of the shifts, modulo 2^32) is taken off once
+        // q = clamp(round(y / s) + z, 0, LV) = round(clamp(y, -z s, (LV - z) s) / s) + z: clamp, then one fma against
+        // 1.5 * 2^23 rounds y / s on its own (ties to even, as the definition has it) and leaves 0x4B400000 + round(y / s)
+        // in the register (two's complement in the low bits), so 8 results chain with shift-adds; the constant part
+        // (0x4B400000 times the sum of the shifts) comes off and the zero point (z in every field) goes on in one
+        // integer addition per 8 codes, all modulo 2^32: every field then holds its code, 0 .. LV, and nothing above.
         const float sl = (inv != 0.0f) ? s : 0.0f;
         const float lim_lo = -z * sl, lim_hi = (LV - z) * sl;
-        const float magic = 12582912.0f + z;
+        constexpr float magic = 12582912.0f;
         constexpr uint32_t kMagicBits = 0x4B400000u;
-        constexpr uint32_t kChainConst = kMagicBits * (1u + (1u << QB) + (1u << 2 * QB) + (1u << 3 * QB) + (QB == 4 ? 0x11110000u : (1u << 4 * QB) + (1u << 5 * QB) + (1u << 6 * QB) + (1u << 7 * QB)));
+        constexpr uint32_t kFields = 1u + (1u << QB) + (1u << 2 * QB) + (1u << 3 * QB) + (QB == 4 ? 0x11110000u : (1u << 4 * QB) + (1u << 5 * QB) + (1u << 6 * QB) + (1u << 7 * QB));
+        const uint32_t chain_fix = (uint32_t)(int)z * kFields - kMagicBits * kFields;
 
         uint8_t* srow = stage + c * KV_STAGE_PITCH;
 #pragma unroll
@@ -219,7 +222,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2))) void
                 }
                 const uint32_t lo4 = lshl_add(lshl_add(bits[3], QB, bits[2]), 2 * QB, lshl_add(bits[1], QB, bits[0]));
                 const uint32_t hi4 = lshl_add(lshl_add(bits[7], QB, bits[6]), 2 * QB, lshl_add(bits[5], QB, bits[4]));
-                const uint32_t pk = lshl_add(hi4, 4 * QB, lo4) - kChainConst;   // 8 codes, 8 QB bits, nothing above
+                const uint32_t pk = lshl_add(hi4, 4 * QB, lo4) + chain_fix;   // 8 codes, 8 QB bits
                 const int dp = 32 * mt + 16 * u + 8 * h;   // first of 8 consecutive output channels
                 if constexpr (QB == 4) {
                     *reinterpret_cast<uint32_t*>(srow + (dp >> 1)) = pk;
@@ -291,8 +294,7 @@ static hipError_t kv_launch_mode(const KvArgs& a, hipStream_t stream) {
     KvDev d;
     d.kv = a.kv; d.P = a.P; d.out_codes = a.out_codes; d.out_scales = a.out_scales; d.out_zeros = a.out_zeros;
     d.T = a.T; d.H = a.H; d.Hp = a.Hp; d.clip = a.clip;
-    hipLaunchKernelGGL(kv_kernel<BITS>, dim3((unsigned)gx, (unsigned)a.H), dim3(KV_NT), LDS, stream, d);
-    return hipGetLastError();
+    return launch(kv_kernel<BITS>, dim3((unsigned)gx, (unsigned)a.H), dim3(KV_NT), LDS, stream, d);
 }
 
 hipError_t kv_launch(const KvArgs& a0, hipStream_t stream) {

@@ -55,21 +55,18 @@ __global__ __launch_bounds__(256) void stream_probe_rows_kernel(const u32x4* __r
 // shape (tuning knob FLATQUANT_PROBE_SHAPE): 0 persistent two-wave workgroups, 1 a wave per row, 2 the same with plain loads
 hipError_t stream_probe_launch(const void* x, int64_t T, int n, int64_t x_stride, uint8_t* out, hipStream_t stream) {
     const int shape = env_int("FLATQUANT_PROBE_SHAPE", 0);
-    (void)hipGetLastError();
     if (shape == 1 || shape == 2) {
         if (T > 0x7fffffff) return hipErrorInvalidConfiguration;
         const unsigned grid = (unsigned)((T + 3) / 4);
         const bool small = (n / 8) % 1024 != 0 && (n / 8) % 512 == 0;   // rows of a whole number of 8-load passes (n = 4096)
         auto fn = shape == 1 ? (small ? &stream_probe_rows_kernel<false, 8> : &stream_probe_rows_kernel<false, 16>)
                              : (small ? &stream_probe_rows_kernel<true, 8> : &stream_probe_rows_kernel<true, 16>);
-        hipLaunchKernelGGL(fn, dim3(grid), dim3(256), 0, stream, static_cast<const u32x4*>(x), T, n / 8, x_stride / 8, reinterpret_cast<u32x4*>(out));
-        return hipGetLastError();
+        return launch(fn, dim3(grid), dim3(256), 0, stream, static_cast<const u32x4*>(x), T, n / 8, x_stride / 8, reinterpret_cast<u32x4*>(out));
     }
     int64_t grid = (int64_t)cu_count() * 8;
     if (grid > T) grid = T;
-    hipLaunchKernelGGL(stream_probe_kernel, dim3((unsigned)grid), dim3(128), 0, stream, static_cast<const u32x4*>(x), T, n / 8,
+    return launch(stream_probe_kernel, dim3((unsigned)grid), dim3(128), 0, stream, static_cast<const u32x4*>(x), T, n / 8,
                        x_stride / 8, reinterpret_cast<u32x4*>(out));
-    return hipGetLastError();
 }
 
 }  // namespace fq

@@ -22,7 +22,7 @@ namespace fq {
 __host__ __device__ constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
 // LDS carve-up, shared by host and device.
-template <int A, int B, int NBUF = 1>
+template <int A, int B, int NBUF = 1, bool MX = false>
 struct FastLds {
     static constexpr int N2 = 32 * B;
     static constexpr int PITCH = N2 + kLdsPad;                       // halves per row of the token tile
@@ -30,7 +30,7 @@ struct FastLds {
     // packed codes of one token, one row of X~ (N2 / 2 bytes) per line; 16 bytes of padding per line spread the
     // 2-byte writes of 32 lanes (one line each) over the banks instead of piling them on two
     static constexpr int SPITCH = N2 / 2 + 16;
-    static constexpr int STAGE_BYTES = 32 * A * SPITCH;
+    static constexpr int STAGE_BYTES = MX ? 32 * A * SPITCH : 0;   // INT4 codes leave from registers
     static constexpr int BODY_BYTES = NBUF * (XS_BYTES + STAGE_BYTES) + 32 * (NBUF < 2 ? 2 : NBUF);   // + one absmax float per wave and buffer
     static constexpr int P2ROWS = (B <= 4) ? N2 : N2 / 2;            // rows of P2 staged per pass
     static constexpr int P2PASSES = N2 / P2ROWS;
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
     static_assert(!MX || (KIND != 1 && SPW == 1 && TPW == 1 && !ID2), "MXFP4 output: plain loop or one token per workgroup");
     static_assert(TPW == 1 || (KIND == 2 && B == SPW && A <= 2), "several tokens per workgroup: loop-free kernel, one wave per token");
     constexpr bool PIPE = (KIND == 1), ONE = (KIND == 2);
-    using L = FastLds<A, B, PIPE ? 2 : TPW>;
+    using L = FastLds<A, B, PIPE ? 2 : TPW, MX>;
     constexpr int WPT = B / SPW;                  // waves per token
     constexpr int NT = 64 * WPT, NTA = NT * TPW, N2 = L::N2, PITCH = L::PITCH;   // threads per token, per workgroup
     constexpr int KB1 = 2 * A, KB2 = 2 * B, NPRE = 2 * A * SPW;
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
     const int64_t G = gridDim.x;
     const bool live = TPW == 1 || t < p.T;        // a last workgroup's spare waves redo token T - 1 and store nothing
     if (TPW > 1 && !live) t = p.T - 1;
-    issue(t, pre0);   // [phase:rows requested]
+    issue(t, pre0);
 
     // ---- stage P1 (flat, n1 x n1) and P2 (in one or two passes of rows) in LDS with coalesced loads.  All loads of
     // a stage are issued before any of them is consumed, so the stage costs one memory latency, not one per element.
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
 #pragma unroll
             for (int k = 0; k < CH / NTA; ++k) reinterpret_cast<u32x4*>(P2flat)[tida + k * NTA] = v2[k];
         }
-        __syncthreads();   // [phase:transforms staged]
+        __syncthreads();
         // B-operand fragments of this wave's slab: lane (c, h) holds P2[16kb + 8h + s][32w + c], s = 0..7
         if constexpr (!ID2) {
 #pragma unroll
@@ -245,7 +245,6 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
             }
         }
     }
-    // [phase:fragments built]
     __syncthreads();   // staging area is free: it becomes the token tile
     if constexpr (!FULL1) {   // tile rows that are never written (whole requests past n1) must be exact zeros
         for (int bf = 0; bf < NBUF; ++bf)
@@ -264,7 +263,7 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
         }
     };
     commit(pre0, ts);
-    token_sync();   // [phase:first tile in LDS]
+    token_sync();
 
     // ---- both contractions for the token tile in LDS buffer `buf`: acc2 = (P1^T X~ P2)^T for this wave's slabs
     // `side(slot)` is called NSLOT times at even intervals of the MFMA stream; the pipelined loop uses it to
@@ -388,36 +387,70 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
         return m;
     };
 
-    // ---- step from the absmax; clamp, round, pack into stage buffer `buf`.  fma against 1.5 * 2^23 + 8 leaves
-    // code + 8 (0..15) in the low mantissa bits with zeros above up to bit 21, so four results chain with shift-adds
-    // and one xor turns offset-binary nibbles into two's complement ones.
-    const int stage_lane = c * L::SPITCH + ((32 * w * SPW + 4 * h) >> 1);   // this lane's byte offset inside the staged codes
-    struct Step { _Float16 sh; float inv, lim_lo, lim_hi; };
+    // ---- step from the absmax; round, clamp, pack, store.  INT4 codes leave from registers.  v_cvt_pknorm_i16_f32
+    // (clamp to [-1, 1], times 32767, round to nearest) applied to r = (4096 (u + 0.5) - 0.5) / 32767, u = y / step,
+    // leaves clamp(rne(u), -8, 7) as the two's-complement top nibble of a 16-bit field: clamping, rounding and half of
+    // the packing cost one fma plus half an instruction per value.  (The thresholds between codes move by less than
+    // 2e-6 code units: fp32 rounding of the two constants and of the fma.)
+    const int stage_lane = c * L::SPITCH + ((32 * w * SPW + 4 * h) >> 1);   // MXFP4 path: this lane's byte offset inside the staged codes
+    struct Step { _Float16 sh; float kmul; };
     auto make_step = [&](float m, float clipv) {
         Step st;
         st.sh = (_Float16)(clipv * m * 0.142857149f);   // step = alpha * max / 7, round-to-nearest-even to fp16
         const float s = (float)st.sh;
-        st.inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;   // 1 ulp: < 1e-6 code units
-        const float sl = (st.inv != 0.0f) ? s : 0.0f;
-        st.lim_hi = 7.0f * sl;
-        st.lim_lo = -8.0f * sl;
+        const float inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;   // 1 ulp: < 1e-6 code units
+        st.kmul = inv * (4096.0f / 32767.0f);
         return st;
     };
-    // one unit = 4 consecutive channels of one lane: clamp, round, pack, 2 bytes into the stage buffer
-    constexpr int NUNIT = SPW * A * 4;
-    auto quant_unit = [&](const f32x16 (&acc2)[SPW][A], const Step& st, int buf, int u) {
-        const int q = u / (4 * A), It = (u / 4) % A, g = u % 4;
-        uint8_t* stg = stage + buf * L::STAGE_BYTES;
-        uint32_t bits[4];
+    // One unit = 8 channels of one lane (accumulator registers 8 mm .. 8 mm + 7 of slab q, row tile It: channels
+    // 32 (w SPW + q) + 8 g + 4 h + k, g = 2 mm, 2 mm + 1) -> one dword of nibbles.  When a row tile's units are done, one
+    // exchange between the half-waves (v_permlane32_swap) turns the lane pair's alternating 2-byte pieces into 8 (one
+    // slab per wave) or 16 (two slabs) consecutive bytes of the code row per lane, which are stored at once.
+    constexpr int NUNIT = SPW * A * 2;
+    constexpr float kadd = 2047.5f / 32767.0f;
+    uint32_t Wq[SPW][A][2];
+    auto quant_unit = [&](const f32x16 (&acc2)[SPW][A], const Step& st, int64_t tok, int u) {
+        const int q = u / (2 * A), It = (u / 2) % A, mm = u % 2;
+        uint32_t D[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const float yc = __builtin_amdgcn_fmed3f(acc2[q][It][4 * g + k], st.lim_lo, st.lim_hi);
-            bits[k] = __builtin_bit_cast(uint32_t, __builtin_fmaf(yc, st.inv, 12582920.0f));
+            const float r0 = __builtin_fmaf(acc2[q][It][8 * mm + k], st.kmul, kadd);
+            const float r1 = __builtin_fmaf(acc2[q][It][8 * mm + 4 + k], st.kmul, kadd);
+            D[k] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pknorm_i16(r0, r1));
         }
-        const uint32_t pk = lshl_add(lshl_add(bits[3], 4, bits[2]), 8, lshl_add(bits[1], 4, bits[0])) ^ 0x8888u;
-        // byte offset of channel (ip, jp) / 2 with ip = 32 It + c, jp = 32 (w SPW + q) + 8 g + 4 h: lane part + constant
-        // rows past n1 land in the unused tail of the stage buffer (it holds 32 A rows): no branch around the write
-        *reinterpret_cast<uint16_t*>(stg + stage_lane + 32 * It * L::SPITCH + (32 * q + 8 * g) / 2) = (uint16_t)pk;
+        // bytes 1 and 3 of D[k] carry nibbles k and k + 4 on top: even nibbles -> E, odd ones -> F
+        const uint32_t E = __builtin_amdgcn_perm(D[2], D[0], 0x07030501u);
+        const uint32_t F = __builtin_amdgcn_perm(D[3], D[1], 0x07030501u);
+        Wq[q][It][mm] = (F & 0xF0F0F0F0u) | ((E >> 4) & 0x0F0F0F0Fu);
+        if (mm == 1 && q == SPW - 1) {
+            const int ip = 32 * It + c;
+            uint8_t* dst = p.out_codes + tok * row_bytes_out + ip * (N2 / 2) + 16 * (w * SPW + (SPW == 2 ? h : 0)) + (SPW == 1 ? 8 * h : 0);
+            if constexpr (SPW == 1) {
+                // afterwards half-wave 0 holds the groups g = 0, 1 of both lanes of the pair, half-wave 1 the groups 2, 3
+                const auto sw = __builtin_amdgcn_permlane32_swap(Wq[0][It][0], Wq[0][It][1], false, false);
+                uint2 o;
+                o.x = __builtin_amdgcn_perm(sw[1], sw[0], 0x05040100u);
+                o.y = __builtin_amdgcn_perm(sw[1], sw[0], 0x07060302u);
+                if (FULL1 || ip < n1) *reinterpret_cast<uint2*>(dst) = o;
+            } else {
+                // afterwards half-wave h holds slab q = h of both lanes of the pair
+                u32x4 o;
+#pragma unroll
+                for (int m2 = 0; m2 < 2; ++m2) {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(Wq[0][It][m2], Wq[1][It][m2], false, false);
+                    o[2 * m2] = __builtin_amdgcn_perm(sw[1], sw[0], 0x05040100u);
+                    o[2 * m2 + 1] = __builtin_amdgcn_perm(sw[1], sw[0], 0x07060302u);
+                }
+                if (FULL1 || ip < n1) *reinterpret_cast<u32x4*>(dst) = o;
+            }
+        }
+    };
+    // all of a token's codes, then its step (every lane writes the same two bytes: cheaper than a branch around the store)
+    auto quant_store = [&](const f32x16 (&acc2)[SPW][A], float m, float clipv, int64_t tok) {
+        const Step st = make_step(m, clipv);
+#pragma unroll
+        for (int u = 0; u < NUNIT; ++u) quant_unit(acc2, st, tok, u);
+        p.out_scales[tok] = st.sh;
     };
     // MXFP4: per (row of X~, slab) block of 32 channels; 4 consecutive channels of a lane -> 2 bytes, as for INT4
     auto mx_quant_to_stage = [&](const f32x16 (&acc2)[SPW][A], float clipv) {
@@ -432,8 +465,9 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
                 m = __builtin_fmaxf(m, __shfl_xor(m, 32)) * clipv;
                 const int be = (int)((__builtin_bit_cast(uint32_t, m) >> 23) & 0xffu);   // biased exponent of alpha * max
                 const int e = be > 2 ? be - 2 : 0;
-                // exponent 0 is reached only by an all-zero block (or one below 2^-125): any scale gives zero codes
-                const float scale = __builtin_bit_cast(float, (uint32_t)(e > 0 ? e : 1) << 23);
+                // the conversion reads the exponent field of its scale operand only, and field 0 means 2^-127 (measured),
+                // so the stored exponent is also the one the elements are converted with, down to the bottom of the range
+                const float scale = __builtin_bit_cast(float, (uint32_t)e << 23);
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     uint32_t pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, acc2[q][It][4 * g], acc2[q][It][4 * g + 1], scale, 0);
@@ -443,15 +477,8 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
                 if (h == 0) mxs[(32 * It + c) * B + w * SPW + q] = (uint8_t)e;
             }
     };
-    auto quant_to_stage = [&](const f32x16 (&acc2)[SPW][A], float m, float clipv, int buf) -> _Float16 {
-        const Step st = make_step(m, clipv);
-#pragma unroll
-        for (int u = 0; u < NUNIT; ++u) quant_unit(acc2, st, buf, u);
-        return st.sh;
-    };
-
-    // ---- staged codes of token t -> global memory with 16-byte stores; no branch around the stores when the
-    // row divides evenly, so that the compiler's count of outstanding memory operations stays exact
+    // ---- MXFP4 path: staged codes of token t -> global memory with 16-byte stores; no branch around the stores when
+    // the row divides evenly, so that the compiler's count of outstanding memory operations stays exact
     auto copy_out = [&](int64_t t, int buf, _Float16 sh) {
         const u32x4* stg = reinterpret_cast<const u32x4*>(stage + buf * L::STAGE_BYTES);
         u32x4* dst = reinterpret_cast<u32x4*>(p.out_codes + t * row_bytes_out);
@@ -493,18 +520,17 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
     if constexpr (ONE) {
         const float clipv = clip[p.clip_mode ? t : 0];
         f32x16 acc2[SPW][A];
-        gemm(ts, acc2, [](int) {});   // [phase:contractions done]
-        _Float16 sh = (_Float16)0.0f;
+        gemm(ts, acc2, [](int) {});
         if constexpr (MX) {
             mx_quant_to_stage(acc2, clipv);
+            token_sync();
+            if (live) copy_out(t, ts, (_Float16)0.0f);
         } else {
             absmax_to_lds(acc2, ts);
-            token_sync();                // [phase:absmax exchanged]
+            token_sync();
             const float m = absmax_from_lds(ts);
-            sh = quant_to_stage(acc2, m, clipv, ts);   // [phase:codes staged]
+            if (live) quant_store(acc2, m, clipv, t);
         }
-        token_sync();
-        if (live) copy_out(t, ts, sh);   // [phase:token done]
     } else if constexpr (!PIPE) {
         // One token per step: the tile of token t is in LDS, `pre_next` holds (or is receiving) the row of token t + G
         // and is written to LDS once every wave is done with the current tile; the row of token t + 2G is requested
@@ -513,20 +539,20 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
             issue_clamped(t + (DEEP ? 2 : 1) * G, pre_far);
             const float clipv = clip[p.clip_mode ? t : 0];   // wave-uniform address, read-only: a scalar load
             f32x16 acc2[SPW][A];
-            gemm(0, acc2, [](int) {});   // [phase:contractions done]
+            gemm(0, acc2, [](int) {});
             if constexpr (!MX) absmax_to_lds(acc2, 0);
-            __syncthreads();   // (A) every wave is also done reading the token tile [phase:absmax exchanged]
-            _Float16 sh = (_Float16)0.0f;
+            __syncthreads();   // (A) every wave is also done reading the token tile
             if constexpr (MX) {
                 mx_quant_to_stage(acc2, clipv);
+                commit(pre_next);   // past the end this is the re-read last row; nobody uses it
+                __syncthreads();    // (B) staged codes and the next tile are visible
+                copy_out(t, 0, (_Float16)0.0f);
             } else {
                 const float m = absmax_from_lds(0);
-                sh = quant_to_stage(acc2, m, clipv, 0);
+                quant_store(acc2, m, clipv, t);
+                commit(pre_next);
+                __syncthreads();    // (B) the next tile is visible
             }
-            // [phase:codes staged]
-            commit(pre_next);   // past the end this is the re-read last row; nobody uses it
-            __syncthreads();    // (B) staged codes and the next tile are visible [phase:next tile in LDS]
-            copy_out(t, 0, sh);   // [phase:token done]
         };
         if constexpr (DEEP) {
             while (true) {
@@ -547,10 +573,10 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
         f32x16 accX[SPW][A], accY[SPW][A];
         // prime: token t0 through the contractions; t1's row into tile 1; t2's row requested
         issue_clamped(t + 2 * G, pre0);
-        gemm(0, accX, [](int) {});   // [phase:prime contractions done]
+        gemm(0, accX, [](int) {});
         absmax_to_lds(accX, 0);
         commit(pre1, 1);
-        __syncthreads();   // [phase:primed]
+        __syncthreads();
         float m_cur = absmax_from_lds(0);
         float clip_cur = clip[p.clip_mode ? t : 0];
         // step j (token t = t_j in acc_cur): request t_{j+3}; contractions for t_{j+1} overlap with quantizing t_j;
@@ -563,21 +589,20 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
             const Step st = make_step(m_cur, clip_cur);
             gemm(jb ^ 1, acc_next, [&](int slot) {
 #pragma unroll
-                for (int u = slot * NUNIT / NSLOT; u < (slot + 1) * NUNIT / NSLOT; ++u) quant_unit(acc_cur, st, jb, u);
+                for (int u = slot * NUNIT / NSLOT; u < (slot + 1) * NUNIT / NSLOT; ++u) quant_unit(acc_cur, st, t, u);
             });
-            // [phase:contractions done]
             absmax_to_lds(acc_next, jb ^ 1);
-            commit(pre_commit, jb);   // [phase:codes staged]
-            __syncthreads();          // [phase:next tile in LDS]
-            copy_out(t, jb, st.sh);   // [phase:token done]
+            commit(pre_commit, jb);
+            __syncthreads();          // the next tile and the absmax partials are visible
+            p.out_scales[t] = st.sh;
             m_cur = absmax_from_lds(jb ^ 1);
             clip_cur = clip_next;
         };
         while (true) {
-            if (t + G >= p.T) { const _Float16 sh = quant_to_stage(accX, m_cur, clip_cur, 0); __syncthreads(); copy_out(t, 0, sh); break; }
+            if (t + G >= p.T) { quant_store(accX, m_cur, clip_cur, t); break; }
             step(t, 0, accX, accY, pre0, pre1);
             t += G;
-            if (t + G >= p.T) { const _Float16 sh = quant_to_stage(accY, m_cur, clip_cur, 1); __syncthreads(); copy_out(t, 1, sh); break; }
+            if (t + G >= p.T) { quant_store(accY, m_cur, clip_cur, t); break; }
             step(t, 1, accY, accX, pre1, pre0);
             t += G;
         }
@@ -648,10 +673,10 @@ static Variant variant(int A, int B, bool full1, int mode) {
 template <int A, int B>
 static Variant variant_mx_ab(bool full1, bool one) {
     if constexpr (A <= 2 && B == 2) {
-        if (one && full1) return Variant{&tq_fast_kernel<A, B, 1, true, 2, false, 1, true>, FastLds<A, B>::TOTAL + 32 * A * B};
+        if (one && full1) return Variant{&tq_fast_kernel<A, B, 1, true, 2, false, 1, true>, FastLds<A, B, 1, true>::TOTAL + 32 * A * B};
     }
-    return full1 ? Variant{&tq_fast_kernel<A, B, 1, true, 0, false, 1, true>, FastLds<A, B>::TOTAL + 32 * A * B}
-                 : Variant{&tq_fast_kernel<A, B, 1, false, 0, false, 1, true>, FastLds<A, B>::TOTAL + 32 * A * B};
+    return full1 ? Variant{&tq_fast_kernel<A, B, 1, true, 0, false, 1, true>, FastLds<A, B, 1, true>::TOTAL + 32 * A * B}
+                 : Variant{&tq_fast_kernel<A, B, 1, false, 0, false, 1, true>, FastLds<A, B, 1, true>::TOTAL + 32 * A * B};
 }
 
 template <int A>
@@ -708,8 +733,7 @@ hipError_t tq_mx_launch(const TqDev& d, hipStream_t stream) {
         const int64_t rounds = (d.T + resident - 1) / resident;
         grid = (d.T + rounds - 1) / rounds;
     }
-    hipLaunchKernelGGL(v.fn, dim3((unsigned)grid), dim3(64 * B), v.lds, stream, d, d.clip);
-    return hipGetLastError();
+    return launch(v.fn, dim3((unsigned)grid), dim3(64 * B), v.lds, stream, d, d.clip);
 }
 
 bool tq_fast_applicable(const TqDev& d) {
@@ -774,8 +798,7 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
             const int64_t rounds = (d.T + resident - 1) / resident;
             grid = (d.T + rounds - 1) / rounds;
         }
-        hipLaunchKernelGGL(v.fn, dim3((unsigned)grid), dim3(256), v.lds, stream, d, d.clip);
-        return hipGetLastError();
+        return launch(v.fn, dim3((unsigned)grid), dim3(256), v.lds, stream, d, d.clip);
     }
     {   // 64-wide rows (n1 = 32 or 64): the wave-per-token kernel (fq_tq_wave.hip).  Mode 5: one token per wave, the
         // hardware hands out workgroups as earlier ones retire; mode 6: persistent workgroups.  Measured on MI355X
@@ -820,8 +843,7 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
         if (d.T > 0x7fffffff) return hipErrorInvalidConfiguration;   // only reachable through the tuning overrides
         grid = mode == 4 ? (d.T + kTokensPerWg - 1) / kTokensPerWg : d.T;
     }
-    hipLaunchKernelGGL(v.fn, dim3((unsigned)grid), dim3(nt), v.lds, stream, d, d.clip);
-    return hipGetLastError();
+    return launch(v.fn, dim3((unsigned)grid), dim3(nt), v.lds, stream, d, d.clip);
 }
 
 }  // namespace fq

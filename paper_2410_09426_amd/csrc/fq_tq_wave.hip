@@ -285,9 +285,7 @@ hipError_t tq_wave_launch(const TqDev& d, hipStream_t stream, int tpw, bool loop
         const int64_t rounds = (grid + resident - 1) / resident;
         grid = (grid + rounds - 1) / rounds;
     }
-    (void)hipGetLastError();
-    hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(64 * tpw), lds, stream, d.P2, d.P1, d.x, d.x_stride, d.T, d.clip, d.out_codes, d.out_scales, d.clip_mode);
-    return hipGetLastError();
+    return launch(fn, dim3((unsigned)grid), dim3(64 * tpw), lds, stream, d.P2, d.P1, d.x, d.x_stride, d.T, d.clip, d.out_codes, d.out_scales, d.clip_mode);
 }
 
 }  // namespace fq

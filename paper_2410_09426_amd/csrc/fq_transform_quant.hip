@@ -338,8 +338,7 @@ hipError_t tq_launch(const TqArgs& a, hipStream_t stream) {
     int64_t grid = (int64_t)cu_count() * occ;
     if (grid > a.T) grid = a.T;
 
-    hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(nt), lds, stream, d);
-    return hipGetLastError();
+    return launch(fn, dim3((unsigned)grid), dim3(nt), lds, stream, d);
 }
 
 }  // namespace fq

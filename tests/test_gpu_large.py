@@ -56,7 +56,7 @@ def test_activation_rows_past_4_gib():
     y = fo.affine_transform(xs, c.P1, c.P2)
     rep = parity.check_sym(y, 0.9, codes[idx].cpu().numpy(), host_f16(scales[idx]), rows=rows)
     print(f"[parity] rows {rows.tolist()}: {rep}", flush=True)
-    assert rep["band_flips"] <= max(4, rep["in_band"])
+    assert rep["band_flips"] <= parity.band_flip_allowance(rep["in_band"])
 
 
 def test_kv_cache_past_4_gib():

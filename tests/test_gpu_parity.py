@@ -37,7 +37,7 @@ def check_case(c, rows=None, with_dequant=True, label=""):
         deq = run_dequant(codes_d, scales_d, None, c.T, c.n)[rows]
     rep = parity.check_sym(y, clipv, codes[rows], scales[rows], deq_dev=deq, rows=rows)
     print(f"[parity] {c.name}: {rep}", flush=True)
-    assert rep["band_flips"] <= max(4, rep["in_band"])
+    assert rep["band_flips"] <= parity.band_flip_allowance(rep["in_band"])
     return rep, codes, scales
 
 
@@ -249,7 +249,7 @@ def test_alignment_and_stride_grid(n1, n2, T, pad, xoff, poff, guard):
     rows = subset_rows(T, 100, 33, must=(0, 1, T - 2))
     y = fo.affine_transform_factored(c.x[rows], c.P1, c.P2)
     rep = parity.check_sym(y, c.clip[rows], codes[rows], scales[rows], rows=rows)
-    assert rep["band_flips"] <= max(4, rep["in_band"])
+    assert rep["band_flips"] <= parity.band_flip_allowance(rep["in_band"])
 
 
 def test_determinism_and_empty_input():
@@ -326,6 +326,17 @@ def test_mxfp4_output(tuning, mode):
         assert not codes[2].any() and not exps[2].any()
 
 
+def test_mxfp4_bottom_of_the_exponent_range():
+    """Blocks whose clipped maximum lies below 2^-124 store exponent 0 (scale 2^-127, the smallest the format has) and
+    their elements are converted with that scale; just above, exponents 1, 2, ...  Reached here through a tiny
+    clipping threshold (it multiplies the block maximum before the exponent is taken)."""
+    c = synth.generic(431, 24, 64, 64, clip_mode=1)
+    c.clip[:] = np.float32(2.0) ** -np.arange(100, 124).astype(np.float32)   # alpha * max from about 2^-97 down to 2^-121
+    c.x[:] = (c.x.astype(np.float32) * 2.0 ** -6).astype(np.float16)          # block maxima around 2^-6 .. 2^2
+    codes, exps = run_mx(c)
+    assert exps.min() <= 2 and exps.max() >= 20, (exps.min(), exps.max())    # the case does reach the bottom
+
+
 def _grid_cases():
     """Left factors around every row-tile edge x right factors of every slab count x token counts below, at and above
     what is resident at once (a seeded selection of the full grid: every value of each axis appears several times)."""
@@ -356,7 +367,7 @@ def test_shape_grid(n1, n2, T):
     y = fo.affine_transform_factored(c.x[rows], c.P1, c.P2)
     rep = parity.check_sym(y, c.clip[rows], codes[rows], scales[rows], rows=rows)
     print(f"[parity] {rep}", flush=True)
-    assert rep["band_flips"] <= max(4, rep["in_band"])
+    assert rep["band_flips"] <= parity.band_flip_allowance(rep["in_band"])
 
 
 # ---- KV-cache variant --------------------------------------------------------------------
@@ -389,6 +400,32 @@ def test_kv_cache(T, H, shared):
         y = fo.kv_transform(tensor, P).reshape(T * H, kv.D)
         rep = parity.check_kv(y, kv.clip, codes, sc, zr, deq_dev=deq)
         print(f"[parity] kv {name}: {rep}", flush=True)
+
+
+def test_kv_ties_round_to_even_before_the_zero_point():
+    """q = clamp(rne(y / s) + z): the rounding acts on y / s alone.  With P = I and clip = 1 a group whose range is
+    [-3, 12] has step 1 and zero point 3 (odd): the exact ties k + 0.5 must go to the even neighbour of k + 0.5 and then
+    be shifted, not to the even neighbour of k + 3.5.  Bit-exact against the oracle (no band)."""
+    D, H = 128, 2
+    vals = np.array([-3.0, 12.0] + [k + 0.5 for k in range(-3, 12)] + [0.0, 1.0, -1.0, 2.25, 7.75], dtype=np.float64)
+    kv = np.zeros((5, H, D), dtype=np.float16)
+    for t in range(5):
+        for hh in range(H):
+            row = np.zeros(D)
+            row[:len(vals)] = vals
+            row = np.roll(row, 7 * t + 3 * hh)
+            if hh == 1:
+                row[row == -3.0] = -5.0      # head 1: range [-5, 12] -> step 17/15 is no power of two: no exact ties, z = rne(5 / s)
+            kv[t, hh] = row
+    P = np.broadcast_to(np.eye(D, dtype=np.float16), (H, D, D)).copy()
+    for bits in (None, 3):
+        codes, sc, zr, _ = run_kv(kv, P, H, 1.0, bits)
+        res = fo.kv_transform_quant(kv, P, 1.0, bits or 4)
+        G = 5 * H
+        if bits is None:
+            assert np.all(sc.reshape(5, H)[:, 0] == 1.0) and np.all(zr.reshape(5, H)[:, 0] == 3.0)
+        assert np.array_equal(sc, res["scales"].reshape(G)) and np.array_equal(zr.astype(np.float64), res["zeros"].reshape(G).astype(np.float64))
+        assert np.array_equal(codes, res["codes"].reshape(G, -1)), "tie handling differs from rne(y / s) + z"
 
 
 @pytest.mark.parametrize("bits", [4, 3])
@@ -511,7 +548,7 @@ def test_weight_side_parity_and_quantized_layer(T, m, n1, n2):
     yw = fo.weight_transform_factored(W, A1, A2)
     rep = parity.check_sym(yw, cw, wcodes.cpu().numpy(), wsc.cpu().numpy().view(np.float16))
     print(f"[parity] weight side {n1}x{n2}: {rep}", flush=True)
-    assert rep["band_flips"] <= max(4, rep["in_band"])
+    assert rep["band_flips"] <= parity.band_flip_allowance(rep["in_band"])
 
     # activation side, then the layer: deq(Q(XP)) deq(Q(P^-1 W^T)) vs X W^T
     xcodes, xsc, xcodes_d, xsc_d = run_tq(dev(c.x), dev(c.P1), dev(c.P2), dev(c.clip), 1, n1, n2)
@@ -811,7 +848,7 @@ def test_one_sided_transforms(n1, n2, T, which):
     y = fo.affine_transform(c.x[rows], P1, P2)
     rep = parity.check_sym(y, c.clip[rows], codes[rows], scales[rows], rows=rows)
     print(f"[parity] one-sided {which}: {rep}", flush=True)
-    assert rep["band_flips"] <= max(4, rep["in_band"])
+    assert rep["band_flips"] <= parity.band_flip_allowance(rep["in_band"])
 
 
 def _one_sided_grid():
@@ -838,7 +875,7 @@ def test_one_sided_shape_grid(n1, n2, T, which):
     y = fo.affine_transform_factored(c.x[rows], P1, P2)
     rep = parity.check_sym(y, c.clip[rows], codes[rows], scales[rows], rows=rows)
     print(f"[parity] {rep}", flush=True)
-    assert rep["band_flips"] <= max(4, rep["in_band"])
+    assert rep["band_flips"] <= parity.band_flip_allowance(rep["in_band"])
 
 
 @pytest.mark.parametrize("T,H,shared", [(4096, 8, False), (1, 8, False), (77, 3, False), (200, 8, True), (31, 2, True), (32, 5, False), (33, 16, True),
