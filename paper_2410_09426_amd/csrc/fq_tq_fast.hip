@@ -134,10 +134,21 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
     auto stage_p1 = [&](auto&& after_first_loads) {
         const int n1sq = n1 * n1;
         bool queued = false;               // after_first_loads() has run
+        constexpr int PW = 32 * A;         // pitch of the LDS copy: n1 rounded up to whole row tiles
+        // `nh` consecutive elements of P1 starting at flat index f0 -> the LDS copy.  With n1 a multiple of 32 the copy
+        // is the matrix as it is; otherwise its rows are re-pitched to PW, one element at a time
+        auto put = [&](int f0, const _Float16* e, int nh) {
+            int row = f0 / n1, col = f0 - row * n1;
+            for (int k = 0; k < nh; ++k) {
+                P1flat[row * PW + col] = e[k];
+                if (++col == n1) { col = 0; ++row; }
+            }
+        };
         auto copy_batched = [&](auto* dst, const auto* src, int count) {
             constexpr int BATCH = 8;
+            using Unit = decltype(*src + 0);
             for (int base = 0; base < count; base += BATCH * NTA) {
-                decltype(*src + 0) v[BATCH];
+                Unit v[BATCH];
 #pragma unroll
                 for (int k = 0; k < BATCH; ++k) {
                     const int idx = base + k * NTA + tida;
@@ -152,20 +163,35 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
 #pragma unroll
                 for (int k = 0; k < BATCH; ++k) {
                     const int idx = base + k * NTA + tida;
-                    if (idx < count) dst[idx] = v[k];
+                    if (idx < count) {
+                        if constexpr (FULL1) dst[idx] = v[k];
+                        else put(idx * (int)(sizeof(Unit) / 2), reinterpret_cast<const _Float16*>(&v[k]), (int)(sizeof(Unit) / 2));
+                    }
                 }
             }
         };
+        if constexpr (!FULL1) {
+            // the padding of the copy must read as zero: whole rows past n1 (16-byte units), then the tails of the rows
+            for (int q = tida; q < (PW - n1) * PW / 8; q += NTA) reinterpret_cast<u32x4*>(P1flat + n1 * PW)[q] = u32x4{0u, 0u, 0u, 0u};
+            for (int r = tida; r < n1; r += NTA)
+                for (int cc = n1; cc < PW; ++cc) P1flat[r * PW + cc] = (_Float16)0;
+        }
         if ((reinterpret_cast<uintptr_t>(p.P1) & 15) == 0) {   // bulk in 16-byte chunks, then up to 7 single elements
             const int done = n1sq & ~7;
             const int ti = done + tida < n1sq ? done + tida : n1sq - 1;
             const _Float16 tail = p.P1[ti];
             copy_batched(reinterpret_cast<u32x4*>(P1flat), reinterpret_cast<const u32x4*>(p.P1), n1sq >> 3);
-            if (done + tida < n1sq) P1flat[ti] = tail;
+            if (done + tida < n1sq) {
+                if constexpr (FULL1) P1flat[ti] = tail;
+                else put(ti, &tail, 1);
+            }
         } else {   // only 4-byte aligned: pairs, plus a last odd element
             const _Float16 tail = p.P1[n1sq - 1];
             copy_batched(reinterpret_cast<uint32_t*>(P1flat), reinterpret_cast<const uint32_t*>(p.P1), n1sq >> 1);
-            if ((n1sq & 1) && tida == 0) P1flat[n1sq - 1] = tail;
+            if ((n1sq & 1) && tida == 0) {
+                if constexpr (FULL1) P1flat[n1sq - 1] = tail;
+                else put(n1sq - 1, &tail, 1);
+            }
         }
         if (!queued) after_first_loads();   // a P1 of fewer elements than one load unit (n1 = 1, 2): no batch ran
     };
@@ -205,43 +231,21 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
         }
         if (pass == 0) {
             // P1 fragments, gathered with the k-permutation of the first contraction's accumulator layout:
-            // K block kk, slot s, half-wave h  <->  i = 32(kk/2) + 8(2(kk%2) + s/4) + 4h + s%4
+            // K block kk, slot s, half-wave h  <->  i = 32(kk/2) + 8(2(kk%2) + s/4) + 4h + s%4.  The LDS copy is padded with
+            // zeros to whole row tiles, so ragged factors take the same transposing reads as full ones.
             if constexpr (P1LDS) {
-                for (int e = tid; e < A * KB1 * 64; e += NT) {
+                for (int e = tid; e < A * KB1 * 64; e += NT) {   // e % 64 is the lane: whole 16-lane blocks cooperate in the reads
                     const int ln = e & 63, kk = (e >> 6) % KB1, It = (e >> 6) / KB1;
-                    const int cc = ln & 31, hh = ln >> 5, ip = 32 * It + cc;
-                    half8 f;
-                    if constexpr (FULL1) {   // e % 64 is the lane: whole 16-lane blocks cooperate in the transposing reads
-                        f = lds_column8(P1flat, 32 * A, 32 * (kk >> 1) + 16 * (kk & 1) + 4 * hh, 8, 32 * It + (cc & 16), ln & 15);
-                    } else {
-#pragma unroll
-                        for (int s = 0; s < 8; ++s) {
-                            const int i = 32 * (kk >> 1) + 8 * (2 * (kk & 1) + (s >> 2)) + 4 * hh + (s & 3);
-                            const bool ok = i < n1 && ip < n1;
-                            const _Float16 v = P1flat[ok ? i * n1 + ip : 0];   // unconditional read, then select: no branch per element
-                            f[s] = ok ? v : (_Float16)0;
-                        }
-                    }
+                    const int cc = ln & 31, hh = ln >> 5;
+                    const half8 f = lds_column8(P1flat, 32 * A, 32 * (kk >> 1) + 16 * (kk & 1) + 4 * hh, 8, 32 * It + (cc & 16), ln & 15);
                     *reinterpret_cast<half8*>(&P1s[e]) = f;
                 }
             } else {
 #pragma unroll
                 for (int It = 0; It < A; ++It)
 #pragma unroll
-                    for (int kk = 0; kk < KB1; ++kk) {
-                        const int ip = 32 * It + c;
-                        if constexpr (FULL1) {
-                            p1f[It][kk] = lds_column8(P1flat, 32 * A, 32 * (kk >> 1) + 16 * (kk & 1) + 4 * h, 8, 32 * It + (c & 16), l & 15);
-                        } else {
-#pragma unroll
-                            for (int s = 0; s < 8; ++s) {
-                                const int i = 32 * (kk >> 1) + 8 * (2 * (kk & 1) + (s >> 2)) + 4 * h + (s & 3);
-                                const bool ok = i < n1 && ip < n1;
-                                const _Float16 v = P1flat[ok ? i * n1 + ip : 0];
-                                p1f[It][kk][s] = ok ? v : (_Float16)0;
-                            }
-                        }
-                    }
+                    for (int kk = 0; kk < KB1; ++kk)
+                        p1f[It][kk] = lds_column8(P1flat, 32 * A, 32 * (kk >> 1) + 16 * (kk & 1) + 4 * h, 8, 32 * It + (c & 16), l & 15);
             }
         }
     }
