@@ -9,10 +9,19 @@
  *
  * General rules for every entry point
  *   - All data pointers are DEVICE pointers unless a comment says "host".
- *   - The caller owns every buffer.  The library allocates nothing, keeps no
- *     state besides a thread-local last-HIP-error code, and never synchronises:
- *     work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
- *     default stream) and outputs are valid once the stream reaches that point.
+ *   - The caller owns every buffer.  The library allocates nothing and never
+ *     synchronises: work is enqueued on `stream` (a hipStream_t passed as
+ *     void*; NULL is the default stream) and outputs are valid once the stream
+ *     reaches that point.
+ *   - State the library keeps: a thread-local last-HIP-error code
+ *     (fq_last_hip_error), per-device launch facts cached on first use (number
+ *     of compute units, workgroups per compute unit of each kernel), and the
+ *     process-wide tuning overrides of fq_set_tuning (launch-shape choices for
+ *     measurements and tests; they never change results).  Nothing else:
+ *     calls are independent and may come from several threads at once.
+ *   - Two entry points are measurement aids and not part of the method:
+ *     flatquant_stream_probe (the activation kernel's memory traffic without
+ *     its arithmetic) and fq_set_tuning.
  *   - Inputs are never modified.  Inputs and outputs must not overlap.
  *   - Errors are reported through the return value only (no abort, no output).
  *     On any error nothing is launched and no output byte is written.
@@ -220,9 +229,11 @@ fq_status flatquant_dequant_bits(const uint8_t* codes, const void* scales, const
 /*
  * Measurement aid (not part of the method): moves the bytes of flatquant_transform_quant without its arithmetic.
  * Reads every row of x once (fp16 [T, n], x_stride halves apart) and writes n/2 bytes per row to out ([T, n/2],
- * an xor-fold of the row, contents meaningless).  Same persistent one-workgroup-per-row traffic pattern, 16-byte
- * non-temporal accesses.  Requires n % 32 == 0, x and out 16-byte aligned, x_stride % 8 == 0.  The time of one
- * call is the ceiling that launch cost and memory latency leave for a launch of that size on this machine.
+ * an xor-fold of the row, contents meaningless) with 16-byte accesses, in one of three launch shapes (tuning override
+ * FLATQUANT_PROBE_SHAPE: 0 persistent two-wave workgroups, one row at a time; 1 one wave per row, every load of the
+ * row in flight at once; 2 the same with ordinary instead of non-temporal loads).  Requires n % 32 == 0, x and out
+ * 16-byte aligned, x_stride % 8 == 0.  The fastest shape's time is the ceiling that launch cost and memory latency
+ * leave for a copy-like launch of that size on this machine.
  */
 fq_status flatquant_stream_probe(const void* x, int64_t T, int n, int64_t x_stride, uint8_t* out, void* stream);
 
@@ -259,13 +270,15 @@ int fq_abi_version(void);
 
 /*
  * Tuning overrides, for measurements and tests (the defaults are what the library measures best).  `name` is one of
- * FLATQUANT_MODE (activation kernel flavour 0..4), FLATQUANT_WG_PER_CU, FLATQUANT_KV_WG_PER_CU (cap on resident
+ * FLATQUANT_MODE (activation kernel flavour: 0..4 the slab kernels, 5 / 6 the wave-per-token kernel of 64-wide rows, one
+ * shot / persistent), FLATQUANT_WAVE_TPW (2 / 4 / 8 waves per workgroup of that kernel), FLATQUANT_PROBE_SHAPE (0..2: launch
+ * shape of flatquant_stream_probe), FLATQUANT_WG_PER_CU, FLATQUANT_KV_WG_PER_CU (cap on resident
  * workgroups), FLATQUANT_FORCE_GENERIC (1: general kernel on shapes the specialised ones would take),
  * FLATQUANT_GEMM_TILED (1: tiled product for any T), FLATQUANT_GEMM_WIDE (0 / 1: 128- or 256-token tiles),
  * FLATQUANT_GEMM_ROWS (16 / 32 output channels per workgroup), FLATQUANT_GEMM_WAVES (4 / 8 / 16) and
  * FLATQUANT_GEMM_DEPTH (1..8 line slots per wave) of the few-token products, FLATQUANT_GEMM_RING_MAX_T (token count up to
- * which the few-token kernel is used), FLATQUANT_KV_FOLD_HEADS (0: a shared P_h is applied head by head like separate ones).  enable != 0 sets the override to `value`, enable == 0
- * removes it.  Each override starts from the environment variable of the same name, read once per process.
+ * which the few-token kernel is used), FLATQUANT_KV_FOLD_HEADS (0: a shared P_h is applied head by head like separate
+ * ones).  enable != 0 sets the override to `value`, enable == 0 removes it.  Each override starts from the environment variable of the same name, read once per process.
  * Process-wide; affects launches issued after the call returns.  Unknown names return FQ_INVALID_ARG.
  */
 fq_status fq_set_tuning(const char* name, int value, int enable);

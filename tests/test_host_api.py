@@ -216,3 +216,97 @@ def test_inverse_transpose_helper_against_numpy():
     assert fq.lib().fq_inverse_transpose(None, 4, None, None) == fq.FQ_INVALID_ARG
     assert fq.flatquant_weight_transform_quant(None, None, None, None, 0, 0, 64, 64, 4096, None, None, check=False) == fq.FQ_OK
     assert fq.flatquant_weight_transform_quant(None, None, None, None, 0, 5, 64, 64, 4096, None, None, check=False) == fq.FQ_INVALID_ARG
+
+
+def test_host_layer_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The host side of the API layer (argument checks, overlap arithmetic, fq_inverse_transpose, fq_choose_factors, the
+    tuning table) compiled with -fsanitize=address,undefined (host pass only; the kernels' objects are the library's own)
+    and driven by a C program through every host-only path and every rejection that returns before a device is touched."""
+    import glob
+    import shutil
+    import subprocess
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    clang = "/opt/rocm/lib/llvm/bin/clang"
+    csrc = os.path.join(ROOT, "paper_2410_09426_amd", "csrc")
+    objs = [o for o in glob.glob(os.path.join(csrc, "*.o")) if os.path.basename(o) != "fq_api.o"]
+    if not (os.path.exists(hipcc) and os.path.exists(clang)) or len(objs) < 5:
+        pytest.skip("needs hipcc, its clang and the library's object files (python -m paper_2410_09426_amd.build)")
+    api_o = tmp_path / "fq_api_san.o"
+    subprocess.run([hipcc, "-O1", "-g", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-w",
+                    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                    "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                    "-Xarch_host", "-fno-sanitize-recover=undefined",
+                    "-c", os.path.join(csrc, "fq_api.hip"), "-o", str(api_o)], check=True, capture_output=True)
+    lib = tmp_path / "libflatquant_san.so"
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-w", "-fsanitize=address", "-fsanitize=undefined",
+                    str(api_o), *objs, "-o", str(lib)], check=True, capture_output=True)
+    src = tmp_path / "drive.c"
+    src.write_text(r"""
+#include "flatquant.h"
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#define CHECK(cond) do { if (!(cond)) { printf("line %d: %s\n", __LINE__, #cond); return 1; } } while (0)
+static unsigned short h(float v) { /* a few exact fp16 constants */
+    if (v == 0.0f) return 0; if (v == 1.0f) return 0x3c00; if (v == 2.0f) return 0x4000; if (v == 0.5f) return 0x3800;
+    if (v == -1.0f) return 0xbc00; if (v == 4.0f) return 0x4400; if (v == 0.25f) return 0x3400; return 0x7e00; }
+int main(void) {
+    int n1 = 0, n2 = 0;
+    CHECK(fq_choose_factors(8192, &n1, &n2) == FQ_OK && n1 == 64 && n2 == 128);
+    CHECK(fq_choose_factors(11008, &n1, &n2) == FQ_OK && n1 == 86 && n2 == 128);
+    CHECK(fq_choose_factors(1, &n1, &n2) == FQ_OK && n1 == 1 && n2 == 1);
+    CHECK(fq_choose_factors(2147483647, &n1, &n2) == FQ_OK && (long long)n1 * n2 == 2147483647LL);
+    CHECK(fq_choose_factors(0, &n1, &n2) == FQ_INVALID_ARG && fq_choose_factors(-5, &n1, &n2) == FQ_INVALID_ARG);
+    CHECK(fq_supported(64, 64) && fq_supported(1, 2) && !fq_supported(129, 64) && !fq_supported(64, 258) && !fq_supported(0, 4) && !fq_supported(-3, -3));
+    CHECK(fq_lds_bytes(64, 64) > 0 && fq_lds_bytes(112, 256) > 0 && fq_lds_bytes(1000, 2) == 0);
+    CHECK(fq_default_design_fits(64, 64, 160 * 1024) == 1 && fq_default_design_fits(112, 256, 160 * 1024) == 0);
+    CHECK(strlen(fq_status_string(FQ_MISALIGNED)) > 0 && strlen(fq_status_string(12345)) > 0 && strlen(fq_status_string(-1)) > 0);
+    /* rejections that return before any device call */
+    char* buf = (char*)malloc(1 << 16);   /* host memory standing in for device pointers: never dereferenced on these paths */
+    float clip = 1.0f;
+    CHECK(flatquant_transform_quant(buf, buf, buf, &clip, 0, -1, 64, 64, 4096, (uint8_t*)buf, buf, 0) == FQ_INVALID_ARG);
+    CHECK(flatquant_transform_quant(buf, buf, buf, &clip, 2, 4, 64, 64, 4096, (uint8_t*)buf, buf, 0) == FQ_INVALID_ARG);
+    CHECK(flatquant_transform_quant(buf, buf, buf, &clip, 0, 4, 3, 5, 15, (uint8_t*)buf, buf, 0) == FQ_INVALID_ARG);      /* odd n */
+    CHECK(flatquant_transform_quant(buf, buf, buf, &clip, 0, 4, 64, 64, 100, (uint8_t*)buf, buf, 0) == FQ_INVALID_ARG);   /* stride < n */
+    CHECK(flatquant_transform_quant(buf, buf, buf, &clip, 0, 4, 200, 64, 12800, (uint8_t*)buf, buf, 0) == FQ_UNSUPPORTED_SHAPE);
+    CHECK(flatquant_transform_quant(0, 0, 0, 0, 0, 0, 64, 64, 4096, 0, 0, 0) == FQ_OK);                                     /* T == 0 */
+    CHECK(flatquant_transform_quant(0, buf, buf, &clip, 0, 4, 64, 64, 4096, (uint8_t*)buf, buf, 0) == FQ_INVALID_ARG);     /* null x */
+    CHECK(flatquant_transform_quant(buf, buf, buf, &clip, 0, 1, 2, 2, 4, (uint8_t*)buf + 1, buf + 4096, 0) != FQ_OK);      /* output inside the input */
+    CHECK(flatquant_kv_transform_quant(buf, buf, 3, 0.9f, 4, 8, 128, (uint8_t*)buf, buf, buf, 0) != FQ_OK);                /* Hp neither 1 nor H */
+    CHECK(flatquant_kv_transform_quant(buf, buf, 1, 0.9f, 4, 8, 64, (uint8_t*)buf, buf, buf, 0) != FQ_OK);                 /* D != 128 */
+    CHECK(flatquant_kv_transform_quant(0, 0, 1, 0.9f, 0, 8, 128, 0, 0, 0, 0) == FQ_OK);                                     /* T == 0 */
+    CHECK(flatquant_dequant((const uint8_t*)buf, buf, 0, -1, 64, (float*)buf, 0) == FQ_INVALID_ARG);
+    CHECK(flatquant_w4a4_gemm(0, 0, 0, 0, 4, 8, 256, 0, 8, 0) == FQ_INVALID_ARG && flatquant_w4a4_gemm(0, 0, 0, 0, 4, 8, 64, 0, 8, 0) == FQ_UNSUPPORTED_SHAPE);
+    CHECK(fq_set_tuning("FLATQUANT_NO_SUCH_KNOB", 1, 1) == FQ_INVALID_ARG && fq_set_tuning(0, 1, 1) == FQ_INVALID_ARG);
+    CHECK(fq_set_tuning("FLATQUANT_MODE", 3, 1) == FQ_OK && fq_set_tuning("FLATQUANT_MODE", 0, 0) == FQ_OK);
+    /* fq_inverse_transpose: diag(1, 2, 0.5) -> diag(1, 0.5, 2); a permutation; a singular matrix; sizes 1 and 256; bad sizes */
+    unsigned short P[9] = {0}, O[9];
+    P[0] = h(1); P[4] = h(2); P[8] = h(0.5f);
+    double res = -1;
+    CHECK(fq_inverse_transpose(P, 3, O, &res) == FQ_OK && O[0] == h(1) && O[4] == h(0.5f) && O[8] == h(2) && O[1] == 0 && res == 0.0);
+    unsigned short Q[4] = {0, 0x3c00, 0x3c00, 0}, R[4];
+    CHECK(fq_inverse_transpose(Q, 2, R, 0) == FQ_OK && R[0] == 0 && R[1] == h(1) && R[2] == h(1) && R[3] == 0);
+    unsigned short S[4] = {0x3c00, 0x4000, 0x4000, 0x4400};   /* [[1, 2], [2, 4]] */
+    CHECK(fq_inverse_transpose(S, 2, R, &res) == FQ_INVALID_ARG);
+    unsigned short one = h(4), inv1 = 0;
+    CHECK(fq_inverse_transpose(&one, 1, &inv1, 0) == FQ_OK && inv1 == h(0.25f));
+    CHECK(fq_inverse_transpose(P, 0, O, 0) == FQ_INVALID_ARG && fq_inverse_transpose(P, 257, O, 0) == FQ_INVALID_ARG);
+    CHECK(fq_inverse_transpose(0, 3, O, 0) == FQ_INVALID_ARG && fq_inverse_transpose(P, 3, 0, 0) == FQ_INVALID_ARG);
+    unsigned short* big = (unsigned short*)calloc(256 * 256, 2);
+    unsigned short* bigo = (unsigned short*)malloc(256 * 256 * 2);
+    for (int i = 0; i < 256; ++i) big[i * 256 + (i * 7 + 3) % 256] = (i & 1) ? h(2) : h(-1);   /* a scaled permutation, 256 x 256 */
+    CHECK(fq_inverse_transpose(big, 256, bigo, &res) == FQ_OK && res == 0.0);
+    for (int i = 0; i < 256; ++i) CHECK(bigo[i * 256 + (i * 7 + 3) % 256] == ((i & 1) ? h(0.5f) : h(-1)));
+    free(big); free(bigo); free(buf);
+    CHECK(fq_mxfp4_tiled_scale_bytes(130, 512) == 2 * 2 * 128 * 8 && fq_mxfp4_tiled_scale_bytes(0, 512) == 0);
+    printf("sanitized host layer ok\n");
+    return 0;
+}
+""")
+    exe = tmp_path / "drive"
+    subprocess.run([clang, "-std=c99", "-g", "-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined",
+                    "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe), "-L", str(tmp_path), "-lflatquant_san",
+                    f"-Wl,-rpath,{tmp_path}"], check=True, capture_output=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
+    assert r.returncode == 0 and "sanitized host layer ok" in r.stdout, r.stdout[-2000:] + r.stderr[-4000:]
