@@ -87,8 +87,8 @@ fq_status flatquant_transform_quant(const void* x, const void* P1, const void* P
  *                                    code = sign << 3 | magnitude index (a negative value that rounds to zero is -0)
  *   out_codes  u8 [T, n/2], even channel in the low nibble, 16-byte aligned.
  *   out_scales u8 [T, n/32], 4-byte aligned.
- * Shapes: n2 = 64, 128 or 256, n1 <= 128, n a multiple of 128; x 16-byte aligned with x_stride a multiple of 8; P1 4-byte
- * and P2 16-byte aligned, both required.  Other arguments, T == 0 and error behaviour as for flatquant_transform_quant.
+ * Shapes: n2 a multiple of 32 up to 256 (a block is then 32 consecutive channels inside one row of X~), n1 <= 128, n a
+ * multiple of 128; x 16-byte aligned with x_stride a multiple of 8; P1 4-byte and P2 16-byte aligned, both required.  Other arguments, T == 0 and error behaviour as for flatquant_transform_quant.
  */
 fq_status flatquant_transform_mxfp4(const void* x, const void* P1, const void* P2,
                                     const float* clip, int clip_mode,

@@ -150,7 +150,7 @@ static fq_status transform_mxfp4(const void* x, const void* P1, const void* P2, 
     if (T < 0 || n1 < 1 || n2 < 1 || (clip_mode != 0 && clip_mode != 1)) return FQ_INVALID_ARG;
     const int64_t n = (int64_t)n1 * n2;
     if (x_stride < n) return FQ_INVALID_ARG;
-    if (n1 > fq::kMaxN1 || !(n2 == 64 || n2 == 128 || n2 == 256) || n % 128 != 0) return FQ_UNSUPPORTED_SHAPE;
+    if (n1 > fq::kMaxN1 || n2 % 32 != 0 || n2 > fq::kMaxN2 || n % 128 != 0) return FQ_UNSUPPORTED_SHAPE;
     if (tiled && n % 256 != 0) return FQ_UNSUPPORTED_SHAPE;
     if (T == 0) return FQ_OK;
     if (!x || !P1 || !P2 || !clip || !out_codes || !out_scales) return FQ_INVALID_ARG;

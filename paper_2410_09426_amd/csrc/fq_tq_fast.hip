@@ -672,7 +672,7 @@ static Variant variant(int A, int B, bool full1, int mode) {
     }
 }
 
-// MXFP4 output: n2 = 64, 128 or 256; loop-free kernel while every token gets a resident workgroup (64-wide rows), else
+// MXFP4 output: n2 a multiple of 32; loop-free kernel while every token gets a resident workgroup (64-wide rows), else
 // the plain persistent loop.  The shared exponents of a token are staged in LDS behind the kernel's usual carve-up.
 template <int A, int B>
 static Variant variant_mx_ab(bool full1, bool one) {
@@ -686,8 +686,13 @@ static Variant variant_mx_ab(bool full1, bool one) {
 template <int A>
 static Variant variant_mx_a(int B, bool full1, bool one) {
     switch (B) {
+        case 1: return variant_mx_ab<A, 1>(full1, one);
         case 2: return variant_mx_ab<A, 2>(full1, one);
+        case 3: return variant_mx_ab<A, 3>(full1, one);
         case 4: return variant_mx_ab<A, 4>(full1, one);
+        case 5: return variant_mx_ab<A, 5>(full1, one);
+        case 6: return variant_mx_ab<A, 6>(full1, one);
+        case 7: return variant_mx_ab<A, 7>(full1, one);
         default: return variant_mx_ab<A, 8>(full1, one);
     }
 }
@@ -702,7 +707,7 @@ static Variant variant_mx(int A, int B, bool full1, bool one) {
 }
 
 bool tq_mx_applicable(const TqDev& d) {
-    if (!(d.n2 == 64 || d.n2 == 128 || d.n2 == 256) || d.n1 < 1 || d.n1 > kMaxN1) return false;
+    if (d.n2 % 32 != 0 || d.n2 < 32 || d.n2 > kMaxN2 || d.n1 < 1 || d.n1 > kMaxN1) return false;
     if (((int64_t)d.n1 * d.n2) % 128 != 0 || !d.vec8 || !d.out_vec16 || !d.P1 || !d.P2) return false;
     if ((reinterpret_cast<uintptr_t>(d.P2) & 15) || (reinterpret_cast<uintptr_t>(d.P1) & 3)) return false;
     return (reinterpret_cast<uintptr_t>(d.out_scales) & 3) == 0;

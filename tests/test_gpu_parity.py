@@ -292,8 +292,8 @@ def _mx_grid():
     r = np.random.Generator(np.random.PCG64(3141))
     cases = set()
     for n1 in [1, 2, 3, 31, 32, 33, 63, 64, 65, 96, 100, 127, 128]:
-        for n2 in (64, 128, 256):
-            if (n1 * n2) % 128 == 0 and r.random() < 0.75:
+        for n2 in (32, 64, 96, 128, 160, 192, 224, 256):
+            if (n1 * n2) % 128 == 0 and r.random() < (0.75 if n2 in (64, 128, 256) else 0.4):
                 T = int(r.choice([1, 2, 63, 300, 2049, 2600]))
                 cases.add((n1, n2, min(T, max(600, 20_000_000 // (n1 * n2)))))
     return sorted(cases)
@@ -316,7 +316,7 @@ def test_mxfp4_output(tuning, mode):
     run_mx(c)
     if mode == "-1":
         for seed, T, n1, n2 in ((411, 33, 86, 128), (412, 9, 112, 256), (413, 1, 32, 64), (414, 300, 2, 64), (415, 40, 50, 256),
-                                (416, 2600, 64, 64)):
+                                (416, 2600, 64, 64), (418, 77, 128, 224), (419, 40, 64, 32), (420, 130, 96, 160), (421, 300, 12, 96)):
             c = synth.generic(seed, T, n1, n2, clip_mode=seed % 2)
             run_mx(c, rows=None if T <= 300 else subset_rows(T, 120, 22, must=(0, T - 1)))
         # zero rows: exponent 0, all codes +0

@@ -39,7 +39,7 @@ def test_header_is_plain_c_and_links_without_python(tmp_path):
         "    if (fq_choose_factors(8192, &n1, &n2) != FQ_OK || n1 != 64 || n2 != 128) return 1;\n"
         "    if (!fq_supported(64, 64) || fq_supported(129, 64)) return 2;\n"
         "    if (flatquant_transform_quant(0, 0, 0, 0, 0, 0, 64, 64, 4096, 0, 0, 0) != FQ_OK) return 3;      /* T == 0 */\n"
-        "    if (flatquant_transform_mxfp4(0, 0, 0, 0, 0, 4, 64, 96, 6144, 0, 0, 0) != FQ_UNSUPPORTED_SHAPE) return 4;\n"
+        "    if (flatquant_transform_mxfp4(0, 0, 0, 0, 0, 4, 64, 172, 11008, 0, 0, 0) != FQ_UNSUPPORTED_SHAPE) return 4;\n"
         '    printf("%s %d\\n", fq_status_string(FQ_MISALIGNED), fq_abi_version());\n'
         "    return 0;\n}\n")
     inc = os.path.join(ROOT, "include")
