@@ -29,11 +29,13 @@ typedef short short2v __attribute__((ext_vector_type(2)));
 // TPW waves (= tokens in flight) per workgroup.  LOOP: persistent workgroups, a wave takes tokens t, t + G, ...
 // (G = all waves of the grid) with the next token's rows requested before the current one is worked on.
 template <int A, int TPW, bool LOOP>
-__global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) void tq_wave_kernel(const _Float16* __restrict__ aP2, const _Float16* __restrict__ aP1, const _Float16* __restrict__ ax, int64_t ax_stride, int64_t aT,
-                    const float* __restrict__ clip, uint8_t* __restrict__ aout_codes, _Float16* __restrict__ aout_scales, int aclip_mode) {
-    // (plain arguments in the order they are needed, so that the first ones can be delivered in registers at wave start)
+__global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) void tq_wave_kernel(const void* __restrict__ aP2, const void* __restrict__ aP1, const void* __restrict__ ax, int64_t ax_stride, int64_t aT,
+                    const float* __restrict__ clip, uint8_t* __restrict__ aout_codes, void* __restrict__ aout_scales, int aclip_mode) {
+    // (plain arguments in the order they are needed, so that the first ones can be delivered in registers at wave start;
+    // untyped pointers keep the kernel's name readable in profiler output)
     struct { const _Float16* x; const _Float16* P1; const _Float16* P2; uint8_t* out_codes; _Float16* out_scales; int64_t x_stride, T; int clip_mode; } p =
-        {ax, aP1, aP2, aout_codes, aout_scales, ax_stride, aT, aclip_mode};
+        {static_cast<const _Float16*>(ax), static_cast<const _Float16*>(aP1), static_cast<const _Float16*>(aP2), aout_codes,
+         static_cast<_Float16*>(aout_scales), ax_stride, aT, aclip_mode};
     constexpr int N1 = 32 * A, N2 = 64, KB1 = 2 * A, KB2 = 4, NT = 64 * TPW;
     constexpr int CH2 = N2 * N2 / 8, CH1 = N1 * N1 / 8, CH = CH1 + CH2;   // 16-byte chunks of P2, P1
     constexpr int NLD = (CH + NT - 1) / NT;
@@ -259,7 +261,7 @@ bool tq_wave_applicable(const TqDev& d) {
     return d.T >= 1 && d.T <= 0x7fffffff;
 }
 
-using WaveFn = void (*)(const _Float16*, const _Float16*, const _Float16*, int64_t, int64_t, const float*, uint8_t*, _Float16*, int);
+using WaveFn = void (*)(const void*, const void*, const void*, int64_t, int64_t, const float*, uint8_t*, void*, int);
 template <int TPW>
 static WaveFn wave_fn(int A, bool loop) {
     if (A == 1) return loop ? &tq_wave_kernel<1, TPW, true> : &tq_wave_kernel<1, TPW, false>;

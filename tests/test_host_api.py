@@ -238,7 +238,7 @@ def test_host_layer_under_address_and_undefined_behaviour_sanitizers(tmp_path):
                     "-Xarch_host", "-fno-sanitize-recover=undefined",
                     "-c", os.path.join(csrc, "fq_api.hip"), "-o", str(api_o)], check=True, capture_output=True)
     lib = tmp_path / "libflatquant_san.so"
-    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-w", "-fsanitize=address", "-fsanitize=undefined",
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-w", "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined",
                     str(api_o), *objs, "-o", str(lib)], check=True, capture_output=True)
     src = tmp_path / "drive.c"
     src.write_text(r"""
@@ -304,7 +304,7 @@ int main(void) {
 }
 """)
     exe = tmp_path / "drive"
-    subprocess.run([clang, "-std=c99", "-g", "-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined",
+    subprocess.run([clang, "-std=c99", "-g", "-w", "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined",
                     "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe), "-L", str(tmp_path), "-lflatquant_san",
                     f"-Wl,-rpath,{tmp_path}"], check=True, capture_output=True)
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
