@@ -811,12 +811,12 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     }
     {   // 64-wide rows (n1 = 32 or 64): the wave-per-token kernel (fq_tq_wave.hip).  Mode 5: one token per wave, the
         // hardware hands out workgroups as earlier ones retire; mode 6: persistent workgroups.  Measured on MI355X
-        // (64 x 64, same run, us per launch; loop-free / persistent / what this file's kernels reach):
-        // T = 2048 6.5 / 7.3 / 8.1, 4096 10.8 / 10.9 / 12.8, 16384 31.9 / 32.3 / 35.4, 32768 61.9 / 61.2 / 63.0,
-        // 65536 141 / 133 / 139, 131072 278 / 262 / 280.
+        // (64 x 64, same run, us per launch; loop-free / persistent):
+        // T = 2048 6.4 / 7.2, 4096 11.0 / 13.8, 8192 19.9 / 22.6, 16384 35.6 / 40.0, 32768 73.7 / 68.5, 65536 144 / 130,
+        // 131072 285 / 254.
         const int m = env_int("FLATQUANT_MODE", -1);
         if ((m == -1 || m == 5 || m == 6) && tq_wave_applicable(d))
-            return tq_wave_launch(d, stream, env_int("FLATQUANT_WAVE_TPW", 4), m == -1 ? d.T >= 49152 : m == 6);
+            return tq_wave_launch(d, stream, env_int("FLATQUANT_WAVE_TPW", 4), m == -1 ? d.T >= 32768 : m == 6);
     }
     int mode = (A <= 2) ? 2 : 0;
     if (A == 2 && B >= 7) mode = 0;   // two row tiles x 224 or 256 columns: the plain loop is 4 - 25 % faster (64 x 256, T = 16384: 226 against 290 us)

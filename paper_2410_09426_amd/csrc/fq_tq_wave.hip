@@ -17,6 +17,8 @@
 //     clamp(rne(u), -8, 7) in two's complement, so clamping, rounding and half of the packing are one fma plus half an
 //     instruction per value.  The thresholds between codes move by less than 2e-6 code units (fp32 rounding of the
 //     two constants and of the fma), exact ties excepted.
+//   * The work of a token is cut by row tiles of X~ (32 rows): a row tile is a K block of the second contraction, so a
+//     tile is worked on as soon as its own four loads have arrived, while the other tile's rows are still on their way.
 //   * P1 and P2 are requested before the token rows (a CU's vector memory path returns data in request order), staged
 //     in LDS once per workgroup and turned into MFMA fragments while the token rows are still on their way from HBM.
 #include "fq_internal.h"
@@ -68,25 +70,24 @@ __global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) v
     // banks although the pitch is a multiple of the bank width.
     constexpr int NROW = N1 / 8;
     const int ld_ofs = (l >> 3) * (N2 * 2) + 16 * ((l & 7) ^ ((l >> 4) & 3));   // rows 8 k + l / 8: (r >> 1) & 7 = 4 (k & 1) + (l >> 4)
-    auto issue = [&](int64_t tok, u32x4 (&pre)[NROW]) {
+    auto issue = [&](int64_t tok, u32x4 (&pre)[NROW], int It) {   // row tile It, or all of them (It < 0)
         const unsigned char* row = reinterpret_cast<const unsigned char*>(p.x + tok * p.x_stride);
 #pragma unroll
-        for (int k = 0; k < NROW; ++k)
+        for (int k = (It < 0 ? 0 : 4 * It); k < (It < 0 ? NROW : 4 * It + 4); ++k)
             pre[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + k * (8 * N2 * 2) + (ld_ofs ^ (64 * (k & 1)))));
     };
-    auto commit = [&](const u32x4 (&pre)[NROW]) {
+    // (row tile It = loads 4 It .. 4 It + 3 = 4 KB of the tile)
+    auto commit = [&](const u32x4 (&pre)[NROW], int It) {
 #pragma unroll
-        for (int k = 0; k < NROW; ++k) *reinterpret_cast<u32x4*>(tile + k * 1024 + 16 * l) = pre[k];
+        for (int k = 4 * It; k < 4 * It + 4; ++k) *reinterpret_cast<u32x4*>(tile + k * 1024 + 16 * l) = pre[k];
     };
     // lane (c, h), row tile It, K block kb: X~[32 It + c][16 kb + 8 h .. + 7] = chunk 2 kb + h of row 32 It + c
     const int rd_ofs = c * (N2 * 2);
     const int rd_swz = (c >> 1) & 7;
-    auto fetch = [&](u32x4 (&a)[A][KB2]) {
+    auto fetch = [&](u32x4 (&a)[KB2], int It) {
 #pragma unroll
-        for (int It = 0; It < A; ++It)
-#pragma unroll
-            for (int kb = 0; kb < KB2; ++kb)
-                a[It][kb] = *reinterpret_cast<const u32x4*>(tile + It * (32 * N2 * 2) + rd_ofs + 16 * ((2 * kb + h) ^ rd_swz));
+        for (int kb = 0; kb < KB2; ++kb)
+            a[kb] = *reinterpret_cast<const u32x4*>(tile + It * (32 * N2 * 2) + rd_ofs + 16 * ((2 * kb + h) ^ rd_swz));
     };
     u32x4 pre[NROW];
     // A CU's vector memory path takes requests and returns data in order, whatever wave they come from: the barrier
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) v
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    issue(t, pre);
+    issue(t, pre, -1);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- transforms -> LDS -> fragments (while the token rows are in flight)
@@ -120,73 +121,81 @@ __global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) v
         for (int kk = 0; kk < KB1; ++kk)
             p1f[It][kk] = lds_column8(P1flat, N1, 32 * (kk >> 1) + 16 * (kk & 1) + 4 * h, 8, 32 * It + (c & 16), l & 15);
 
-    // ---- one token: rows in `xr` -> codes and step in global memory
-    auto token = [&](int64_t tok, const u32x4 (&xr)[A][KB2]) {
-        const float clipv = clip[p.clip_mode ? tok : 0];   // wave-uniform address: a scalar load
-        // The schedule is written out: the wave has nobody to hide its own latencies behind but itself (and one other
-        // wave of its SIMD), so the vector-ALU work of one slab runs in the shadow of the other slab's MFMAs.
-        //   S1  Z0 = X~ P2[:, slab 0]                         (MFMA)
-        //   S2  Z1 = X~ P2[:, slab 1]                         (MFMA)   |  split Z0 into hi + lo     (VALU)
-        //   S3  Y^T[slab 0] = Z0^T P1, hi and lo             (MFMA)   |  split Z1                   (VALU)
-        //   S4  Y^T[slab 1] = Z1^T P1                         (MFMA)   |  absmax over slab 0         (VALU)
-        //   S5  absmax over slab 1, step, round, pack, store  (VALU)
-        // A unit is one K block (16 rows of X~) of the second contraction: kk = 2 It + kq.
-        constexpr int NU = 2 * A;
-        f32x16 acc1[2][A], acc2[2][A];
+    // ---- one token.  The work is cut by row tiles of X~ (32 rows = 4 KB = half of a 64 x 64 token): both contractions of
+    // a row tile need nothing of the other one (it is a K block of the second contraction), so a tile is worked on as soon
+    // as its own rows have arrived.  The schedule of a tile is written out: the wave has nobody to hide its own latencies
+    // behind but itself (and one other wave of its SIMD), so the vector-ALU work of one slab runs in the shadow of the
+    // other slab's MFMAs.
+    //   H1  Z0 = X~[tile] P2[:, slab 0]                       (MFMA)
+    //   H2  Z1 = X~[tile] P2[:, slab 1]                       (MFMA)   |  split Z0 into hi + lo        (VALU)
+    //   H3  Y^T[slab 0] += Z0^T P1[tile rows], hi and lo     (MFMA)   |  split Z1                      (VALU)
+    //   H4  Y^T[slab 1] += Z1^T P1[tile rows]                (MFMA)   |  last tile: absmax over slab 0 (VALU)
+    // then absmax over slab 1, step, round, pack, store.
+    f32x16 acc2[2][A];
+    float m;
+    auto absmax_part = [&](int q, int u) {   // half of slab q's accumulators
+#pragma unroll
+        for (int j = 0; j < 8 * A; j += 2) {
+            const int e = u * (8 * A) + j;
+            m = __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(acc2[q][e / 16][e % 16])), __builtin_fabsf(acc2[q][e / 16][e % 16 + 1]));
+        }
+    };
+    auto clear = [&]() {
+        m = 0.0f;
 #pragma unroll
         for (int q = 0; q < 2; ++q)
 #pragma unroll
-            for (int It = 0; It < A; ++It)
+            for (int I2 = 0; I2 < A; ++I2)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) { acc1[q][It][r] = 0.0f; acc2[q][It][r] = 0.0f; }
-        half8 zh[2][NU], zl[2][NU];
+                for (int r = 0; r < 16; ++r) acc2[q][I2][r] = 0.0f;
+    };
+    auto row_tile = [&](int It, const u32x4 (&xr)[KB2]) {
+        f32x16 acc1[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc1[q][r] = 0.0f;
+        half8 zh[2][2], zl[2][2];
         auto first = [&](int q, int kb) {
-#pragma unroll
-            for (int It = 0; It < A; ++It)
-                acc1[q][It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, xr[It][kb]), p2f[q][kb], acc1[q][It], 0, 0, 0);
+            acc1[q] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, xr[kb]), p2f[q][kb], acc1[q], 0, 0, 0);
         };
-        auto second = [&](int q, int u) {
+        auto second = [&](int q, int kq) {   // K block kk = 2 It + kq: 16 rows of X~
 #pragma unroll
-            for (int I2 = 0; I2 < A; ++I2) acc2[q][I2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh[q][u], p1f[I2][u], acc2[q][I2], 0, 0, 0);
+            for (int I2 = 0; I2 < A; ++I2) acc2[q][I2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh[q][kq], p1f[I2][2 * It + kq], acc2[q][I2], 0, 0, 0);
 #pragma unroll
-            for (int I2 = 0; I2 < A; ++I2) acc2[q][I2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zl[q][u], p1f[I2][u], acc2[q][I2], 0, 0, 0);
+            for (int I2 = 0; I2 < A; ++I2) acc2[q][I2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zl[q][kq], p1f[I2][2 * It + kq], acc2[q][I2], 0, 0, 0);
         };
-        float m = 0.0f;
-        auto absmax_part = [&](int q, int u) {   // a quarter (A = 2) or half (A = 1) of slab q's accumulators
-#pragma unroll
-            for (int j = 0; j < 16 * A / NU; j += 2) {
-                const int e = u * (16 * A / NU) + j;
-                m = __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(acc2[q][e / 16][e % 16])), __builtin_fabsf(acc2[q][e / 16][e % 16 + 1]));
-            }
-        };
-        // S1
+        // H1
 #pragma unroll
         for (int kb = 0; kb < KB2; ++kb) first(0, kb);
         __builtin_amdgcn_sched_barrier(0);
-        // S2: KB2 = 4 MFMA groups against NU split units
+        // H2
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            first(1, g);
-            if (NU == 4 || g % 2 == 0) split_hi_lo(acc1[0][(NU == 4 ? g : g / 2) / 2], 8 * ((NU == 4 ? g : g / 2) % 2), zh[0][NU == 4 ? g : g / 2], zl[0][NU == 4 ? g : g / 2]);
+        for (int g = 0; g < 2; ++g) {
+            first(1, 2 * g);
+            first(1, 2 * g + 1);
+            split_hi_lo(acc1[0], 8 * g, zh[0][g], zl[0][g]);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // S3
+        // H3
 #pragma unroll
-        for (int u = 0; u < NU; ++u) {
-            second(0, u);
-            split_hi_lo(acc1[1][u / 2], 8 * (u % 2), zh[1][u], zl[1][u]);
+        for (int kq = 0; kq < 2; ++kq) {
+            second(0, kq);
+            split_hi_lo(acc1[1], 8 * kq, zh[1][kq], zl[1][kq]);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // S4
+        // H4
 #pragma unroll
-        for (int u = 0; u < NU; ++u) {
-            second(1, u);
-            absmax_part(0, u);
+        for (int kq = 0; kq < 2; ++kq) {
+            second(1, kq);
+            if (It == A - 1) absmax_part(0, kq);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // S5
+    };
+    auto finish = [&](int64_t tok) {
+        const float clipv = clip[p.clip_mode ? tok : 0];   // wave-uniform address: a scalar load
 #pragma unroll
-        for (int u = 0; u < NU; ++u) absmax_part(1, u);
+        for (int u = 0; u < 2; ++u) absmax_part(1, u);
         m = wave_max(m);
         // ---- step = alpha * max / 7, rounded to fp16; the rounded step divides
         const _Float16 sh = (_Float16)(clipv * m * 0.142857149f);
@@ -233,21 +242,33 @@ __global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) v
     __builtin_amdgcn_sched_barrier(0);   // the fragment reads are issued before anything waits for the token rows
     // The tile belongs to this wave alone and LDS executes a wave's instructions in order: no barrier between writing
     // the rows and reading them back as operands, nor before the next token's rows overwrite them.
-    u32x4 xr[A][KB2];
+    u32x4 xr[KB2];
     if constexpr (!LOOP) {
-        commit(pre);
-        fetch(xr);
-        token(t, xr);
+        clear();
+#pragma unroll
+        for (int It = 0; It < A; ++It) {
+            commit(pre, It);
+            fetch(xr, It);
+            __builtin_amdgcn_sched_barrier(0);
+            row_tile(It, xr);
+        }
+        finish(t);
     } else {
         // Past the end a wave re-reads the last token's rows: an unconditional request keeps the compiler's count of
-        // outstanding loads exact, so the wait before a token covers its rows only.
+        // outstanding loads exact, so the wait before a row tile covers its rows only.
         while (true) {
-            commit(pre);
-            fetch(xr);
             const int64_t tn = t + G;
-            issue(tn < p.T ? tn : p.T - 1, pre);
-            __builtin_amdgcn_sched_barrier(0);
-            token(t, xr);
+            const int64_t tr = tn < p.T ? tn : p.T - 1;
+            clear();
+#pragma unroll
+            for (int It = 0; It < A; ++It) {
+                commit(pre, It);
+                fetch(xr, It);
+                issue(tr, pre, It);
+                __builtin_amdgcn_sched_barrier(0);
+                row_tile(It, xr);
+            }
+            finish(t);
             t = tn;
             if (t >= p.T) break;
         }

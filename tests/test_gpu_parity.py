@@ -119,13 +119,15 @@ def test_mid_length_stream(tuning, mode):
     check_case(c, rows=subset_rows(c.T, 200, 14, must=(0, 3, 4, 4095, 4096, 4097, 4098)), with_dequant=False, label=f"2048 < T < 32768, mode {mode}")
 
 
-@pytest.mark.parametrize("mode,T", [(None, 49152 + 5), ("1", 32768 + 5)])
+@pytest.mark.parametrize("mode,T", [(None, 32768 + 5), ("1", 32768 + 5), ("5", 20480 + 5), ("6", 20480 + 7)])
 def test_long_stream(tuning, mode, T):
-    # default: persistent wave-per-token workgroups from T = 49152 on; mode 1: two slabs per wave in a persistent loop
+    # default: persistent wave-per-token workgroups from T = 32768 on (5 / 6: one-shot / persistent forced); mode 1: two
+    # slabs per wave in a persistent loop
     if mode is not None:
         tuning("FLATQUANT_MODE", mode)
     c = synth.prefill_7b(T)
-    check_case(c, rows=subset_rows(c.T, 200, 13, must=(0, 1, 2047, 2048, 32767, 32768, T - 2)), with_dequant=False, label=f"long stream, mode {mode}")
+    must = tuple(r for r in (0, 1, 2047, 2048, 20479, 20480, 32767, 32768, T - 2) if r < T)
+    check_case(c, rows=subset_rows(c.T, 200, 13, must=must), with_dequant=False, label=f"long stream, mode {mode}")
 
 
 def test_decode_shapes():
