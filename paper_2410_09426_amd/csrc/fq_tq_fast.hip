@@ -714,6 +714,12 @@ bool tq_mx_applicable(const TqDev& d) {
 }
 
 hipError_t tq_mx_launch(const TqDev& d, hipStream_t stream) {
+    {   // 64-wide rows: the wave-per-token kernel with the MXFP4 quantizer (modes as for INT4; the tile order of the
+        // exponents needs whole K iterations of 256 channels, which 32 x 64 and 64 x 64 have)
+        const int m = env_int("FLATQUANT_MODE", -1);
+        if ((m == -1 || m == 5 || m == 6) && tq_wave_applicable(d) && (reinterpret_cast<uintptr_t>(d.out_scales) & 7) == 0)
+            return tq_wave_launch(d, stream, env_int("FLATQUANT_WAVE_TPW", 4), m == -1 ? d.T >= 32768 : m == 6, true);
+    }
     const int A = (d.n1 + 31) / 32, B = d.n2 / 32;
     const bool full1 = (d.n1 % 32) == 0;
     static OccCache occ_cache[4][8][2][2];
@@ -816,7 +822,7 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
         // 131072 285 / 254.
         const int m = env_int("FLATQUANT_MODE", -1);
         if ((m == -1 || m == 5 || m == 6) && tq_wave_applicable(d))
-            return tq_wave_launch(d, stream, env_int("FLATQUANT_WAVE_TPW", 4), m == -1 ? d.T >= 32768 : m == 6);
+            return tq_wave_launch(d, stream, env_int("FLATQUANT_WAVE_TPW", 4), m == -1 ? d.T >= 32768 : m == 6, false);
     }
     int mode = (A <= 2) ? 2 : 0;
     if (A == 2 && B >= 7) mode = 0;   // two row tiles x 224 or 256 columns: the plain loop is 4 - 25 % faster (64 x 256, T = 16384: 226 against 290 us)

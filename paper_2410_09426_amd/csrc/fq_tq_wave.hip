@@ -1,5 +1,5 @@
-// Fused transform + INT4 kernel for 64-wide rows (n2 = 64, n1 = 32 or 64): one wavefront per token, nothing shared
-// between tokens after the prologue.
+// Fused transform + quantization kernel for 64-wide rows (n2 = 64, n1 = 32 or 64): one wavefront per token, nothing
+// shared between tokens after the prologue.  INT4 codes with a step per token, or MXFP4 (template flag).
 //
 // Same method as the other activation kernels (Eq. (2) left factor, fused as in Sec. 3.3: Z = X~ P2, Y^T = Z^T P1 with Z
 // split into fp16 hi + lo, per-token absmax, clip, round, pack), different data movement:
@@ -30,14 +30,16 @@ typedef short short2v __attribute__((ext_vector_type(2)));
 
 // TPW waves (= tokens in flight) per workgroup.  LOOP: persistent workgroups, a wave takes tokens t, t + G, ...
 // (G = all waves of the grid) with the next token's rows requested before the current one is worked on.
-template <int A, int TPW, bool LOOP>
+// MX: MXFP4 output (E2M1 codes, one E8M0 exponent per 32 channels) instead of INT4 codes and a step: the 32 channels of a
+// block are the ones a lane pair holds of one slab, so the quantizer needs no wave-wide absmax.
+template <int A, int TPW, bool LOOP, bool MX>
 __global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) void tq_wave_kernel(const void* __restrict__ aP2, const void* __restrict__ aP1, const void* __restrict__ ax, int64_t ax_stride, int64_t aT,
-                    const float* __restrict__ clip, uint8_t* __restrict__ aout_codes, void* __restrict__ aout_scales, int aclip_mode) {
+                    const float* __restrict__ clip, uint8_t* __restrict__ aout_codes, void* __restrict__ aout_scales, int aclip_mode, int amx_tiled) {
     // (plain arguments in the order they are needed, so that the first ones can be delivered in registers at wave start;
     // untyped pointers keep the kernel's name readable in profiler output)
-    struct { const _Float16* x; const _Float16* P1; const _Float16* P2; uint8_t* out_codes; _Float16* out_scales; int64_t x_stride, T; int clip_mode; } p =
+    struct { const _Float16* x; const _Float16* P1; const _Float16* P2; uint8_t* out_codes; void* out_scales; int64_t x_stride, T; int clip_mode, mx_tiled; } p =
         {static_cast<const _Float16*>(ax), static_cast<const _Float16*>(aP1), static_cast<const _Float16*>(aP2), aout_codes,
-         static_cast<_Float16*>(aout_scales), ax_stride, aT, aclip_mode};
+         aout_scales, ax_stride, aT, aclip_mode, amx_tiled};
     constexpr int N1 = 32 * A, N2 = 64, KB1 = 2 * A, KB2 = 4, NT = 64 * TPW;
     constexpr int CH2 = N2 * N2 / 8, CH1 = N1 * N1 / 8, CH = CH1 + CH2;   // 16-byte chunks of P2, P1
     constexpr int NLD = (CH + NT - 1) / NT;
@@ -188,55 +190,112 @@ __global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) v
 #pragma unroll
         for (int kq = 0; kq < 2; ++kq) {
             second(1, kq);
-            if (It == A - 1) absmax_part(0, kq);
+            if (!MX && It == A - 1) absmax_part(0, kq);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    // lane pair exchange of the packed codes: W[q][mm] holds, for slab q, the lane's 4 + 4 channels of groups g = 2 mm
+    // and 2 mm + 1 (2 + 2 bytes); afterwards lane (c, h) holds slab q = h of both lanes, 16 consecutive bytes of the row
+    auto store_codes = [&](uint8_t* dst, const uint32_t (&W)[2][2]) {
+        u32x4 o;
+#pragma unroll
+        for (int mm = 0; mm < 2; ++mm) {
+            const auto sw = __builtin_amdgcn_permlane32_swap(W[0][mm], W[1][mm], false, false);
+            const uint32_t P = sw[0], Q = sw[1];                        // half-wave 0's, half-wave 1's
+            o[2 * mm] = __builtin_amdgcn_perm(Q, P, 0x05040100u);       // group g = 2 mm: 2 bytes of P, 2 bytes of Q
+            o[2 * mm + 1] = __builtin_amdgcn_perm(Q, P, 0x07060302u);   // group g = 2 mm + 1
+        }
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(dst));
+    };
     auto finish = [&](int64_t tok) {
         const float clipv = clip[p.clip_mode ? tok : 0];   // wave-uniform address: a scalar load
-#pragma unroll
-        for (int u = 0; u < 2; ++u) absmax_part(1, u);
-        m = wave_max(m);
-        // ---- step = alpha * max / 7, rounded to fp16; the rounded step divides
-        const _Float16 sh = (_Float16)(clipv * m * 0.142857149f);
-        const float s = (float)sh;
-        const float inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;   // 1 ulp: < 1e-6 code units
-        const float kmul = inv * (4096.0f / 32767.0f);
-        constexpr float kadd = 2047.5f / 32767.0f;
-        // ---- round, clamp, pack.  Lane (c, h) holds, of row ip = 32 It + c of X~, the channels 32 q + 8 g + 4 h + k
-        // in acc2[q][It][4 g + k].  Eight of them (g = 2 m, 2 m + 1) become one dword of nibbles.
+        // Lane (c, h) holds, of row ip = 32 It + c of X~, the channels 32 q + 8 g + 4 h + k in acc2[q][It][4 g + k].
         uint8_t* out_row = p.out_codes + tok * (int64_t)(N1 * N2 / 2) + c * (N2 / 2) + 16 * h;
+        if constexpr (MX) {
+            // Block (ip, q) = the 32 values of the lane pair (c, 0), (c, 1) in acc2[q][It]: exponent floor(log2(alpha max)) - 2
+            // (0 for an all-zero block), elements converted with the stored exponent (the conversion reads the exponent
+            // field of its scale operand only, and field 0 means 2^-127).
+            uint8_t* exps = reinterpret_cast<uint8_t*>(p.out_scales);
 #pragma unroll
-        for (int It = 0; It < A; ++It) {
-            uint32_t W[2][2];
+            for (int It = 0; It < A; ++It) {
+                uint32_t W[2][2], e2 = 0;
 #pragma unroll
-            for (int q = 0; q < 2; ++q)
+                for (int q = 0; q < 2; ++q) {
+                    float bm = 0.0f;
 #pragma unroll
-                for (int mm = 0; mm < 2; ++mm) {
-                    uint32_t D[4];
+                    for (int r = 0; r < 16; r += 2) bm = __builtin_fmaxf(__builtin_fmaxf(bm, __builtin_fabsf(acc2[q][It][r])), __builtin_fabsf(acc2[q][It][r + 1]));
+                    const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, bm), __builtin_bit_cast(uint32_t, bm), false, false);
+                    bm = __builtin_fmaxf(__builtin_bit_cast(float, (uint32_t)sw[0]), __builtin_bit_cast(float, (uint32_t)sw[1])) * clipv;
+                    const uint32_t be = (__builtin_bit_cast(uint32_t, bm) >> 23) & 0xffu;
+                    const uint32_t e = be > 2 ? be - 2 : 0;
+                    const float scale = __builtin_bit_cast(float, e << 23);
+                    e2 |= e << (8 * q);
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const float r0 = __builtin_fmaf(acc2[q][It][8 * mm + k], kmul, kadd);
-                        const float r1 = __builtin_fmaf(acc2[q][It][8 * mm + 4 + k], kmul, kadd);
-                        D[k] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pknorm_i16(r0, r1));
+                    for (int mm = 0; mm < 2; ++mm) {
+                        // byte j: channels 2 (j % 2), 2 (j % 2) + 1 of group g = 2 mm + j / 2 (the byte index must be a literal)
+                        const f32x16& y = acc2[q][It];
+                        uint32_t pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, y[8 * mm], y[8 * mm + 1], scale, 0);
+                        pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(pk, y[8 * mm + 2], y[8 * mm + 3], scale, 1);
+                        pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(pk, y[8 * mm + 4], y[8 * mm + 5], scale, 2);
+                        pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(pk, y[8 * mm + 6], y[8 * mm + 7], scale, 3);
+                        W[q][mm] = pk;
                     }
-                    // bytes 1 and 3 of D[k] carry nibbles k and k + 4 on top: even nibbles -> E, odd ones -> F
-                    const uint32_t E = __builtin_amdgcn_perm(D[2], D[0], 0x07030501u);
-                    const uint32_t F = __builtin_amdgcn_perm(D[3], D[1], 0x07030501u);
-                    W[q][mm] = (F & 0xF0F0F0F0u) | ((E >> 4) & 0x0F0F0F0Fu);
                 }
-            // lane pair exchange: afterwards lane (c, h) holds slab q = h of both lanes: P = half-wave 0's, Q = half-wave 1's
-            u32x4 o;
-#pragma unroll
-            for (int mm = 0; mm < 2; ++mm) {
-                const auto sw = __builtin_amdgcn_permlane32_swap(W[0][mm], W[1][mm], false, false);
-                const uint32_t P = sw[0], Q = sw[1];
-                o[2 * mm] = __builtin_amdgcn_perm(Q, P, 0x05040100u);       // group g = 2 mm: 2 bytes of P, 2 bytes of Q
-                o[2 * mm + 1] = __builtin_amdgcn_perm(Q, P, 0x07060302u);   // group g = 2 mm + 1
+                store_codes(out_row + It * (32 * N2 / 2), W);
+                // exponents: two bytes per row of X~ (index 2 ip + q)
+                const int ip = 32 * It + c;
+                if (!p.mx_tiled) {
+                    if (h == 0) *reinterpret_cast<uint16_t*>(exps + tok * (int64_t)(2 * N1) + 2 * ip) = (uint16_t)e2;
+                } else {
+                    // tile order of the MXFP4 product: tokens in tiles of 128; per tile and K iteration j (256 channels = 4
+                    // rows of X~ = 8 exponents) the 128 tokens' 8 bytes are contiguous.  The four lanes of a quad hold the
+                    // four rows of one iteration: lane 0 of the quad gathers them and stores 8 bytes.
+                    const uint32_t a1 = __builtin_amdgcn_mov_dpp((int)e2, 0x55, 0xF, 0xF, true);   // quad lane 1's
+                    const uint32_t a2 = __builtin_amdgcn_mov_dpp((int)e2, 0xAA, 0xF, 0xF, true);
+                    const uint32_t a3 = __builtin_amdgcn_mov_dpp((int)e2, 0xFF, 0xF, 0xF, true);
+                    constexpr int KI = N1 * N2 / 256;
+                    if (h == 0 && (c & 3) == 0) {
+                        uint2 v;
+                        v.x = e2 | (a1 << 16);
+                        v.y = a2 | (a3 << 16);
+                        reinterpret_cast<uint2*>(exps)[((tok >> 7) * KI + (ip >> 2)) * 128 + (tok & 127)] = v;
+                    }
+                }
             }
-            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(out_row + It * (32 * N2 / 2)));
+        } else {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) absmax_part(1, u);
+            m = wave_max(m);
+            // ---- step = alpha * max / 7, rounded to fp16; the rounded step divides
+            const _Float16 sh = (_Float16)(clipv * m * 0.142857149f);
+            const float s = (float)sh;
+            const float inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;   // 1 ulp: < 1e-6 code units
+            const float kmul = inv * (4096.0f / 32767.0f);
+            constexpr float kadd = 2047.5f / 32767.0f;
+            // ---- round, clamp, pack: eight values (g = 2 m, 2 m + 1) become one dword of nibbles
+#pragma unroll
+            for (int It = 0; It < A; ++It) {
+                uint32_t W[2][2];
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int mm = 0; mm < 2; ++mm) {
+                        uint32_t D[4];
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const float r0 = __builtin_fmaf(acc2[q][It][8 * mm + k], kmul, kadd);
+                            const float r1 = __builtin_fmaf(acc2[q][It][8 * mm + 4 + k], kmul, kadd);
+                            D[k] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pknorm_i16(r0, r1));
+                        }
+                        // bytes 1 and 3 of D[k] carry nibbles k and k + 4 on top: even nibbles -> E, odd ones -> F
+                        const uint32_t E = __builtin_amdgcn_perm(D[2], D[0], 0x07030501u);
+                        const uint32_t F = __builtin_amdgcn_perm(D[3], D[1], 0x07030501u);
+                        W[q][mm] = (F & 0xF0F0F0F0u) | ((E >> 4) & 0x0F0F0F0Fu);
+                    }
+                store_codes(out_row + It * (32 * N2 / 2), W);
+            }
+            reinterpret_cast<_Float16*>(p.out_scales)[tok] = sh;   // every lane writes the same two bytes: cheaper than a branch around the store
         }
-        p.out_scales[tok] = sh;   // every lane writes the same two bytes: cheaper than a branch around the store
     };
 
     __builtin_amdgcn_sched_barrier(0);   // the fragment reads are issued before anything waits for the token rows
@@ -282,23 +341,25 @@ bool tq_wave_applicable(const TqDev& d) {
     return d.T >= 1 && d.T <= 0x7fffffff;
 }
 
-using WaveFn = void (*)(const void*, const void*, const void*, int64_t, int64_t, const float*, uint8_t*, void*, int);
-template <int TPW>
+using WaveFn = void (*)(const void*, const void*, const void*, int64_t, int64_t, const float*, uint8_t*, void*, int, int);
+template <int TPW, bool MX>
 static WaveFn wave_fn(int A, bool loop) {
-    if (A == 1) return loop ? &tq_wave_kernel<1, TPW, true> : &tq_wave_kernel<1, TPW, false>;
-    return loop ? &tq_wave_kernel<2, TPW, true> : &tq_wave_kernel<2, TPW, false>;
+    if (A == 1) return loop ? &tq_wave_kernel<1, TPW, true, MX> : &tq_wave_kernel<1, TPW, false, MX>;
+    return loop ? &tq_wave_kernel<2, TPW, true, MX> : &tq_wave_kernel<2, TPW, false, MX>;
 }
 
-// tpw: 2, 4 or 8 waves per workgroup; loop: persistent workgroups (grid = as many as are resident), else one token per wave
-hipError_t tq_wave_launch(const TqDev& d, hipStream_t stream, int tpw, bool loop) {
+// tpw: 2, 4 or 8 waves per workgroup; loop: persistent workgroups (grid = as many as are resident), else one token per
+// wave; mx: MXFP4 output (d.mx_tiled: exponents in the product's tile order)
+hipError_t tq_wave_launch(const TqDev& d, hipStream_t stream, int tpw, bool loop, bool mx) {
     const int A = d.n1 / 32;
-    WaveFn fn = tpw == 2 ? wave_fn<2>(A, loop) : tpw == 4 ? wave_fn<4>(A, loop) : wave_fn<8>(A, loop);
     if (tpw != 2 && tpw != 4) tpw = 8;
+    WaveFn fn = mx ? (tpw == 2 ? wave_fn<2, true>(A, loop) : tpw == 4 ? wave_fn<4, true>(A, loop) : wave_fn<8, true>(A, loop))
+                   : (tpw == 2 ? wave_fn<2, false>(A, loop) : tpw == 4 ? wave_fn<4, false>(A, loop) : wave_fn<8, false>(A, loop));
     const int lds = (64 * 64 + d.n1 * d.n1) * 2 + tpw * d.n1 * 64 * 2;   // P2, P1, one tile per wave
-    static OccCache occ_cache[2][3][2];   // per variant and device; the first call also raises the kernel's LDS limit
+    static OccCache occ_cache[2][2][3][2];   // per variant and device; the first call also raises the kernel's LDS limit
     int occ = 0;
     {
-        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(fn), 64 * tpw, lds, occ_cache[A - 1][tpw == 2 ? 0 : tpw == 4 ? 1 : 2][loop], occ);
+        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(fn), 64 * tpw, lds, occ_cache[mx][A - 1][tpw == 2 ? 0 : tpw == 4 ? 1 : 2][loop], occ);
         if (e != hipSuccess) return e;
     }
     int64_t grid = (d.T + tpw - 1) / tpw;
@@ -308,7 +369,7 @@ hipError_t tq_wave_launch(const TqDev& d, hipStream_t stream, int tpw, bool loop
         const int64_t rounds = (grid + resident - 1) / resident;
         grid = (grid + rounds - 1) / rounds;
     }
-    return launch(fn, dim3((unsigned)grid), dim3(64 * tpw), lds, stream, d.P2, d.P1, d.x, d.x_stride, d.T, d.clip, d.out_codes, d.out_scales, d.clip_mode);
+    return launch(fn, dim3((unsigned)grid), dim3(64 * tpw), lds, stream, d.P2, d.P1, d.x, d.x_stride, d.T, d.clip, d.out_codes, d.out_scales, d.clip_mode, d.mx_tiled);
 }
 
 }  // namespace fq

@@ -328,6 +328,27 @@ def test_mxfp4_output(tuning, mode):
         assert not codes[2].any() and not exps[2].any()
 
 
+@pytest.mark.parametrize("mode", ["5", "6"])
+@pytest.mark.parametrize("tpw", ["2", "4", "8"])
+def test_mxfp4_wave_per_token_kernel(tuning, mode, tpw):
+    # 64-wide rows take the wave-per-token kernel with the MXFP4 quantizer (5: one token per wave, 6: persistent loop);
+    # row-major exponents against the oracle, the tile order against the row-major output
+    tuning("FLATQUANT_MODE", mode)
+    tuning("FLATQUANT_WAVE_TPW", tpw)
+    c = synth.prefill_7b(2048 + 37)
+    run_mx(c, rows=subset_rows(c.T, 200, 21, must=(0, 1, 7, 8, 2047, 2048, 2084)))
+    c = synth.generic(500 + int(mode), 4099, 32, 64, clip_mode=1)
+    run_mx(c, rows=subset_rows(c.T, 160, 22, must=(0, 4095, 4096, 4098)))
+    for T in (1, 3, 9, 130):
+        run_mx(synth.generic(510 + T, T, 64, 64))
+    c = synth.generic(533, 40, 64, 64)
+    c.x[3] = 0
+    codes, exps = run_mx(c)
+    assert not codes[3].any() and not exps[3].any()
+    for n1, T in ((64, 300), (32, 1029), (64, 2600)):
+        test_mxfp4_tiled_exponents_equal_row_major(n1, 64, T)
+
+
 def test_mxfp4_bottom_of_the_exponent_range():
     """Blocks whose clipped maximum lies below 2^-124 store exponent 0 (scale 2^-127, the smallest the format has) and
     their elements are converted with that scale; just above, exponents 1, 2, ...  Reached here through a tiny
