@@ -42,6 +42,7 @@ struct TqDev {
     int vec8;       // rows can be moved in 16-byte chunks that never straddle a row of X~
     int out_vec16;  // code rows are whole 16-byte units at 16-byte aligned addresses
     int mx_tiled = 0;   // MXFP4 output only: exponents in the tile order the MXFP4 product reads (see flatquant.h)
+    uint32_t n1_magic = 0;   // floor(2^32 / n1) + 1 (n1 >= 2): floor(f / n1) = umulhi(f, n1_magic) for f < 2^16
 };
 
 // Specialised kernels for n2 a multiple of 32 and 16-byte aligned buffers (fq_tq_fast.hip).

@@ -14,6 +14,8 @@
 //   * A wave may own SPW adjacent slabs (template parameter).  With SPW = n2/32 a
 //     token belongs to a single wave: no workgroup barrier partner to wait for,
 //     and the token tile is read from LDS once instead of once per slab.
+#include <type_traits>
+
 #include "fq_internal.h"
 #include "fq_device.h"
 
@@ -96,12 +98,10 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
         for (int k = 0; k < NPRE; ++k) {
             int off = k * NT;
             if constexpr (!FULL1) {
-                // Rows past n1 (only possible in the last row tile): a request whose rows all lie past n1 is left out
-                // (same decision for every thread); in a request that straddles n1 the rows past it re-read row
-                // n1 - 1, so there is no per-lane branch.  Their products meet all-zero rows of the P1 fragments, so
-                // whatever they hold (finite) drops out.
-                if (RSTEP * k >= 32 * (A - 1) && RSTEP * k >= n1) continue;   // first test at compile time: last row tile only
-                if (RSTEP * (k + 1) > 32 * (A - 1)) {
+                // Rows past n1 (only possible in the last row tile) re-read row n1 - 1: no branch, per lane or per
+                // request, so the requests are scheduled as for a full tile.  The products of those tile rows meet
+                // all-zero rows of the P1 fragments, so whatever they hold (finite) drops out.
+                if (RSTEP * (k + 1) > 32 * (A - 1)) {   // at compile time: last row tile only
                     const int over = xrow0 + RSTEP * k - (n1 - 1);
                     off -= (over > 0 ? over : 0) * CPR;
                 }
@@ -113,7 +113,6 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
         _Float16* Xt = Xs + buf * (L::XS_BYTES / 2);
 #pragma unroll
         for (int k = 0; k < NPRE; ++k) {
-            if (!FULL1 && RSTEP * k >= 32 * (A - 1) && RSTEP * k >= n1) continue;   // never requested: those tile rows stay zero
             *reinterpret_cast<u32x4*>(Xt + xbase + RSTEP * k * PITCH) = pre[k];
         }
     };
@@ -134,18 +133,9 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
     auto stage_p1 = [&](auto&& after_first_loads) {
         const int n1sq = n1 * n1;
         bool queued = false;               // after_first_loads() has run
-        constexpr int PW = 32 * A;         // pitch of the LDS copy: n1 rounded up to whole row tiles
-        // `nh` consecutive elements of P1 starting at flat index f0 -> the LDS copy.  With n1 a multiple of 32 the copy
-        // is the matrix as it is; otherwise its rows are re-pitched to PW, one element at a time
-        auto put = [&](int f0, const _Float16* e, int nh) {
-            int row = f0 / n1, col = f0 - row * n1;
-            for (int k = 0; k < nh; ++k) {
-                P1flat[row * PW + col] = e[k];
-                if (++col == n1) { col = 0; ++row; }
-            }
-        };
-        auto copy_batched = [&](auto* dst, const auto* src, int count) {
-            constexpr int BATCH = 8;
+        // `count` units from `src`, a batch of 8 per thread in flight; store(idx, unit) puts one into LDS
+        auto copy_batched = [&](auto batch, const auto* src, int count, auto&& store) {
+            constexpr int BATCH = decltype(batch)::value;
             using Unit = decltype(*src + 0);
             for (int base = 0; base < count; base += BATCH * NTA) {
                 Unit v[BATCH];
@@ -163,37 +153,38 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
 #pragma unroll
                 for (int k = 0; k < BATCH; ++k) {
                     const int idx = base + k * NTA + tida;
-                    if (idx < count) {
-                        if constexpr (FULL1) dst[idx] = v[k];
-                        else put(idx * (int)(sizeof(Unit) / 2), reinterpret_cast<const _Float16*>(&v[k]), (int)(sizeof(Unit) / 2));
-                    }
+                    if (idx < count) store(idx, v[k]);
                 }
             }
         };
-        if constexpr (!FULL1) {
-            // the padding of the copy must read as zero: whole rows past n1 (16-byte units), then the tails of the rows
+        if constexpr (FULL1) {   // the LDS copy is the matrix as it is
+            if ((reinterpret_cast<uintptr_t>(p.P1) & 15) == 0) {
+                copy_batched(std::integral_constant<int, 8>{}, reinterpret_cast<const u32x4*>(p.P1), n1sq >> 3, [&](int idx, u32x4 v) { reinterpret_cast<u32x4*>(P1flat)[idx] = v; });
+            } else {             // only 4-byte aligned: pairs
+                copy_batched(std::integral_constant<int, 8>{}, reinterpret_cast<const uint32_t*>(p.P1), n1sq >> 1, [&](int idx, uint32_t v) { reinterpret_cast<uint32_t*>(P1flat)[idx] = v; });
+            }
+        } else {
+            // Rows re-pitched to PW = n1 rounded up to whole row tiles, the padding zero.  One short code path (these
+            // launches are latency-bound and every instruction line is fetched cold; a variant that moves 16-byte
+            // chunks and places their four pairs was slower): pairs of elements, P1 being 4-byte aligned, 16 of them per
+            // thread in flight (one batch up to n1 = 90), each half written on its own since a pair straddles two rows
+            // when n1 is odd; floor(f / n1) = umulhi(f, magic) for f < 2^16, the magic number comes from the host.
+            constexpr int PW = 32 * A;
+            uint16_t* dst = reinterpret_cast<uint16_t*>(P1flat);
             for (int q = tida; q < (PW - n1) * PW / 8; q += NTA) reinterpret_cast<u32x4*>(P1flat + n1 * PW)[q] = u32x4{0u, 0u, 0u, 0u};
             for (int r = tida; r < n1; r += NTA)
-                for (int cc = n1; cc < PW; ++cc) P1flat[r * PW + cc] = (_Float16)0;
+                for (int cc = n1; cc < PW; ++cc) dst[r * PW + cc] = 0;
+            const uint32_t magic = p.n1_magic;
+            const uint16_t tail = reinterpret_cast<const uint16_t*>(p.P1)[n1sq - 1];
+            copy_batched(std::integral_constant<int, 16>{}, reinterpret_cast<const uint32_t*>(p.P1), n1sq >> 1, [&](int idx, uint32_t v) {
+                const uint32_t f = 2u * (uint32_t)idx;
+                const int row = (int)__umulhi(f, magic), col = (int)f - row * n1, a0 = row * PW + col;
+                dst[a0] = (uint16_t)v;
+                dst[a0 + 1 + (col + 1 == n1 ? PW - n1 : 0)] = (uint16_t)(v >> 16);
+            });
+            if ((n1sq & 1) && tida == 0) dst[(n1 - 1) * PW + n1 - 1] = tail;
         }
-        if ((reinterpret_cast<uintptr_t>(p.P1) & 15) == 0) {   // bulk in 16-byte chunks, then up to 7 single elements
-            const int done = n1sq & ~7;
-            const int ti = done + tida < n1sq ? done + tida : n1sq - 1;
-            const _Float16 tail = p.P1[ti];
-            copy_batched(reinterpret_cast<u32x4*>(P1flat), reinterpret_cast<const u32x4*>(p.P1), n1sq >> 3);
-            if (done + tida < n1sq) {
-                if constexpr (FULL1) P1flat[ti] = tail;
-                else put(ti, &tail, 1);
-            }
-        } else {   // only 4-byte aligned: pairs, plus a last odd element
-            const _Float16 tail = p.P1[n1sq - 1];
-            copy_batched(reinterpret_cast<uint32_t*>(P1flat), reinterpret_cast<const uint32_t*>(p.P1), n1sq >> 1);
-            if ((n1sq & 1) && tida == 0) {
-                if constexpr (FULL1) P1flat[n1sq - 1] = tail;
-                else put(n1sq - 1, &tail, 1);
-            }
-        }
-        if (!queued) after_first_loads();   // a P1 of fewer elements than one load unit (n1 = 1, 2): no batch ran
+        if (!queued) after_first_loads();   // a P1 of fewer elements than one load unit (n1 = 1): no batch ran
     };
     half8 p2f[ID2 ? 1 : SPW][ID2 ? 1 : KB2];
     half8 p1f[P1LDS ? 1 : A][P1LDS ? 1 : KB1];
@@ -250,12 +241,6 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
         }
     }
     __syncthreads();   // staging area is free: it becomes the token tile
-    if constexpr (!FULL1) {   // tile rows that are never written (whole requests past n1) must be exact zeros
-        for (int bf = 0; bf < NBUF; ++bf)
-            for (int q = tida; q < (32 * A - n1) * (PITCH / 8); q += NTA)
-                reinterpret_cast<u32x4*>(Xs + bf * (L::XS_BYTES / 2) + n1 * PITCH)[q] = u32x4{0u, 0u, 0u, 0u};
-        __syncthreads();
-    }
     // with one wave per token the tile, the staged codes and the absmax slot of a token are touched by that wave only:
     // LDS executes a wave's instructions in order, so program order is all that has to be kept
     auto token_sync = [&]() {
@@ -353,7 +338,7 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
 #pragma unroll
                 for (int kq = 0; kq < 2; ++kq) {
                     const int kk = 2 * (I0 + d) + kq;
-                    if (d < ni && (FULL1 || 16 * kk < n1)) {
+                    if (d < ni) {   // (K blocks past n1 meet all-zero rows of the P1 fragments)
                         half8 zh, zl;
                         split_hi_lo(acc1[d], 8 * kq, zh, zl);
                         half8 b[A];
@@ -819,19 +804,27 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
         // hardware hands out workgroups as earlier ones retire; mode 6: persistent workgroups.  Measured on MI355X
         // (64 x 64, same run, us per launch; loop-free / persistent):
         // T = 2048 6.4 / 7.2, 4096 11.0 / 13.8, 8192 19.9 / 22.6, 16384 35.6 / 40.0, 32768 73.7 / 68.5, 65536 144 / 130,
-        // 131072 285 / 254.
+        // 131072 285 / 254.  Up to 256 tokens the latency of a token's chain of MFMAs is what counts, and the loop-free
+        // slab kernel below, which splits a token over two waves, is faster (replayed from a HIP graph, us per launch,
+        // wave kernel / slab kernel: T = 64 3.87 / 3.33, 256 4.01 / 3.84, 384 4.15 / 4.60, 512 4.28 / 4.84).
         const int m = env_int("FLATQUANT_MODE", -1);
-        if ((m == -1 || m == 5 || m == 6) && tq_wave_applicable(d))
+        if ((m == 5 || m == 6 || (m == -1 && d.T > 256)) && tq_wave_applicable(d))
             return tq_wave_launch(d, stream, env_int("FLATQUANT_WAVE_TPW", 4), m == -1 ? d.T >= 32768 : m == 6, false);
     }
+    // 128-wide rows (replayed from a HIP graph up to T = 8192, cold rotation above; us per launch, loop-free / plain
+    // loop / pipelined loop): 64 x 128: T = 64 4.2 / 4.4 / 4.9, 512 7.7 / 7.7 / 9.3, 1024 10.5 / 10.7 / 11.4,
+    // 2048 17.0 / 15.7 / 16.6, 4096 29.5 / 25.6 / 27.2, 8192 53.5 / 45.2 / 46.7, 16384 - / 75 / 94, 32768 - / 162 / 189;
+    // 32 x 128: T = 512 5.4 / 5.4 / 6.6, 1536 10.6 / 8.7 / 9.4, 4096 20.5 / 14.3 / 15.6, 8192 35.8 / 24.5 / 25.6,
+    // 16384 - / 41.4 / 38.0.
     int mode = (A <= 2) ? 2 : 0;
-    if (A == 2 && B >= 7) mode = 0;   // two row tiles x 224 or 256 columns: the plain loop is 4 - 25 % faster (64 x 256, T = 16384: 226 against 290 us)
+    if (A == 2 && (B == 4 || B >= 7)) mode = 0;   // (64 x 256, T = 16384: 226 against 290 us)
+    if (A == 1 && B == 4 && d.T <= 8192) mode = 0;
     if (A <= 2 && B == 2 && d.T >= 32768) mode = 1;
-    if (A <= 2 && B <= 2) {
+    if (A <= 2 && (B <= 2 || B == 4)) {
         int occ3 = 0;
         hipError_t e = occupancy(3, occ3);
         if (e != hipSuccess) return e;
-        if (d.T <= (int64_t)cu_count() * occ3) mode = 3;
+        if (B == 4 ? d.T <= (A == 2 ? 1024 : 512) : d.T <= (int64_t)cu_count() * occ3) mode = 3;
         // past that, and up to where the wave-per-token loop takes over, 64-wide rows do best without a loop as well:
         // workgroups of kTokensPerWg single-wave tokens, handed out by the hardware as earlier ones retire
         // (measured at T = 3072 .. 16384: 3 - 8 % over the pipelined loop)

@@ -311,6 +311,7 @@ TqDev tq_dev_args(const TqArgs& a) {
     d.out_codes = a.out_codes; d.out_scales = a.out_scales;
     d.x_stride = a.x_stride; d.T = a.T; d.n1 = a.n1; d.n2 = a.n2; d.clip_mode = a.clip_mode;
     d.mx_tiled = a.mx_tiled;
+    d.n1_magic = a.n1 >= 2 ? (uint32_t)(0x100000000ull / (uint64_t)a.n1) + 1u : 0u;
     d.vec8 = (a.n2 % 8 == 0) && (a.x_stride % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0);
     const int64_t n = (int64_t)a.n1 * a.n2;
     d.out_vec16 = (n % 32 == 0) && ((reinterpret_cast<uintptr_t>(a.out_codes) & 15) == 0);
