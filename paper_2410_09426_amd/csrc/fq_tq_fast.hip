@@ -338,7 +338,9 @@ __global__ __launch_bounds__(64 * (B / SPW) * TPW) __attribute__((amdgpu_waves_p
 #pragma unroll
                 for (int kq = 0; kq < 2; ++kq) {
                     const int kk = 2 * (I0 + d) + kq;
-                    if (d < ni) {   // (K blocks past n1 meet all-zero rows of the P1 fragments)
+                    // K blocks past n1 meet all-zero rows of the P1 fragments: multiplied like the others, except with four
+                    // row tiles, where the kernel is MFMA-bound and a skipped block (112 rows: one of eight) pays for its branch
+                    if (d < ni && (FULL1 || A < 4 || 16 * kk < n1)) {
                         half8 zh, zl;
                         split_hi_lo(acc1[d], 8 * kq, zh, zl);
                         half8 b[A];
