@@ -116,7 +116,7 @@ def test_argument_validation_without_a_device():
     mx = lambda **k: fq.flatquant_transform_mxfp4(**{**dict(x=A, P1=A + 0x100000, P2=A + 0x200000, clip=A + 0x300000, clip_mode=1, T=4, n1=64,
                                                          n2=64, x_stride=4096, out_codes=A + 0x400000, out_scales=A + 0x500000, check=False), **k})
     assert mx(T=0) == fq.FQ_OK
-    assert mx(n2=96, x_stride=64 * 96) == fq.FQ_UNSUPPORTED_SHAPE and mx(n1=129, x_stride=129 * 64) == fq.FQ_UNSUPPORTED_SHAPE
+    assert mx(n2=172, x_stride=64 * 172) == fq.FQ_UNSUPPORTED_SHAPE and mx(n1=129, x_stride=129 * 64) == fq.FQ_UNSUPPORTED_SHAPE
     assert mx(n1=3, n2=64, x_stride=192) == fq.FQ_UNSUPPORTED_SHAPE      # n not a multiple of 128
     assert mx(P2=None) == fq.FQ_INVALID_ARG and mx(clip_mode=2) == fq.FQ_INVALID_ARG
     assert mx(x=A + 8) == fq.FQ_MISALIGNED and mx(out_scales=A + 0x500002) == fq.FQ_MISALIGNED and mx(x_stride=4100) == fq.FQ_MISALIGNED
