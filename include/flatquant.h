@@ -87,8 +87,11 @@ fq_status flatquant_transform_quant(const void* x, const void* P1, const void* P
  *                                    code = sign << 3 | magnitude index (a negative value that rounds to zero is -0)
  *   out_codes  u8 [T, n/2], even channel in the low nibble, 16-byte aligned.
  *   out_scales u8 [T, n/32], 4-byte aligned.
- * Shapes: n2 a multiple of 32 up to 256 (a block is then 32 consecutive channels inside one row of X~), n1 <= 128, n a
- * multiple of 128; x 16-byte aligned with x_stride a multiple of 8; P1 4-byte and P2 16-byte aligned, both required.  Other arguments, T == 0 and error behaviour as for flatquant_transform_quant.
+ * Shapes: n1 <= 128, n2 even and <= 256, n a multiple of 32.  With n2 a multiple of 32 and n a multiple of 128 a block is
+ * 32 consecutive channels inside one row of X~ and the specialised kernels run; any other such shape (64 x 172: a block
+ * straddles two rows of X~) goes through the general kernel, which stages the token's Y in LDS as fp32 and needs
+ * 4 n + 64 (n1 + 31) / 32 * ((n2 + 31) / 32 * 32 + 8) bytes of it beside P1's fragments: FQ_UNSUPPORTED_SHAPE beyond 160 KB
+ * (n above about 24000).  x 16-byte aligned with x_stride a multiple of 8; P1 4-byte and P2 16-byte aligned, both required.  Other arguments, T == 0 and error behaviour as for flatquant_transform_quant.
  */
 fq_status flatquant_transform_mxfp4(const void* x, const void* P1, const void* P2,
                                     const float* clip, int clip_mode,

@@ -150,7 +150,7 @@ static fq_status transform_mxfp4(const void* x, const void* P1, const void* P2, 
     if (T < 0 || n1 < 1 || n2 < 1 || (clip_mode != 0 && clip_mode != 1)) return FQ_INVALID_ARG;
     const int64_t n = (int64_t)n1 * n2;
     if (x_stride < n) return FQ_INVALID_ARG;
-    if (n1 > fq::kMaxN1 || n2 % 32 != 0 || n2 > fq::kMaxN2 || n % 128 != 0) return FQ_UNSUPPORTED_SHAPE;
+    if (n1 > fq::kMaxN1 || n2 > fq::kMaxN2 || n2 % 2 != 0 || n % 32 != 0) return FQ_UNSUPPORTED_SHAPE;
     if (tiled && n % 256 != 0) return FQ_UNSUPPORTED_SHAPE;
     if (T == 0) return FQ_OK;
     if (!x || !P1 || !P2 || !clip || !out_codes || !out_scales) return FQ_INVALID_ARG;
@@ -171,8 +171,9 @@ static fq_status transform_mxfp4(const void* x, const void* P1, const void* P2, 
     a.out_codes = out_codes; a.out_scales = reinterpret_cast<_Float16*>(out_scales);
     a.mx_tiled = tiled;
     const fq::TqDev d = fq::tq_dev_args(a);
-    if (!fq::tq_mx_applicable(d)) return FQ_UNSUPPORTED_SHAPE;
-    return fq::finish(fq::tq_mx_launch(d, static_cast<hipStream_t>(stream)));
+    if (fq::tq_mx_applicable(d)) return fq::finish(fq::tq_mx_launch(d, static_cast<hipStream_t>(stream)));
+    if (fq::tq_mx_generic_applicable(d)) return fq::finish(fq::tq_mx_generic_launch(d, static_cast<hipStream_t>(stream)));
+    return FQ_UNSUPPORTED_SHAPE;
 }
 
 fq_status flatquant_weight_transform_quant(const void* w, const void* A1, const void* A2, const float* clip, int clip_mode,

@@ -55,6 +55,9 @@ hipError_t tq_wave_launch(const TqDev& d, hipStream_t stream, int tpw, bool loop
 // MXFP4 output variant of the specialised kernels (d.out_scales points at the u8 [T, n/32] shared exponents).
 bool tq_mx_applicable(const TqDev& d);
 hipError_t tq_mx_launch(const TqDev& d, hipStream_t stream);
+// ... and of the general kernel, for the shapes those do not take (fq_transform_quant.hip).
+bool tq_mx_generic_applicable(const TqDev& d);
+hipError_t tq_mx_generic_launch(const TqDev& d, hipStream_t stream);
 // Fills the kernel-side block from the checked arguments (alignment facts included).
 TqDev tq_dev_args(const TqArgs& a);
 

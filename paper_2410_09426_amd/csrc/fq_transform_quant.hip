@@ -63,12 +63,15 @@ __device__ __forceinline__ uint32_t nibble(float y, float inv) {
     return (uint32_t)(int)__builtin_rintf(u) & 0xFu;
 }
 
-template <int A, int B, bool P1LDS>
+// MX: MXFP4 output for the shapes the specialised kernels do not take (n2 not a multiple of 32, where a block of 32
+// consecutive channels straddles rows of X~ and column slabs): the token's Y is staged in LDS as fp32 in channel order,
+// then one thread per block takes its 32 values, forms the shared exponent and converts.
+template <int A, int B, bool P1LDS, bool MX = false>
 __global__ __launch_bounds__(64 * B) void tq_kernel(TqDev p) {
     constexpr int NT = 64 * B;
     constexpr int PITCH = 32 * B + kLdsPad;      // halves per LDS row of the token tile
     constexpr int XS_HALVES = 32 * A * PITCH;
-    constexpr int STAGE_BYTES = 512 * A * B;     // >= n / 2
+    constexpr int STAGE_BYTES = (MX ? 4096 : 512) * A * B;     // >= n / 2 bytes of codes, or 4 n bytes of fp32 values
     constexpr int NPRE = 2 * A;                  // 16-byte chunks per thread per token (upper bound)
     constexpr int KB2 = 2 * B;                   // K blocks (of 16) over j
     constexpr int KB1 = 2 * A;                   // K blocks (of 16) over i
@@ -214,6 +217,23 @@ __global__ __launch_bounds__(64 * B) void tq_kernel(TqDev p) {
             }
         }
 
+        const float clipv = p.clip[p.clip_mode ? t : 0];
+        _Float16 sh = (_Float16)0.0f;
+        if constexpr (MX) {
+            __syncthreads();   // (A) all waves are done reading the token tile
+            float* stagef = reinterpret_cast<float*>(stage);
+#pragma unroll
+            for (int It = 0; It < A; ++It) {
+                const int ip = 32 * It + c;
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int jp = 32 * w + 8 * g + 4 * h + k;
+                        if (ip < n1 && jp < n2) stagef[ip * n2 + jp] = acc2[It][4 * g + k];
+                    }
+            }
+        } else {
         // ---- per-token absmax (padded rows/columns are exact zeros)
         float m = 0.0f;
 #pragma unroll
@@ -227,8 +247,7 @@ __global__ __launch_bounds__(64 * B) void tq_kernel(TqDev p) {
 #pragma unroll
         for (int b = 0; b < B; ++b) m = __builtin_fmaxf(m, red[b]);
 
-        const float clipv = p.clip[p.clip_mode ? t : 0];
-        const _Float16 sh = (_Float16)(clipv * m / 7.0f);   // round-to-nearest-even to fp16
+        sh = (_Float16)(clipv * m / 7.0f);   // round-to-nearest-even to fp16
         const float s = (float)sh;
         const float inv = (s > 0.0f && s <= 65504.0f) ? 1.0f / s : 0.0f;
 
@@ -252,6 +271,7 @@ __global__ __launch_bounds__(64 * B) void tq_kernel(TqDev p) {
                 }
             }
         }
+        }
         // ---- next token tile into LDS (its loads were issued before the MFMA work)
         if (have_next) {
             if (p.vec8) commit(pre); else load_slow(tn);
@@ -259,13 +279,49 @@ __global__ __launch_bounds__(64 * B) void tq_kernel(TqDev p) {
         __syncthreads();   // (B) staged codes and next tile visible
 
         uint8_t* dst = p.out_codes + t * (int64_t)(n >> 1);
-        if (p.out_vec16) {
-            for (int q = tid; q < (n >> 5); q += NT)
-                __builtin_nontemporal_store(reinterpret_cast<const u32x4*>(stage)[q], reinterpret_cast<u32x4*>(dst) + q);
+        if constexpr (MX) {
+            // Block b = channels 32 b .. 32 b + 31: exponent floor(log2(alpha max)) - 2 (0 for an all-zero block), elements
+            // converted with the stored exponent (the conversion reads the exponent field of its scale operand only,
+            // and field 0 means 2^-127); 16 bytes of codes per block, exponents row-major or in the product's tile order
+            const float* stagef = reinterpret_cast<const float*>(stage);
+            uint8_t* exps = reinterpret_cast<uint8_t*>(p.out_scales);
+            const int nblk = n >> 5;
+            for (int b = tid; b < nblk; b += NT) {
+                float y[32];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const float4 v = reinterpret_cast<const float4*>(stagef + 32 * b)[k];
+                    y[4 * k] = v.x; y[4 * k + 1] = v.y; y[4 * k + 2] = v.z; y[4 * k + 3] = v.w;
+                }
+                float bm = 0.0f;
+#pragma unroll
+                for (int k = 0; k < 32; ++k) bm = __builtin_fmaxf(bm, __builtin_fabsf(y[k]));
+                bm *= clipv;
+                const uint32_t be = (__builtin_bit_cast(uint32_t, bm) >> 23) & 0xffu;
+                const uint32_t e = be > 2 ? be - 2 : 0;
+                const float scale = __builtin_bit_cast(float, e << 23);
+                u32x4 o;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    uint32_t pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, y[8 * d], y[8 * d + 1], scale, 0);
+                    pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(pk, y[8 * d + 2], y[8 * d + 3], scale, 1);
+                    pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(pk, y[8 * d + 4], y[8 * d + 5], scale, 2);
+                    pk = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(pk, y[8 * d + 6], y[8 * d + 7], scale, 3);
+                    o[d] = pk;
+                }
+                reinterpret_cast<u32x4*>(dst)[b] = o;
+                if (p.mx_tiled) exps[((((t >> 7) * (int64_t)(n >> 8) + (b >> 3)) * 128 + (t & 127)) << 3) + (b & 7)] = (uint8_t)e;
+                else exps[t * (int64_t)nblk + b] = (uint8_t)e;
+            }
         } else {
-            for (int q = tid; q < (n >> 1); q += NT) dst[q] = stage[q];
+            if (p.out_vec16) {
+                for (int q = tid; q < (n >> 5); q += NT)
+                    __builtin_nontemporal_store(reinterpret_cast<const u32x4*>(stage)[q], reinterpret_cast<u32x4*>(dst) + q);
+            } else {
+                for (int q = tid; q < (n >> 1); q += NT) dst[q] = stage[q];
+            }
+            if (tid == 0) p.out_scales[t] = sh;
         }
-        if (tid == 0) p.out_scales[t] = sh;
     }
 }
 
@@ -287,6 +343,19 @@ static KernelFn kernel_table(int A, int B) {
     return tab[A - 1][B - 1];
 }
 
+template <int A, int B>
+static constexpr KernelFn mx_kernel_for() { return &tq_kernel<A, B, (A >= 3), true>; }
+
+static KernelFn mx_kernel_table(int A, int B) {
+    static const KernelFn tab[4][8] = {
+        {mx_kernel_for<1, 1>(), mx_kernel_for<1, 2>(), mx_kernel_for<1, 3>(), mx_kernel_for<1, 4>(), mx_kernel_for<1, 5>(), mx_kernel_for<1, 6>(), mx_kernel_for<1, 7>(), mx_kernel_for<1, 8>()},
+        {mx_kernel_for<2, 1>(), mx_kernel_for<2, 2>(), mx_kernel_for<2, 3>(), mx_kernel_for<2, 4>(), mx_kernel_for<2, 5>(), mx_kernel_for<2, 6>(), mx_kernel_for<2, 7>(), mx_kernel_for<2, 8>()},
+        {mx_kernel_for<3, 1>(), mx_kernel_for<3, 2>(), mx_kernel_for<3, 3>(), mx_kernel_for<3, 4>(), mx_kernel_for<3, 5>(), mx_kernel_for<3, 6>(), mx_kernel_for<3, 7>(), mx_kernel_for<3, 8>()},
+        {mx_kernel_for<4, 1>(), mx_kernel_for<4, 2>(), mx_kernel_for<4, 3>(), mx_kernel_for<4, 4>(), mx_kernel_for<4, 5>(), mx_kernel_for<4, 6>(), mx_kernel_for<4, 7>(), mx_kernel_for<4, 8>()},
+    };
+    return tab[A - 1][B - 1];
+}
+
 bool tq_supported(int n1, int n2) {
     return n1 >= 1 && n1 <= kMaxN1 && n2 >= 2 && n2 <= kMaxN2 && (n2 % 2) == 0;
 }
@@ -303,6 +372,33 @@ int64_t tq_lds_bytes(int n1, int n2) {
     const int64_t b = generic_lds_bytes(n1, n2);
     const int64_t f = tq_fast_lds_bytes(n1, n2);   // the specialised kernels stage P1/P2 in LDS as well
     return f > b ? f : b;
+}
+
+static int64_t generic_mx_lds_bytes(int n1, int n2) {
+    const int A = (n1 + 31) / 32, B = (n2 + 31) / 32;
+    return generic_lds_bytes(n1, n2) + (int64_t)(4096 - 512) * A * B;
+}
+
+// MXFP4 output through the general kernel: any supported (n1, n2) with whole blocks of 32 channels per row whose
+// fp32 staging fits in LDS beside the token tile (64 x 172: 74 KB), 16-byte aligned code rows.
+bool tq_mx_generic_applicable(const TqDev& d) {
+    const int64_t n = (int64_t)d.n1 * d.n2;
+    return tq_supported(d.n1, d.n2) && n % 32 == 0 && d.out_vec16 && d.P1 && d.P2 && generic_mx_lds_bytes(d.n1, d.n2) <= 160 * 1024;
+}
+
+hipError_t tq_mx_generic_launch(const TqDev& d, hipStream_t stream) {
+    const int A = (d.n1 + 31) / 32, B = (d.n2 + 31) / 32;
+    KernelFn fn = mx_kernel_table(A, B);
+    const int lds = (int)generic_mx_lds_bytes(d.n1, d.n2);
+    static OccCache occ_cache[4][8];
+    int occ = 0;
+    {
+        hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(fn), 64 * B, lds, occ_cache[A - 1][B - 1], occ);
+        if (e != hipSuccess) return e;
+    }
+    int64_t grid = (int64_t)cu_count() * occ;
+    if (grid > d.T) grid = d.T;
+    return launch(fn, dim3((unsigned)grid), dim3(64 * B), lds, stream, d);
 }
 
 TqDev tq_dev_args(const TqArgs& a) {

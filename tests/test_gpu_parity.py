@@ -349,6 +349,19 @@ def test_mxfp4_wave_per_token_kernel(tuning, mode, tpw):
         test_mxfp4_tiled_exponents_equal_row_major(n1, 64, T)
 
 
+@pytest.mark.parametrize("n1,n2,T", [(64, 172, 70), (64, 172, 2049), (10, 48, 33), (3, 32, 7), (64, 34, 300), (86, 16, 129), (128, 130, 40), (1, 32, 5)])
+def test_mxfp4_output_general_kernel(n1, n2, T):
+    """Right factors that are not a multiple of 32 (a block of 32 channels then straddles rows of X~; 64 x 172 is the
+    paper's other factorization of 11008), and rows of fewer than 128 channels: the general kernel stages Y in LDS and
+    quantizes block by block.  Row-major exponents against the oracle; the tile order, where the row has whole groups of
+    256 channels, against the row-major output."""
+    c = synth.generic(1700 + n1 + n2 + T, T, n1, n2, clip_mode=T % 2)
+    print(f"[case] mxfp4 general kernel {n1}x{n2} T={T}", flush=True)
+    run_mx(c, rows=None if T <= 300 else subset_rows(T, 100, 5, must=(0, 1, 2047, 2048, T - 1)))
+    if (n1 * n2) % 256 == 0:
+        test_mxfp4_tiled_exponents_equal_row_major(n1, n2, T)
+
+
 def test_mxfp4_bottom_of_the_exponent_range():
     """Blocks whose clipped maximum lies below 2^-124 store exponent 0 (scale 2^-127, the smallest the format has) and
     their elements are converted with that scale; just above, exponents 1, 2, ...  Reached here through a tiny

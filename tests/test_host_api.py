@@ -39,7 +39,7 @@ def test_header_is_plain_c_and_links_without_python(tmp_path):
         "    if (fq_choose_factors(8192, &n1, &n2) != FQ_OK || n1 != 64 || n2 != 128) return 1;\n"
         "    if (!fq_supported(64, 64) || fq_supported(129, 64)) return 2;\n"
         "    if (flatquant_transform_quant(0, 0, 0, 0, 0, 0, 64, 64, 4096, 0, 0, 0) != FQ_OK) return 3;      /* T == 0 */\n"
-        "    if (flatquant_transform_mxfp4(0, 0, 0, 0, 0, 4, 64, 172, 11008, 0, 0, 0) != FQ_UNSUPPORTED_SHAPE) return 4;\n"
+        "    if (flatquant_transform_mxfp4(0, 0, 0, 0, 0, 4, 3, 34, 102, 0, 0, 0) != FQ_UNSUPPORTED_SHAPE) return 4;\n"
         '    printf("%s %d\\n", fq_status_string(FQ_MISALIGNED), fq_abi_version());\n'
         "    return 0;\n}\n")
     inc = os.path.join(ROOT, "include")
@@ -116,8 +116,9 @@ def test_argument_validation_without_a_device():
     mx = lambda **k: fq.flatquant_transform_mxfp4(**{**dict(x=A, P1=A + 0x100000, P2=A + 0x200000, clip=A + 0x300000, clip_mode=1, T=4, n1=64,
                                                          n2=64, x_stride=4096, out_codes=A + 0x400000, out_scales=A + 0x500000, check=False), **k})
     assert mx(T=0) == fq.FQ_OK
-    assert mx(n2=172, x_stride=64 * 172) == fq.FQ_UNSUPPORTED_SHAPE and mx(n1=129, x_stride=129 * 64) == fq.FQ_UNSUPPORTED_SHAPE
-    assert mx(n1=3, n2=64, x_stride=192) == fq.FQ_UNSUPPORTED_SHAPE      # n not a multiple of 128
+    assert mx(n1=3, n2=34, x_stride=3 * 34) == fq.FQ_UNSUPPORTED_SHAPE      # 102 channels: no whole blocks of 32
+    assert mx(n1=129, x_stride=129 * 64) == fq.FQ_UNSUPPORTED_SHAPE
+    assert mx(n1=3, n2=33, x_stride=99) == fq.FQ_UNSUPPORTED_SHAPE          # odd right factor
     assert mx(P2=None) == fq.FQ_INVALID_ARG and mx(clip_mode=2) == fq.FQ_INVALID_ARG
     assert mx(x=A + 8) == fq.FQ_MISALIGNED and mx(out_scales=A + 0x500002) == fq.FQ_MISALIGNED and mx(x_stride=4100) == fq.FQ_MISALIGNED
     assert mx(out_scales=A + 0x400000) == fq.FQ_INVALID_ARG            # exponents inside the code buffer
