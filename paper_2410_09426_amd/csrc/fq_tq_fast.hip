@@ -761,12 +761,12 @@ int64_t tq_fast_lds_bytes(int n1, int n2) {
 hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
     const int A = (d.n1 + 31) / 32, B = d.n2 / 32;
     const bool full1 = (d.n1 % 32) == 0;
-    // Kernel flavour (see variant_ab), from measurements on MI355X: the pipelined loop wins or ties the plain loop
-    // wherever it fits; very long 64-wide streams sustain ~10 % more with one wave per token; and when every token can
-    // have its own resident workgroup (4 waves per SIMD) the loop-free kernel is ~10 % faster still.  What the
-    // loop-free kernel pays per workgroup is the staging of P1 and P2: 16 KB through the CU's vector memory path per
-    // 8 KB token at 64 x 64 (about 0.8 us of the launch at T = 2048, measured by staging from a single cache line).
-    // FLATQUANT_MODE overrides the choice for tuning and tests.
+    // Kernel flavour (see variant_ab), from measurements on MI355X (tables below): 64-wide rows belong to the
+    // wave-per-token kernel except for the smallest launches; when every token can have its own resident workgroup the
+    // loop-free kernel wins; of the two persistent loops the pipelined one wins for 32 x 128 from 16384 tokens on and
+    // for the other shapes with at most two row tiles, the plain one for 64 x 128 and for three or four row tiles.
+    // What the loop-free kernel pays per workgroup is the staging of P1 and P2.  FLATQUANT_MODE overrides the choice
+    // for tuning and tests.
     static OccCache occ_cache[4][8][2][5];   // per variant and device
     auto occupancy = [&](int mode, int& occ) -> hipError_t {
         const Variant v = variant(A, B, full1, mode);
