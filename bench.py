@@ -124,15 +124,56 @@ def main() -> int:
     scales = [torch.empty((T,), dtype=torch.float16, device="cuda") for _ in range(nsets)]
     clips = [clip] + [clip.clone() for _ in range(nsets - 1)]
 
-    step_cold = Rotation(lambda k: fq.flatquant_transform_quant(xs[k], P1, P2, clips[k], 1, T, n1, n2, n, codes[k], scales[k], stream=stream), nsets)
-    step_warm = Rotation(lambda k: fq.flatquant_transform_quant(xs[0], P1, P2, clips[0], 1, T, n1, n2, n, codes[0], scales[0], stream=stream), 1)
+    # Device addresses are taken once: the host has to enqueue a launch in less time than the kernel runs (6 us), and
+    # marshalling six tensors per call costs about 1 us of that in a short region (the binding takes plain addresses too).
+    xa, ca, oa, sa = ([t.data_ptr() for t in v] for v in (xs, clips, codes, scales))
+    p1a, p2a, st = P1.data_ptr(), P2.data_ptr(), stream.cuda_stream
+
+    def launch_cold(k, s=st):
+        fq.flatquant_transform_quant(xa[k], p1a, p2a, ca[k], 1, T, n1, n2, n, oa[k], sa[k], stream=s)
+
+    def launch_probe(k, s=st):
+        fq.flatquant_stream_probe(xa[k], T, n, n, oa[k], stream=s)
+
+    step_cold = Rotation(launch_cold, nsets)
+    step_warm = Rotation(lambda k: launch_cold(0), 1)
     # the same buffers and the same rotation without the arithmetic: what a copy-like launch of this size reaches on this
     # box.  Three launch shapes of the probe are timed; the fastest is the ceiling.
-    step_probe = Rotation(lambda k: fq.flatquant_stream_probe(xs[k], T, n, n, codes[k], stream=stream), nsets)
+    step_probe = Rotation(launch_probe, nsets)
+
+    def rotation_graph_us(launch, replays=9):
+        """One launch per buffer set, all sets in order, captured in a HIP graph and replayed: us per launch with the host
+        out of the loop (cold data as in the eager rotation).  None if capture is not available."""
+        try:
+            gs = torch.cuda.Stream()
+            gs.wait_stream(stream)
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(gs):
+                launch(0, gs.cuda_stream)
+                gs.synchronize()
+                with torch.cuda.graph(gr, stream=gs):
+                    for k in range(nsets):
+                        launch(k, gs.cuda_stream)
+                gr.replay()
+                v = []
+                for _ in range(replays):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(gs)
+                    gr.replay()
+                    e1.record(gs)
+                    gs.synchronize()
+                    v.append(e0.elapsed_time(e1) / nsets * 1e3)
+            stream.wait_stream(gs)
+            return float(np.median(v))
+        except Exception as ex:   # a measurement nicety only
+            print(f"bench.py: graph replay of the rotation skipped ({type(ex).__name__})", file=sys.stderr)
+            return None
     probe_us = {}
     for shape, label in ((0, "persistent_two_wave_workgroups"), (1, "wave_per_row_nontemporal"), (2, "wave_per_row_plain_loads")):
         fq.fq_set_tuning("FLATQUANT_PROBE_SHAPE", shape)
         probe_us[label] = median_regions(step_probe, args.steps, args.warmup)[0] * 1e3
+    fq.fq_set_tuning("FLATQUANT_PROBE_SHAPE", min(range(3), key=lambda i: list(probe_us.values())[i]))
+    us_graph_probe = rotation_graph_us(launch_probe)   # (the probe writes into the code buffers: it runs before the kernel)
     fq.fq_set_tuning("FLATQUANT_PROBE_SHAPE", None)
     ms_probe = min(probe_us.values()) * 1e-3
 
@@ -140,6 +181,7 @@ def main() -> int:
     us_single_cold = single_launch_us(step_cold)
     ms_cold_long = median_regions(step_cold, 1000, 0, reps=3)[0]   # steady state, whatever --steps is
     ms_warm, _, _ = median_regions(step_warm, args.steps, args.warmup)
+    us_graph_cold = rotation_graph_us(launch_cold)
     used = min(nsets, step_cold.count)
     for k in range(1, used):    # every rotation set that was used produced the same bytes
         assert torch.equal(codes[k], codes[0]) and torch.equal(scales[k].view(torch.int16), scales[0].view(torch.int16))
@@ -180,6 +222,7 @@ def main() -> int:
             "us_per_call_cold": ms_cold * 1e3, "us_per_call_cold_regions": [v * 1e3 for v in cold_regions], "us_per_call_warm": ms_warm * 1e3,
             "us_single_launch_cold_idle_stream": us_single_cold, "us_per_call_cold_1000_step_regions": ms_cold_long * 1e3,
             "host_wall_us_per_call_cold": wall_cold * 1e3,
+            "us_per_call_cold_graph_replay": us_graph_cold, "stream_probe_us_per_call_cold_graph_replay": us_graph_probe,
             "stream_probe_us_per_call_cold": ms_probe * 1e3, "stream_probe_us_by_shape": probe_us,
             "stream_probe_gbs": T * (2 * n + n // 2) / (ms_probe * 1e-3) / 1e9,
             "tokens_per_s_warm": T / (ms_warm * 1e-3),
