@@ -49,7 +49,7 @@ struct TqDev {
 bool tq_fast_applicable(const TqDev& d);
 int64_t tq_fast_lds_bytes(int n1, int n2);
 hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream);
-// One wavefront per token, token rows straight from global memory into MFMA operands (fq_tq_wave.hip; n2 = 64).
+// One wavefront per token, rows through a wave-private LDS tile (fq_tq_wave.hip; n2 = 64, n1 = 32 or 64; INT4 or MXFP4).
 bool tq_wave_applicable(const TqDev& d);
 hipError_t tq_wave_launch(const TqDev& d, hipStream_t stream, int tpw, bool loop, bool mx);
 // MXFP4 output variant of the specialised kernels (d.out_scales points at the u8 [T, n/32] shared exponents).

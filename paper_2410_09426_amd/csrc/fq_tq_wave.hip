@@ -26,8 +26,6 @@
 
 namespace fq {
 
-typedef short short2v __attribute__((ext_vector_type(2)));
-
 // TPW waves (= tokens in flight) per workgroup.  LOOP: persistent workgroups, a wave takes tokens t, t + G, ...
 // (G = all waves of the grid) with the next token's rows requested before the current one is worked on.
 // MX: MXFP4 output (E2M1 codes, one E8M0 exponent per 32 channels) instead of INT4 codes and a step: the 32 channels of a
