@@ -39,7 +39,9 @@ struct FastLds {
     static constexpr int P1FLAT_BYTES = 32 * A * 32 * A * 2;
     static constexpr int STG_BYTES = P1FLAT_BYTES + P2ROWS * N2 * 2;
     static constexpr int R0 = (cmax(BODY_BYTES, STG_BYTES) + 15) & ~15;
-    static constexpr bool P1LDS = (A >= 3);
+    // P1's fragments stay in registers up to three row tiles x six column slabs (86 x 128: 137 -> 130 us at T=16384,
+    // 6.7 -> 6.4 us at 64 tokens); beyond that they would spill, and are read from a table in LDS at every use
+    static constexpr bool P1LDS = (A >= 4) || (A == 3 && B >= 7);
     static constexpr int P1S_BYTES = P1LDS ? A * 2 * A * 64 * 16 : 0;
     static constexpr int TOTAL = R0 + P1S_BYTES;
 };
