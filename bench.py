@@ -177,9 +177,12 @@ def main() -> int:
     fq.fq_set_tuning("FLATQUANT_PROBE_SHAPE", None)
     ms_probe = min(probe_us.values()) * 1e-3
 
+    # The long regions run first: a chip that has just come out of idle takes a few hundred launches to settle (the
+    # first regions of a fresh process measure 0.4 - 0.8 us per launch more than the later ones), and the K-launch
+    # regions are meant to measure the kernel, not that transient.
+    ms_cold_long = median_regions(step_cold, 1000, args.warmup, reps=3)[0]   # steady state, whatever --steps is
     ms_cold, wall_cold, cold_regions = median_regions(step_cold, args.steps, args.warmup)
     us_single_cold = single_launch_us(step_cold)
-    ms_cold_long = median_regions(step_cold, 1000, 0, reps=3)[0]   # steady state, whatever --steps is
     ms_warm, _, _ = median_regions(step_warm, args.steps, args.warmup)
     us_graph_cold = rotation_graph_us(launch_cold)
     used = min(nsets, step_cold.count)
