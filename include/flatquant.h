@@ -274,7 +274,7 @@ int fq_abi_version(void);
 /*
  * Tuning overrides, for measurements and tests (the defaults are what the library measures best).  `name` is one of
  * FLATQUANT_MODE (activation kernel flavour: 0..4 the slab kernels, 5 / 6 the wave-per-token kernel of 64-wide rows, one
- * shot / persistent), FLATQUANT_WAVE_TPW (2 / 4 / 8 waves per workgroup of that kernel), FLATQUANT_PROBE_SHAPE (0..2: launch
+ * shot / persistent; 5 also forces the wave-per-token kernel of the left-factor-only case), FLATQUANT_WAVE_TPW (2 / 4 / 8 waves per workgroup of that kernel), FLATQUANT_PROBE_SHAPE (0..2: launch
  * shape of flatquant_stream_probe), FLATQUANT_WG_PER_CU, FLATQUANT_KV_WG_PER_CU (cap on resident
  * workgroups), FLATQUANT_FORCE_GENERIC (1: general kernel on shapes the specialised ones would take),
  * FLATQUANT_GEMM_TILED (1: tiled product for any T), FLATQUANT_GEMM_WIDE (0 / 1: 128- or 256-token tiles),

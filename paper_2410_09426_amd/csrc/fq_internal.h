@@ -52,6 +52,9 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream);
 // One wavefront per token, rows through a wave-private LDS tile (fq_tq_wave.hip; n2 = 64, n1 = 32 or 64; INT4 or MXFP4).
 bool tq_wave_applicable(const TqDev& d);
 hipError_t tq_wave_launch(const TqDev& d, hipStream_t stream, int tpw, bool loop, bool mx);
+// ... and its left-factor-only sibling for 128-wide rows (P2 == nullptr, n1 = 32 or 64; loop-free).
+bool po_wave_applicable(const TqDev& d);
+hipError_t po_wave_launch(const TqDev& d, hipStream_t stream);
 // MXFP4 output variant of the specialised kernels (d.out_scales points at the u8 [T, n/32] shared exponents).
 bool tq_mx_applicable(const TqDev& d);
 hipError_t tq_mx_launch(const TqDev& d, hipStream_t stream);

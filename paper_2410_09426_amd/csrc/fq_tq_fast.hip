@@ -776,6 +776,12 @@ hipError_t tq_fast_launch(const TqDev& d, hipStream_t stream) {
         return kernel_occupancy(reinterpret_cast<const void*>(v.fn), threads, v.lds, occ_cache[A - 1][B - 1][full1][mode], occ);
     };
     if (!d.P2) {   // left factor only (n1 = 32 or 64, n2 = 128): loop-free kernel while every token gets a resident workgroup
+        {   // wave-per-token kernel (fq_tq_wave.hip), measured against the kernels below (us per launch, cold rotation):
+            // 32 x 128: T = 512 4.35 / 4.45, 2048 5.6 / 7.2, 4096 9.0 / 10.8, 8192 15.7 / 17.9, 16384 28.7 / 32.1;
+            // 64 x 128: T = 2048 9.6 / 12.1, 8192 35.7 / 32.3, 16384 64.7 / 59.8.  FLATQUANT_MODE = 5 forces it.
+            const int m = env_int("FLATQUANT_MODE", -1);
+            if ((m == 5 || (m == -1 && d.T > 256 && (d.n1 == 32 || d.T <= 4096))) && po_wave_applicable(d)) return po_wave_launch(d, stream);
+        }
         const bool two = (A == 2);
         static OccCache occ_id2[2][2];
         auto kern = [&](int one) -> Variant {

@@ -333,6 +333,156 @@ __global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) v
 }
 
 // ------------------------------------------------------------------------------------
+// Left factor only, 128-wide rows (the online part of P_o: heads x head_dim with P2 = I; n1 = 32 or 64): Y = P1^T X~,
+// one wavefront per token, loop-free.  There is no first contraction and no hi / lo split: the second contraction's
+// operand is X~ itself (exact fp16), gathered from the wave's tile with transposing reads (rows i = K, columns = the
+// slab's 32 channels), so the tile keeps plain rows at a padded pitch instead of the swizzle.  A token row is
+// contiguous in memory, so load k is simply bytes 1024 k .. of the token (4 rows of X~).  Row tiles as above: the
+// K blocks of a 32-row tile are multiplied as soon as its eight loads have arrived.
+template <int A, int TPW>
+__global__ __launch_bounds__(64 * TPW) __attribute__((amdgpu_waves_per_eu(2))) void po_wave_kernel(const void* __restrict__ aP1, const void* __restrict__ ax, int64_t x_stride, int64_t T,
+                    const float* __restrict__ clip, uint8_t* __restrict__ out_codes, void* __restrict__ out_scales, int clip_mode) {
+    constexpr int N1 = 32 * A, N2 = 128, KB1 = 2 * A, NT = 64 * TPW, NQ = 4;
+    constexpr int CH1 = N1 * N1 / 8;                  // 16-byte chunks of P1
+    constexpr int NLD = (CH1 + NT - 1) / NT;
+    constexpr int PITCH = N2 + 8;                     // halves per tile row: 16 bytes of padding keep the transposing reads off one bank group
+    constexpr int TILE_BYTES = N1 * PITCH * 2;
+    constexpr int LPT = 8, NROW = A * LPT;            // loads of 1 KB per row tile, per token
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    _Float16* P1flat = reinterpret_cast<_Float16*>(smem);
+    const int tid = threadIdx.x;
+    const int l = tid & 63, c = l & 31, h = l >> 5;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    _Float16* tile = reinterpret_cast<_Float16*>(smem + CH1 * 16 + wv * TILE_BYTES);
+    int64_t t = (int64_t)blockIdx.x * TPW + wv;
+    if (t >= T) t = T - 1;                            // spare waves of the last workgroup redo token T - 1: same bytes stored twice
+
+    u32x4 pv[NLD];
+#pragma unroll
+    for (int k = 0; k < NLD; ++k) {
+        const int idx = tid + k * NT;
+        pv[k] = reinterpret_cast<const u32x4*>(aP1)[idx < CH1 ? idx : CH1 - 1];
+    }
+    // P1 (L2) in front of every wave's token rows (HBM) in the CU's request queue, as in the kernel above
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 pre[NROW];
+    {
+        const unsigned char* row = reinterpret_cast<const unsigned char*>(static_cast<const _Float16*>(ax) + t * x_stride);
+#pragma unroll
+        for (int k = 0; k < NROW; ++k) pre[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + k * 1024 + 16 * l));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < NLD; ++k) {
+        const int idx = tid + k * NT;
+        if (CH1 % NT == 0 || idx < CH1) reinterpret_cast<u32x4*>(smem)[idx] = pv[k];
+    }
+    __syncthreads();
+    // B operand, gathered with the K permutation of the operand layout that feeds it (see the kernel above)
+    half8 p1f[A][KB1];
+#pragma unroll
+    for (int It = 0; It < A; ++It)
+#pragma unroll
+        for (int kk = 0; kk < KB1; ++kk)
+            p1f[It][kk] = lds_column8(P1flat, N1, 32 * (kk >> 1) + 16 * (kk & 1) + 4 * h, 8, 32 * It + (c & 16), l & 15);
+    __builtin_amdgcn_sched_barrier(0);
+
+    const float clipv = clip[clip_mode ? t : 0];
+    f32x16 acc2[NQ][A];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+        for (int It = 0; It < A; ++It)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc2[q][It][r] = 0.0f;
+#pragma unroll
+    for (int Ir = 0; Ir < A; ++Ir) {
+        // rows 32 Ir .. 32 Ir + 31 of X~: load k covers rows 4 k .. 4 k + 3 (16 lanes per row)
+#pragma unroll
+        for (int k = LPT * Ir; k < LPT * Ir + LPT; ++k)
+            *reinterpret_cast<u32x4*>(tile + (4 * k + (l >> 4)) * PITCH + 8 * (l & 15)) = pre[k];
+        // (the tile is this wave's alone and LDS executes a wave's instructions in order; the fences only keep the compiler
+        // from moving the transposing reads above the writes)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int kq = 0; kq < 2; ++kq) {
+            const int kk = 2 * Ir + kq;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const half8 z = lds_column8(tile, PITCH, 32 * (kk >> 1) + 16 * (kk & 1) + 4 * h, 8, 32 * q + (c & 16), l & 15);
+#pragma unroll
+                for (int It = 0; It < A; ++It) acc2[q][It] = __builtin_amdgcn_mfma_f32_32x32x16_f16(z, p1f[It][kk], acc2[q][It], 0, 0, 0);
+            }
+        }
+    }
+    // ---- absmax, step, round, pack, store: as in the kernel above, two slab pairs per row of X~
+    float m = 0.0f;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+        for (int It = 0; It < A; ++It)
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) m = __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(acc2[q][It][r])), __builtin_fabsf(acc2[q][It][r + 1]));
+    m = wave_max(m);
+    const _Float16 sh = (_Float16)(clipv * m * 0.142857149f);
+    const float s = (float)sh;
+    const float inv = (s > 0.0f && s <= 65504.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;
+    const float kmul = inv * (4096.0f / 32767.0f);
+    constexpr float kadd = 2047.5f / 32767.0f;
+    uint8_t* out_row = out_codes + t * (int64_t)(N1 * N2 / 2) + c * (N2 / 2) + 16 * h;
+#pragma unroll
+    for (int It = 0; It < A; ++It)
+#pragma unroll
+        for (int qp = 0; qp < NQ / 2; ++qp) {
+            u32x4 o;
+#pragma unroll
+            for (int mm = 0; mm < 2; ++mm) {
+                uint32_t W[2];
+#pragma unroll
+                for (int qq = 0; qq < 2; ++qq) {
+                    const f32x16& y = acc2[2 * qp + qq][It];
+                    uint32_t D[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        D[k] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pknorm_i16(__builtin_fmaf(y[8 * mm + k], kmul, kadd), __builtin_fmaf(y[8 * mm + 4 + k], kmul, kadd)));
+                    const uint32_t E = __builtin_amdgcn_perm(D[2], D[0], 0x07030501u);
+                    const uint32_t F = __builtin_amdgcn_perm(D[3], D[1], 0x07030501u);
+                    W[qq] = (F & 0xF0F0F0F0u) | ((E >> 4) & 0x0F0F0F0Fu);
+                }
+                const auto sw = __builtin_amdgcn_permlane32_swap(W[0], W[1], false, false);
+                o[2 * mm] = __builtin_amdgcn_perm(sw[1], sw[0], 0x05040100u);
+                o[2 * mm + 1] = __builtin_amdgcn_perm(sw[1], sw[0], 0x07060302u);
+            }
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(out_row + It * (32 * N2 / 2) + 32 * qp));
+        }
+    static_cast<_Float16*>(out_scales)[t] = sh;
+}
+
+bool po_wave_applicable(const TqDev& d) {
+    if (d.P2 || !d.P1 || d.n2 != 128 || (d.n1 != 32 && d.n1 != 64) || !d.vec8 || !d.out_vec16) return false;
+    if (reinterpret_cast<uintptr_t>(d.P1) & 15) return false;
+    return d.T >= 1 && d.T <= 0x7fffffff;
+}
+
+hipError_t po_wave_launch(const TqDev& d, hipStream_t stream) {
+    constexpr int TPW = 4;
+    using Fn = void (*)(const void*, const void*, int64_t, int64_t, const float*, uint8_t*, void*, int);
+    const bool two = d.n1 == 64;
+    Fn fn = two ? &po_wave_kernel<2, TPW> : &po_wave_kernel<1, TPW>;
+    const int lds = d.n1 * d.n1 * 2 + TPW * d.n1 * (128 + 8) * 2;
+    static OccCache occ_cache[2];   // the first call also raises the kernel's LDS limit
+    int occ = 0;
+    hipError_t e = kernel_occupancy(reinterpret_cast<const void*>(fn), 64 * TPW, lds, occ_cache[two], occ);
+    if (e != hipSuccess) return e;
+    return launch(fn, dim3((unsigned)((d.T + TPW - 1) / TPW)), dim3(64 * TPW), lds, stream, d.P1, d.x, d.x_stride, d.T, d.clip, d.out_codes, d.out_scales, d.clip_mode);
+}
+
+// ------------------------------------------------------------------------------------
 bool tq_wave_applicable(const TqDev& d) {
     if (d.n2 != 64 || (d.n1 != 32 && d.n1 != 64) || !d.P1 || !d.P2 || !d.vec8 || !d.out_vec16) return false;
     if ((reinterpret_cast<uintptr_t>(d.P1) | reinterpret_cast<uintptr_t>(d.P2)) & 15) return false;

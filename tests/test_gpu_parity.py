@@ -887,6 +887,25 @@ def test_one_sided_transforms(n1, n2, T, which):
     assert rep["band_flips"] <= parity.band_flip_allowance(rep["in_band"])
 
 
+@pytest.mark.parametrize("mode", ["5", "0", "3"])
+@pytest.mark.parametrize("n1,T", [(32, 2048 + 3), (32, 1), (32, 9), (64, 2500), (64, 130), (32, 9001)])
+def test_left_factor_only_every_kernel(tuning, mode, n1, T):
+    """128-wide rows with the left factor alone: the wave-per-token kernel (5) and the slab kernels' persistent loop (0)
+    and loop-free launch (3), each forced (the default picks by token count); a zero row and large magnitudes included."""
+    tuning("FLATQUANT_MODE", mode)
+    c = synth.generic(860 + n1 + T, T, n1, 128)
+    if T > 8:
+        c.x[3] = 0
+        c.x[5] = (np.sign(c.x[5].astype(np.float32)) * 700).astype(np.float16)
+    print(f"[case] left factor only, mode {mode}, {n1}x128 T={T}", flush=True)
+    codes, scales, _, _ = run_tq(dev(c.x), dev(c.P1), None, dev(c.clip), c.clip_mode, n1, 128)
+    rows = subset_rows(T, 200, 33, must=(0, 3, 5, T - 1))
+    y = fo.affine_transform_factored(c.x[rows], c.P1, np.eye(128, dtype=np.float16))
+    rep = parity.check_sym(y, c.clip[rows], codes[rows], scales[rows], rows=rows)
+    print(f"[parity] {rep}", flush=True)
+    assert rep["band_flips"] <= parity.band_flip_allowance(rep["in_band"])
+
+
 def _one_sided_grid():
     r = np.random.Generator(np.random.PCG64(2718))
     cases = set()
