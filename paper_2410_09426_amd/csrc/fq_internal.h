@@ -43,6 +43,7 @@ struct TqDev {
     int out_vec16;  // code rows are whole 16-byte units at 16-byte aligned addresses
     int mx_tiled = 0;   // MXFP4 output only: exponents in the tile order the MXFP4 product reads (see flatquant.h)
     uint32_t n1_magic = 0;   // floor(2^32 / n1) + 1 (n1 >= 2): floor(f / n1) = umulhi(f, n1_magic) for f < 2^16
+    uint32_t n2_magic = 0;   // the same for n2
 };
 
 // Specialised kernels for n2 a multiple of 32 and 16-byte aligned buffers (fq_tq_fast.hip).

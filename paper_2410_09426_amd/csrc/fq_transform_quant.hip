@@ -154,11 +154,27 @@ __global__ __launch_bounds__(64 * B) void tq_kernel(TqDev p) {
         for (int k = 0; k < NPRE; ++k)
             if (xoff[k] >= 0) *reinterpret_cast<u32x4*>(Xs + xoff[k]) = pre[k];
     };
-    auto load_slow = [&](int64_t t) {   // rows that cannot move in 16-byte chunks: pairs of halves
+    // rows that cannot move in 16-byte chunks (n2 not a multiple of 8, or an unaligned x): pairs of halves, requested
+    // into registers before the MFMA work like the chunks above (n / 2 pairs over the workgroup: at most 8 A per thread);
+    // a pair never straddles a row (n2 is even), and its row is umulhi(2 u, magic) with the magic divisor from the host
+    constexpr int NPS = 8 * A;
+    uint32_t pres[NPS];
+    auto issue_slow = [&](int64_t t) {
         const uint32_t* src = reinterpret_cast<const uint32_t*>(p.x + t * p.x_stride);
-        for (int u = tid; u < (n >> 1); u += NT) {
-            const int e = 2 * u, i = e / n2;
-            *reinterpret_cast<uint32_t*>(Xs + i * PITCH + (e - i * n2)) = src[u];
+#pragma unroll
+        for (int k = 0; k < NPS; ++k) {
+            const int u = tid + k * NT;
+            if (u < (n >> 1)) pres[k] = src[u];
+        }
+    };
+    auto commit_slow = [&]() {
+#pragma unroll
+        for (int k = 0; k < NPS; ++k) {
+            const int u = tid + k * NT;
+            if (u < (n >> 1)) {
+                const int e = 2 * u, i = (int)__umulhi((uint32_t)e, p.n2_magic);
+                *reinterpret_cast<uint32_t*>(Xs + i * PITCH + (e - i * n2)) = pres[k];
+            }
         }
     };
 
@@ -166,14 +182,16 @@ __global__ __launch_bounds__(64 * B) void tq_kernel(TqDev p) {
     u32x4 pre[NPRE];
     int64_t t = blockIdx.x;
     if (t < p.T) {
-        if (p.vec8) { issue(t, pre); commit(pre); } else { load_slow(t); }
+        if (p.vec8) { issue(t, pre); commit(pre); } else { issue_slow(t); commit_slow(); }
     }
     __syncthreads();
 
     for (; t < p.T; t += gridDim.x) {
         const int64_t tn = t + gridDim.x;
         const bool have_next = tn < p.T;
-        if (have_next && p.vec8) issue(tn, pre);
+        if (have_next) {
+            if (p.vec8) issue(tn, pre); else issue_slow(tn);
+        }
 
         f32x16 acc2[A];
 #pragma unroll
@@ -274,7 +292,7 @@ __global__ __launch_bounds__(64 * B) void tq_kernel(TqDev p) {
         }
         // ---- next token tile into LDS (its loads were issued before the MFMA work)
         if (have_next) {
-            if (p.vec8) commit(pre); else load_slow(tn);
+            if (p.vec8) commit(pre); else commit_slow();
         }
         __syncthreads();   // (B) staged codes and next tile visible
 
@@ -408,6 +426,7 @@ TqDev tq_dev_args(const TqArgs& a) {
     d.x_stride = a.x_stride; d.T = a.T; d.n1 = a.n1; d.n2 = a.n2; d.clip_mode = a.clip_mode;
     d.mx_tiled = a.mx_tiled;
     d.n1_magic = a.n1 >= 2 ? (uint32_t)(0x100000000ull / (uint64_t)a.n1) + 1u : 0u;
+    d.n2_magic = a.n2 >= 2 ? (uint32_t)(0x100000000ull / (uint64_t)a.n2) + 1u : 0u;
     d.vec8 = (a.n2 % 8 == 0) && (a.x_stride % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.x) & 15) == 0);
     const int64_t n = (int64_t)a.n1 * a.n2;
     d.out_vec16 = (n % 32 == 0) && ((reinterpret_cast<uintptr_t>(a.out_codes) & 15) == 0);
